@@ -1,0 +1,190 @@
+/*
+ * sbgemm.h - C ABI of the StridedBatchedGemm / tensor-contraction library for AMD MI355X (gfx950).
+ *
+ * The library implements the hot path of "Tensor Contractions with Extended BLAS Kernels on CPU
+ * and GPU": the StridedBatchedGemm primitive (section III-D, Listing 1) and the mapping of
+ * single-index tensor contractions in Einstein notation (section II-B, eq. (1)) onto one
+ * flattened GEMM, one StridedBatchedGemm or a nest of them, without copying or transposing
+ * any operand (sections III-B to III-F, Tables I and II, Algorithm 2).
+ *
+ * Conventions common to every entry point
+ *   - Storage (section III-B): dense column-major tensors.  Mode i of a tensor has an element
+ *     stride ld<i>; a packed tensor has ld<0> = 1 and ld<i> = prod_{j<i} dim<j>.  A matrix
+ *     operand is column-major with leading dimension ld: stored element (i,j) is X[i + j*ld].
+ *     All sizes, leading dimensions and strides are counted in ELEMENTS and are 64-bit.
+ *   - Memory: every tensor pointer is DEVICE memory owned by the caller (for example a torch
+ *     tensor's data_ptr()).  The library never allocates, frees, copies or synchronises, and
+ *     needs no workspace.  C must not overlap A or B; A and B may alias.
+ *   - Streams: `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; they return before the kernels have run.
+ *   - Scalars: alpha and beta are passed as double and converted to the arithmetic type of the
+ *     call (double for SB_F64, float for SB_F32 and SB_BF16).
+ *   - beta == 0 means C is not read (NaN/Inf in it are overwritten); alpha == 0 or k == 0 give
+ *     C = beta*C.  The paper defines the beta term in eq. (1) but only ever calls with beta = 0;
+ *     this is the BLAS convention.
+ *   - Errors: functions return an int.  0 = SB_OK.  A negative value -i means the i-th argument
+ *     (1-based, in declaration order) is invalid; nothing was launched.  Positive values are the
+ *     SB_ERR_* codes below.  Nothing is printed and nothing aborts.
+ *   - Quick returns: batch == 0, m == 0 or n == 0 return SB_OK without touching memory.
+ */
+#ifndef SBGEMM_H
+#define SBGEMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Operation applied to a stored matrix operand.
+ * SB_OP_N / SB_OP_T: the stored matrix or its transpose, as in GEMM.
+ * SB_OP_EX_N / SB_OP_EX_T: the "extended" operations proposed in section III-E for the
+ * exceptional cases of Table II, where the batched mode is the FIRST (unit-stride) mode of the
+ * operand.  The batch stride of such an operand is 1 by definition, so its two stride arguments
+ * carry the strides of the other two modes in row-column order of the stored matrix:
+ * `ld` = stride between stored rows, `stride` = stride between stored columns; stored element
+ * (i,j) of batch b is X[b + i*ld + j*stride].  EX_T uses the transpose of that stored matrix. */
+typedef enum { SB_OP_N = 0, SB_OP_T = 1, SB_OP_EX_N = 2, SB_OP_EX_T = 3 } sb_op;
+
+/* Element type of A, B and C.  SB_BF16: bf16 inputs and output, fp32 products and accumulation,
+ * output rounded to nearest-even. */
+typedef enum { SB_F64 = 0, SB_F32 = 1, SB_BF16 = 2 } sb_dtype;
+
+/* How sb_contract chooses among the legal evaluations of a contraction (section IV-D).
+ * Mode strings that carry [ ] or ( ) annotations select the evaluation themselves and need SB_AUTO. */
+typedef enum {
+    SB_AUTO = 0,       /* flatten whenever possible; GEMM over the largest legal mode, batch the rest */
+    SB_FLATTEN = 1,    /* a single flattened GEMM, or SB_ERR_ILLEGAL_EVAL if flattening cannot remove every batch mode */
+    SB_BATCH_LAST = 2, /* no flattening; GEMM columns = 2nd mode of C, every later mode batched ("[p]") */
+    SB_BATCH_MID = 3,  /* no flattening; GEMM columns = last mode of C, the modes between batched ("[n]") */
+    SB_NESTED = 4,     /* no flattening; GEMM over the largest legal mode, all other free modes batched */
+    SB_LEVEL2 = 5      /* batched matrix-vector evaluation (Table II's second kernel of the exceptional rows) */
+} sb_strategy;
+
+enum {
+    SB_OK = 0,
+    SB_ERR_MODES = 1,        /* malformed mode string: bad character, unbalanced [ ] ( ), repeated index, too many modes */
+    SB_ERR_CONTRACTION = 2,  /* index sets violate eq. (1), or not exactly one contracted index */
+    SB_ERR_EXTENT = 3,       /* an index has different extents in two tensors, or a negative extent */
+    SB_ERR_STRIDE = 4,       /* strides unusable: not positive, or matrix columns / batches of C overlap */
+    SB_ERR_ILLEGAL_EVAL = 5, /* the requested evaluation breaks rules 1-4 of section III-B or does not exist */
+    SB_ERR_NO_DEVICE_CODE = 6, /* the library holds no kernel for this device (not gfx950) */
+    SB_ERR_LAUNCH = 1000     /* SB_ERR_LAUNCH + hipError_t of a failed kernel launch */
+};
+
+/*
+ * StridedBatchedGemm (section III-D, Listing 1):
+ *     C_p = alpha * opA(A_p) * opB(B_p) + beta * C_p,   X_p = X + p*strideX,   p = 0 .. batch-1
+ * opA(A_p) is m x k, opB(B_p) is k x n, C_p is m x n.  lda/ldb/ldc are the usual leading
+ * dimensions ("stride between columns"), strideA/B/C the paper's "leading order" loa/lob/loc
+ * ("stride between matrices of the batch").
+ *   - strideA or strideB may be 0 (the operand is shared by all batches, Listing 2).
+ *   - strideC may be smaller than ldc*n (batches interleaved inside one tensor, as in the
+ *     C_m[n]p evaluations of Table II), but two batches must not share an element:
+ *     strideC == 0 with batch > 1 is rejected (-17).
+ *   - ld >= max(1, stored rows) is required for SB_OP_N / SB_OP_T operands and for C.
+ *   - For SB_OP_EX_* see sb_op.
+ * Argument numbers for the error code: dt=1 transA=2 transB=3 m=4 n=5 k=6 alpha=7 A=8 lda=9
+ * strideA=10 B=11 ldb=12 strideB=13 beta=14 C=15 ldc=16 strideC=17 batch=18 stream=19.
+ */
+int sb_gemm(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+            double alpha, const void *A, int64_t lda, int64_t strideA,
+            const void *B, int64_t ldb, int64_t strideB,
+            double beta, void *C, int64_t ldc, int64_t strideC,
+            int64_t batch, void *stream);
+
+/*
+ * Nested batching in ONE launch (section III-F, Listing 2): two batch levels,
+ *     X_{p,q} = X + p*strideX0 + q*strideX1,   p < batch0,  q < batch1.
+ * Equivalent to `for q: sb_gemm(..., A + q*strideA1, ..., batch0)`.  For an SB_OP_EX_* operand
+ * strideX0 is the stored-column stride (see sb_op) and its level-0 batch stride is 1.
+ * Distinct (p,q) must address disjoint C_pq.
+ * Argument numbers: dt=1 transA=2 transB=3 m=4 n=5 k=6 alpha=7 A=8 lda=9 strideA0=10 strideA1=11
+ * B=12 ldb=13 strideB0=14 strideB1=15 beta=16 C=17 ldc=18 strideC0=19 strideC1=20 batch0=21
+ * batch1=22 stream=23.
+ */
+int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+             double alpha, const void *A, int64_t lda, int64_t strideA0, int64_t strideA1,
+             const void *B, int64_t ldb, int64_t strideB0, int64_t strideB1,
+             double beta, void *C, int64_t ldc, int64_t strideC0, int64_t strideC1,
+             int64_t batch0, int64_t batch1, void *stream);
+
+/* The evaluation chosen for a contraction: the arguments of one (nested) StridedBatchedGemm. */
+#define SB_MAX_MODES 8          /* largest tensor order accepted */
+#define SB_MAX_BATCH_LEVELS 8   /* batch levels 0 and 1 run inside one launch, further levels loop on the host */
+typedef struct {
+    int32_t nbatch;       /* number of batched modes: 0 = one flattened GEMM, 1 = one StridedBatchedGemm, >1 = nested */
+    int32_t exceptional;  /* 1 if the evaluation needs an extended operation or a matrix-vector form (section III-E) */
+    int32_t left_is_B;    /* 0: tensor A feeds the first GEMM operand and B the second; 1: the reverse (rule 4, C = B.. A..) */
+    int32_t opL, opR;     /* sb_op of the first / second GEMM operand */
+    int64_t m, n, k;      /* GEMM extents (products of extents for flattened modes) */
+    int64_t ldL, ldR, ldC;    /* leading dimensions; for an SB_OP_EX_* operand: its stored-row stride */
+    int64_t exL, exR;         /* stored-column stride of an SB_OP_EX_* operand, else 0 */
+    int64_t batch[SB_MAX_BATCH_LEVELS];    /* extent of each batched mode, level 0 first */
+    int64_t strideL[SB_MAX_BATCH_LEVELS];  /* element stride of that mode in each operand (0 = operand lacks it) */
+    int64_t strideR[SB_MAX_BATCH_LEVELS];
+    int64_t strideC[SB_MAX_BATCH_LEVELS];
+    char notation[192];   /* the evaluation in the paper's notation, e.g. "C_m[n]p = B_k[n]m^T A_pk^T" */
+} sb_plan;
+
+/*
+ * Contraction planner (host only, touches no device): maps
+ *     C_modesC = alpha * A_modesA * B_modesB + beta * C_modesC            (eq. (1))
+ * with exactly one contracted index onto StridedBatchedGemm arguments, following the notation
+ * rules of section III-B, the case analysis behind Table II and the priorities of section IV-D /
+ * Algorithm 2.
+ *   - modesX: one letter per mode, first mode first ("knp").  The strings may be annotated in the
+ *     paper's notation to demand a specific evaluation: "[p]" batches mode p, "(np)" flattens
+ *     modes n and p, e.g. ("mk", "k[n]p", "m[n]p") or ("mk", "k(np)", "m(np)").  An annotation
+ *     given on one tensor applies to the same indices of the others.  Annotated strings need
+ *     strat == SB_AUTO.
+ *   - dimsX: extent of each mode of X, in X's mode order.  dimsC may be NULL (derived from A, B).
+ *   - stridesX: element stride of each mode, or NULL for packed storage.
+ * Operand placement follows rule 4: the tensor holding C's first mode becomes the first GEMM
+ * operand; transposes are read off from which mode of an operand has unit stride; a batched mode
+ * may not be an operand's unit-stride mode (rule 1) unless an extended operation is used;
+ * flattening needs ld<j> = ld<i>*dim<i> and the same modes in the same order on both sides
+ * (rules 2, 3).
+ * Argument numbers: modesA=1 modesB=2 modesC=3 dimsA=4 stridesA=5 dimsB=6 stridesB=7 dimsC=8
+ * stridesC=9 strat=10 out=11.
+ */
+int sb_contract_plan(const char *modesA, const char *modesB, const char *modesC,
+                     const int64_t *dimsA, const int64_t *stridesA,
+                     const int64_t *dimsB, const int64_t *stridesB,
+                     const int64_t *dimsC, const int64_t *stridesC,
+                     sb_strategy strat, sb_plan *out);
+
+/*
+ * Tensor contraction on device tensors: plans as sb_contract_plan does, then launches the plan
+ * (one launch for up to two batched modes; deeper nests loop over launches on the host, as in
+ * Listing 2).  No operand is copied or transposed.
+ * Argument numbers: dt=1 modesA=2 modesB=3 modesC=4 alpha=5 A=6 dimsA=7 stridesA=8 B=9 dimsB=10
+ * stridesB=11 beta=12 C=13 dimsC=14 stridesC=15 strat=16 stream=17.
+ */
+int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char *modesC,
+                double alpha, const void *A, const int64_t *dimsA, const int64_t *stridesA,
+                const void *B, const int64_t *dimsB, const int64_t *stridesB,
+                double beta, void *C, const int64_t *dimsC, const int64_t *stridesC,
+                sb_strategy strat, void *stream);
+
+/* Launch a plan produced by sb_contract_plan on the tensors it was planned for (device pointers
+ * A, B, C of the ORIGINAL contraction; the plan knows which one feeds which GEMM slot).
+ * Argument numbers: dt=1 plan=2 alpha=3 A=4 B=5 beta=6 C=7 stream=8. */
+int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
+                   double beta, void *C, void *stream);
+
+/* Static text for a status code returned by any function above. */
+const char *sb_status_string(int status);
+
+/* Kernel families behind sb_gemm (diagnostics: tests and the benchmark use these to make sure the
+ * intended path ran).  sb_force_kernel(id) makes later calls use that family when it supports the
+ * problem (SB_KERNEL_AUTO restores the selector); sb_last_kernel() is the family of the most
+ * recent launch of this thread's process (-1 before any).  Neither is thread-safe. */
+enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2 };
+int sb_force_kernel(int kernel_id);
+int sb_last_kernel(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBGEMM_H */

@@ -117,14 +117,14 @@ def contract(modesA, A, modesB, B, modesC, C=None, alpha=1.0, beta=0.0, wide=Tru
     A = np.asarray(A)
     B = np.asarray(B)
     dimsC = _dims_of(modesA, A, modesB, B, modesC)
-    a = np.asfortranarray(A, dtype=np.float64)
-    b = np.asfortranarray(B, dtype=np.float64)
+    a = np.array(A, dtype=np.float64, order="F")
+    b = np.array(B, dtype=np.float64, order="F")
     if C is None:
         if beta != 0.0:
             raise ValueError("beta != 0 needs the old C")
         c = np.zeros(dimsC, dtype=np.float64, order="F")
     else:
-        c = np.asfortranarray(C, dtype=np.float64)
+        c = np.array(C, dtype=np.float64, order="F")
         if list(c.shape) != dimsC:
             raise ValueError("C has the wrong shape")
     out = contract_strided(modesA, a.shape, packed_ld(a.shape), a.ravel(order="F"),
@@ -140,15 +140,15 @@ def contract_at(modesA, A, modesB, B, modesC, cidx, C=None, alpha=1.0, beta=0.0,
     A = np.asarray(A)
     B = np.asarray(B)
     dimsC = _dims_of(modesA, A, modesB, B, modesC)
-    a = np.asfortranarray(A, dtype=np.float64)
-    b = np.asfortranarray(B, dtype=np.float64)
+    a = np.array(A, dtype=np.float64, order="F")
+    b = np.array(B, dtype=np.float64, order="F")
     if C is None:
         if beta != 0.0:
             raise ValueError("beta != 0 needs the old C")
         c = np.zeros(1, dtype=np.float64)
         ldC = [0] * len(dimsC)
     else:
-        c = np.asfortranarray(C, dtype=np.float64)
+        c = np.array(C, dtype=np.float64, order="F")
         ldC = packed_ld(dimsC)
     idx = np.ascontiguousarray(np.asarray(cidx, dtype=np.int64).reshape(-1, max(len(dimsC), 1)))
     ns = idx.shape[0] if len(dimsC) else 1

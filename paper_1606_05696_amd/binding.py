@@ -1,0 +1,201 @@
+"""ctypes binding of libsbgemm.so: the same entry points as include/sbgemm.h, same names.
+
+Only argument marshalling happens here; every step of the path (planning, kernel selection,
+kernels) runs inside the library.  torch is used for device memory and streams only.  There is
+no fallback: if the library has not been built, every call raises.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsbgemm.so")
+
+SB_OP_N, SB_OP_T, SB_OP_EX_N, SB_OP_EX_T = 0, 1, 2, 3
+SB_F64, SB_F32, SB_BF16 = 0, 1, 2
+SB_AUTO, SB_FLATTEN, SB_BATCH_LAST, SB_BATCH_MID, SB_NESTED, SB_LEVEL2 = 0, 1, 2, 3, 4, 5
+SB_OK = 0
+SB_ERR_MODES, SB_ERR_CONTRACTION, SB_ERR_EXTENT, SB_ERR_STRIDE, SB_ERR_ILLEGAL_EVAL, SB_ERR_NO_DEVICE_CODE = 1, 2, 3, 4, 5, 6
+SB_ERR_LAUNCH = 1000
+SB_KERNEL_AUTO, SB_KERNEL_GENERIC, SB_KERNEL_TINY, SB_KERNEL_MFMA = -1, 0, 1, 2
+SB_MAX_MODES = 8
+SB_MAX_BATCH_LEVELS = 8
+
+OPS = {"N": SB_OP_N, "T": SB_OP_T, "EX_N": SB_OP_EX_N, "EX_T": SB_OP_EX_T}
+DTYPES = {"f64": SB_F64, "f32": SB_F32, "bf16": SB_BF16}
+STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAST,
+              "batch_mid": SB_BATCH_MID, "nested": SB_NESTED, "level2": SB_LEVEL2}
+
+
+__all__ = [n for n in dir() if n.startswith("SB_")] + [
+    "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
+    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_force_kernel", "sb_last_kernel"]
+
+
+class sb_plan(ctypes.Structure):
+    _fields_ = [("nbatch", ctypes.c_int32), ("exceptional", ctypes.c_int32), ("left_is_B", ctypes.c_int32),
+                ("opL", ctypes.c_int32), ("opR", ctypes.c_int32),
+                ("m", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+                ("ldL", ctypes.c_int64), ("ldR", ctypes.c_int64), ("ldC", ctypes.c_int64),
+                ("exL", ctypes.c_int64), ("exR", ctypes.c_int64),
+                ("batch", ctypes.c_int64 * SB_MAX_BATCH_LEVELS),
+                ("strideL", ctypes.c_int64 * SB_MAX_BATCH_LEVELS),
+                ("strideR", ctypes.c_int64 * SB_MAX_BATCH_LEVELS),
+                ("strideC", ctypes.c_int64 * SB_MAX_BATCH_LEVELS),
+                ("notation", ctypes.c_char * 192)]
+
+    def text(self):
+        return self.notation.decode()
+
+
+class SbError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__("%s failed with status %d: %s" % (fn, status, sb_status_string(status)))
+
+
+_lib = None
+
+
+def load():
+    """Load libsbgemm.so (once).  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libsbgemm.so is missing at %s; build it with "
+                           "`python -m paper_1606_05696_amd.build` (needs hipcc)" % LIB_PATH)
+    import torch  # noqa: F401  (loads the HIP runtime that owns torch's device memory first)
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, dbl, vp, cp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p, ctypes.c_char_p
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    ci = ctypes.c_int
+    lib.sb_gemm.restype = ci
+    lib.sb_gemm.argtypes = [ci, ci, ci, i64, i64, i64, dbl, vp, i64, i64, vp, i64, i64, dbl, vp, i64, i64, i64, vp]
+    lib.sb_gemm2.restype = ci
+    lib.sb_gemm2.argtypes = [ci, ci, ci, i64, i64, i64, dbl, vp, i64, i64, i64, vp, i64, i64, i64,
+                             dbl, vp, i64, i64, i64, i64, i64, vp]
+    lib.sb_contract_plan.restype = ci
+    lib.sb_contract_plan.argtypes = [cp, cp, cp, i64p, i64p, i64p, i64p, i64p, i64p, ci, ctypes.POINTER(sb_plan)]
+    lib.sb_contract.restype = ci
+    lib.sb_contract.argtypes = [ci, cp, cp, cp, dbl, vp, i64p, i64p, vp, i64p, i64p, dbl, vp, i64p, i64p, ci, vp]
+    lib.sb_plan_launch.restype = ci
+    lib.sb_plan_launch.argtypes = [ci, ctypes.POINTER(sb_plan), dbl, vp, vp, dbl, vp, vp]
+    lib.sb_status_string.restype = cp
+    lib.sb_status_string.argtypes = [ci]
+    lib.sb_force_kernel.restype = ci
+    lib.sb_force_kernel.argtypes = [ci]
+    lib.sb_last_kernel.restype = ci
+    lib.sb_last_kernel.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor, or an integer address passed through."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _dtype_of(dt, *tensors):
+    if dt is not None:
+        return DTYPES[dt] if isinstance(dt, str) else int(dt)
+    import torch
+    table = {torch.float64: SB_F64, torch.float32: SB_F32, torch.bfloat16: SB_BF16}
+    kinds = {table[t.dtype] for t in tensors if hasattr(t, "dtype")}
+    if len(kinds) != 1:
+        raise TypeError("cannot infer one element type from the tensors; pass dt")
+    return kinds.pop()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _i64arr(seq):
+    if seq is None:
+        return None
+    seq = [int(v) for v in seq]
+    return (ctypes.c_int64 * max(len(seq), 1))(*seq)
+
+
+def _op(op):
+    return OPS[op] if isinstance(op, str) else int(op)
+
+
+def _strat(s):
+    return STRATEGIES[s] if isinstance(s, str) else int(s)
+
+
+def sb_status_string(status):
+    return load().sb_status_string(int(status)).decode()
+
+
+def sb_gemm(transA, transB, m, n, k, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+            batch, dt=None, stream=None, check=True):
+    """C_p = alpha*opA(A_p)*opB(B_p) + beta*C_p over device buffers (see sbgemm.h: sb_gemm)."""
+    rc = load().sb_gemm(_dtype_of(dt, A, B, C), _op(transA), _op(transB), m, n, k, float(alpha),
+                        _ptr(A), lda, strideA, _ptr(B), ldb, strideB, float(beta), _ptr(C), ldc, strideC,
+                        batch, _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_gemm", rc)
+    return rc
+
+
+def sb_gemm2(transA, transB, m, n, k, alpha, A, lda, strideA0, strideA1, B, ldb, strideB0, strideB1,
+             beta, C, ldc, strideC0, strideC1, batch0, batch1, dt=None, stream=None, check=True):
+    """Two batch levels in one launch (see sbgemm.h: sb_gemm2)."""
+    rc = load().sb_gemm2(_dtype_of(dt, A, B, C), _op(transA), _op(transB), m, n, k, float(alpha),
+                         _ptr(A), lda, strideA0, strideA1, _ptr(B), ldb, strideB0, strideB1,
+                         float(beta), _ptr(C), ldc, strideC0, strideC1, batch0, batch1, _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_gemm2", rc)
+    return rc
+
+
+def sb_contract_plan(modesA, modesB, modesC, dimsA, dimsB, dimsC=None, stridesA=None, stridesB=None,
+                     stridesC=None, strat=SB_AUTO, check=True):
+    """Plan a contraction on the host (see sbgemm.h: sb_contract_plan).  Returns (status, sb_plan)."""
+    plan = sb_plan()
+    rc = load().sb_contract_plan(modesA.encode(), modesB.encode(), modesC.encode(),
+                                 _i64arr(dimsA), _i64arr(stridesA), _i64arr(dimsB), _i64arr(stridesB),
+                                 _i64arr(dimsC), _i64arr(stridesC), _strat(strat), ctypes.byref(plan))
+    if check and rc != SB_OK:
+        raise SbError("sb_contract_plan", rc)
+    return rc, plan
+
+
+def sb_contract(modesA, modesB, modesC, alpha, A, dimsA, B, dimsB, beta, C, dimsC=None,
+                stridesA=None, stridesB=None, stridesC=None, strat=SB_AUTO, dt=None, stream=None, check=True):
+    """C_modesC = alpha*A_modesA*B_modesB + beta*C_modesC on device tensors (see sbgemm.h: sb_contract)."""
+    rc = load().sb_contract(_dtype_of(dt, A, B, C), modesA.encode(), modesB.encode(), modesC.encode(),
+                            float(alpha), _ptr(A), _i64arr(dimsA), _i64arr(stridesA),
+                            _ptr(B), _i64arr(dimsB), _i64arr(stridesB),
+                            float(beta), _ptr(C), _i64arr(dimsC), _i64arr(stridesC), _strat(strat), _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_contract", rc)
+    return rc
+
+
+def sb_plan_launch(plan, alpha, A, B, beta, C, dt=None, stream=None, check=True):
+    """Launch a plan made by sb_contract_plan (see sbgemm.h: sb_plan_launch)."""
+    rc = load().sb_plan_launch(_dtype_of(dt, A, B, C), ctypes.byref(plan), float(alpha), _ptr(A), _ptr(B),
+                               float(beta), _ptr(C), _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_plan_launch", rc)
+    return rc
+
+
+def sb_force_kernel(kernel_id):
+    return load().sb_force_kernel(int(kernel_id))
+
+
+def sb_last_kernel():
+    return load().sb_last_kernel()

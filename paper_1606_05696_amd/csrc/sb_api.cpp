@@ -1,0 +1,205 @@
+// C-ABI front end: argument validation, normalisation of the operations into strides, kernel
+// selection and launch (section III-D, Listing 1; section III-F, Listing 2).
+#include "sb_internal.h"
+
+#include <algorithm>
+#include <cstring>
+
+namespace {
+
+int g_force_kernel = SB_KERNEL_AUTO;
+int g_last_kernel = -1;
+
+bool valid_op(int op) { return op >= SB_OP_N && op <= SB_OP_EX_T; }
+bool is_ex(int op) { return op == SB_OP_EX_N || op == SB_OP_EX_T; }
+
+// Strides of op(X)(row, col) for a stored matrix described by (op, ld, stride0).
+void op_strides(int op, int64_t ld, int64_t stride0, int64_t &rs, int64_t &cs, int64_t &bs0)
+{
+    switch (op) {
+    case SB_OP_N:    rs = 1;       cs = ld;      bs0 = stride0; break;
+    case SB_OP_T:    rs = ld;      cs = 1;       bs0 = stride0; break;
+    case SB_OP_EX_N: rs = ld;      cs = stride0; bs0 = 1;       break;   // section III-E
+    default:         rs = stride0; cs = ld;      bs0 = 1;       break;   // SB_OP_EX_T
+    }
+}
+
+int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
+{
+    int kernel = SB_KERNEL_GENERIC;
+    if (g_force_kernel == SB_KERNEL_TINY && sb_tiny_supports(dt, a)) kernel = SB_KERNEL_TINY;
+    else if (g_force_kernel == SB_KERNEL_MFMA && sb_mfma_supports(dt, a)) kernel = SB_KERNEL_MFMA;
+    else if (g_force_kernel == SB_KERNEL_AUTO) {
+        if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) kernel = SB_KERNEL_TINY;
+        else if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) kernel = SB_KERNEL_MFMA;
+    }
+    hipError_t err;
+    switch (kernel) {
+    case SB_KERNEL_TINY: err = sb_launch_tiny(dt, a, stream); break;
+    case SB_KERNEL_MFMA: err = sb_launch_mfma(dt, a, stream); break;
+    default:             err = sb_launch_generic(dt, a, stream); break;
+    }
+    g_last_kernel = kernel;
+    if (err == hipErrorNoBinaryForGpu) return SB_ERR_NO_DEVICE_CODE;
+    return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
+}
+
+}  // namespace
+
+extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                        double alpha, const void *A, int64_t lda, int64_t strideA0, int64_t strideA1,
+                        const void *B, int64_t ldb, int64_t strideB0, int64_t strideB1,
+                        double beta, void *C, int64_t ldc, int64_t strideC0, int64_t strideC1,
+                        int64_t batch0, int64_t batch1, void *stream)
+{
+    if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
+    if (!valid_op(transA)) return -2;
+    if (!valid_op(transB)) return -3;
+    if (m < 0) return -4;
+    if (n < 0) return -5;
+    if (k < 0) return -6;
+    if (batch0 < 0) return -21;
+    if (batch1 < 0) return -22;
+    if (m == 0 || n == 0 || batch0 == 0 || batch1 == 0) return SB_OK;
+    const bool use_ab = (k > 0 && alpha != 0.0);
+    // leading dimensions: at least the number of stored rows (N/T), at least 1 (extended)
+    const int64_t rowsA = is_ex(transA) ? 1 : (transA == SB_OP_N ? m : k);
+    const int64_t rowsB = is_ex(transB) ? 1 : (transB == SB_OP_N ? k : n);
+    if (use_ab && !A) return -8;
+    if (lda < std::max<int64_t>(1, rowsA)) return -9;
+    if (strideA0 < 0 || (is_ex(transA) && strideA0 < 1)) return -10;
+    if (strideA1 < 0) return -11;
+    if (use_ab && !B) return -12;
+    if (ldb < std::max<int64_t>(1, rowsB)) return -13;
+    if (strideB0 < 0 || (is_ex(transB) && strideB0 < 1)) return -14;
+    if (strideB1 < 0) return -15;
+    if (!C) return -17;
+    if (ldc < std::max<int64_t>(1, m)) return -18;
+    if (strideC0 < 0 || (strideC0 == 0 && batch0 > 1)) return -19;
+    if (strideC1 < 0 || (strideC1 == 0 && batch1 > 1)) return -20;
+
+    SbArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.A = A;  a.B = B;  a.C = C;
+    a.m = m;  a.n = n;
+    a.k = use_ab ? k : 0;                  // alpha == 0: A and B are not read, C = beta*C
+    a.alpha = alpha;  a.beta = beta;
+    op_strides(transA, lda, strideA0, a.rsA, a.csA, a.bsA[0]);
+    op_strides(transB, ldb, strideB0, a.rsB, a.csB, a.bsB[0]);
+    a.bsA[1] = strideA1;  a.bsB[1] = strideB1;
+    a.ldc = ldc;
+    a.bsC[0] = strideC0;  a.bsC[1] = strideC1;
+    a.batch0 = batch0;  a.batch1 = batch1;
+    return run(dt, a, (hipStream_t)stream);
+}
+
+extern "C" int sb_gemm(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                       double alpha, const void *A, int64_t lda, int64_t strideA,
+                       const void *B, int64_t ldb, int64_t strideB,
+                       double beta, void *C, int64_t ldc, int64_t strideC,
+                       int64_t batch, void *stream)
+{
+    int rc = sb_gemm2(dt, transA, transB, m, n, k, alpha, A, lda, strideA, 0, B, ldb, strideB, 0,
+                      beta, C, ldc, strideC, 0, batch, 1, stream);
+    if (rc >= 0) return rc;
+    // renumber sb_gemm2's argument positions to sb_gemm's
+    static const int map[24] = {0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 10, 11, 12, 13, 13, 14, 15, 16, 17, 17, 18, 18, 19};
+    return -map[-rc];
+}
+
+extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
+                              double beta, void *C, void *stream)
+{
+    if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
+    if (!plan || plan->nbatch < 0 || plan->nbatch > SB_MAX_BATCH_LEVELS) return -2;
+    const size_t esz = (dt == SB_F64) ? 8 : (dt == SB_F32 ? 4 : 2);
+    const char *L = (const char *)(plan->left_is_B ? B : A);
+    const char *R = (const char *)(plan->left_is_B ? A : B);
+    char *Cb = (char *)C;
+    const int nb = plan->nbatch;
+    // levels 0 and 1 run inside the launch; an extended operand passes its stored-column stride
+    // in place of the (implied, unit) level-0 batch stride
+    const int64_t b0 = nb > 0 ? plan->batch[0] : 1, b1 = nb > 1 ? plan->batch[1] : 1;
+    const bool exL = plan->opL > SB_OP_T, exR = plan->opR > SB_OP_T;
+    const int64_t sL0 = exL ? plan->exL : (nb > 0 ? plan->strideL[0] : 0);
+    const int64_t sR0 = exR ? plan->exR : (nb > 0 ? plan->strideR[0] : 0);
+    const int64_t sC0 = nb > 0 ? plan->strideC[0] : 0;
+    const int64_t sL1 = nb > 1 ? plan->strideL[1] : 0, sR1 = nb > 1 ? plan->strideR[1] : 0, sC1 = nb > 1 ? plan->strideC[1] : 0;
+    // deeper levels: an odometer of host-side launches (Listing 2)
+    int64_t idx[SB_MAX_BATCH_LEVELS] = {0};
+    int64_t outer = 1;
+    for (int q = 2; q < nb; ++q) outer *= plan->batch[q];
+    for (int64_t it = 0; it < outer; ++it) {
+        int64_t oL = 0, oR = 0, oC = 0;
+        for (int q = 2; q < nb; ++q) {
+            oL += idx[q] * plan->strideL[q];
+            oR += idx[q] * plan->strideR[q];
+            oC += idx[q] * plan->strideC[q];
+        }
+        int rc = sb_gemm2(dt, (sb_op)plan->opL, (sb_op)plan->opR, plan->m, plan->n, plan->k, alpha,
+                          L ? L + oL * esz : nullptr, plan->ldL, sL0, sL1,
+                          R ? R + oR * esz : nullptr, plan->ldR, sR0, sR1,
+                          beta, Cb ? Cb + oC * esz : nullptr, plan->ldC, sC0, sC1, b0, b1, stream);
+        if (rc > 0) return rc;
+        if (rc < 0) {            // map the failing sb_gemm2 argument back to this function's
+            int p = -rc;
+            if (p >= 8 && p <= 15) return (((p <= 11) != (plan->left_is_B != 0)) ? -4 : -5);
+            if (p >= 17 && p <= 20) return -7;
+            return -2;
+        }
+        for (int q = 2; q < nb; ++q) {
+            if (++idx[q] < plan->batch[q]) break;
+            idx[q] = 0;
+        }
+    }
+    return SB_OK;
+}
+
+extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char *modesC,
+                           double alpha, const void *A, const int64_t *dimsA, const int64_t *stridesA,
+                           const void *B, const int64_t *dimsB, const int64_t *stridesB,
+                           double beta, void *C, const int64_t *dimsC, const int64_t *stridesC,
+                           sb_strategy strat, void *stream)
+{
+    if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
+    sb_plan plan;
+    int rc = sb_contract_plan(modesA, modesB, modesC, dimsA, stridesA, dimsB, stridesB, dimsC, stridesC, strat, &plan);
+    if (rc < 0) {
+        // planner argument numbers -> sb_contract argument numbers
+        static const int map[12] = {0, 2, 3, 4, 7, 8, 10, 11, 14, 15, 16, 16};
+        return -map[-rc];
+    }
+    if (rc != SB_OK) return rc;
+    rc = sb_plan_launch(dt, &plan, alpha, A, B, beta, C, stream);
+    if (rc < 0) {
+        static const int map[9] = {0, 1, 16, 5, 6, 9, 12, 13, 17};
+        return -map[-rc];
+    }
+    return rc;
+}
+
+extern "C" const char *sb_status_string(int status)
+{
+    if (status == SB_OK) return "success";
+    if (status < 0) return "invalid argument (the negated status is the argument's position)";
+    switch (status) {
+    case SB_ERR_MODES: return "malformed mode string";
+    case SB_ERR_CONTRACTION: return "index sets do not form a single-index contraction";
+    case SB_ERR_EXTENT: return "inconsistent or negative extent";
+    case SB_ERR_STRIDE: return "unusable strides";
+    case SB_ERR_ILLEGAL_EVAL: return "the requested evaluation is not legal for this contraction";
+    case SB_ERR_NO_DEVICE_CODE: return "no kernel for this device (the library is built for gfx950)";
+    default: break;
+    }
+    if (status >= SB_ERR_LAUNCH) return "kernel launch failed (status - 1000 is the hipError_t)";
+    return "unknown status";
+}
+
+extern "C" int sb_force_kernel(int kernel_id)
+{
+    if (kernel_id < SB_KERNEL_AUTO || kernel_id > SB_KERNEL_MFMA) return -1;
+    g_force_kernel = kernel_id;
+    return SB_OK;
+}
+
+extern "C" int sb_last_kernel(void) { return g_last_kernel; }

@@ -1,0 +1,33 @@
+// Internal interface between the C-ABI front end and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sbgemm.h"
+
+// One (two-level) StridedBatchedGemm in stride-normal form.  op(A)(i,l) sits at
+// A + i*rsA + l*csA, op(B)(l,j) at B + l*rsB + j*csB, C(i,j) at C + i + j*ldc; batch (p,q) adds
+// p*bsX[0] + q*bsX[1] to each pointer.  N, T and the extended operations of section III-E are all
+// instances of this form.
+struct SbArgs {
+    const void *A;
+    const void *B;
+    void *C;
+    int64_t m, n, k;
+    int64_t rsA, csA, rsB, csB, ldc;
+    int64_t bsA[2], bsB[2], bsC[2];
+    int64_t batch0, batch1;
+    double alpha, beta;
+};
+
+// Each launcher returns a hipError_t (0 = launched).  The *_supports predicates say whether a
+// kernel family can run the problem at all; the selector decides whether it should.
+hipError_t sb_launch_generic(sb_dtype dt, const SbArgs &a, hipStream_t stream);
+
+bool sb_tiny_supports(sb_dtype dt, const SbArgs &a);
+bool sb_tiny_preferred(sb_dtype dt, const SbArgs &a);
+hipError_t sb_launch_tiny(sb_dtype dt, const SbArgs &a, hipStream_t stream);
+
+bool sb_mfma_supports(sb_dtype dt, const SbArgs &a);
+bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a);
+hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream);

@@ -1,0 +1,111 @@
+"""The C-ABI library loads, exports every declared symbol, and validates arguments on the host
+(no test here launches a kernel, so this module runs without a GPU)."""
+import os
+import re
+
+import paper_1606_05696_amd as sb
+from paper_1606_05696_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000      # never dereferenced: validation fails (or the problem is empty) before any launch
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sbgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^(?:int|const char \*)\s*(sb_\w+)\s*\(", text, flags=re.M)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch",
+                          "sb_status_string", "sb_force_kernel", "sb_last_kernel"}
+    lib = binding.load()
+    for n in names:
+        assert getattr(lib, n) is not None
+        assert hasattr(binding, n), "the Python binding must expose %s under the same name" % n
+
+
+def gemm(**over):
+    a = dict(dt=sb.SB_F32, transA="N", transB="N", m=4, n=5, k=6, alpha=1.0, A=FAKE, lda=4, strideA=0,
+             B=FAKE, ldb=6, strideB=30, beta=0.0, C=FAKE, ldc=4, strideC=20, batch=3)
+    a.update(over)
+    return sb.sb_gemm(a["transA"], a["transB"], a["m"], a["n"], a["k"], a["alpha"], a["A"], a["lda"], a["strideA"],
+                      a["B"], a["ldb"], a["strideB"], a["beta"], a["C"], a["ldc"], a["strideC"], a["batch"],
+                      dt=a["dt"], stream=0, check=False)
+
+
+def test_sb_gemm_argument_validation():
+    assert gemm(dt=7) == -1
+    assert gemm(transA=9) == -2
+    assert gemm(transB=-1) == -3
+    assert gemm(m=-1) == -4
+    assert gemm(n=-1) == -5
+    assert gemm(k=-1) == -6
+    assert gemm(A=None) == -8
+    assert gemm(lda=3) == -9                      # N: lda >= m
+    assert gemm(transA="T", lda=5) == -9          # T: lda >= k
+    assert gemm(strideA=-1) == -10
+    assert gemm(B=None) == -11
+    assert gemm(ldb=5) == -12                     # N: ldb >= k
+    assert gemm(transB="T", ldb=4) == -12         # T: ldb >= n
+    assert gemm(strideB=-2) == -13
+    assert gemm(C=None) == -15
+    assert gemm(ldc=3) == -16
+    assert gemm(strideC=0) == -17                 # batches of C would coincide
+    assert gemm(strideC=-4) == -17
+    assert gemm(batch=-1) == -18
+    assert gemm(transA="EX_N", strideA=0) == -10  # extended op: the stride argument is a column stride
+    # quick returns: nothing to do, nothing launched
+    assert gemm(m=0) == sb.SB_OK
+    assert gemm(n=0) == sb.SB_OK
+    assert gemm(batch=0) == sb.SB_OK
+    assert gemm(batch=0, C=None) == sb.SB_OK
+
+
+def test_sb_gemm2_argument_validation():
+    def g2(**over):
+        a = dict(sA0=0, sA1=0, sB0=30, sB1=90, sC0=20, sC1=60, b0=3, b1=2, lda=4, ldb=6, ldc=4)
+        a.update(over)
+        return sb.sb_gemm2("N", "N", 4, 5, 6, 1.0, FAKE, a["lda"], a["sA0"], a["sA1"], FAKE, a["ldb"], a["sB0"], a["sB1"],
+                           0.0, FAKE, a["ldc"], a["sC0"], a["sC1"], a["b0"], a["b1"], dt=sb.SB_F64, stream=0, check=False)
+    assert g2(sA1=-1) == -11
+    assert g2(sB1=-1) == -15
+    assert g2(sC0=0) == -19
+    assert g2(sC1=0) == -20
+    assert g2(b0=-1) == -21
+    assert g2(b1=-1) == -22
+    assert g2(ldc=2) == -18
+    assert g2(b1=0) == sb.SB_OK
+
+
+def test_sb_contract_argument_validation():
+    def c(**over):
+        a = dict(dt=sb.SB_F32, A="mk", B="knp", C="mnp", dA=[4, 6], dB=[6, 5, 3], pa=FAKE, pb=FAKE, pc=FAKE, strat=0)
+        a.update(over)
+        return sb.sb_contract(a["A"], a["B"], a["C"], 1.0, a["pa"], a["dA"], a["pb"], a["dB"], 0.0, a["pc"],
+                              strat=a["strat"], dt=a["dt"], stream=0, check=False)
+    assert c(dt=5) == -1
+    assert c(dA=None) == -7
+    assert c(dB=None) == -10
+    assert c(strat=17) == -16
+    assert c(C="mn") == sb.SB_ERR_CONTRACTION
+    assert c(A="m(k") == sb.SB_ERR_MODES
+    assert c(pa=None) == -6
+    assert c(pb=None) == -9
+    assert c(pc=None) == -13
+    assert c(A="nk", B="pkm", dA=[5, 6], dB=[3, 6, 4], strat=sb.SB_FLATTEN) == sb.SB_ERR_ILLEGAL_EVAL
+    # an empty contraction needs no launch
+    assert c(dA=[0, 6], dB=[6, 5, 3]) == sb.SB_OK
+
+
+def test_status_strings():
+    assert sb.sb_status_string(0) == "success"
+    for code in (-3, 1, 2, 3, 4, 5, 6, 1000 + 98):
+        assert len(sb.sb_status_string(code)) > 5
+    assert "launch" in sb.sb_status_string(1098)
+
+
+def test_force_kernel_rejects_unknown_ids():
+    assert sb.sb_force_kernel(12) == -1
+    assert sb.sb_force_kernel(sb.SB_KERNEL_AUTO) == sb.SB_OK

@@ -1,0 +1,303 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Tolerances are relative Frobenius errors: 1e-12 (fp64), 1e-5 (fp32), 2e-2 (bf16 in /
+fp32 accumulate / bf16 out)."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_1606_05696_amd as sb
+from helpers import TOL, cases_2x3, from_dev, packed, quantise, rel_fro, strip_annotations, to_dev
+from oracle import oracle
+from paper_1606_05696_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+KERNELS = {"auto": sb.SB_KERNEL_AUTO, "generic": sb.SB_KERNEL_GENERIC, "tiny": sb.SB_KERNEL_TINY, "mfma": sb.SB_KERNEL_MFMA}
+
+
+@pytest.fixture(autouse=True)
+def _reset_kernel_choice():
+    yield
+    sb.sb_force_kernel(sb.SB_KERNEL_AUTO)
+
+
+def sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed, kernel="auto"):
+    """One sb_gemm call on random buffers vs Listing 1 on the CPU; returns the relative error."""
+    rng = np.random.default_rng(seed)
+
+    def span(op, rows, cols, ld, lo):
+        r, c = (rows, cols) if op == "N" else (cols, rows)
+        return max(1, (batch - 1) * lo + (c - 1) * ld + r + 3)
+
+    a = quantise(rng.uniform(-1, 1, span(opA, m, k, lda, loa)), dtype)
+    b = quantise(rng.uniform(-1, 1, span(opB, k, n, ldb, lob)), dtype)
+    c0 = quantise(rng.uniform(-1, 1, span("N", m, n, ldc, loc)), dtype)
+    dA, dB, dC = to_dev(a, dtype), to_dev(b, dtype), to_dev(c0, dtype)
+    sb.sb_force_kernel(KERNELS[kernel])
+    sb.sb_gemm(opA, opB, m, n, k, alpha, dA, lda, loa, dB, ldb, lob, beta, dC, ldc, loc, batch, dt=dtype)
+    sync()
+    if kernel != "auto" and sb.sb_last_kernel() != KERNELS[kernel]:
+        pytest.skip("kernel family %s does not take this problem" % kernel)
+    ref = oracle.sb_gemm(opA, opB, m, n, k, alpha, a, lda, loa, b, ldb, lob, beta, c0, ldc, loc, batch,
+                         wide=(dtype == "f64"))
+    got = from_dev(dC)
+    # elements outside the m x n windows must be untouched: they are equal in got and ref
+    return rel_fro(got, ref), got, ref
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiny", "mfma"])
+def test_sb_gemm_ragged_tiles(dtype, opA, opB, kernel):
+    # several 64-wide tiles plus a ragged tail in every dimension, padded leading dimensions,
+    # alpha and beta both active
+    m, n, k, batch = 150, 77, 45, 3
+    lda = (m if opA == "N" else k) + 3
+    ldb = (k if opB == "N" else n) + 5
+    ldc = m + 2
+    loa = lda * (k if opA == "N" else m) + 7
+    lob = ldb * (n if opB == "N" else k) + 1
+    loc = ldc * n + 11
+    err, got, ref = run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, 0.75, -0.5, 7, kernel)
+    assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiny", "mfma"])
+@pytest.mark.parametrize("m,n,k,batch", [(1, 1, 1, 1), (1, 9, 5, 4), (9, 1, 5, 4), (16, 16, 16, 1000), (8, 8, 8, 70001),
+                                          (33, 17, 1, 3), (5, 6, 7, 2), (64, 64, 64, 5), (128, 128, 96, 2), (200, 130, 260, 2)])
+def test_sb_gemm_shapes(dtype, kernel, m, n, k, batch):
+    # stride 0 on A (shared operand, as in every order-2 x order-3 evaluation), packed B and C
+    err, got, ref = run_sb_gemm(dtype, "N", "N", m, n, k, batch, m, k, m, 0, k * n, m * n, 1.0, 0.0, 11, kernel)
+    assert err <= TOL[dtype], err
+    err, got, ref = run_sb_gemm(dtype, "T", "N", m, n, k, batch, k, k, m, m * k, 0, m * n, -1.5, 1.0, 12, kernel)
+    assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_blas_conventions(dtype):
+    import torch
+    m, n, k, batch = 20, 10, 8, 3
+    rng = np.random.default_rng(5)
+    a = quantise(rng.uniform(-1, 1, m * k), dtype)
+    b = quantise(rng.uniform(-1, 1, k * n * batch), dtype)
+    c0 = quantise(rng.uniform(-1, 1, m * n * batch), dtype)
+    dA, dB = to_dev(a, dtype), to_dev(b, dtype)
+    # beta == 0: C is not read, NaNs in it vanish
+    dC = to_dev(np.full(m * n * batch, np.nan), dtype)
+    sb.sb_gemm("N", "N", m, n, k, 1.0, dA, m, 0, dB, k, k * n, 0.0, dC, m, m * n, batch, dt=dtype)
+    got = from_dev(dC)
+    ref = oracle.sb_gemm("N", "N", m, n, k, 1.0, a, m, 0, b, k, k * n, 0.0, np.zeros_like(c0), m, m * n, batch)
+    assert np.isfinite(got).all() and rel_fro(got, ref) <= TOL[dtype]
+    # alpha == 0: A and B are not read (NaNs in them are harmless), C = beta*C
+    dAn = to_dev(np.full(m * k, np.nan), dtype)
+    dC = to_dev(c0, dtype)
+    sb.sb_gemm("N", "N", m, n, k, 0.0, dAn, m, 0, dB, k, k * n, 0.5, dC, m, m * n, batch, dt=dtype)
+    assert rel_fro(from_dev(dC), 0.5 * c0) <= TOL[dtype]
+    # k == 0 with beta == 0 zeroes C
+    dC = to_dev(c0, dtype)
+    sb.sb_gemm("N", "N", m, n, 0, 1.0, dA, m, 0, dB, 1, 0, 0.0, dC, m, m * n, batch, dt=dtype)
+    assert np.array_equal(from_dev(dC), np.zeros(m * n * batch))
+    # empty problems touch nothing
+    dC = to_dev(c0, dtype)
+    sb.sb_gemm("N", "N", 0, n, k, 1.0, dA, 1, 0, dB, k, k * n, 0.0, dC, 1, m * n, batch, dt=dtype)
+    sb.sb_gemm("N", "N", m, n, k, 1.0, dA, m, 0, dB, k, k * n, 0.0, dC, m, m * n, 0, dt=dtype)
+    assert np.array_equal(from_dev(dC), quantise(c0, dtype))
+    torch.cuda.synchronize()
+
+
+def contract_case(dtype, ma, mb, mc, ext, strat="auto", alpha=1.0, beta=0.0, seed=0, pad=None, kernel="auto",
+                  tensors=None):
+    """sb_contract on device vs the oracle; mode strings may be annotated.  Returns (error, plan text)."""
+    pa, pb, pc = (strip_annotations(s) for s in (ma, mb, mc))
+    dA, dB, dC = ([ext[c] for c in s] for s in (pa, pb, pc))
+    if tensors is None:
+        A = inputs.make_tensor(seed, dA, dtype)
+        B = inputs.make_tensor(seed + 1, dB, dtype)
+    else:
+        A, B = tensors
+    C0 = quantise(inputs.uniform_tensor(seed + 2, dC), dtype)
+    sA = sB = sC = None
+    hA, hB, hC = A, B, C0
+    if pad:                       # embed each tensor in a larger packed one: padded strides
+        def embed(X, extra):
+            big = np.zeros([d + e for d, e in zip(X.shape, extra)], dtype=X.dtype, order="F")
+            big[tuple(slice(0, d) for d in X.shape)] = X
+            return big, packed(big.shape)
+        hA, sA = embed(A, pad[0])
+        hB, sB = embed(B, pad[1])
+        hC, sC = embed(C0, pad[2])
+    tA, tB, tC = to_dev(hA, dtype), to_dev(hB, dtype), to_dev(hC, dtype)
+    sb.sb_force_kernel(KERNELS[kernel])
+    rc, plan = sb.sb_contract_plan(ma, mb, mc, dA, dB, stridesA=sA, stridesB=sB, stridesC=sC, strat=strat)
+    sb.sb_contract(ma, mb, mc, alpha, tA, dA, tB, dB, beta, tC, dC, stridesA=sA, stridesB=sB, stridesC=sC,
+                   strat=strat, dt=dtype)
+    sync()
+    ref = oracle.contract(pa, A, pb, B, pc, C=C0, alpha=alpha, beta=beta, wide=(dtype == "f64"))
+    got = from_dev(tC, hC.shape)
+    if pad:
+        inner = tuple(slice(0, d) for d in C0.shape)
+        outside = got.copy()
+        outside[inner] = 0
+        assert not outside.any(), "padding of C was written"
+        got = got[inner]
+    return rel_fro(got, ref), plan.text()
+
+
+def test_cfg1_small_reference_case():
+    # C_mnp = A_mk B_knp, 32^4, fp64: strided-batched over p, plus the other two legal evaluations
+    w = inputs.WORKLOADS[1]
+    A, B = inputs.workload_tensors(1)
+    for ma, mb, mc in (w["eval"], ("mk", "k[n]p", "m[n]p"), ("mk", "k(np)", "m(np)")):
+        err, text = contract_case("f64", ma, mb, mc, w["ext"], tensors=(A, B))
+        assert err <= TOL["f64"], (text, err)
+        err, text = contract_case("f64", ma, mb, mc, w["ext"], alpha=0.75, beta=-0.5, tensors=(A, B))
+        assert err <= TOL["f64"], (text, err)
+
+
+@pytest.mark.parametrize("strat", ["auto", "flatten", "batch_last", "batch_mid", "level2"])
+def test_cfg2_all_36_cases_at_64(strat):
+    # every order-2 x order-3 contraction at dim 64, fp32, every strategy: the 8 flattened GEMMs,
+    # the 32 StridedBatchedGemm evaluations, the extended-operation and matrix-vector forms
+    ext = dict(m=64, n=64, p=64, k=64)
+    done = 0
+    for i, (ma, mb) in enumerate(cases_2x3()):
+        rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [64, 64], [64, 64, 64], strat=strat, check=False)
+        if rc == sb.SB_ERR_ILLEGAL_EVAL:
+            continue
+        err, text = contract_case("f32", ma, mb, "mnp", ext, strat=strat, seed=20 + i)
+        assert err <= TOL["f32"], (text, err)
+        done += 1
+    # 12 cases have no [p] form and 12 no [n] form even with an extended operation: the GEMM's
+    # column mode would have to come from the tensor that already supplies the rows
+    assert done == {"auto": 36, "flatten": 8, "batch_last": 24, "batch_mid": 24, "level2": 36}[strat]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_all_36_cases_odd_extents_alpha_beta_padding(dtype):
+    ext = dict(m=37, n=21, p=13, k=29)
+    for i, (ma, mb) in enumerate(cases_2x3()):
+        err, text = contract_case(dtype, ma, mb, "mnp", ext, alpha=0.75, beta=-0.5, seed=100 + i)
+        assert err <= TOL[dtype], (text, err)
+        pad = ([1, 0], [2, 0, 1], [3, 1, 0])
+        err, text = contract_case(dtype, ma, mb, "mnp", ext, strat="nested", alpha=1.0, beta=0.0, seed=200 + i, pad=pad)
+        assert err <= TOL[dtype], (text, err)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiny"])
+def test_cfg3_tiny_batch_full_size(kernel):
+    # m = n = k = 16, p = 65536, fp32: the bandwidth-bound regime, compared element by element
+    w = inputs.WORKLOADS[3]
+    A, B = inputs.workload_tensors(3)
+    err, text = contract_case("f32", *w["eval"], w["ext"], tensors=(A, B), kernel=kernel)
+    assert err <= TOL["f32"], (text, err)
+
+
+def sample_indices(dimsC, n, seed):
+    """Random output positions plus the corners and tile-boundary positions of every mode."""
+    rng = np.random.default_rng(seed)
+    idx = [tuple(int(rng.integers(0, d)) for d in dimsC) for _ in range(n)]
+    edge = [sorted({0, 1, d // 2 - 1, d // 2, d - 2, d - 1} & set(range(d))) for d in dimsC]
+    idx += list(itertools.islice(itertools.product(*edge), 4096))
+    return np.array(sorted(set(idx)), dtype=np.int64)
+
+
+@pytest.mark.parametrize("cfg", [40, 41])
+@pytest.mark.parametrize("form", ["eval", "mid", "flat"])
+def test_cfg4_large_cube_full_size_sampled(cfg, form):
+    # C_mnp = A_km B_knp at 512^4 in the launch configuration the benchmark times; 68.7 G
+    # multiply-adds are too many for the CPU loop, so a few thousand outputs are checked one by one
+    w = inputs.WORKLOADS[cfg]
+    dtype = w["dtype"]
+    A, B = inputs.workload_tensors(cfg)
+    ma, mb, mc = {"eval": w["eval"], "mid": ("km", "k[n]p", "m[n]p"), "flat": ("km", "k(np)", "m(np)")}[form]
+    dA, dB, dC = ([w["ext"][c] for c in strip_annotations(s)] for s in (ma, mb, mc))
+    tA, tB = to_dev(A, dtype), to_dev(B, dtype)
+    tC = to_dev(np.full(1, np.nan), dtype).repeat(int(np.prod(dC)))
+    sb.sb_contract(ma, mb, mc, 1.0, tA, dA, tB, dB, 0.0, tC, dC, dt=dtype)
+    sync()
+    got_full = from_dev(tC, dC)
+    assert np.isfinite(got_full).all()
+    idx = sample_indices(dC, 6000, 404)
+    ref = oracle.contract_at("km", A, "knp", B, "mnp", idx, wide=(dtype == "f64"))
+    got = got_full[idx[:, 0], idx[:, 1], idx[:, 2]]
+    assert rel_fro(got, ref) <= TOL[dtype]
+    assert np.max(np.abs(got - ref)) <= 50 * TOL[dtype] * np.sqrt(512 / 3)       # no single wild element
+
+
+def test_cfg4_shape_reduced_full_compare():
+    for dtype in ("f64", "f32"):
+        err, text = contract_case(dtype, "km", "kn[p]", "mn[p]", dict(m=192, n=160, p=5, k=136), seed=41)
+        assert err <= TOL[dtype], (text, err)
+
+
+def test_cfg5_order3_x_order3_full_size():
+    # C_mpnq = A_mpk B_knq, 64^4 x 128, bf16 in / fp32 accumulate: nested batching over (p,q) in one
+    # launch, the flattened GEMM and the two partly flattened forms, all against one oracle result
+    w = inputs.WORKLOADS[5]
+    A, B = inputs.workload_tensors(5)
+    ref = oracle.contract("mpk", A, "knq", B, "mpnq", wide=False)
+    dA, dB, dC = list(A.shape), list(B.shape), list(ref.shape)
+    tA, tB = to_dev(A, "bf16"), to_dev(B, "bf16")
+    forms = [w["eval"], ("(mp)k", "k(nq)", "(mp)(nq)"), ("(mp)k", "kn[q]", "(mp)n[q]"), ("m[p]k", "k(nq)", "m[p](nq)")]
+    for ma, mb, mc in forms:
+        tC = to_dev(np.full(1, np.nan), "bf16").repeat(ref.size)
+        sb.sb_contract(ma, mb, mc, 1.0, tA, dA, tB, dB, 0.0, tC, dC, dt="bf16")
+        sync()
+        err = rel_fro(from_dev(tC, dC), ref)
+        assert err <= TOL["bf16"], (mc, err)
+    # same contraction in fp32 and fp64 at reduced extents, with alpha and beta
+    ext = dict(m=24, p=5, n=40, q=3, k=50)
+    for dtype in ("f64", "f32", "bf16"):
+        for strat in ("auto", "nested"):
+            err, text = contract_case(dtype, "mpk", "knq", "mpnq", ext, strat=strat, alpha=-0.5, beta=2.0, seed=55)
+            assert err <= TOL[dtype], (text, err)
+
+
+def test_three_level_nest_loops_on_the_host():
+    ext = dict(m=20, n=12, p=3, q=4, r=2, k=9)
+    err, text = contract_case("f32", "mpk", "knqr", "mnpqr", ext, strat="nested", seed=77)
+    assert err <= TOL["f32"], (text, err)
+
+
+def test_extended_operations_directly():
+    # section III-E: sb_gemm(OP_EX_N, OP_T, M, N, K, 1, B, ldb<1>, ldb<2>, A, lda<1>, 0, 0, C, ldc<1>, ldc<2>, P)
+    M, N, P, K = 40, 30, 17, 23
+    A = inputs.uniform_tensor(1, [N, K], np.float32)          # A_nk
+    B = inputs.uniform_tensor(2, [P, M, K], np.float32)       # B_pmk  (case 3.6)
+    tA, tB = to_dev(A, "f32"), to_dev(B, "f32")
+    tC = to_dev(np.zeros(M * N * P), "f32")
+    sb.sb_gemm("EX_N", "T", M, N, K, 1.0, tB, P, P * M, tA, N, 0, 0.0, tC, M, M * N, P, dt="f32")
+    sync()
+    ref = oracle.contract("nk", A, "pmk", B, "mnp", wide=False)
+    assert rel_fro(from_dev(tC, [M, N, P]), ref) <= TOL["f32"]
+    # case 6.4: sb_gemm(OP_EX_T, OP_N, M, P, K, 1, B, ldb<1>, ldb<2>, A, lda<1>, 0, 0, C, ldc<2>, ldc<1>, N)
+    A = inputs.uniform_tensor(3, [K, P], np.float32)          # A_kp
+    B = inputs.uniform_tensor(4, [N, K, M], np.float32)       # B_nkm
+    tA, tB = to_dev(A, "f32"), to_dev(B, "f32")
+    tC = to_dev(np.zeros(M * N * P), "f32")
+    sb.sb_gemm("EX_T", "N", M, P, K, 1.0, tB, N, N * K, tA, K, 0, 0.0, tC, M * N, M, N, dt="f32")
+    sync()
+    ref = oracle.contract("kp", A, "nkm", B, "mnp", wide=False)
+    assert rel_fro(from_dev(tC, [M, N, P]), ref) <= TOL["f32"]
+
+
+def test_runs_on_a_side_stream():
+    import torch
+    s = torch.cuda.Stream()
+    A = inputs.uniform_tensor(1, [48, 40], np.float32)
+    B = inputs.uniform_tensor(2, [40, 24, 9], np.float32)
+    tA, tB = to_dev(A, "f32"), to_dev(B, "f32")
+    tC = to_dev(np.zeros(48 * 24 * 9), "f32")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        sb.sb_contract("mk", "knp", "mnp", 1.0, tA, [48, 40], tB, [40, 24, 9], 0.0, tC)
+    s.synchronize()
+    ref = oracle.contract("mk", A, "knp", B, "mnp", wide=False)
+    assert rel_fro(from_dev(tC, [48, 24, 9]), ref) <= TOL["f32"]

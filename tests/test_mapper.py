@@ -1,0 +1,288 @@
+"""Host-side tests of the contraction planner (no GPU): Tables I and II, rules 1-4, counts, and
+execution of every plan by a numpy interpreter against the oracle."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_1606_05696_amd as sb
+from conftest import golden_lines
+from helpers import cases_2x3, cases_general, packed, run_plan_numpy, split_kernel, strip_annotations
+from oracle import oracle
+
+EXT = dict(m=3, n=5, p=7, k=4, q=2, r=6)
+EXCEPTIONAL = {"3.4", "3.6", "4.4", "4.6", "5.4", "5.6", "6.4", "6.6"}    # section III-E
+
+
+def dims(modes, ext=EXT):
+    return [ext.get(c, 2) for c in strip_annotations(modes)]
+
+
+def plan(ma, mb, mc, strat="auto", ext=EXT, check=True, **kw):
+    return sb.sb_contract_plan(ma, mb, mc, dims(ma, ext), dims(mb, ext), strat=strat, check=check, **kw)
+
+
+def check_numerics(pl, ma, mb, mc, ext=EXT, seed=0):
+    rng = np.random.default_rng(seed)
+    A = rng.uniform(-1, 1, dims(ma, ext))
+    B = rng.uniform(-1, 1, dims(mb, ext))
+    C0 = rng.uniform(-1, 1, dims(mc, ext))
+    got = run_plan_numpy(pl, A.ravel(order="F"), B.ravel(order="F"), C0.ravel(order="F"), 0.75, -0.5)
+    ref = oracle.contract(strip_annotations(ma), A, strip_annotations(mb), B, strip_annotations(mc),
+                          C=C0, alpha=0.75, beta=-0.5)
+    assert np.allclose(got, ref.ravel(order="F"), rtol=0, atol=1e-12), pl.text()
+
+
+def test_table2_fixture_is_the_full_enumeration(table2):
+    assert len(table2) == 36
+    assert sorted((a, b) for _, a, b, _ in table2) == sorted(cases_2x3())
+    # section III-F: (|A|+|B|-2)! |A| |B| contractions
+    assert len(cases_general(2, 3)) == 36 and len(set(cases_general(2, 3))) == 36
+    assert len(set(cases_general(3, 3))) == 24 * 3 * 3
+
+
+def test_every_table2_kernel_is_reproduced(table2):
+    # feed each printed evaluation as annotated mode strings: the planner must accept it, put the
+    # same tensor first, apply the same transposes, and compute the right numbers
+    n_flat = n_batched = 0
+    for case, ma, mb, kernels in table2:
+        for text in kernels:
+            if text.startswith("TRANS("):
+                continue                                      # needs an explicit transpose: not copy-free
+            ann = split_kernel(text)
+            assert strip_annotations(ann["A"]) == ma and strip_annotations(ann["B"]) == mb
+            rc, pl = plan(ann["A"], ann["B"], ann["C"])
+            assert pl.text() == text, (case, pl.text(), text)
+            assert pl.opL in (0, 1) and pl.opR in (0, 1)
+            check_numerics(pl, ann["A"], ann["B"], ann["C"])
+            if "[m]" in ann["C"]:
+                assert case in EXCEPTIONAL and pl.m == 1 and pl.exceptional == 1
+            elif pl.nbatch == 0:
+                n_flat += 1
+            else:
+                assert pl.nbatch == 1
+                n_batched += 1
+    assert n_flat == 8 and n_batched == 32
+
+
+def test_legal_level3_evaluations_are_exactly_table2(table2):
+    # enumerate every annotation of C_mnp; those that lower to a plain N/T level-3 call must be
+    # the evaluations the table lists, no more and no fewer
+    annots = ["mnp", "mn[p]", "m[n]p", "[m]np", "m[n][p]", "m(np)", "(mn)p", "(mnp)", "[m](np)", "(mn)[p]"]
+    with_gemm = with_sb = 0
+    exceptional = set()
+    for case, ma, mb, kernels in table2:
+        listed = {k for k in kernels if not k.startswith("TRANS(") and "[m]" not in k}
+        found = set()
+        for mc in annots:
+            rc, pl = plan(ma, mb, mc, check=False)
+            if rc != sb.SB_OK or pl.opL > 1 or pl.opR > 1 or pl.m == 1 or pl.n == 1:
+                continue
+            found.add(pl.text())
+        assert found == listed, (case, found, listed)
+        with_gemm += any("(" in k for k in found)
+        with_sb += any("[" in k for k in found)
+        if not found:
+            exceptional.add(case)
+    assert with_gemm == 8 and with_sb == 28 and exceptional == EXCEPTIONAL      # caption of Table II
+
+
+def test_auto_strategy_follows_the_priorities(table2):
+    cubic = dict(m=6, n=6, p=6, k=6)
+    for case, ma, mb, kernels in table2:
+        rc, pl = plan(ma, mb, "mnp", "auto", ext=cubic)
+        if case in EXCEPTIONAL:
+            # no plain evaluation: the extended operation of section III-E, batch in the operand's first mode
+            assert pl.exceptional == 1 and (pl.opL > 1) != (pl.opR > 1) and pl.nbatch == 1
+        else:
+            assert pl.text() == kernels[0], (case, pl.text())           # kernel 1: flatten first, else batch last
+            assert pl.exceptional == 0
+        flat = [k for k in kernels if k.startswith("C_") and "(" in k]
+        rc, pf = plan(ma, mb, "mnp", "flatten", ext=cubic, check=False)
+        assert (rc == sb.SB_OK) == bool(flat)
+        if flat:
+            assert pf.text() == flat[0] and pf.nbatch == 0
+        for strat, tag in (("batch_last", "mn[p]"), ("batch_mid", "m[n]p")):
+            rc, pb = plan(ma, mb, "mnp", strat, ext=cubic, check=False)
+            want = [k for k in kernels if k.startswith("C_" + tag)]
+            if want:
+                assert rc == sb.SB_OK and pb.text() == want[0]
+            else:
+                assert rc == sb.SB_ERR_ILLEGAL_EVAL or pb.opL > 1 or pb.opR > 1
+        rc, p2 = plan(ma, mb, "mnp", "level2", ext=cubic)
+        assert p2.m == 1 and p2.nbatch == 2
+        if case in EXCEPTIONAL:
+            assert p2.text() == kernels[1]                               # the table's batched GEMV form
+
+
+def test_largest_mode_goes_to_the_gemm():
+    # Algorithm 2 / section IV-D: GEMM over the largest legal mode, batch the next
+    rc, pl = plan("mk", "kpn", "mnp", "auto", ext=dict(m=4, n=3, p=9, k=5))
+    assert pl.text() == "C_m[n]p = A_mk B_kp[n]" and pl.n == 9 and list(pl.batch[:1]) == [3]
+    rc, pl = plan("mk", "kpn", "mnp", "auto", ext=dict(m=4, n=9, p=3, k=5))
+    assert pl.text() == "C_mn[p] = A_mk B_k[p]n" and pl.n == 9 and list(pl.batch[:1]) == [3]
+
+
+@pytest.mark.parametrize("strat", ["auto", "nested", "batch_last", "batch_mid", "level2"])
+def test_all_36_cases_execute_correctly(strat):
+    for ma, mb in cases_2x3():
+        rc, pl = plan(ma, mb, "mnp", strat, check=False)
+        if rc == sb.SB_ERR_ILLEGAL_EVAL:
+            assert strat in ("batch_last", "batch_mid")
+            continue
+        assert rc == sb.SB_OK
+        check_numerics(pl, ma, mb, "mnp")
+
+
+def test_extended_operation_calls_of_section_3e():
+    # case 3.6: sb_gemm(OP_EX_N, OP_T, M, N, K, 1, B, ldb<1>, ldb<2>, A, lda<1>, 0, 0, C, ldc<1>, ldc<2>, P)
+    rc, pl = plan("nk", "pmk", "mnp", "batch_last")
+    ldb, lda, ldc = packed(dims("pmk")), packed(dims("nk")), packed(dims("mnp"))
+    assert (pl.left_is_B, pl.opL, pl.opR) == (1, sb.SB_OP_EX_N, sb.SB_OP_T)
+    assert (pl.m, pl.n, pl.k) == (EXT["m"], EXT["n"], EXT["k"])
+    assert (pl.ldL, pl.exL, pl.ldR, pl.strideR[0]) == (ldb[1], ldb[2], lda[1], 0)
+    assert (pl.ldC, pl.strideC[0], pl.batch[0], pl.strideL[0]) == (ldc[1], ldc[2], EXT["p"], 1)
+    assert pl.text() == "C_mn[p] = B_[p]mk A_nk^T"
+    # case 6.4: sb_gemm(OP_EX_T, OP_N, M, P, K, 1, B, ldb<1>, ldb<2>, A, lda<1>, 0, 0, C, ldc<2>, ldc<1>, N)
+    rc, pl = plan("kp", "nkm", "mnp", "batch_mid")
+    ldb, lda = packed(dims("nkm")), packed(dims("kp"))
+    assert (pl.left_is_B, pl.opL, pl.opR) == (1, sb.SB_OP_EX_T, sb.SB_OP_N)
+    assert (pl.m, pl.n, pl.k) == (EXT["m"], EXT["p"], EXT["k"])
+    assert (pl.ldL, pl.exL, pl.ldR, pl.strideR[0]) == (ldb[1], ldb[2], lda[1], 0)
+    assert (pl.ldC, pl.strideC[0], pl.batch[0]) == (ldc[2], ldc[1], EXT["n"])
+    assert pl.text() == "C_m[n]p = B_[n]km^T A_kp"
+
+
+def test_table1_arguments():
+    ext = EXT
+    for ln in golden_lines("table1_blas_calls.txt"):
+        f = [x.strip() for x in ln.split("|")]
+        text, loop, routine, ops, sizes = f[0], f[1], f[2], f[3].split(), f[4].split()
+        first, second, cfield = f[5].split(), f[6].split(), f[7].split()
+        ann = split_kernel(text)
+        rc, pl = plan(ann["A"], ann["B"], ann["C"])
+        ld = {t: packed(dims(ann[t])) for t in "ABC"}
+        val = lambda tok: 0 if tok == "-" else (int(tok) if tok.isdigit() else ld[tok[2].upper()][int(tok[4])])
+        size = lambda tok: int(np.prod([ext[c] for c in tok])) if tok != "-" else 1
+        check_numerics(pl, ann["A"], ann["B"], ann["C"])
+        if routine == "GEMM":
+            assert pl.text() == text
+            assert ("NT"[pl.opL], "NT"[pl.opR]) == (ops[0], ops[1])
+            assert (pl.m, pl.n, pl.k) == (size(sizes[0]), size(sizes[1]), size(sizes[2]))
+            assert pl.left_is_B == (first[0] == "B")
+            assert (pl.ldL, pl.ldR, pl.ldC) == (val(first[2]), val(second[2]), val(cfield[1]))
+            assert pl.nbatch == (0 if loop == "-" else 1)
+            if loop != "-":
+                assert pl.batch[0] == ext[loop]
+                assert (pl.strideL[0], pl.strideR[0], pl.strideC[0]) == (val(first[1]), val(second[1]), val(cfield[0]))
+        else:
+            # GEMV y = B x per n with a strided result (incy = ldc<1>): as a GEMM it is the row
+            # form y^T = x^T B^T: one row, p columns, B transposed in the second slot
+            assert (pl.m, pl.n, pl.k, pl.nbatch, pl.batch[0]) == (1, size(sizes[0]), size(sizes[1]), 1, ext[loop])
+            assert pl.left_is_B == 0 and pl.opR == sb.SB_OP_T and pl.ldR == val(first[2])
+            assert pl.ldL == val(second[2]) and pl.ldC == val(cfield[1])          # incx, incy
+            assert (pl.strideL[0], pl.strideR[0], pl.strideC[0]) == (val(second[1]), 0, val(cfield[0]))
+            assert pl.text() == text
+
+
+def test_rules_1_to_4_reject_illegal_notation():
+    ill = sb.SB_ERR_ILLEGAL_EVAL
+    # rule 1: a batched mode may not be the first mode of a matrix term (without an extended op the
+    # planner has nothing to offer; with it the evaluation is flagged exceptional)
+    rc, pl = plan("mk", "[n]kp", "m[n]p", check=False)
+    assert rc == sb.SB_OK and pl.opR == sb.SB_OP_EX_N and pl.exceptional == 1
+    rc, pl = plan("[m]k", "knp", "[m]np", check=False)
+    assert rc == ill                                          # two free modes left in one tensor
+    # rule 2: flattening needs ld<j> = ld<i> * dim<i>: a padded B cannot be flattened, a padded C neither
+    rc, _ = sb.sb_contract_plan("mk", "k(np)", "m(np)", dims("mk"), dims("knp"),
+                                stridesB=[1, 4, 4 * 5 + 1], check=False)
+    assert rc == ill
+    rc, _ = sb.sb_contract_plan("mk", "k(np)", "m(np)", dims("mk"), dims("knp"),
+                                stridesC=[1, 3, 3 * 5 + 2], check=False)
+    assert rc == ill
+    rc, pl = sb.sb_contract_plan("mk", "knp", "mnp", dims("mk"), dims("knp"), stridesC=[1, 3, 17])
+    assert pl.nbatch == 1                                     # AUTO falls back to batching when flattening is impossible
+    rc, pl = sb.sb_contract_plan("mk", "k(np)", "m(np)", dims("mk"), dims("knp"),
+                                 stridesB=[1, 6, 30], stridesC=[1, 4, 20])
+    assert pl.nbatch == 0 and (pl.ldR, pl.ldC) == (6, 4)      # padded first mode still flattens (n,p)
+    # rule 3: the same modes in the same order on both sides
+    assert plan("mk", "k(pn)", "m(np)", check=False)[0] == ill
+    assert plan("mk", "kpn", "m(np)", check=False)[0] == ill
+    assert plan("mk", "k(np)", "m(np)", check=False)[0] == sb.SB_OK
+    # flattening a mode of A with a mode of B, or the contracted index, is meaningless
+    assert plan("mk", "knp", "(mn)p", check=False)[0] == ill
+    assert plan("m(kn)", "kp", "mnp", check=False)[0] in (ill, sb.SB_ERR_MODES)
+    # batching the contracted index
+    assert plan("m[k]", "knp", "mnp", check=False)[0] == ill
+    # rule 4: operand order follows C's first mode: C_nm... here the tensor holding m goes first
+    rc, pl = plan("nk", "kmp", "mn[p]")
+    assert pl.left_is_B == 1 and pl.text() == "C_mn[p] = B_km[p]^T A_nk^T"
+    # an annotated string plus a strategy is contradictory
+    assert plan("mk", "kn[p]", "mn[p]", "batch_last", check=False)[0] == -10
+
+
+def test_malformed_inputs():
+    assert plan("m-k", "knp", "mnp", check=False)[0] == sb.SB_ERR_MODES
+    assert plan("mk", "k[np", "mnp", check=False)[0] == sb.SB_ERR_MODES
+    assert plan("mk", "k(n)p", "mnp", check=False)[0] == sb.SB_ERR_MODES
+    assert plan("mm", "mnp", "np", check=False)[0] == sb.SB_ERR_MODES
+    assert plan("mk", "knp", "mnk", check=False)[0] == sb.SB_ERR_CONTRACTION
+    assert plan("mk", "knp", "mn", check=False)[0] == sb.SB_ERR_CONTRACTION
+    assert plan("mk", "knp", "mnpq", check=False)[0] == sb.SB_ERR_CONTRACTION
+    assert plan("mq", "knp", "mqknp", check=False)[0] == sb.SB_ERR_CONTRACTION       # no contracted index
+    assert sb.sb_contract_plan("mkq", "kqn", "mn", [3, 4, 2], [4, 2, 5], check=False)[0] == sb.SB_ERR_CONTRACTION
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, 4], [5, 5, 7], check=False)[0] == sb.SB_ERR_EXTENT
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, 4], [4, 5, 7], dimsC=[3, 5, 8], check=False)[0] == sb.SB_ERR_EXTENT
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, -4], [-4, 5, 7], check=False)[0] == sb.SB_ERR_EXTENT
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, 4], [4, 5, 7], stridesB=[1, 0, 20], check=False)[0] == sb.SB_ERR_STRIDE
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, 4], [4, 5, 7], stridesC=[1, 2, 15], check=False)[0] == sb.SB_ERR_STRIDE
+    assert sb.sb_contract_plan("mk", "knp", "mnp", [3, 4], [4, 5, 7], strat=9, check=False)[0] == -10
+    assert sb.sb_contract_plan("abcdefghk", "kz", "abcdefghz", [2] * 9, [2, 2], check=False)[0] == sb.SB_ERR_MODES
+
+
+def test_order3_times_order3_forms_of_the_benchmark_contraction():
+    ext = dict(m=4, p=3, n=5, q=2, k=6)
+    ma, mb, mc = "mpk", "knq", "mpnq"
+    ldA, ldB, ldC = packed(dims(ma, ext)), packed(dims(mb, ext)), packed(dims(mc, ext))
+    rc, pl = plan(ma, mb, mc, "auto", ext=ext)
+    assert pl.text() == "C_(mp)(nq) = A_(mp)k B_k(nq)"
+    assert (pl.m, pl.n, pl.k, pl.nbatch, pl.ldL, pl.ldR, pl.ldC) == (12, 10, 6, 0, ldA[2], ldB[1], ldC[2])
+    check_numerics(pl, ma, mb, mc, ext)
+    rc, pl = plan(ma, mb, mc, "nested", ext=ext)
+    assert pl.text() == "C_m[p]n[q] = A_m[p]k B_kn[q]" and pl.nbatch == 2
+    assert (pl.m, pl.n, pl.k, pl.ldL, pl.ldR, pl.ldC) == (4, 5, 6, ldA[2], ldB[1], ldC[2])
+    assert list(pl.batch[:2]) == [3, 2]
+    assert list(pl.strideL[:2]) == [ldA[1], 0] and list(pl.strideR[:2]) == [0, ldB[2]]
+    assert list(pl.strideC[:2]) == [ldC[1], ldC[3]]
+    check_numerics(pl, ma, mb, mc, ext)
+    for a, b, c in (("(mp)k", "kn[q]", "(mp)n[q]"), ("m[p]k", "k(nq)", "m[p](nq)"), ("m[p]k", "k[n]q", "m[p][n]q")):
+        rc, pl = plan(a, b, c, ext=ext)
+        check_numerics(pl, a, b, c, ext)
+    # the example of section III-F: C_mn[p][q] = A_mk[p] B_nk[q], larger mode innermost
+    rc, pl = plan("mkp", "nkq", "mnpq", "nested", ext=dict(m=4, n=5, k=6, p=2, q=3))
+    assert pl.text() == "C_mn[p][q] = A_mk[p] B_nk[q]^T" and list(pl.batch[:2]) == [3, 2]
+
+
+def test_every_order3_x_order3_contraction_plans_and_executes():
+    ext = dict(m=2, n=3, p=4, q=5, k=3)
+    cases = cases_general(3, 3)
+    assert len(cases) == 216
+    n_ex = 0
+    for i, (ma, mb, mc) in enumerate(cases):
+        rc, pl = plan(ma, mb, mc, "auto", ext=ext)
+        n_ex += pl.exceptional
+        if i % 3 == 0:
+            check_numerics(pl, ma, mb, mc, ext, seed=i)
+    assert 0 < n_ex < 216
+
+
+def test_three_batch_levels_and_vectors():
+    ext = dict(m=2, n=3, p=2, q=3, r=2, k=3)
+    rc, pl = plan("mpk", "knqr", "mnpqr", "nested", ext=ext)
+    assert pl.nbatch == 3
+    check_numerics(pl, "mpk", "knqr", "mnpqr", ext)
+    # matrix-vector and vector-matrix contractions come out as one-column / one-row GEMMs
+    for ma, mb, mc in (("mk", "k", "m"), ("km", "k", "m"), ("k", "kn", "n"), ("k", "nk", "n"), ("k", "k", ""),
+                       ("mnk", "k", "mn"), ("k", "mnk", "mn")):
+        rc, pl = plan(ma, mb, mc, ext=ext)
+        check_numerics(pl, ma, mb, mc, ext)
