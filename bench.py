@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the contraction hot path on one MI355X.
+
+A "step" is one pass of the whole path for one contraction: sb_contract() parses the mode strings,
+plans the evaluation, selects a kernel and launches it on tensors that are already resident in
+HBM.  The headline workload is the large cube C_mnp = sum_k A_km B_knp at 512^4 in fp32 evaluated
+as one StridedBatchedGemm over p; the other benchmark contractions are timed too and reported in
+the same JSON line under "workloads".
+
+Prints ONE JSON line: metric / value (GFLOP/s) / ms_per_step ..., plus
+  "roofline":     achieved vs peak for the dominant kernel (HIP events on the launch stream),
+  "cpu_baseline": the CPU oracle timed on the host cores on a bounded sample of the same workload,
+  "baselines":    the conventional evaluation on the same GPU (torch permute/copy + vendor GEMM).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks used for the roofline fractions
+PEAK = {"hbm": 8000.0,                                   # GB/s
+        "mfma": {"f64": 78.6, "f32": 157.3, "bf16": 2500.0}}   # TFLOP/s, dense
+ESIZE = {"f64": 8, "f32": 4, "bf16": 2}
+# which roofline binds each workload: dense high-intensity contractions are priced against the
+# matrix cores, the batch-dominated / output-dominated ones against HBM
+BOUND = {1: "hbm", 3: "hbm", 40: "mfma", 41: "mfma", 5: "hbm"}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), null until measured
+MEASURED_TRAFFIC = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=41, help="headline workload id (inputs.WORKLOADS)")
+    ap.add_argument("--only-headline", action="store_true", help="skip the other workloads")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-torch-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one device copy of known size (to scale rocprofv3 byte counters)")
+    return ap.parse_args()
+
+
+def dev(x, dtype):
+    import torch
+    from paper_1606_05696_amd import inputs
+    flat = np.ascontiguousarray(x.ravel(order="F"))
+    if dtype == "bf16":
+        return torch.from_numpy(inputs.bf16_bits(flat).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(flat).cuda()
+
+
+def workload_numbers(w):
+    ext = w["ext"]
+    strip = lambda s: "".join(c for c in s if c.isalpha())
+    nel = lambda s: int(np.prod([ext[c] for c in strip(s)], dtype=np.int64))
+    labels = set(strip(w["A"])) | set(strip(w["B"]))
+    flops = 2 * int(np.prod([ext[c] for c in labels], dtype=np.int64))
+    nbytes = (nel(w["A"]) + nel(w["B"]) + nel(w["C"])) * ESIZE[w["dtype"]]    # each tensor touched once (beta = 0)
+    return flops, nbytes
+
+
+def time_steps(fn, steps, warmup):
+    """Wall time per step (host clock around a synchronised region) and device time per launch
+    (HIP events recorded on the launch stream around the same region)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+
+def run_workload(cfg, steps, warmup, torch_baseline=True):
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    w = inputs.WORKLOADS[cfg]
+    dtype = w["dtype"]
+    A, B = inputs.workload_tensors(cfg)
+    ext = w["ext"]
+    dA, dB, dC = ([ext[c] for c in w[t]] for t in "ABC")
+    tA, tB = dev(A, dtype), dev(B, dtype)
+    tC = torch.empty(int(np.prod(dC)), dtype=tA.dtype, device="cuda")
+    ma, mb, mc = w["eval"]
+    flops, nbytes = workload_numbers(w)
+    rc, plan = sb.sb_contract_plan(ma, mb, mc, dA, dB)
+
+    def step():
+        sb.sb_contract(ma, mb, mc, 1.0, tA, dA, tB, dB, 0.0, tC, dC)
+
+    ms, kernel_ms = time_steps(step, steps, warmup)
+    kernel = sb.sb_last_kernel()
+    out = dict(workload=w["name"], dtype=dtype, evaluation=plan.text(), kernel_family=kernel,
+               ms_per_step=ms, kernel_ms=kernel_ms, gflops=flops / ms / 1e6, flops=flops, bytes=nbytes)
+    bound = BOUND[cfg]
+    if bound == "mfma":
+        ach, peak, unit = flops / kernel_ms / 1e9, PEAK["mfma"][dtype], "TFLOP/s"
+    else:
+        ach, peak, unit = nbytes / kernel_ms / 1e6, PEAK["hbm"], "GB/s"
+    out["roofline"] = dict(bound=bound, achieved=ach, peak=peak, unit=unit, frac=ach / peak,
+                           traffic=MEASURED_TRAFFIC.get(cfg))
+    if torch_baseline:
+        out["torch_matmul"] = conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops)
+    del tA, tB, tC
+    torch.cuda.empty_cache()
+    return out, (A, B)
+
+
+def conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops):
+    """The conventional evaluation on the same GPU: bring the operands into matricised form
+    (explicit permute + copy where the layout needs one) and call the vendor GEMM through torch.
+    A column-major tensor with extents (d0, d1, ..) is a row-major torch tensor of shape (.., d1, d0)."""
+    import torch
+    from paper_1606_05696_amd import inputs
+    w = inputs.WORKLOADS[cfg]
+    a = tA.view(*reversed(dA))
+    b = tB.view(*reversed(dB))
+    la, lb, lc = w["A"][::-1], w["B"][::-1], w["C"][::-1]     # torch (row-major) index order
+    expr = "%s,%s->%s" % (la, lb, lc)
+
+    def step():
+        return torch.einsum(expr, a, b).contiguous()
+
+    ms, _ = time_steps(step, steps, warmup)
+    return dict(ms_per_step=ms, gflops=flops / ms / 1e6, how="torch.einsum('%s') + contiguous()" % expr)
+
+
+def cpu_baseline(cfg, tensors, budget_s=12.0):
+    """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
+    last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
+    from oracle import oracle
+    from paper_1606_05696_amd import inputs
+    w = inputs.WORKLOADS[cfg]
+    A, B = tensors
+    wide = w["dtype"] == "f64"
+    last = w["C"][-1]
+    ext = w["ext"]
+    in_a = last in w["A"]
+
+    def run(nslices):
+        sl = lambda X, modes: X[tuple(slice(0, nslices) if c == last else slice(None) for c in modes)]
+        As = np.asfortranarray(sl(A, w["A"])) if in_a else A
+        Bs = B if in_a else np.asfortranarray(sl(B, w["B"]))
+        t0 = time.perf_counter()
+        oracle.contract(w["A"], As, w["B"], Bs, w["C"], wide=wide)
+        return time.perf_counter() - t0
+
+    flops_per_slice = workload_numbers(w)[0] / ext[last]
+    probe = min(2, ext[last])
+    t_probe = run(probe)
+    n = int(max(probe, min(ext[last], budget_s / max(t_probe / probe, 1e-9))))
+    t = run(n) if n > probe else t_probe
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return dict(value=flops_per_slice * n / t / 1e9, unit="GFLOP/s", cores=threads, kind="oracle",
+                sample="%d of %d slices of mode %s of C (%.3g GFLOP in %.2f s, %s accumulation)"
+                       % (n, ext[last], last, flops_per_slice * n / 1e9, t, "long double" if wide else "double"))
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the contraction path has no multi-GPU part (every box here has "
+              "one GPU); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    sb.binding.load()
+    torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    head, tensors = run_workload(args.workload, args.steps, args.warmup, not args.no_torch_baseline)
+    w = inputs.WORKLOADS[args.workload]
+    result = {
+        "metric": "GFLOP/s per contraction (StridedBatchedGemm path), 1 GPU",
+        "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w["dtype"], "data": "synthetic",
+        "config": {"workload": w["name"], "evaluation": head["evaluation"], "kernel_family": head["kernel_family"],
+                   "flops_per_step": head["flops"], "algorithmic_bytes_per_step": head["bytes"]},
+        "roofline": head["roofline"],
+    }
+    if not args.no_torch_baseline:
+        result["baselines"] = {"conventional_same_gpu": head["torch_matmul"]}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(args.workload, tensors)
+    del tensors
+    if not args.only_headline:
+        others = []
+        for cfg in inputs.WORKLOADS:
+            if cfg == args.workload:
+                continue
+            steps = args.steps if cfg in (40, 41) else max(args.steps, 200)
+            r, _ = run_workload(cfg, steps, args.warmup, not args.no_torch_baseline)
+            others.append(r)
+        result["workloads"] = others
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
