@@ -1,7 +1,267 @@
-// Tiny-matrix StridedBatchedGemm path (placeholder until the kernel lands: nothing is supported,
-// so the selector never routes here).
+// Tiny-matrix StridedBatchedGemm: the batch-dominated, bandwidth-bound regime (m, n <= 32).
+//
+// Here a single GEMM is far too small to fill a workgroup, and the whole problem moves only a
+// few bytes per flop, so the kernel is organised around memory traffic, not around tiles
+// (section III-C: many small GEMMs; section IV-B: on a GPU such shapes are governed by the
+// number of global memory transactions).  One WAVEFRONT owns one C_p at a time and walks over
+// the batch with a grid-wide stride; nothing is staged through LDS and there is no barrier.
+//   - Every operand element is fetched from global memory exactly once, by the lane that feeds
+//     it to the matrix core: for a k-contiguous operand a lane reads 4 consecutive k of its
+//     row/column as one 16- or 32-byte vector, so the 64 lanes of a load instruction together
+//     cover one contiguous block of the matrix.
+//   - The product uses the 16x16x4 MFMA (4 lane groups x 4 steps = 16 k per round).  Even here
+//     the matrix core pays: it needs no cross-lane traffic to form the 16x16 outer products and
+//     runs at a fraction of its rate while memory is the limit.
+//   - fp32 results are stored as one 16-byte vector per lane (a lane holds 4 consecutive rows of
+//     one column); fp64 results are produced transposed so that 16 lanes write 128 contiguous bytes.
+//   - Several batches per wave are in flight at once (UNROLL) to cover memory latency.
+//   - An operand shared by all batches (batch strides 0, as A is in every order-2 x order-3
+//     contraction) is read once per wave and kept in registers when k <= 16.
+#include "sb_device.h"
 #include "sb_internal.h"
 
-bool sb_tiny_supports(sb_dtype, const SbArgs &) { return false; }
-bool sb_tiny_preferred(sb_dtype, const SbArgs &) { return false; }
-hipError_t sb_launch_tiny(sb_dtype, const SbArgs &, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct TinyMfma;
+
+// v_mfma_f32_16x16x4_f32: operand lane l holds X[l%16][k = l/16]; result slot r is D[4*(l/16) + r][l%16].
+template <> struct TinyMfma<float> {
+    typedef f32x4 Acc;
+    typedef f32x4 Vec4;
+    static constexpr bool SWAP = false;     // lane = column of C, slots = 4 consecutive rows
+    static __device__ __forceinline__ void mma(Acc &c, float first, float second)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(first, second, c, 0, 0, 0);
+    }
+};
+
+// v_mfma_f64_16x16x4_f64: same operand layout; result slot r is D[l/16 + 4*r][l%16].
+template <> struct TinyMfma<double> {
+    typedef f64x4 Acc;
+    typedef f64x4 Vec4;
+    static constexpr bool SWAP = true;      // computes C^T: lane = row of C, slots = columns h, h+4, ..
+    static __device__ __forceinline__ void mma(Acc &c, double first, double second)
+    {
+        c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0);
+    }
+};
+
+constexpr int TINY_THREADS = 256;
+constexpr int WAVES = TINY_THREADS / 64;
+
+// 4 consecutive-k elements of row/column `rc` of an operand, starting at k0.
+// KC: k is contiguous in memory (stride 1) and rows/columns stride by ld; else the reverse.
+template <typename T, bool KC>
+__device__ __forceinline__ void load_frag(T (&f)[4], const T *p, int64_t ld, int rc, int rc_count, int64_t k0, int64_t kcount, bool vec_ok)
+{
+    typedef typename TinyMfma<T>::Vec4 Vec4;
+    if (KC) {
+        const T *src = p + (int64_t)rc * ld + k0;
+        if (vec_ok && rc < rc_count && k0 + 4 <= kcount) {
+            Vec4 v = *(const Vec4 *)src;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = v[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) f[e] = (rc < rc_count && k0 + e < kcount) ? src[e] : T(0);
+        }
+    } else {
+        const T *src = p + rc + k0 * ld;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = (rc < rc_count && k0 + e < kcount) ? src[e * ld] : T(0);
+    }
+}
+
+// TM x TN MFMA blocks of 16 x 16 per C_p; U batches in flight per wave.
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, bool HOIST_A, int U>
+__global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int vec_a, int vec_b, int vec_c)
+{
+    typedef TinyMfma<T> MF;
+    typedef typename MF::Acc Acc;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int h = lane >> 4, c16 = lane & 15;
+    const int64_t total = g.batch0 * g.batch1;
+    const int64_t nwaves = (int64_t)gridDim.x * WAVES;
+    const int64_t wid = (int64_t)blockIdx.x * WAVES + wave;
+    const int64_t ldA = A_KC ? g.rsA : g.csA;          // stride between rows (KC) or between k (else)
+    const int64_t ldB = B_KC ? g.csB : g.rsB;
+    const int m = (int)g.m, n = (int)g.n;
+    const T alpha = (T)g.alpha, beta = (T)g.beta;
+
+    T fa_shared[TM][4];
+    if (HOIST_A) {
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+            load_frag<T, A_KC>(fa_shared[a], (const T *)g.A, ldA, a * 16 + c16, m, 4 * h, g.k, vec_a);
+    }
+
+    // U consecutive batches per step: a wave's loads for all of them are issued before any is used
+    for (int64_t base = wid * U; base < total; base += nwaves * U) {
+        Acc acc[U][TM][TN];
+        const T *Ap[U], *Bp[U];
+        T *Cp[U];
+        bool live[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t b = base + u;
+            live[u] = b < total;
+            const int64_t bb = live[u] ? b : 0;
+            const int64_t b1 = bb / g.batch0, b0 = bb - b1 * g.batch0;
+            Ap[u] = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1];
+            Bp[u] = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1];
+            Cp[u] = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int c = 0; c < TN; ++c)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[u][a][c][r] = T(0);
+        }
+        for (int64_t k0 = 0; k0 < g.k; k0 += 16) {
+            T fa[U][TM][4], fb[U][TN][4];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (!live[u]) continue;                 // wave-uniform
+#pragma unroll
+                for (int c = 0; c < TN; ++c)
+                    load_frag<T, B_KC>(fb[u][c], Bp[u], ldB, c * 16 + c16, n, k0 + 4 * h, g.k, vec_b);
+                if (!HOIST_A) {
+#pragma unroll
+                    for (int a = 0; a < TM; ++a)
+                        load_frag<T, A_KC>(fa[u][a], Ap[u], ldA, a * 16 + c16, m, k0 + 4 * h, g.k, vec_a);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (!live[u]) continue;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int a = 0; a < TM; ++a)
+#pragma unroll
+                        for (int c = 0; c < TN; ++c) {
+                            const T av = HOIST_A ? fa_shared[a][e] : fa[u][a][e];
+                            if (MF::SWAP) MF::mma(acc[u][a][c], fb[u][c][e], av);
+                            else          MF::mma(acc[u][a][c], av, fb[u][c][e]);
+                        }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!live[u]) continue;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int c = 0; c < TN; ++c) {
+                    if (!MF::SWAP) {
+                        // lane: column j, rows i..i+3
+                        const int j = c * 16 + c16, i = a * 16 + 4 * h;
+                        if (j >= n || i >= m) continue;
+                        T *dst = Cp[u] + i + (int64_t)j * g.ldc;
+                        if (vec_c && i + 4 <= m) {
+                            typename MF::Vec4 v;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[r] = alpha * acc[u][a][c][r];
+                            if (beta != T(0)) {
+                                typename MF::Vec4 old = *(const typename MF::Vec4 *)dst;
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) v[r] += beta * old[r];
+                            }
+                            *(typename MF::Vec4 *)dst = v;
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                if (i + r >= m) continue;
+                                T v = alpha * acc[u][a][c][r];
+                                if (beta != T(0)) v += beta * dst[r];
+                                dst[r] = v;
+                            }
+                        }
+                    } else {
+                        // lane: row i, columns h, h+4, h+8, h+12 of the block
+                        const int i = a * 16 + c16;
+                        if (i >= m) continue;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int j = c * 16 + h + 4 * r;
+                            if (j >= n) continue;
+                            T *dst = Cp[u] + i + (int64_t)j * g.ldc;
+                            T v = alpha * acc[u][a][c][r];
+                            if (beta != T(0)) v += beta * *dst;
+                            *dst = v;
+                        }
+                    }
+                }
+        }
+    }
+}
+
+template <typename T, int TM, int TN, bool A_KC, bool B_KC>
+hipError_t launch3(const SbArgs &a, hipStream_t stream)
+{
+    const int64_t total = a.batch0 * a.batch1;
+    constexpr int U = (TM * TN == 1) ? 4 : (TM * TN == 2 ? 2 : 1);
+    const bool hoist = (a.bsA[0] == 0 || a.batch0 == 1) && (a.bsA[1] == 0 || a.batch1 == 1) && a.k <= 16;
+    // vector accesses need 16-byte (fp32) / 32-byte (fp64) alignment of every address they touch
+    const int64_t V = 4;
+    const uintptr_t bytes = V * sizeof(T);
+    auto al = [&](int64_t v) { return v % V == 0; };
+    const int vec_a = A_KC && (uintptr_t)a.A % bytes == 0 && al(a.rsA) && al(a.bsA[0]) && al(a.bsA[1]);
+    const int vec_b = B_KC && (uintptr_t)a.B % bytes == 0 && al(a.csB) && al(a.bsB[0]) && al(a.bsB[1]);
+    const int vec_c = (uintptr_t)a.C % bytes == 0 && al(a.ldc) && al(a.bsC[0]) && al(a.bsC[1]);
+    // enough workgroups to fill the chip several waves deep, no more than the work needs
+    int64_t groups = (total + (int64_t)WAVES * U - 1) / ((int64_t)WAVES * U);
+    const int64_t cap = 256 * 8;
+    if (groups > cap) groups = cap;
+    if (groups < 1) return hipSuccess;
+    dim3 grid((unsigned)groups), block(TINY_THREADS);
+    if (hoist) hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, true, U>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    else       hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    return hipGetLastError();
+}
+
+template <typename T, int TM, int TN>
+hipError_t launch2(const SbArgs &a, hipStream_t stream)
+{
+    const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
+    if (a_kc && b_kc)  return launch3<T, TM, TN, true, true>(a, stream);
+    if (a_kc && !b_kc) return launch3<T, TM, TN, true, false>(a, stream);
+    if (!a_kc && b_kc) return launch3<T, TM, TN, false, true>(a, stream);
+    return launch3<T, TM, TN, false, false>(a, stream);
+}
+
+template <typename T>
+hipError_t launch1(const SbArgs &a, hipStream_t stream)
+{
+    const int tm = a.m > 16 ? 2 : 1, tn = a.n > 16 ? 2 : 1;
+    if (tm == 1 && tn == 1) return launch2<T, 1, 1>(a, stream);
+    if (tm == 2 && tn == 1) return launch2<T, 2, 1>(a, stream);
+    if (tm == 1 && tn == 2) return launch2<T, 1, 2>(a, stream);
+    return launch2<T, 2, 2>(a, stream);
+}
+
+}  // namespace
+
+bool sb_tiny_supports(sb_dtype dt, const SbArgs &a)
+{
+    if (dt != SB_F32 && dt != SB_F64) return false;
+    if (a.k <= 0 || a.m > 32 || a.n > 32) return false;
+    const bool a_ok = (a.csA == 1) || (a.rsA == 1);
+    const bool b_ok = (a.rsB == 1) || (a.csB == 1);
+    return a_ok && b_ok;
+}
+
+bool sb_tiny_preferred(sb_dtype, const SbArgs &) { return true; }
+
+hipError_t sb_launch_tiny(sb_dtype dt, const SbArgs &a, hipStream_t stream)
+{
+    switch (dt) {
+    case SB_F32: return launch1<float>(a, stream);
+    case SB_F64: return launch1<double>(a, stream);
+    default: break;
+    }
+    return hipErrorInvalidValue;
+}
