@@ -31,7 +31,7 @@ template <typename T> struct Mfma;
 // v_mfma_f32_32x32x2_f32: operands hold X[l%32][k = l/32]; result slot r of lane l is
 // D[8*(r/4) + 4*(l/32) + r%4][l%32].
 template <> struct Mfma<float> {
-    static constexpr int MI = 32, KL = 2, VEC = 4, NREG = 16;
+    static constexpr int MI = 32, VEC = 4, NREG = 16;       // 64/MI lane groups x VEC = 8 k per group
     typedef f32x16 Acc;
     typedef float Vec __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ void mma(Acc &c, float first, float second)
@@ -43,7 +43,7 @@ template <> struct Mfma<float> {
 
 // v_mfma_f64_16x16x4_f64: operands hold X[l%16][k = l/16]; result slot r of lane l is D[l/16 + 4*r][l%16].
 template <> struct Mfma<double> {
-    static constexpr int MI = 16, KL = 4, VEC = 2, NREG = 4;
+    static constexpr int MI = 16, VEC = 2, NREG = 4;
     typedef f64x4 Acc;
     typedef double Vec __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ void mma(Acc &c, double first, double second)
@@ -257,7 +257,6 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
 // N and T operands only: one of the two strides of each operand must be 1.
 bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 {
-    if (dt != SB_F32 && dt != SB_F64) return false;
     if (a.k <= 0) return false;
     const bool a_ok = (a.csA == 1) || (a.rsA == 1);
     const bool b_ok = (a.rsB == 1) || (a.csB == 1);
@@ -269,7 +268,7 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 
 bool sb_mfma_preferred(sb_dtype, const SbArgs &a)
 {
-    return a.m >= 64 && a.n >= 64 && a.k >= 16;
+    return a.m >= 32 && a.n >= 32 && a.k >= 16;
 }
 
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
@@ -277,6 +276,7 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     switch (dt) {
     case SB_F32: return launch<float, 16>(a, stream);
     case SB_F64: return launch<double, 16>(a, stream);
+    case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;
     }
     return hipErrorInvalidValue;

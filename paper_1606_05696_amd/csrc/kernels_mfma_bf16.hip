@@ -1,0 +1,214 @@
+// MFMA-tiled StridedBatchedGemm for bf16 inputs with fp32 accumulation and bf16 output.
+//
+// Same organisation as the fp32/fp64 kernel (one workgroup of four waves per C tile, batch folded
+// into the grid, double-buffered LDS panels, XCD-aware tile order, C^T trick for coalesced
+// stores), built on v_mfma_f32_32x32x16_bf16.  That instruction wants 8 consecutive k per lane
+// for both operands (lane l holds X[l%32][8*(l/32) .. +7]):
+//   k contiguous operand (A with T, B with N): LDS [row][k], one 16-byte LDS read per fragment;
+//   m/n contiguous operand (A with N, B with T): LDS [k][row]; the 8 k of a fragment are gathered
+//     with 2-byte LDS reads (conflict-free: the lanes of a read run along the row dimension).
+// The epilogue rounds alpha*acc + beta*C to bf16 (nearest even).
+#include "sb_device.h"
+#include "sb_internal.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int NTHREADS = 256;
+constexpr int NXCD = 8;
+constexpr int BK = 32;          // two MFMA k-steps of 16 per panel
+
+template <bool KC, int ROWS>
+struct PanelBf16 {
+    static constexpr int NVEC = ROWS * BK / 8 / NTHREADS;             // 16-byte vectors per lane
+    static constexpr int LDS_LD = (KC ? BK : ROWS) + 8;               // padded by 16 bytes
+    static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
+    static_assert(ROWS * BK % (8 * NTHREADS) == 0, "panel must split evenly over the lanes");
+
+    static __device__ __forceinline__ void coords(int f, int &row, int &k)
+    {
+        if (KC) { row = f / (BK / 8); k = (f % (BK / 8)) * 8; }
+        else    { k = f / (ROWS / 8); row = (f % (ROWS / 8)) * 8; }
+    }
+
+    static __device__ __forceinline__ void load(u16x8 (&v)[NVEC], const uint16_t *p, int64_t ld, int64_t rows_left, int64_t k_left, bool vec_ok)
+    {
+#pragma unroll
+        for (int q = 0; q < NVEC; ++q) {
+            int row, k;
+            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            const uint16_t *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
+            const bool inside = KC ? (row < rows_left && k + 8 <= k_left) : (row + 8 <= rows_left && k < k_left);
+            if (vec_ok && inside) {
+                v[q] = *(const u16x8 *)src;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = KC ? (row < rows_left && k + e < k_left) : (row + e < rows_left && k < k_left);
+                    v[q][e] = ok ? src[e] : (uint16_t)0;
+                }
+            }
+        }
+    }
+
+    static __device__ __forceinline__ void store(uint16_t *lds, const u16x8 (&v)[NVEC])
+    {
+#pragma unroll
+        for (int q = 0; q < NVEC; ++q) {
+            int row, k;
+            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            uint16_t *dst = KC ? lds + row * LDS_LD + k : lds + k * LDS_LD + row;
+            *(u16x8 *)dst = v[q];
+        }
+    }
+
+    // operand fragment of the 32-row block starting at row0 for MFMA k-step ks (16 k)
+    static __device__ __forceinline__ bf16x8 fragment(const uint16_t *lds, int row0, int ks, int lane)
+    {
+        const int row = row0 + (lane & 31);
+        const int k = ks * 16 + (lane >> 5) * 8;
+        u16x8 v;
+        if (KC) {
+            v = *(const u16x8 *)(lds + row * LDS_LD + k);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = lds[(k + e) * LDS_LD + row];
+        }
+        return __builtin_bit_cast(bf16x8, v);
+    }
+};
+
+// WT: wave tile edge (64 -> 128x128 workgroup tile, 32 -> 64x64)
+template <bool A_KC, bool B_KC, int WT>
+__global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
+{
+    constexpr int BM = 2 * WT, BN = 2 * WT, NB = WT / 32;
+    typedef PanelBf16<A_KC, BM> PA;
+    typedef PanelBf16<B_KC, BN> PB;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
+
+    // hardware deals consecutive workgroup ids to the 8 XCDs in turn: renumber so that each XCD
+    // owns a contiguous range of tiles and batches
+    const int64_t total = (int64_t)gridDim.x;
+    const int64_t bid = blockIdx.x;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t xcd = bid % NXCD, slot = bid / NXCD;
+    const int64_t logical = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t b = logical / tiles;
+    const int tile = (int)(logical - b * tiles);
+    const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
+    const int tm = tile % tiles_m, tn = tile / tiles_m;
+    const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
+
+    const uint16_t *A = (const uint16_t *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
+    const uint16_t *B = (const uint16_t *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
+    uint16_t *C = (uint16_t *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+    const int64_t ldA = A_KC ? g.rsA : g.csA;
+    const int64_t ldB = B_KC ? g.csB : g.rsB;
+    const int64_t kstepA = A_KC ? 1 : g.csA;
+    const int64_t kstepB = B_KC ? 1 : g.rsB;
+    const int64_t m_left = g.m - i0, n_left = g.n - j0;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave & 1) * WT, wn = (wave >> 1) * WT;
+
+    f32x16 acc[NB][NB];
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int c = 0; c < NB; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+
+    u16x8 ra[PA::NVEC], rb[PB::NVEC];
+    const int64_t nkb = (g.k + BK - 1) / BK;
+    if (nkb > 0) {
+        PA::load(ra, A, ldA, m_left, g.k, vec_ok);
+        PB::load(rb, B, ldB, n_left, g.k, vec_ok);
+        PA::store(As[0], ra);
+        PB::store(Bs[0], rb);
+    }
+    __syncthreads();
+    for (int64_t kb = 0; kb < nkb; ++kb) {
+        const int cur = (int)(kb & 1);
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            const int64_t k0 = (kb + 1) * BK;
+            PA::load(ra, A + k0 * kstepA, ldA, m_left, g.k - k0, vec_ok);
+            PB::load(rb, B + k0 * kstepB, ldB, n_left, g.k - k0, vec_ok);
+        }
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 fa[NB], fb[NB];
+#pragma unroll
+            for (int a = 0; a < NB; ++a) fa[a] = PA::fragment(As[cur], wm + a * 32, ks, lane);
+#pragma unroll
+            for (int c = 0; c < NB; ++c) fb[c] = PB::fragment(Bs[cur], wn + c * 32, ks, lane);
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int c = 0; c < NB; ++c)      // C^T = B^T A^T: lanes run along rows of C
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], fa[a], acc[a][c], 0, 0, 0);
+        }
+        if (more) {
+            PA::store(As[cur ^ 1], ra);
+            PB::store(Bs[cur ^ 1], rb);
+        }
+        __syncthreads();
+    }
+
+    const float alpha = (float)g.alpha, beta = (float)g.beta;
+#pragma unroll
+    for (int a = 0; a < NB; ++a) {
+        const int64_t i = i0 + wm + a * 32 + (lane & 31);
+        if (i >= g.m) continue;
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t j = j0 + wn + c * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (j >= g.n) continue;
+                uint16_t *dst = C + i + j * g.ldc;
+                float v = alpha * acc[a][c][r];
+                if (beta != 0.f) v += beta * sb_bf16_to_f32(*dst);
+                *dst = sb_f32_to_bf16(v);
+            }
+        }
+    }
+}
+
+template <int WT>
+hipError_t launch(const SbArgs &a, hipStream_t stream)
+{
+    constexpr int BM = 2 * WT, BN = 2 * WT;
+    const int64_t tiles_m = (a.m + BM - 1) / BM, tiles_n = (a.n + BN - 1) / BN;
+    const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
+    if (total <= 0) return hipSuccess;
+    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
+    auto aligned = [](int64_t v) { return v % 8 == 0; };
+    const int vec_ok = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
+                       aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
+                       aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    dim3 grid((unsigned)total), block(NTHREADS);
+    const int tm = (int)tiles_m, tn = (int)tiles_n;
+    if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<true, true, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else if (a_kc && !b_kc)  hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<true, false, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else if (!a_kc && b_kc)  hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<false, true, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else                     hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<false, false, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
+{
+    // small matrices per batch: 64x64 tiles waste less and give more workgroups
+    if (a.m <= 64 || a.n <= 64) return launch<32>(a, stream);
+    return launch<64>(a, stream);
+}
