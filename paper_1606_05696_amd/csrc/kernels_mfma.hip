@@ -53,21 +53,19 @@ template <> struct Mfma<double> {
     static __device__ __forceinline__ int result_row(int r, int lane) { return (lane >> 4) + 4 * r; }
 };
 
-constexpr int BM = 128, BN = 128, WT = 64;      // workgroup tile, wave tile (square)
-constexpr int NTHREADS = 256;
 constexpr int NXCD = 8;
 
 // Stage one BK-deep panel (ROWS rows of the operand) from global memory into registers.
 // KC: the panel is stored [row][k] with k contiguous in memory (row stride `ld`);
 // otherwise rows are contiguous and k strides by `ld`.
-template <typename T, bool KC, int ROWS, int BK>
+template <typename T, bool KC, int ROWS, int BK, int NT>
 struct Panel {
     typedef typename Mfma<T>::Vec Vec;
     static constexpr int VEC = Mfma<T>::VEC;
-    static constexpr int NVEC = ROWS * BK / VEC / NTHREADS;          // 16-byte vectors per lane
+    static constexpr int NVEC = ROWS * BK / VEC / NT;                  // 16-byte vectors per lane
     static constexpr int LDS_LD = (KC ? BK : ROWS) + VEC;              // padded by 16 bytes
     static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
-    static_assert(ROWS * BK % (VEC * NTHREADS) == 0, "panel must split evenly over the lanes");
+    static_assert(ROWS * BK % (VEC * NT) == 0, "panel must split evenly over the lanes");
 
     static __device__ __forceinline__ void coords(int f, int &row, int &k)
     {
@@ -75,14 +73,20 @@ struct Panel {
         else    { k = f / (ROWS / VEC); row = (f % (ROWS / VEC)) * VEC; }
     }
 
-    // rows_left / k_left: how much of the panel lies inside the matrix (for edge tiles)
+    // GUARD = false: the whole panel lies inside the matrix and every vector is 16-byte aligned.
+    // GUARD = true: rows_left / k_left say how much of the panel is inside (edge tiles, odd strides).
+    template <bool GUARD>
     static __device__ __forceinline__ void load(Vec (&v)[NVEC], const T *p, int64_t ld, int64_t rows_left, int64_t k_left, bool vec_ok)
     {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
-            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            coords((int)threadIdx.x + NT * q, row, k);
             const T *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
+            if (!GUARD) {
+                v[q] = *(const Vec *)src;
+                continue;
+            }
             const bool inside = KC ? (row < rows_left && k + VEC <= k_left) : (row + VEC <= rows_left && k < k_left);
             if (vec_ok && inside) {
                 v[q] = *(const Vec *)src;
@@ -101,13 +105,13 @@ struct Panel {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
-            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            coords((int)threadIdx.x + NT * q, row, k);
             T *dst = KC ? lds + row * LDS_LD + k : lds + k * LDS_LD + row;
             *(Vec *)dst = v[q];
         }
     }
 
-    // Fragment of MFMA block `blk` (rows row0 + blk*MI ..) for k-group kg: VEC consecutive MFMA steps.
+    // Fragment of the MFMA block whose first row is row0, for k-group kg: VEC consecutive MFMA steps.
     static __device__ __forceinline__ void fragment(T (&frag)[VEC], const T *lds, int row0, int kg, int lane)
     {
         constexpr int MI = Mfma<T>::MI;
@@ -124,16 +128,75 @@ struct Panel {
     }
 };
 
-template <typename T, bool A_KC, bool B_KC, int BK>
-__global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
-{
+// Tile configuration: each wave owns WM x WN of C; WAVES_M x WAVES_N waves form the workgroup tile.
+template <typename T, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+struct Config {
+    static constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
     typedef Mfma<T> MF;
-    typedef Panel<T, A_KC, BM, BK> PA;
-    typedef Panel<T, B_KC, BN, BK> PB;
+    typedef Panel<T, A_KC, BM, BK, NT> PA;
+    typedef Panel<T, B_KC, BN, BK, NT> PB;
+    static constexpr int NBM = WM / MF::MI, NBN = WN / MF::MI;         // MFMA blocks per wave tile
+};
+
+// The k loop of one tile.  GUARD selects bounds-checked scalar loads (edge tiles, unaligned
+// operands) or plain 16-byte vector loads (interior tiles): the latter is branch-free, so the
+// compiler can keep the next panel's global loads in flight under the current panel's MFMAs.
+template <typename CF, typename T, bool GUARD>
+__device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::NBN], T (*As)[CF::PA::LDS_SIZE], T (*Bs)[CF::PB::LDS_SIZE],
+                                        const T *A, const T *B, int64_t ldA, int64_t ldB, int64_t kstepA, int64_t kstepB,
+                                        int64_t m_left, int64_t n_left, int64_t K, bool vec_ok, int wm, int wn, int lane, int BKc)
+{
+    typedef typename CF::MF MF;
+    typedef typename CF::PA PA;
+    typedef typename CF::PB PB;
     constexpr int MI = MF::MI, VEC = MF::VEC;
-    constexpr int NB = WT / MI;                       // MFMA blocks per wave tile edge
-    __shared__ __attribute__((aligned(16))) T As[2][PA::LDS_SIZE];
-    __shared__ __attribute__((aligned(16))) T Bs[2][PB::LDS_SIZE];
+    typename PA::Vec ra[PA::NVEC];
+    typename PB::Vec rb[PB::NVEC];
+    const int64_t nkb = (K + BKc - 1) / BKc;
+    PA::template load<GUARD>(ra, A, ldA, m_left, K, vec_ok);
+    PB::template load<GUARD>(rb, B, ldB, n_left, K, vec_ok);
+    PA::store(As[0], ra);
+    PB::store(Bs[0], rb);
+    __syncthreads();
+    for (int64_t kb = 0; kb < nkb; ++kb) {
+        const int cur = (int)(kb & 1);
+        const bool more = kb + 1 < nkb;
+        if (more) {                                   // next panel's global loads fly during the MFMAs
+            const int64_t k0 = (kb + 1) * BKc;
+            PA::template load<GUARD>(ra, A + k0 * kstepA, ldA, m_left, K - k0, vec_ok);
+            PB::template load<GUARD>(rb, B + k0 * kstepB, ldB, n_left, K - k0, vec_ok);
+        }
+#pragma unroll
+        for (int kg = 0; kg < BKc / 8; ++kg) {
+            T fa[CF::NBM][VEC], fb[CF::NBN][VEC];
+#pragma unroll
+            for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[a], As[cur], wm + a * MI, kg, lane);
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[c], Bs[cur], wn + c * MI, kg, lane);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+                    for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[c][e], fa[a][e]);   // C^T = B^T A^T
+        }
+        if (more) {
+            PA::store(As[cur ^ 1], ra);
+            PB::store(Bs[cur ^ 1], rb);
+        }
+        __syncthreads();
+    }
+}
+
+template <typename T, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
+{
+    typedef Config<T, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N> CF;
+    typedef typename CF::MF MF;
+    constexpr int MI = MF::MI, BM = CF::BM, BN = CF::BN;
+    __shared__ __attribute__((aligned(16))) T As[2][CF::PA::LDS_SIZE];
+    __shared__ __attribute__((aligned(16))) T Bs[2][CF::PB::LDS_SIZE];
 
     // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn; renumber so
     // that each XCD works on a contiguous range of tiles (the tiles of one batch share B_p in its L2)
@@ -160,63 +223,31 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_kernel(SbArgs g, int til
     const int64_t m_left = g.m - i0, n_left = g.n - j0;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave & 1) * WT, wn = (wave >> 1) * WT;
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
 
-    typename MF::Acc acc[NB][NB];
+    typename MF::Acc acc[CF::NBM][CF::NBN];
 #pragma unroll
-    for (int a = 0; a < NB; ++a)
+    for (int a = 0; a < CF::NBM; ++a)
 #pragma unroll
-        for (int c = 0; c < NB; ++c)
+        for (int c = 0; c < CF::NBN; ++c)
 #pragma unroll
             for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
 
-    typename PA::Vec ra[PA::NVEC];
-    typename PB::Vec rb[PB::NVEC];
-    const int64_t nkb = (g.k + BK - 1) / BK;
-    if (nkb > 0) {
-        PA::load(ra, A, ldA, m_left, g.k, vec_ok);
-        PB::load(rb, B, ldB, n_left, g.k, vec_ok);
-        PA::store(As[0], ra);
-        PB::store(Bs[0], rb);
-    }
-    __syncthreads();
-    for (int64_t kb = 0; kb < nkb; ++kb) {
-        const int cur = (int)(kb & 1);
-        const bool more = kb + 1 < nkb;
-        if (more) {                                   // next panel's global loads fly during the MFMAs
-            const int64_t k0 = (kb + 1) * BK;
-            PA::load(ra, A + k0 * kstepA, ldA, m_left, g.k - k0, vec_ok);
-            PB::load(rb, B + k0 * kstepB, ldB, n_left, g.k - k0, vec_ok);
-        }
-#pragma unroll
-        for (int kg = 0; kg < BK / 8; ++kg) {
-            T fa[NB][VEC], fb[NB][VEC];
-#pragma unroll
-            for (int a = 0; a < NB; ++a) PA::fragment(fa[a], As[cur], wm + a * MI, kg, lane);
-#pragma unroll
-            for (int c = 0; c < NB; ++c) PB::fragment(fb[c], Bs[cur], wn + c * MI, kg, lane);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e)
-#pragma unroll
-                for (int a = 0; a < NB; ++a)
-#pragma unroll
-                    for (int c = 0; c < NB; ++c) MF::mma(acc[a][c], fb[c][e], fa[a][e]);   // C^T = B^T A^T
-        }
-        if (more) {
-            PA::store(As[cur ^ 1], ra);
-            PB::store(Bs[cur ^ 1], rb);
-        }
-        __syncthreads();
-    }
+    // workgroup-uniform: interior tile with aligned operands -> branch-free loop
+    const bool interior = vec_ok && m_left >= BM && n_left >= BN && (g.k % BK == 0);
+    if (interior)
+        k_loop<CF, T, false>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
+    else
+        k_loop<CF, T, true>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
 
     // epilogue: lane = row of C within the block, result slot = column
     const T alpha = (T)g.alpha, beta = (T)g.beta;
 #pragma unroll
-    for (int a = 0; a < NB; ++a) {
+    for (int a = 0; a < CF::NBM; ++a) {
         const int64_t i = i0 + wm + a * MI + (lane % MI);
         if (i >= g.m) continue;
 #pragma unroll
-        for (int c = 0; c < NB; ++c) {
+        for (int c = 0; c < CF::NBN; ++c) {
 #pragma unroll
             for (int r = 0; r < MF::NREG; ++r) {
                 const int64_t j = j0 + wn + c * MI + MF::result_row(r, lane);
@@ -230,9 +261,10 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_kernel(SbArgs g, int til
     }
 }
 
-template <typename T, int BK>
+template <typename T, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
+    constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N, NT = 64 * WAVES_M * WAVES_N;
     const int64_t tiles_m = (a.m + BM - 1) / BM, tiles_n = (a.n + BN - 1) / BN;
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
@@ -243,12 +275,12 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int vec_ok = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                        aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
                        aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
-    dim3 grid((unsigned)total), block(NTHREADS);
+    dim3 grid((unsigned)total), block(NT);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-    if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, true, BK>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else if (a_kc && !b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, false, BK>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else if (!a_kc && b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, true, BK>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else                     hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, false, BK>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else if (a_kc && !b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else if (!a_kc && b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
+    else                     hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
     return hipGetLastError();
 }
 
@@ -262,7 +294,7 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
     const bool b_ok = (a.rsB == 1) || (a.csB == 1);
     if (!a_ok || !b_ok) return false;
     // a k-contiguous operand with a single row or a single k is also "row contiguous": either view works
-    const int64_t tiles = ((a.m + BM - 1) / BM) * ((a.n + BN - 1) / BN);
+    const int64_t tiles = ((a.m + 63) / 64) * ((a.n + 63) / 64);       // smallest tile used below
     return tiles * a.batch0 * a.batch1 < ((int64_t)1 << 31);
 }
 
@@ -274,8 +306,12 @@ bool sb_mfma_preferred(sb_dtype, const SbArgs &a)
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
     switch (dt) {
-    case SB_F32: return launch<float, 16>(a, stream);
-    case SB_F64: return launch<double, 16>(a, stream);
+    case SB_F32:
+        if (a.m <= 64 || a.n <= 64) return launch<float, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        return launch<float, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
+    case SB_F64:
+        if (a.m <= 64 || a.n <= 64) return launch<double, 16, 32, 32, 2, 2>(a, stream);
+        return launch<double, 16, 64, 32, 2, 4>(a, stream);                                 // 128 x 128 tiles, 8 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;
     }
