@@ -20,37 +20,57 @@
 // read feeds several consecutive MFMAs; the sum over k does not depend on that order.
 #include "sb_device.h"
 #include "sb_internal.h"
+#include <type_traits>
 
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-template <typename T> struct Mfma;
+// Instruction traits.  MI: block edge; the 64/MI lane groups each hold VEC consecutive k, so one
+// fragment read covers KGROUP = (64/MI)*VEC values of k and feeds VEC consecutive MFMAs.
 
 // v_mfma_f32_32x32x2_f32: operands hold X[l%32][k = l/32]; result slot r of lane l is
-// D[8*(r/4) + 4*(l/32) + r%4][l%32].
-template <> struct Mfma<float> {
-    static constexpr int MI = 32, VEC = 4, NREG = 16;       // 64/MI lane groups x VEC = 8 k per group
+// D[8*(r/4) + 4*(l/32) + r%4][l%32] (a lane part plus a register part).
+struct MfmaF32x32 {
+    typedef float T;
+    static constexpr int MI = 32, VEC = 4, NREG = 16, KGROUP = 8;
     typedef f32x16 Acc;
     typedef float Vec __attribute__((ext_vector_type(4)));
     static __device__ __forceinline__ void mma(Acc &c, float first, float second)
     {
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(first, second, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int result_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+    static __device__ __forceinline__ int result_row_lane(int lane) { return 4 * (lane >> 5); }
+    static constexpr int result_row_reg(int r) { return 8 * (r >> 2) + (r & 3); }
 };
 
 // v_mfma_f64_16x16x4_f64: operands hold X[l%16][k = l/16]; result slot r of lane l is D[l/16 + 4*r][l%16].
-template <> struct Mfma<double> {
-    static constexpr int MI = 16, VEC = 2, NREG = 4;
+struct MfmaF64x16 {
+    typedef double T;
+    static constexpr int MI = 16, VEC = 2, NREG = 4, KGROUP = 8;
     typedef f64x4 Acc;
     typedef double Vec __attribute__((ext_vector_type(2)));
     static __device__ __forceinline__ void mma(Acc &c, double first, double second)
     {
         c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ int result_row(int r, int lane) { return (lane >> 4) + 4 * r; }
+    static __device__ __forceinline__ int result_row_lane(int lane) { return lane >> 4; }
+    static constexpr int result_row_reg(int r) { return 4 * r; }
+};
+
+// v_mfma_f32_16x16x4_f32: operands hold X[l%16][k = l/16]; result slot r of lane l is D[4*(l/16) + r][l%16].
+struct MfmaF32x16 {
+    typedef float T;
+    static constexpr int MI = 16, VEC = 4, NREG = 4, KGROUP = 16;
+    typedef float Acc __attribute__((ext_vector_type(4)));
+    typedef float Vec __attribute__((ext_vector_type(4)));
+    static __device__ __forceinline__ void mma(Acc &c, float first, float second)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(first, second, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int result_row_lane(int lane) { return 4 * (lane >> 4); }
+    static constexpr int result_row_reg(int r) { return r; }
 };
 
 constexpr int NXCD = 8;
@@ -58,10 +78,11 @@ constexpr int NXCD = 8;
 // Stage one BK-deep panel (ROWS rows of the operand) from global memory into registers.
 // KC: the panel is stored [row][k] with k contiguous in memory (row stride `ld`);
 // otherwise rows are contiguous and k strides by `ld`.
-template <typename T, bool KC, int ROWS, int BK, int NT>
+template <typename MF, bool KC, int ROWS, int BK, int NT>
 struct Panel {
-    typedef typename Mfma<T>::Vec Vec;
-    static constexpr int VEC = Mfma<T>::VEC;
+    typedef typename MF::T T;
+    typedef typename MF::Vec Vec;
+    static constexpr int VEC = MF::VEC;
     static constexpr int NVEC = ROWS * BK / VEC / NT;                  // 16-byte vectors per lane
     static constexpr int LDS_LD = (KC ? BK : ROWS) + VEC;              // padded by 16 bytes
     static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
@@ -114,9 +135,9 @@ struct Panel {
     // Fragment of the MFMA block whose first row is row0, for k-group kg: VEC consecutive MFMA steps.
     static __device__ __forceinline__ void fragment(T (&frag)[VEC], const T *lds, int row0, int kg, int lane)
     {
-        constexpr int MI = Mfma<T>::MI;
+        constexpr int MI = MF::MI;
         const int row = row0 + (lane % MI);
-        const int k = kg * 8 + (lane / MI) * VEC;
+        const int k = kg * MF::KGROUP + (lane / MI) * VEC;
         if (KC) {
             Vec v = *(const Vec *)(lds + row * LDS_LD + k);
 #pragma unroll
@@ -129,19 +150,26 @@ struct Panel {
 };
 
 // Tile configuration: each wave owns WM x WN of C; WAVES_M x WAVES_N waves form the workgroup tile.
-template <typename T, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 struct Config {
-    static constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N;
+    static constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N, BKC = BK;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
-    typedef Mfma<T> MF;
-    typedef Panel<T, A_KC, BM, BK, NT> PA;
-    typedef Panel<T, B_KC, BN, BK, NT> PB;
+    typedef MFT MF;
+    static_assert((BK / MF::KGROUP) % 2 == 0, "the fragment double buffer needs an even number of k-groups per panel");
+    typedef Panel<MF, A_KC, BM, BK, NT> PA;
+    typedef Panel<MF, B_KC, BN, BK, NT> PB;
     static constexpr int NBM = WM / MF::MI, NBN = WN / MF::MI;         // MFMA blocks per wave tile
 };
 
-// The k loop of one tile.  GUARD selects bounds-checked scalar loads (edge tiles, unaligned
-// operands) or plain 16-byte vector loads (interior tiles): the latter is branch-free, so the
-// compiler can keep the next panel's global loads in flight under the current panel's MFMAs.
+// The k loop of one tile, software-pipelined at two levels:
+//   - global -> registers: the panel for block kb+2 is requested while block kb is being multiplied
+//     (two staging register sets), so a full iteration of MFMAs covers the memory latency;
+//   - LDS -> registers: the fragments of the next k-group are read while the current group's
+//     MFMAs run (two fragment register sets).  The hand-over to the next block (LDS store of the
+//     staged panel, barrier, first fragment read of the new block) is placed BEFORE the last
+//     k-group's MFMAs of the current block, which then hide its latency.
+// GUARD selects bounds-checked scalar loads (edge tiles, unaligned operands) or plain 16-byte
+// vector loads (interior tiles, branch-free).
 template <typename CF, typename T, bool GUARD>
 __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::NBN], T (*As)[CF::PA::LDS_SIZE], T (*Bs)[CF::PB::LDS_SIZE],
                                         const T *A, const T *B, int64_t ldA, int64_t ldB, int64_t kstepA, int64_t kstepB,
@@ -150,138 +178,216 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     typedef typename CF::MF MF;
     typedef typename CF::PA PA;
     typedef typename CF::PB PB;
-    constexpr int MI = MF::MI, VEC = MF::VEC;
-    typename PA::Vec ra[PA::NVEC];
-    typename PB::Vec rb[PB::NVEC];
-    const int64_t nkb = (K + BKc - 1) / BKc;
-    PA::template load<GUARD>(ra, A, ldA, m_left, K, vec_ok);
-    PB::template load<GUARD>(rb, B, ldB, n_left, K, vec_ok);
-    PA::store(As[0], ra);
-    PB::store(Bs[0], rb);
-    __syncthreads();
-    for (int64_t kb = 0; kb < nkb; ++kb) {
-        const int cur = (int)(kb & 1);
-        const bool more = kb + 1 < nkb;
-        if (more) {                                   // next panel's global loads fly during the MFMAs
-            const int64_t k0 = (kb + 1) * BKc;
-            PA::template load<GUARD>(ra, A + k0 * kstepA, ldA, m_left, K - k0, vec_ok);
-            PB::template load<GUARD>(rb, B + k0 * kstepB, ldB, n_left, K - k0, vec_ok);
-        }
+    constexpr int MI = MF::MI, VEC = MF::VEC, BK = CF::BKC, KG = BK / MF::KGROUP;
+    (void)BKc;
+    typename PA::Vec ra[2][PA::NVEC];
+    typename PB::Vec rb[2][PB::NVEC];
+    T fa[2][CF::NBM][VEC], fb[2][CF::NBN][VEC];
+    const int64_t nkb = (K + BK - 1) / BK;
+
+    auto read_frags = [&](auto set, auto buf, int kg) {
 #pragma unroll
-        for (int kg = 0; kg < BKc / 8; ++kg) {
-            T fa[CF::NBM][VEC], fb[CF::NBN][VEC];
+        for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[set][a], As[buf], wm + a * MI, kg, lane);
 #pragma unroll
-            for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[a], As[cur], wm + a * MI, kg, lane);
+        for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[set][c], Bs[buf], wn + c * MI, kg, lane);
+    };
+    auto gload = [&](auto set, int64_t kb) {
+        const int64_t k0 = kb * BK;
+        PA::template load<GUARD>(ra[set], A + k0 * kstepA, ldA, m_left, K - k0, vec_ok);
+        PB::template load<GUARD>(rb[set], B + k0 * kstepB, ldB, n_left, K - k0, vec_ok);
+    };
+    // one k block; CUR (= kb & 1) is a compile-time constant so that every register array is
+    // indexed statically.  STEADY = true is the steady state (block kb+2 exists): the prefetch
+    // and the hand-over are unconditional, which lets the compiler count outstanding loads exactly
+    // and wait only for the older staging set.
+    auto block = [&](auto cur_c, auto steady_c, int64_t kb) {
+        constexpr int CUR = decltype(cur_c)::value;
+        constexpr bool STEADY = decltype(steady_c)::value;
+        if (STEADY || kb + 2 < nkb) gload(std::integral_constant<int, CUR>(), kb + 2);   // this staging set was consumed one block ago
 #pragma unroll
-            for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[c], Bs[cur], wn + c * MI, kg, lane);
+        for (int kg = 0; kg < KG; ++kg) {
+            const int fs = kg & 1;
+            if (kg + 1 < KG) {
+                if (fs == 0) read_frags(std::integral_constant<int, 1>(), std::integral_constant<int, CUR>(), kg + 1);
+                else         read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR>(), kg + 1);
+            } else if (STEADY || kb + 1 < nkb) {
+                PA::store(As[CUR ^ 1], ra[CUR ^ 1]);
+                PB::store(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                __syncthreads();
+                read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR ^ 1>(), 0);
+            }
+            // Raised priority inside the MFMA cluster: the wave that enters first keeps the matrix
+            // core until its cluster ends instead of sharing it turn by turn, so the co-resident
+            // waves drift out of phase and one wave's memory phase hides under another's MFMAs.
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
 #pragma unroll
                 for (int a = 0; a < CF::NBM; ++a)
 #pragma unroll
-                    for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[c][e], fa[a][e]);   // C^T = B^T A^T
+                    for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[fs][c][e], fa[fs][a][e]);   // C^T = B^T A^T
+            __builtin_amdgcn_s_setprio(0);
         }
-        if (more) {
-            PA::store(As[cur ^ 1], ra);
-            PB::store(Bs[cur ^ 1], rb);
-        }
-        __syncthreads();
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+
+    gload(I0(), 0);
+    if (nkb > 1) gload(I1(), 1);
+    PA::store(As[0], ra[0]);
+    PB::store(Bs[0], rb[0]);
+    __syncthreads();
+    read_frags(I0(), I0(), 0);
+    int64_t kb = 0;
+    for (; kb + 3 < nkb; kb += 2) {                    // steady state, two blocks per trip
+        block(I0(), std::true_type(), kb);
+        block(I1(), std::true_type(), kb + 1);
+    }
+    for (; kb < nkb; kb += 2) {                        // last one to three blocks
+        block(I0(), std::false_type(), kb);
+        if (kb + 1 < nkb) block(I1(), std::false_type(), kb + 1);
     }
 }
 
-template <typename T, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
 {
-    typedef Config<T, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N> CF;
+    typedef Config<MFT, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N> CF;
     typedef typename CF::MF MF;
+    typedef typename MF::T T;
     constexpr int MI = MF::MI, BM = CF::BM, BN = CF::BN;
     __shared__ __attribute__((aligned(16))) T As[2][CF::PA::LDS_SIZE];
     __shared__ __attribute__((aligned(16))) T Bs[2][CF::PB::LDS_SIZE];
 
-    // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn; renumber so
-    // that each XCD works on a contiguous range of tiles (the tiles of one batch share B_p in its L2)
-    const int64_t total = (int64_t)gridDim.x;
-    const int64_t bid = blockIdx.x;
-    const int64_t q8 = total / NXCD, r8 = total % NXCD;
-    const int64_t xcd = bid % NXCD, slot = bid / NXCD;
-    const int64_t logical = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
-    const int64_t tiles = (int64_t)tiles_m * tiles_n;
-    const int64_t b = logical / tiles;
-    const int tile = (int)(logical - b * tiles);
-    const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
-    const int tm = tile % tiles_m, tn = tile / tiles_m;
-    const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
-
-    // op(A)(i,l) = A[i*rsA + l*csA]: with k contiguous the row stride is rsA, else the k stride is csA
-    const T *A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
-    const T *B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
-    T *C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
     const int64_t ldA = A_KC ? g.rsA : g.csA;
     const int64_t ldB = B_KC ? g.csB : g.rsB;
     const int64_t kstepA = A_KC ? 1 : g.csA;
     const int64_t kstepB = B_KC ? 1 : g.rsB;
-    const int64_t m_left = g.m - i0, n_left = g.n - j0;
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
-
-    typename MF::Acc acc[CF::NBM][CF::NBN];
-#pragma unroll
-    for (int a = 0; a < CF::NBM; ++a)
-#pragma unroll
-        for (int c = 0; c < CF::NBN; ++c)
-#pragma unroll
-            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
-
-    // workgroup-uniform: interior tile with aligned operands -> branch-free loop
-    const bool interior = vec_ok && m_left >= BM && n_left >= BN && (g.k % BK == 0);
-    if (interior)
-        k_loop<CF, T, false>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
-    else
-        k_loop<CF, T, true>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
-
-    // epilogue: lane = row of C within the block, result slot = column
     const T alpha = (T)g.alpha, beta = (T)g.beta;
+
+    // Persistent workgroups: the grid holds as many workgroups as the chip can keep resident and
+    // each walks over several tiles.  The stores of one tile are only queued, not waited for, so
+    // they drain while the next tile's panels are fetched and multiplied; with one tile per
+    // workgroup all workgroups would reach their store phase together and the matrix cores
+    // would idle during every such burst.
+    // XCD-aware order: hardware hands consecutive workgroup ids to the 8 XCDs in turn, so workgroup
+    // w sits on XCD w % 8; each XCD gets one contiguous range of tiles (the tiles of one batch
+    // share B_p in its L2) and its workgroups take them round-robin.
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t total = tiles * g.batch0 * g.batch1;
+    const int64_t nslots = (int64_t)gridDim.x / NXCD;              // the launcher makes gridDim.x a multiple of 8
+    const int64_t xcd = blockIdx.x % NXCD, slot = blockIdx.x / NXCD;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t first = xcd * q8 + (xcd < r8 ? xcd : r8);
+    const int64_t last = first + q8 + (xcd < r8 ? 1 : 0);
+
+    for (int64_t logical = first + slot; logical < last; logical += nslots) {
+        const int64_t b = logical / tiles;
+        const int tile = (int)(logical - b * tiles);
+        const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
+        const int tm = tile % tiles_m, tn = tile / tiles_m;
+        const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
+
+        // op(A)(i,l) = A[i*rsA + l*csA]: with k contiguous the row stride is rsA, else the k stride is csA
+        const T *A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
+        const T *B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
+        T *C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+        const int64_t m_left = g.m - i0, n_left = g.n - j0;
+
+        typename MF::Acc acc[CF::NBM][CF::NBN];
 #pragma unroll
-    for (int a = 0; a < CF::NBM; ++a) {
-        const int64_t i = i0 + wm + a * MI + (lane % MI);
-        if (i >= g.m) continue;
+        for (int a = 0; a < CF::NBM; ++a)
 #pragma unroll
-        for (int c = 0; c < CF::NBN; ++c) {
+            for (int c = 0; c < CF::NBN; ++c)
 #pragma unroll
-            for (int r = 0; r < MF::NREG; ++r) {
-                const int64_t j = j0 + wn + c * MI + MF::result_row(r, lane);
-                if (j >= g.n) continue;
-                T *dst = C + i + j * g.ldc;
-                T v = alpha * acc[a][c][r];
-                if (beta != T(0)) v += beta * *dst;
-                *dst = v;
+                for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
+
+        // workgroup-uniform: interior tile with aligned operands -> branch-free loop
+        const bool interior = vec_ok && m_left >= BM && n_left >= BN && (g.k % BK == 0);
+        if (interior)
+            k_loop<CF, T, false>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
+        else
+            k_loop<CF, T, true>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
+
+        // epilogue: lane = row of C within the block, result slot = column.  The four variants
+        // (edge tile or not, beta or not) are chosen by workgroup-uniform branches so that the
+        // common one is a straight run of stores.
+        auto store_tile = [&](auto guard_c, auto beta_c) {
+            constexpr bool GUARD = decltype(guard_c)::value, BETA = decltype(beta_c)::value;
+#pragma unroll
+            for (int a = 0; a < CF::NBM; ++a) {
+                const int64_t i = i0 + wm + a * MI + (lane % MI);
+                if (GUARD && i >= g.m) continue;
+#pragma unroll
+                for (int c = 0; c < CF::NBN; ++c) {
+                    const int64_t jl = j0 + wn + c * MI + MF::result_row_lane(lane);
+                    T *col = C + i + jl * g.ldc;
+#pragma unroll
+                    for (int r = 0; r < MF::NREG; ++r) {
+                        if (GUARD && jl + MF::result_row_reg(r) >= g.n) continue;
+                        T *dst = col + MF::result_row_reg(r) * g.ldc;
+                        T v = alpha * acc[a][c][r];
+                        if (BETA) v += beta * *dst;
+                        *dst = v;
+                    }
+                }
             }
+        };
+        const bool edge = m_left < BM || n_left < BN;
+        if (!edge) {
+            if (beta == T(0)) store_tile(std::false_type(), std::false_type());
+            else              store_tile(std::false_type(), std::true_type());
+        } else {
+            if (beta == T(0)) store_tile(std::true_type(), std::false_type());
+            else              store_tile(std::true_type(), std::true_type());
         }
+        __syncthreads();      // every wave is done with the LDS panels before the next tile refills them
     }
 }
 
-template <typename T, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+// Launch `kernel` with as many workgroups as can be resident at once (a multiple of the XCD
+// count), or fewer if there are fewer tiles.  The residency of a kernel is asked once per process.
+template <typename K>
+hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, int vec_ok)
+{
+    static int resident = 0;                   // one instance per kernel instantiation
+    if (resident == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, nthreads, 0);
+        if (e != hipSuccess) return e;
+        if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
+        resident = per_cu * cus;
+    }
+    int64_t grid = total_tiles < resident ? total_tiles : resident;
+    grid = (grid + NXCD - 1) / NXCD * NXCD;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, vec_ok);
+    return hipGetLastError();
+}
+
+template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
+    typedef MFT T;
     constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N, NT = 64 * WAVES_M * WAVES_N;
     const int64_t tiles_m = (a.m + BM - 1) / BM, tiles_n = (a.n + BN - 1) / BN;
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    constexpr int VEC = Mfma<T>::VEC;
+    constexpr int VEC = MFT::VEC;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
     auto aligned = [](int64_t v) { return v % VEC == 0; };
     const int vec_ok = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
                        aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
                        aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
-    dim3 grid((unsigned)total), block(NT);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-    if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else if (a_kc && !b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else if (!a_kc && b_kc)  hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    else                     hipLaunchKernelGGL((sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N>), grid, block, 0, stream, a, tm, tn, vec_ok);
-    return hipGetLastError();
+    if (a_kc && b_kc)        return launch_persistent(sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
+    else if (a_kc && !b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
+    else if (!a_kc && b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
+    return launch_persistent(sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
 }
 
 }  // namespace
@@ -307,11 +413,11 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
     switch (dt) {
     case SB_F32:
-        if (a.m <= 64 || a.n <= 64) return launch<float, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
-        return launch<float, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
+        if (a.m <= 64 || a.n <= 64) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
-        if (a.m <= 64 || a.n <= 64) return launch<double, 16, 32, 32, 2, 2>(a, stream);
-        return launch<double, 16, 64, 32, 2, 4>(a, stream);                                 // 128 x 128 tiles, 8 waves
+        if (a.m <= 64 || a.n <= 64) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
+        return launch<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);                                 // 128 x 128 tiles, 16 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;
     }
