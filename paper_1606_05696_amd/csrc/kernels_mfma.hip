@@ -59,20 +59,6 @@ struct MfmaF64x16 {
     static constexpr int result_row_reg(int r) { return 4 * r; }
 };
 
-// v_mfma_f32_16x16x4_f32: operands hold X[l%16][k = l/16]; result slot r of lane l is D[4*(l/16) + r][l%16].
-struct MfmaF32x16 {
-    typedef float T;
-    static constexpr int MI = 16, VEC = 4, NREG = 4, KGROUP = 16;
-    typedef float Acc __attribute__((ext_vector_type(4)));
-    typedef float Vec __attribute__((ext_vector_type(4)));
-    static __device__ __forceinline__ void mma(Acc &c, float first, float second)
-    {
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(first, second, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int result_row_lane(int lane) { return 4 * (lane >> 4); }
-    static constexpr int result_row_reg(int r) { return r; }
-};
-
 constexpr int NXCD = 8;
 
 // Stage one BK-deep panel (ROWS rows of the operand) from global memory into registers.

@@ -208,6 +208,8 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
 
 hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
 {
+    // many small GEMMs with short k: whole-K panels, batches pipelined inside persistent workgroups
+    if (sb_panel_bf16_supports(a)) return sb_launch_panel_bf16(a, stream);
     // small matrices per batch: 64x64 tiles waste less and give more workgroups
     if (a.m <= 64 || a.n <= 64) return launch<32>(a, stream);
     return launch<64>(a, stream);

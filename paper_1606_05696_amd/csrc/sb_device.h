@@ -8,13 +8,11 @@ struct sb_bf16 { uint16_t bits; };
 
 __device__ __forceinline__ float sb_bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (quiet).
+// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN.  gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32), which is what the cast compiles to.
 __device__ __forceinline__ uint16_t sb_f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
 template <typename T, typename Acc> __device__ __forceinline__ Acc sb_load(const T *p) { return (Acc)*p; }

@@ -260,6 +260,39 @@ def test_cfg5_order3_x_order3_full_size():
             assert err <= TOL[dtype], (text, err)
 
 
+@pytest.mark.parametrize("ma,mb,mc", [("m[p]k", "kn[q]", "m[p]n[q]"), ("k[p]m", "nk[q]", "m[p]n[q]"), ("mk[p]", "nk[q]", "mn[p][q]"),
+                                      ("km[p]", "kn[q]", "mn[p][q]"), ("m[p]k", "kn[q]", "mn[p][q]")])
+def test_two_level_batches_with_one_operand_per_level(ma, mb, mc):
+    # C_..[p]..[q] = A_..[p] B_..[q]: every A_p meets every B_q (the nested example of section III-F);
+    # ragged group counts, all operand orientations, short and full k, m and n below and at 64
+    for ext in (dict(m=64, n=64, p=6, q=5, k=128), dict(m=40, n=24, p=9, q=4, k=72), dict(m=64, n=48, p=4, q=7, k=32)):
+        for dtype in ("bf16", "f32"):
+            err, text = contract_case(dtype, ma, mb, mc, ext, seed=91)
+            assert err <= TOL[dtype], (text, ext, err)
+            err, text = contract_case(dtype, ma, mb, mc, ext, alpha=0.5, beta=-1.0, seed=92)
+            assert err <= TOL[dtype], (text, ext, err)
+
+
+@pytest.mark.parametrize("kernel", ["auto", "generic", "mfma"])
+def test_bf16_output_rounding_is_nearest_even(kernel):
+    # k = 1 and B = 1: C = alpha * a, one fp32 multiply and one rounding; both sides round the same
+    # fp32 number, so the bf16 bit patterns must agree exactly
+    import torch
+    m, n, batch = 96, 64, 70
+    a = inputs.normal_bf16_tensor(7, [m * batch])
+    a[:8] = [1.0, 1.00390625, 1.01171875, -1.00390625, 0.0, 3.0e38, -3.0e38, 1e-40]     # ties, overflow, denormal
+    a = inputs.round_to_bf16(a)
+    alpha = np.float32(1.0) / np.float32(3.0)
+    tA, tB = to_dev(a, "bf16"), to_dev(np.ones(n), "bf16")
+    tC = to_dev(np.zeros(m * n * batch), "bf16")
+    sb.sb_force_kernel(KERNELS[kernel])
+    sb.sb_gemm("N", "N", m, n, 1, float(alpha), tA, m, m, tB, 1, 0, 0.0, tC, m, m * n, batch, dt="bf16")
+    sync()
+    want = inputs.bf16_bits(inputs.round_to_bf16((a.astype(np.float32) * alpha).astype(np.float32)))
+    got = tC.view(torch.int16).cpu().numpy().view(np.uint16).reshape(batch, n, m)
+    assert np.array_equal(got, np.broadcast_to(want.reshape(batch, 1, m), got.shape))
+
+
 def test_three_level_nest_loops_on_the_host():
     ext = dict(m=20, n=12, p=3, q=4, r=2, k=9)
     err, text = contract_case("f32", "mpk", "knqr", "mnpqr", ext, strat="nested", seed=77)
