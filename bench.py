@@ -31,8 +31,11 @@ ESIZE = {"f64": 8, "f32": 4, "bf16": 2}
 # which roofline binds each workload: dense high-intensity contractions are priced against the
 # matrix cores, the batch-dominated / output-dominated ones against HBM
 BOUND = {1: "hbm", 3: "hbm", 40: "mfma", 41: "mfma", 5: "hbm"}
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), null until measured
-MEASURED_TRAFFIC = {}
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same counters'
+# readings for a 1 GiB copy (profiles/bench_default_hbm_traffic.txt); measured offline, not in this run
+MIB = 1 << 20
+MEASURED_TRAFFIC = {41: int(1176.73 * MIB), 40: int(2563.44 * MIB), 3: int(128.14 * MIB), 5: int(41.17 * MIB),
+                    1: int(0.65 * MIB)}
 
 
 def parse_args():
@@ -160,6 +163,52 @@ def conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops):
     return dict(ms_per_step=ms, gflops=flops / ms / 1e6, how="torch.einsum('%s') + contiguous()" % expr)
 
 
+def run_table2_cases(steps, warmup):
+    """cfg2: every order-2 x order-3 single-mode contraction (Table II) at extent 64, fp32, in the
+    evaluation SB_AUTO picks, against the conventional route (explicit permute/copy + vendor GEMM).
+    These calls are launch-bound: the figure of merit is time per call, back to back."""
+    import itertools
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    n = 64
+    rows = []
+    tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+    for free_a in "mnp":
+        rest = [c for c in "mnp" if c != free_a]
+        for ma in (free_a + "k", "k" + free_a):
+            for perm in itertools.permutations(["k"] + rest):
+                mb = "".join(perm)
+                tA = dev(inputs.uniform_tensor(21, [n, n], np.float32), "f32")
+                tB = dev(inputs.uniform_tensor(22, [n, n, n], np.float32), "f32")
+                rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
+
+                def ours():
+                    sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+
+                a, b = tA.view(n, n), tB.view(n, n, n)
+                expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
+
+                def conventional():
+                    return torch.einsum(expr, a, b).contiguous()
+
+                _, t_ours = time_steps(ours, steps, warmup)
+                _, t_conv = time_steps(conventional, steps, warmup)
+                rows.append(dict(A=ma, B=mb, evaluation=plan.text(), exceptional=int(plan.exceptional),
+                                 us_per_call=t_ours * 1e3, conventional_us_per_call=t_conv * 1e3))
+    flops = 2 * n ** 4
+    ours = np.array([r["us_per_call"] for r in rows])
+    conv = np.array([r["conventional_us_per_call"] for r in rows])
+    return dict(workload="cfg2: all 36 order-2 x order-3 contractions at 64^4, f32, SB_AUTO evaluation",
+                calls_timed_per_case=steps, mean_us_per_call=float(ours.mean()), max_us_per_call=float(ours.max()),
+                mean_gflops=float(flops / ours.mean() / 1e3),
+                conventional_mean_us_per_call=float(conv.mean()),
+                speedup_over_conventional_mean=float((conv / ours).mean()),
+                speedup_over_conventional_min=float((conv / ours).min()),
+                speedup_over_conventional_max=float((conv / ours).max()),
+                cases=rows)
+
+
 def cpu_baseline(cfg, tensors, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
     last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
@@ -235,6 +284,7 @@ def main():
             steps = args.steps if cfg in (40, 41) else max(args.steps, 200)
             r, _ = run_workload(cfg, steps, args.warmup, not args.no_torch_baseline)
             others.append(r)
+        others.append(run_table2_cases(max(args.steps, 200), args.warmup))
         result["workloads"] = others
     print(json.dumps(result))
 

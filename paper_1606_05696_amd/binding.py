@@ -94,14 +94,14 @@ def _ptr(x):
     """Device pointer of a torch tensor, or an integer address passed through."""
     if x is None:
         return None
-    if isinstance(x, int):
-        return ctypes.c_void_p(x)
-    return ctypes.c_void_p(x.data_ptr())
+    if x.__class__ is int:
+        return x
+    return x.data_ptr()
 
 
 def _dtype_of(dt, *tensors):
     if dt is not None:
-        return DTYPES[dt] if isinstance(dt, str) else int(dt)
+        return DTYPES[dt] if dt.__class__ is str else dt
     import torch
     table = {torch.float64: SB_F64, torch.float32: SB_F32, torch.bfloat16: SB_BF16}
     kinds = {table[t.dtype] for t in tensors if hasattr(t, "dtype")}
@@ -113,25 +113,45 @@ def _dtype_of(dt, *tensors):
 def _stream(stream):
     if stream is None:
         import torch
-        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
-    if isinstance(stream, int):
-        return ctypes.c_void_p(stream)
-    return ctypes.c_void_p(stream.cuda_stream)
+        return torch.cuda.current_stream().cuda_stream
+    if stream.__class__ is int:
+        return stream
+    return stream.cuda_stream
+
+
+_ARRAYS = {}
+_BYTES = {}
 
 
 def _i64arr(seq):
+    """ctypes int64 array for a sequence of extents/strides (cached: calls repeat the same shapes)."""
     if seq is None:
         return None
-    seq = [int(v) for v in seq]
-    return (ctypes.c_int64 * max(len(seq), 1))(*seq)
+    key = tuple(seq)
+    arr = _ARRAYS.get(key)
+    if arr is None:
+        vals = [int(v) for v in key]
+        arr = (ctypes.c_int64 * max(len(vals), 1))(*vals)
+        if len(_ARRAYS) < 4096:
+            _ARRAYS[key] = arr
+    return arr
+
+
+def _b(text):
+    out = _BYTES.get(text)
+    if out is None:
+        out = text.encode()
+        if len(_BYTES) < 4096:
+            _BYTES[text] = out
+    return out
 
 
 def _op(op):
-    return OPS[op] if isinstance(op, str) else int(op)
+    return OPS[op] if op.__class__ is str else op
 
 
 def _strat(s):
-    return STRATEGIES[s] if isinstance(s, str) else int(s)
+    return STRATEGIES[s] if s.__class__ is str else s
 
 
 def sb_status_string(status):
@@ -164,7 +184,7 @@ def sb_contract_plan(modesA, modesB, modesC, dimsA, dimsB, dimsC=None, stridesA=
                      stridesC=None, strat=SB_AUTO, check=True):
     """Plan a contraction on the host (see sbgemm.h: sb_contract_plan).  Returns (status, sb_plan)."""
     plan = sb_plan()
-    rc = load().sb_contract_plan(modesA.encode(), modesB.encode(), modesC.encode(),
+    rc = load().sb_contract_plan(_b(modesA), _b(modesB), _b(modesC),
                                  _i64arr(dimsA), _i64arr(stridesA), _i64arr(dimsB), _i64arr(stridesB),
                                  _i64arr(dimsC), _i64arr(stridesC), _strat(strat), ctypes.byref(plan))
     if check and rc != SB_OK:
@@ -175,7 +195,7 @@ def sb_contract_plan(modesA, modesB, modesC, dimsA, dimsB, dimsC=None, stridesA=
 def sb_contract(modesA, modesB, modesC, alpha, A, dimsA, B, dimsB, beta, C, dimsC=None,
                 stridesA=None, stridesB=None, stridesC=None, strat=SB_AUTO, dt=None, stream=None, check=True):
     """C_modesC = alpha*A_modesA*B_modesB + beta*C_modesC on device tensors (see sbgemm.h: sb_contract)."""
-    rc = load().sb_contract(_dtype_of(dt, A, B, C), modesA.encode(), modesB.encode(), modesC.encode(),
+    rc = load().sb_contract(_dtype_of(dt, A, B, C), _b(modesA), _b(modesB), _b(modesC),
                             float(alpha), _ptr(A), _i64arr(dimsA), _i64arr(stridesA),
                             _ptr(B), _i64arr(dimsB), _i64arr(stridesB),
                             float(beta), _ptr(C), _i64arr(dimsC), _i64arr(stridesC), _strat(strat), _stream(stream))
