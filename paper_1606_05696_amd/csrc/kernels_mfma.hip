@@ -381,6 +381,7 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
 // N and T operands only: one of the two strides of each operand must be 1.
 bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 {
+    if (sb_mfma_exa_supports(dt, a)) return true;           // extended operation on the first operand
     if (a.k <= 0) return false;
     const bool a_ok = (a.csA == 1) || (a.rsA == 1);
     const bool b_ok = (a.rsB == 1) || (a.csB == 1);
@@ -390,13 +391,15 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
     return tiles * a.batch0 * a.batch1 < ((int64_t)1 << 31);
 }
 
-bool sb_mfma_preferred(sb_dtype, const SbArgs &a)
+bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a)
 {
+    if (sb_mfma_exa_supports(dt, a)) return a.m >= 16 && a.n >= 16 && a.k >= 8;
     return a.m >= 32 && a.n >= 32 && a.k >= 16;
 }
 
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
+    if (sb_mfma_exa_supports(dt, a)) return sb_launch_mfma_exa(dt, a, stream);
     switch (dt) {
     case SB_F32:
         if (a.m <= 64 || a.n <= 64) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles

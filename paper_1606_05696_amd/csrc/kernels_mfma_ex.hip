@@ -1,0 +1,250 @@
+// MFMA kernel for the extended operation on the first operand (section III-E): the batched mode is
+// the FIRST, unit-stride mode of the tensor, so each batch's matrix is strided in rows and columns,
+//     op(A_b)(i,l) = A[b + i*rs + l*cs],        C_b(i,j) = C[b*strideC + i + j*ldc].
+// This is the kernel the paper asks for when it says an extended-transpose implementation should
+// "perform a 3D tiling of B into cache": reading one batch at a time would use one element per
+// cache line, so a workgroup takes a 3-D brick of the tensor instead, PB consecutive batches x
+// MB rows x BK columns, which is read along b (contiguous runs of PB elements) and, because the
+// brick holds MB consecutive rows of every batch, written along i (contiguous runs of MB
+// elements of every C_b).  The brick's PB*MB (batch,row) pairs are simply the rows of one MFMA
+// tile: all PB batches share the same B panel, so the PB small products are one tall GEMM.
+// The transposition between "b contiguous" and "i contiguous" happens for free in the LDS
+// addressing of the MFMA fragments (lanes run along i, the panel is stored with b fastest).
+#include "sb_device.h"
+#include "sb_internal.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int NXCD = 8;
+constexpr int ET = 256;                 // lanes per workgroup (4 waves)
+
+// Instruction traits (layouts as measured on gfx950): operands hold X[l%MI][k = l/MI]; result slot
+// r of lane l is D[row_lane(l) + row_reg(r)][l%MI].
+struct ExF32 {
+    typedef float T;
+    typedef f32x16 Acc;
+    typedef float Vec __attribute__((ext_vector_type(4)));
+    static constexpr int MI = 32, VEC = 4, NREG = 16;       // 64/MI lane groups along k, VEC k each: 8 k per fragment
+    static __device__ __forceinline__ void mma(Acc &c, float first, float second) { c = __builtin_amdgcn_mfma_f32_32x32x2f32(first, second, c, 0, 0, 0); }
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 5); }
+    static constexpr int row_reg(int r) { return 8 * (r >> 2) + (r & 3); }
+};
+struct ExF64 {
+    typedef double T;
+    typedef f64x4 Acc;
+    typedef double Vec __attribute__((ext_vector_type(2)));
+    static constexpr int MI = 16, VEC = 2, NREG = 4;
+    static __device__ __forceinline__ void mma(Acc &c, double first, double second) { c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0); }
+    static __device__ __forceinline__ int row_lane(int lane) { return lane >> 4; }
+    static constexpr int row_reg(int r) { return 4 * r; }
+};
+
+// PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK = 8 deep panels.
+template <typename MF, bool B_KC, int PB, int MB, int BN>
+__global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a)
+{
+    typedef typename MF::T T;
+    typedef typename MF::Vec Vec;
+    constexpr int MI = MF::MI, VEC = MF::VEC, BK = 8;
+    constexpr int BM = PB * MB;                       // tile rows = (batch, row) pairs
+    constexpr int PBP = PB + 16 / (int)sizeof(T);     // b-run padded by 16 bytes: lanes that differ in i hit different banks
+    constexpr int A_K = MB * PBP;                     // elements per k slab of the A panel: [k][i][b]
+    constexpr int B_LD = B_KC ? BK + VEC : BN + VEC;  // B panel: [col][k] (k contiguous) or [k][col]
+    constexpr int B_SIZE = B_KC ? BN * B_LD : BK * B_LD;
+    constexpr int NVA = BM * BK / VEC / ET;           // 16-byte vectors of A per lane and panel
+    constexpr int NBM = BM / 4 / MI, NBN = BN / MI;   // MFMA blocks per wave: 4 waves split the tile rows
+    static_assert(BM * BK % (VEC * ET) == 0 && BM % (4 * MI) == 0 && BN % MI == 0 && PB % VEC == 0, "tile shape");
+    static_assert(BN * BK / VEC <= ET, "one vector of B per lane at most");
+    __shared__ __attribute__((aligned(16))) T As[2][BK * A_K];
+    __shared__ __attribute__((aligned(16))) T Bs[2][B_SIZE];
+
+    // XCD-aware order: consecutive workgroup ids go to the 8 XCDs in turn; renumber so that an XCD
+    // owns a contiguous range of tiles.  Column tiles run fastest: the tiles that read the same
+    // brick of A are neighbours and share it in one L2.
+    const int64_t total = (int64_t)gridDim.x;
+    const int64_t bid = blockIdx.x;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t xcd = bid % NXCD, slot = bid / NXCD;
+    int64_t logical = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+    const int tn = (int)(logical % tiles_n); logical /= tiles_n;
+    const int tb = (int)(logical % tiles_b); logical /= tiles_b;
+    const int ti = (int)(logical % tiles_i);
+    const int64_t b1 = logical / tiles_i;
+    const int64_t bb = (int64_t)tb * PB, i0 = (int64_t)ti * MB, j0 = (int64_t)tn * BN;
+    const int64_t b_left = g.batch0 - bb, m_left = g.m - i0, n_left = g.n - j0;
+
+    const T *A = (const T *)g.A + bb + b1 * g.bsA[1] + i0 * g.rsA;        // batch stride of level 0 is 1
+    const T *B = (const T *)g.B + b1 * g.bsB[1] + j0 * g.csB;             // B ignores level 0 here (checked by the launcher)
+    const int64_t ldB = B_KC ? g.csB : g.rsB, kstepB = B_KC ? 1 : g.rsB;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    typename MF::Acc acc[NBM][NBN];
+#pragma unroll
+    for (int a = 0; a < NBM; ++a)
+#pragma unroll
+        for (int c = 0; c < NBN; ++c)
+#pragma unroll
+            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
+
+    // A panel vector f: k = f / (MB * PB/VEC), i = (f / (PB/VEC)) % MB, b = (f % (PB/VEC)) * VEC
+    auto load_a = [&](Vec (&v)[NVA], int64_t k0) {
+#pragma unroll
+        for (int q = 0; q < NVA; ++q) {
+            const int f = (int)threadIdx.x + ET * q;
+            const int k = f / (MB * (PB / VEC)), i = (f / (PB / VEC)) % MB, b = (f % (PB / VEC)) * VEC;
+            const T *src = A + b + (int64_t)i * g.rsA + (k0 + k) * g.csA;
+            const bool row_ok = i < m_left && k0 + k < g.k;
+            if (vec_a && row_ok && b + VEC <= b_left) {
+                v[q] = *(const Vec *)src;
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[q][e] = (row_ok && b + e < b_left) ? src[e] : T(0);
+            }
+        }
+    };
+    auto store_a = [&](T *lds, const Vec (&v)[NVA]) {
+#pragma unroll
+        for (int q = 0; q < NVA; ++q) {
+            const int f = (int)threadIdx.x + ET * q;
+            const int k = f / (MB * (PB / VEC)), i = (f / (PB / VEC)) % MB, b = (f % (PB / VEC)) * VEC;
+            *(Vec *)(lds + k * A_K + i * PBP + b) = v[q];
+        }
+    };
+    // B panel: one (guarded) vector per lane for the first BN*BK/VEC lanes
+    auto load_b = [&](Vec &v, int64_t k0) {
+        const int f = threadIdx.x;
+        if (f >= BN * BK / VEC) return;
+        int col, k;
+        if (B_KC) { col = f / (BK / VEC); k = (f % (BK / VEC)) * VEC; }
+        else      { k = f / (BN / VEC); col = (f % (BN / VEC)) * VEC; }
+        const T *src = B_KC ? B + (int64_t)col * ldB + (k0 + k) : B + (k0 + k) * kstepB + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const bool ok = B_KC ? (col < n_left && k0 + k + e < g.k) : (col + e < n_left && k0 + k < g.k);
+            v[e] = ok ? src[e] : T(0);
+        }
+    };
+    auto store_b = [&](T *lds, const Vec &v) {
+        const int f = threadIdx.x;
+        if (f >= BN * BK / VEC) return;
+        int col, k;
+        if (B_KC) { col = f / (BK / VEC); k = (f % (BK / VEC)) * VEC; }
+        else      { k = f / (BN / VEC); col = (f % (BN / VEC)) * VEC; }
+        *(Vec *)(B_KC ? lds + col * B_LD + k : lds + k * B_LD + col) = v;
+    };
+
+    // tile row rho (0 .. BM-1) = (batch rho / MB, row rho % MB): lanes of an MFMA block run along i
+    const int rho0 = wave * (BM / 4);
+    const int kl = lane / MI;                          // lane group along k
+
+    Vec ra[NVA], rb;
+    const int64_t nkb = (g.k + BK - 1) / BK;
+    load_a(ra, 0);
+    load_b(rb, 0);
+    store_a(As[0], ra);
+    store_b(Bs[0], rb);
+    __syncthreads();
+    for (int64_t kb = 0; kb < nkb; ++kb) {
+        const int cur = (int)(kb & 1);
+        const bool more = kb + 1 < nkb;
+        if (more) {
+            load_a(ra, (kb + 1) * BK);
+            load_b(rb, (kb + 1) * BK);
+        }
+        // one group of 8 k: lane group kl takes k = kl*VEC + e (VEC*KL = 8)
+        T fa[NBM][VEC], fb[NBN][VEC];
+#pragma unroll
+        for (int a = 0; a < NBM; ++a) {
+            const int rho = rho0 + a * MI + (lane % MI);
+            const T *p = As[cur] + (rho % MB) * PBP + (rho / MB);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) fa[a][e] = p[(kl * VEC + e) * A_K];
+        }
+#pragma unroll
+        for (int c = 0; c < NBN; ++c) {
+            const int col = c * MI + (lane % MI);
+            if (B_KC) {
+                Vec v = *(const Vec *)(Bs[cur] + col * B_LD + kl * VEC);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) fb[c][e] = v[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[cur][(kl * VEC + e) * B_LD + col];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+#pragma unroll
+            for (int a = 0; a < NBM; ++a)
+#pragma unroll
+                for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[c][e], fa[a][e]);     // C^T: lanes run along rows
+        if (more) {
+            store_a(As[cur ^ 1], ra);
+            store_b(Bs[cur ^ 1], rb);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: lane = tile row rho = (batch, row); consecutive lanes are consecutive rows of one C_b
+    const T alpha = (T)g.alpha, beta = (T)g.beta;
+#pragma unroll
+    for (int a = 0; a < NBM; ++a) {
+        const int rho = rho0 + a * MI + (lane % MI);
+        const int bl = rho / MB, il = rho % MB;
+        if (bl >= b_left || il >= m_left) continue;
+        T *Cb = (T *)g.C + (bb + bl) * g.bsC[0] + b1 * g.bsC[1] + (i0 + il);
+#pragma unroll
+        for (int c = 0; c < NBN; ++c) {
+            const int64_t jl = j0 + c * MI + MF::row_lane(lane);
+#pragma unroll
+            for (int r = 0; r < MF::NREG; ++r) {
+                const int64_t j = jl + MF::row_reg(r);
+                if (j >= g.n) continue;
+                T *dst = Cb + j * g.ldc;
+                T v = alpha * acc[a][c][r];
+                if (beta != T(0)) v += beta * *dst;
+                *dst = v;
+            }
+        }
+    }
+}
+
+template <typename MF, int PB, int MB, int BN>
+hipError_t launch(const SbArgs &a, hipStream_t stream)
+{
+    const int64_t tiles_b = (a.batch0 + PB - 1) / PB, tiles_i = (a.m + MB - 1) / MB, tiles_n = (a.n + BN - 1) / BN;
+    const int64_t total = tiles_b * tiles_i * tiles_n * a.batch1;
+    if (total <= 0) return hipSuccess;
+    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    constexpr int VEC = MF::VEC;
+    const int vec_a = ((uintptr_t)a.A % 16 == 0) && a.rsA % VEC == 0 && a.csA % VEC == 0 && a.bsA[1] % VEC == 0;
+    dim3 grid((unsigned)total), block(ET);
+    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a);
+    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// The first operand is "extended" (level-0 batch stride 1, rows and columns both strided), the second
+// is a plain N/T matrix that does not move with batch level 0, C_b are ordinary column-major matrices.
+bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
+{
+    if (dt != SB_F32 && dt != SB_F64) return false;
+    if (a.k <= 0 || a.batch0 < 8) return false;
+    if (a.bsA[0] != 1 || a.rsA == 1 || a.csA == 1) return false;
+    if (a.bsB[0] != 0) return false;
+    if (a.rsB != 1 && a.csB != 1) return false;
+    return a.m >= 8 && a.n >= 16;
+}
+
+hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream)
+{
+    if (dt == SB_F32) return launch<ExF32, 16, 32, 32>(a, stream);
+    if (dt == SB_F64) return launch<ExF64, 16, 16, 32>(a, stream);
+    return hipErrorInvalidValue;
+}
