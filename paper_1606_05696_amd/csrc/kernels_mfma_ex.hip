@@ -244,7 +244,7 @@ bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
 
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
-    if (dt == SB_F32) return launch<ExF32, 16, 32, 32>(a, stream);
+    if (dt == SB_F32) return launch<ExF32, 16, 16, 64>(a, stream);     // 16 batches x 16 rows x 64 columns per tile
     if (dt == SB_F64) return launch<ExF64, 16, 16, 32>(a, stream);
     return hipErrorInvalidValue;
 }
