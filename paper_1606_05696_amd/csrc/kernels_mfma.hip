@@ -136,8 +136,9 @@ struct Panel {
 };
 
 // Tile configuration: each wave owns WM x WN of C; WAVES_M x WAVES_N waves form the workgroup tile.
-template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD = 2>
 struct Config {
+    static constexpr int GDIST = GD;      // how many panels ahead the global loads run (1 or 2)
     static constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N, BKC = BK;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     typedef MFT MF;
@@ -166,8 +167,9 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     typedef typename CF::PB PB;
     constexpr int MI = MF::MI, VEC = MF::VEC, BK = CF::BKC, KG = BK / MF::KGROUP;
     (void)BKc;
-    typename PA::Vec ra[2][PA::NVEC];
-    typename PB::Vec rb[2][PB::NVEC];
+    constexpr int GD = CF::GDIST;
+    typename PA::Vec ra[GD][PA::NVEC];
+    typename PB::Vec rb[GD][PB::NVEC];
     T fa[2][CF::NBM][VEC], fb[2][CF::NBN][VEC];
     const int64_t nkb = (K + BK - 1) / BK;
 
@@ -189,7 +191,7 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     auto block = [&](auto cur_c, auto steady_c, int64_t kb) {
         constexpr int CUR = decltype(cur_c)::value;
         constexpr bool STEADY = decltype(steady_c)::value;
-        if (STEADY || kb + 2 < nkb) gload(std::integral_constant<int, CUR>(), kb + 2);   // this staging set was consumed one block ago
+        if (STEADY || kb + GD < nkb) gload(std::integral_constant<int, (GD == 2 ? CUR : 0)>(), kb + GD);   // this staging set was consumed one block ago
 #pragma unroll
         for (int kg = 0; kg < KG; ++kg) {
             const int fs = kg & 1;
@@ -197,8 +199,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
                 if (fs == 0) read_frags(std::integral_constant<int, 1>(), std::integral_constant<int, CUR>(), kg + 1);
                 else         read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR>(), kg + 1);
             } else if (STEADY || kb + 1 < nkb) {
-                PA::store(As[CUR ^ 1], ra[CUR ^ 1]);
-                PB::store(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                PA::store(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0]);
+                PB::store(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0]);
                 __syncthreads();
                 read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR ^ 1>(), 0);
             }
@@ -219,13 +221,13 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     typedef std::integral_constant<int, 1> I1;
 
     gload(I0(), 0);
-    if (nkb > 1) gload(I1(), 1);
+    if (GD == 2 && nkb > 1) gload(std::integral_constant<int, GD - 1>(), 1);
     PA::store(As[0], ra[0]);
     PB::store(Bs[0], rb[0]);
     __syncthreads();
     read_frags(I0(), I0(), 0);
     int64_t kb = 0;
-    for (; kb + 3 < nkb; kb += 2) {                    // steady state, two blocks per trip
+    for (; kb + 1 + GD < nkb; kb += 2) {               // steady state, two blocks per trip
         block(I0(), std::true_type(), kb);
         block(I1(), std::true_type(), kb + 1);
     }
@@ -235,10 +237,10 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     }
 }
 
-template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
 {
-    typedef Config<MFT, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N> CF;
+    typedef Config<MFT, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N, GD> CF;
     typedef typename CF::MF MF;
     typedef typename MF::T T;
     constexpr int MI = MF::MI, BM = CF::BM, BN = CF::BN;
@@ -354,7 +356,7 @@ hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStr
     return hipGetLastError();
 }
 
-template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD = 2>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
     typedef MFT T;
@@ -370,10 +372,10 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
                        aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
                        aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
-    if (a_kc && b_kc)        return launch_persistent(sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
-    else if (a_kc && !b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
-    else if (!a_kc && b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
-    return launch_persistent(sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn, vec_ok);
+    if (a_kc && b_kc)        return launch_persistent(sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
+    else if (a_kc && !b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
+    else if (!a_kc && b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
+    return launch_persistent(sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
 }
 
 }  // namespace
