@@ -209,6 +209,39 @@ def run_table2_cases(steps, warmup):
                 cases=rows)
 
 
+def run_exceptional_cases(steps, warmup, n=512):
+    """Two exceptional cases of Table II (3.6 and 6.4, the ones section III-E writes out) at n^4 in
+    fp32: the extended-operation kernel against the two-step route the paper benchmarks it against
+    (explicit mode transposition + GEMM, here torch permute/copy + vendor GEMM)."""
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    rows = []
+    tA = dev(inputs.uniform_tensor(31, [n, n], np.float32), "f32")
+    tB = dev(inputs.uniform_tensor(32, [n, n, n], np.float32), "f32")
+    tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+    flops = 2 * n ** 4
+    for case, ma, mb in (("3.6", "nk", "pmk"), ("6.4", "kp", "nkm")):
+        rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
+
+        def ours():
+            sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+
+        a, b = tA.view(n, n), tB.view(n, n, n)
+        expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
+
+        def conventional():
+            return torch.einsum(expr, a, b).contiguous()
+
+        _, t_ours = time_steps(ours, steps, warmup)
+        family = sb.sb_last_kernel()
+        _, t_conv = time_steps(conventional, steps, warmup)
+        rows.append(dict(case=case, evaluation=plan.text(), kernel_family=family, kernel_ms=t_ours,
+                         gflops=flops / t_ours / 1e6, frac_of_fp32_mfma_peak=flops / t_ours / 1e9 / PEAK["mfma"]["f32"],
+                         conventional_ms=t_conv, speedup_over_conventional=t_conv / t_ours))
+    return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, cases=rows)
+
+
 def cpu_baseline(cfg, tensors, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
     last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
@@ -285,6 +318,7 @@ def main():
             r, _ = run_workload(cfg, steps, args.warmup, not args.no_torch_baseline)
             others.append(r)
         others.append(run_table2_cases(max(args.steps, 200), args.warmup))
+        others.append(run_exceptional_cases(args.steps, args.warmup))
         result["workloads"] = others
     print(json.dumps(result))
 
