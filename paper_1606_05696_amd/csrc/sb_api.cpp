@@ -155,6 +155,49 @@ extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, co
     return SB_OK;
 }
 
+namespace {
+
+// Iterative algorithms issue the same contraction over and over (only the pointers change), so the
+// most recent plan of each thread is kept and reused when every planning input is identical.
+struct PlanKey {
+    char modes[3][4 * SB_MAX_MODES];
+    int64_t dims[3][SB_MAX_MODES], strides[3][SB_MAX_MODES];
+    int8_t has_dims[3], has_strides[3];
+    int32_t strat;
+};
+
+bool fill_key(PlanKey &k, const char *const modes[3], const int64_t *const dims[3], const int64_t *const strides[3], int strat)
+{
+    std::memset(&k, 0, sizeof(k));
+    for (int t = 0; t < 3; ++t) {
+        if (!modes[t]) return false;
+        const size_t len = std::strlen(modes[t]);
+        if (len >= sizeof(k.modes[t])) return false;
+        std::memcpy(k.modes[t], modes[t], len);
+        int order = 0;
+        for (size_t i = 0; i < len; ++i)
+            order += (modes[t][i] >= 'a' && modes[t][i] <= 'z') || (modes[t][i] >= 'A' && modes[t][i] <= 'Z');
+        if (order > SB_MAX_MODES) return false;
+        k.has_dims[t] = dims[t] != nullptr;
+        k.has_strides[t] = strides[t] != nullptr;
+        for (int j = 0; j < order; ++j) {
+            if (dims[t]) k.dims[t][j] = dims[t][j];
+            if (strides[t]) k.strides[t][j] = strides[t][j];
+        }
+    }
+    k.strat = strat;
+    return true;
+}
+
+struct PlanCache {
+    bool valid = false;
+    PlanKey key;
+    sb_plan plan;
+};
+thread_local PlanCache g_plan_cache;
+
+}  // namespace
+
 extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char *modesC,
                            double alpha, const void *A, const int64_t *dimsA, const int64_t *stridesA,
                            const void *B, const int64_t *dimsB, const int64_t *stridesB,
@@ -163,7 +206,24 @@ extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, 
 {
     if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
     sb_plan plan;
-    int rc = sb_contract_plan(modesA, modesB, modesC, dimsA, stridesA, dimsB, stridesB, dimsC, stridesC, strat, &plan);
+    int rc;
+    const char *const modes[3] = {modesA, modesB, modesC};
+    const int64_t *const dims[3] = {dimsA, dimsB, dimsC};
+    const int64_t *const strides[3] = {stridesA, stridesB, stridesC};
+    PlanKey key;
+    const bool keyed = fill_key(key, modes, dims, strides, (int)strat);
+    PlanCache &cache = g_plan_cache;
+    if (keyed && cache.valid && std::memcmp(&cache.key, &key, sizeof(key)) == 0) {
+        plan = cache.plan;
+        rc = SB_OK;
+    } else {
+        rc = sb_contract_plan(modesA, modesB, modesC, dimsA, stridesA, dimsB, stridesB, dimsC, stridesC, strat, &plan);
+        if (rc == SB_OK && keyed) {
+            cache.key = key;
+            cache.plan = plan;
+            cache.valid = true;
+        }
+    }
     if (rc < 0) {
         // planner argument numbers -> sb_contract argument numbers
         static const int map[12] = {0, 2, 3, 4, 7, 8, 10, 11, 14, 15, 16, 16};
