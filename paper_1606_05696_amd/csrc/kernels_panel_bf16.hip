@@ -42,10 +42,16 @@ __device__ __forceinline__ bf16x8 panel_fragment(const uint16_t *lds, int row0, 
 constexpr int GP = 4, GQ = 4, OT = 1024;
 constexpr int ONVEC = (GP + GQ) * TM * KMAX / 8 / OT;     // 16-byte vectors per lane for all panels (8)
 
+// Results leave through LDS: a wave parks its 32 x 64 x 2 block as bf16, column by column, and
+// writes it out as 16-byte vectors along the rows of C (64 two-byte stores per lane become 8).
+constexpr int SPITCH = 36;                        // elements per staged column: 32 rows + 8 bytes (bank spread)
+constexpr int STAGE = 2 * TN * SPITCH;            // per wave: two GEMMs x 64 columns
+constexpr int OUTER_LDS = ((GP + GQ) * PANEL > (OT / 64) * STAGE) ? (GP + GQ) * PANEL : (OT / 64) * STAGE;   // elements
+
 template <bool A_KC, bool B_KC, int KS>
-__global__ __launch_bounds__(OT) void sbgemm_outer_bf16_kernel(SbArgs g, int groups_p)
+__global__ __launch_bounds__(OT) void sbgemm_outer_bf16_kernel(SbArgs g, int groups_p, int vec_store)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [GP + GQ][PANEL]
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [GP + GQ][PANEL], later [wave][STAGE]
     const int gp = (int)(blockIdx.x % groups_p), gq = (int)(blockIdx.x / groups_p);
     const int64_t p0 = (int64_t)gp * GP, q0 = (int64_t)gq * GQ;
     const int m = (int)g.m, n = (int)g.n, kk = (int)g.k;
@@ -111,32 +117,72 @@ __global__ __launch_bounds__(OT) void sbgemm_outer_bf16_kernel(SbArgs g, int gro
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 const bf16x8 fb = panel_fragment<B_KC>(lb, cb * 32, ks, lane);
-                acc[qq][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb, fa, acc[qq][cb], 0, 0, 0);   // C^T: lanes along rows of C
+                // result register r of lane l: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
+                acc[qq][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[qq][cb], 0, 0, 0);
             }
         }
     }
+    __syncthreads();                 // every wave is done with the panels: the space becomes the staging area
 
     const float alpha = (float)g.alpha, beta = (float)g.beta;
     const int64_t p = p0 + pi;
-    const int row = rb * 32 + (lane & 31);
-    if (p < g.batch0 && row < m) {
+    const int row0 = rb * 32;
+    uint16_t *st = lds + wave * STAGE;
+    uint16_t *Cp = (uint16_t *)g.C + p * g.bsC[0] + row0;
 #pragma unroll
-        for (int qq = 0; qq < 2; ++qq) {
-            const int64_t q = q0 + 2 * qh + qq;
-            if (q >= g.batch1) continue;
-            uint16_t *Cq = (uint16_t *)g.C + p * g.bsC[0] + q * g.bsC[1] + row;
+    for (int qq = 0; qq < 2; ++qq) {
+        const int64_t q = q0 + 2 * qh + qq;
+        const bool live = p < g.batch0 && q < g.batch1;
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
+        for (int cb = 0; cb < 2; ++cb) {
+            const int j = cb * 32 + (lane & 31);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = cb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                    if (j < n) {
-                        uint16_t *dst = Cq + (int64_t)j * g.ldc;
-                        float v = alpha * acc[qq][cb][r];
-                        if (beta != 0.f) v += beta * sb_bf16_to_f32(*dst);
-                        *dst = sb_f32_to_bf16(v);
-                    }
+            for (int gq4 = 0; gq4 < 4; ++gq4) {
+                const int i0 = 8 * gq4 + 4 * (lane >> 5);
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = alpha * acc[qq][cb][4 * gq4 + e];
+                if (beta != 0.f && live && j < n) {
+                    const uint16_t *old = Cp + q * g.bsC[1] + (int64_t)j * g.ldc + i0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (row0 + i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
                 }
+                typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+                u16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
+                *(u16x4 *)(st + (qq * TN + j) * SPITCH + i0) = pk;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+        const int64_t q = q0 + 2 * qh + qq;
+        if (!(p < g.batch0 && q < g.batch1)) continue;
+        uint16_t *Cq = Cp + q * g.bsC[1];
+        const uint16_t *sq = st + qq * TN * SPITCH;
+        if (vec_store) {             // m is a multiple of 8 and every column of C starts 16-byte aligned
+            typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+            const int seg = 8 * (lane & 3);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int j = 16 * t + (lane >> 2);
+                const u16x4 lo = *(const u16x4 *)(sq + j * SPITCH + seg);
+                const u16x4 hi = *(const u16x4 *)(sq + j * SPITCH + seg + 4);
+                if (row0 + seg < m && j < n) {
+                    u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
+                }
+            }
+        } else {
+            const int i = lane & 31;
+#pragma unroll 4
+            for (int jj = 0; jj < TN; jj += 2) {
+                const int j = jj + (lane >> 5);
+                const uint16_t v = sq[j * SPITCH + i];
+                if (row0 + i < m && j < n) Cq[(int64_t)j * g.ldc + i] = v;
             }
         }
     }
@@ -167,7 +213,9 @@ template <bool A_KC, bool B_KC>
 static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
 {
     const int64_t groups_p = (a.batch0 + GP - 1) / GP, groups_q = (a.batch1 + GQ - 1) / GQ;
-    const size_t lds_bytes = (size_t)(GP + GQ) * PANEL * sizeof(uint16_t);
+    const size_t lds_bytes = (size_t)OUTER_LDS * sizeof(uint16_t);
+    auto al8 = [](int64_t v) { return v % 8 == 0; };
+    const int vec_store = (uintptr_t)a.C % 16 == 0 && al8(a.ldc) && al8(a.bsC[0]) && al8(a.bsC[1]) && al8(a.m);
     dim3 grid((unsigned)(groups_p * groups_q)), block(OT);
     const int ks = (int)((a.k + 15) / 16);
 #define SB_OUTER(KS_)                                                                                                  \
@@ -179,7 +227,7 @@ static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
             if (e != hipSuccess) return e;                                                                              \
             configured = true;                                                                                          \
         }                                                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p);                                     \
+        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p, vec_store);                               \
     } while (0)
     if (ks <= 2)      SB_OUTER(2);
     else if (ks <= 4) SB_OUTER(4);

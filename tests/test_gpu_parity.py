@@ -265,7 +265,8 @@ def test_cfg5_order3_x_order3_full_size():
 def test_two_level_batches_with_one_operand_per_level(ma, mb, mc):
     # C_..[p]..[q] = A_..[p] B_..[q]: every A_p meets every B_q (the nested example of section III-F);
     # ragged group counts, all operand orientations, short and full k, m and n below and at 64
-    for ext in (dict(m=64, n=64, p=6, q=5, k=128), dict(m=40, n=24, p=9, q=4, k=72), dict(m=64, n=48, p=4, q=7, k=32)):
+    for ext in (dict(m=64, n=64, p=6, q=5, k=128), dict(m=40, n=24, p=9, q=4, k=72), dict(m=64, n=48, p=4, q=7, k=32),
+                dict(m=36, n=24, p=5, q=6, k=40)):
         for dtype in ("bf16", "f32"):
             err, text = contract_case(dtype, ma, mb, mc, ext, seed=91)
             assert err <= TOL[dtype], (text, ext, err)
