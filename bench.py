@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--only-headline", action="store_true", help="skip the other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-torch-baseline", action="store_true")
+    ap.add_argument("--sweeps", action="store_true",
+                    help="instead of the other workloads, add the size sweeps (cubic tensors, n = 8 .. 512) to the line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device copy of known size (to scale rocprofv3 byte counters)")
     return ap.parse_args()
@@ -242,6 +244,79 @@ def run_exceptional_cases(steps, warmup, n=512):
     return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, cases=rows)
 
 
+def run_sweeps(steps, warmup):
+    """Size sweeps over cubic tensors in fp32, the shapes of the paper's GPU plots (section IV):
+    batches of n small GEMMs (n x n x n) against the vendor's strided-batched GEMM; case 1.1 in its
+    three evaluations (flattened, batched in p, batched in n); the exceptional case 6.4 with the
+    extended operation, as batched matrix-vector products and by transposition + GEMM."""
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    sizes = [8, 16, 32, 64, 128, 256, 512]
+    out = {}
+    reps = lambda n: max(steps, 200) if n <= 128 else steps
+
+    rows = []
+    for n in sizes:      # n independent GEMMs of n x n x n, every operand batched (stride n^2)
+        tA = dev(inputs.uniform_tensor(51, [n, n, n], np.float32), "f32")
+        tB = dev(inputs.uniform_tensor(52, [n, n, n], np.float32), "f32")
+        tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+
+        def ours():
+            sb.sb_gemm("N", "N", n, n, n, 1.0, tA, n, n * n, tB, n, n * n, 0.0, tC, n, n * n, n, dt="f32")
+
+        a3, b3, c3 = tA.view(n, n, n), tB.view(n, n, n), tC.view(n, n, n)
+
+        def vendor():      # row-major views: C_p^T = B_p^T A_p^T
+            torch.bmm(b3, a3, out=c3)
+
+        _, t_ours = time_steps(ours, reps(n), warmup)
+        _, t_vend = time_steps(vendor, reps(n), warmup)
+        flops, nbytes = 2 * n ** 4, 3 * 4 * n ** 3
+        rows.append(dict(n=n, us=t_ours * 1e3, gflops=flops / t_ours / 1e6, gbps=nbytes / t_ours / 1e6,
+                         vendor_bmm_us=t_vend * 1e3, kernel_family=sb.sb_last_kernel()))
+    out["batched_gemm_n_of_nxnxn"] = rows
+
+    rows = []
+    for n in sizes:      # case 1.1, C_mnp = A_mk B_knp: flattened, batched in p, batched in n
+        tA = dev(inputs.uniform_tensor(53, [n, n], np.float32), "f32")
+        tB = dev(inputs.uniform_tensor(54, [n, n, n], np.float32), "f32")
+        tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+        row = dict(n=n)
+        for name, (ma, mb, mc) in (("flat", ("mk", "k(np)", "m(np)")), ("batch_p", ("mk", "kn[p]", "mn[p]")),
+                                   ("batch_n", ("mk", "k[n]p", "m[n]p"))):
+            def ours():
+                sb.sb_contract(ma, mb, mc, 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+            _, t = time_steps(ours, reps(n), warmup)
+            row[name + "_us"] = t * 1e3
+            row[name + "_gflops"] = 2 * n ** 4 / t / 1e6
+        rows.append(row)
+    out["case_1_1_flat_vs_batched"] = rows
+
+    rows = []
+    for n in sizes[2:]:  # exceptional case 6.4, C_mnp = B_nkm A_kp
+        tA = dev(inputs.uniform_tensor(55, [n, n], np.float32), "f32")
+        tB = dev(inputs.uniform_tensor(56, [n, n, n], np.float32), "f32")
+        tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+        row = dict(n=n)
+        for name, strat in (("extended_op", "auto"), ("batched_gemv", "level2")):
+            def ours():
+                sb.sb_contract("kp", "nkm", "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n], strat=strat)
+            _, t = time_steps(ours, reps(n) if name == "extended_op" else max(3, steps // 4), min(warmup, 3))
+            row[name + "_us"] = t * 1e3
+        a, b = tA.view(n, n), tB.view(n, n, n)
+
+        def conventional():
+            return torch.einsum("pk,mkn->pnm", a, b).contiguous()
+
+        _, t = time_steps(conventional, reps(n), warmup)
+        row["transpose_gemm_us"] = t * 1e3
+        row["extended_op_gflops"] = 2 * n ** 4 / row["extended_op_us"] / 1e3
+        rows.append(row)
+    out["case_6_4_exceptional"] = rows
+    return out
+
+
 def cpu_baseline(cfg, tensors, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
     last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
@@ -309,7 +384,9 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.workload, tensors)
     del tensors
-    if not args.only_headline:
+    if args.sweeps:
+        result["sweeps"] = run_sweeps(args.steps, args.warmup)
+    elif not args.only_headline:
         others = []
         for cfg in inputs.WORKLOADS:
             if cfg == args.workload:

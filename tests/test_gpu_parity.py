@@ -335,3 +335,55 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     ref = oracle.contract("mk", A, "knp", B, "mnp", wide=False)
     assert rel_fro(from_dev(tC, [48, 24, 9]), ref) <= TOL["f32"]
+
+
+def test_general_orders_sampled():
+    # the planner's procedure is the same for any order (Algorithm 2): a sample of the 216 order-3 x
+    # order-3 cases, and order 4 x 2 / 2 x 4 / 4 x 3 contractions with C in scrambled mode order
+    from helpers import cases_general
+    ext = dict(m=20, n=9, p=12, q=7, r=5, k=17)
+    cases = cases_general(3, 3)[::9]
+    cases += [("mkpq", "nk", "qnmp"), ("km", "qknp", "npmq"), ("pmkq", "rkn", "mqrnp"), ("qpkm", "nrk", "pmnqr")]
+    for i, (ma, mb, mc) in enumerate(cases):
+        for strat in ("auto", "nested"):
+            err, text = contract_case("f32", ma, mb, mc, ext, strat=strat, alpha=1.25, beta=0.5, seed=300 + i)
+            assert err <= TOL["f32"], (ma, mb, mc, strat, text, err)
+
+
+def test_replays_inside_a_hip_graph():
+    # the library allocates nothing and never synchronises, so a sequence of contractions can be
+    # captured once and replayed; every replay is checked, with eager work between the replays
+    import torch
+    ext = dict(m=48, n=40, p=9, k=24)
+    A = inputs.uniform_tensor(1, [ext["k"], ext["m"]], np.float32)
+    B = inputs.uniform_tensor(2, [ext["k"], ext["n"], ext["p"]], np.float32)
+    tA, tB = to_dev(A, "f32"), to_dev(B, "f32")
+    tC = to_dev(np.zeros(ext["m"] * ext["n"] * ext["p"]), "f32")
+    tD = to_dev(np.zeros(ext["k"] * ext["n"] * ext["p"]), "f32")
+    dA, dB = [ext["k"], ext["m"]], [ext["k"], ext["n"], ext["p"]]
+
+    def work():
+        sb.sb_contract("km", "knp", "mnp", 1.0, tA, dA, tB, dB, 0.0, tC)                                   # C_mnp
+        sb.sb_contract("ms", "mnp", "snp", 2.0, tA, [ext["m"], ext["k"]], tC, [ext["m"], ext["n"], ext["p"]], 0.0, tD)
+
+    A2 = A.reshape(-1, order="F")[: ext["m"] * ext["k"]].reshape([ext["m"], ext["k"]], order="F")
+    ref_c = oracle.contract("km", A, "knp", B, "mnp", wide=False)
+    ref_d = oracle.contract("ms", A2, "mnp", ref_c, "snp", alpha=2.0, wide=False)
+    work()                                   # warm-up outside the capture (first-use set-up of the kernels)
+    sync()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            work()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        tC.fill_(float("nan"))
+        tD.fill_(float("nan"))
+        sync()
+        graph.replay()
+        sync()
+        assert rel_fro(from_dev(tC, ref_c.shape), ref_c) <= TOL["f32"], rep
+        assert rel_fro(from_dev(tD, [ext["k"], ext["n"], ext["p"]]), ref_d) <= 2 * TOL["f32"], rep
+        tB.mul_(1.0)                         # eager work between replays
