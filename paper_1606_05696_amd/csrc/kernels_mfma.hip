@@ -195,12 +195,13 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
 #pragma unroll
         for (int kg = 0; kg < KG; ++kg) {
             const int fs = kg & 1;
+            const bool hand_over = STEADY || kb + 1 < nkb;
             if (kg + 1 < KG) {
                 if (fs == 0) read_frags(std::integral_constant<int, 1>(), std::integral_constant<int, CUR>(), kg + 1);
                 else         read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR>(), kg + 1);
-            } else if (STEADY || kb + 1 < nkb) {
-                PA::store(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0]);
-                PB::store(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0]);
+            } else if (hand_over) {
+                // the staged panel went to LDS in the middle of the previous cluster, so this
+                // barrier finds the stores complete and costs only the skew between the waves
                 __syncthreads();
                 read_frags(std::integral_constant<int, 0>(), std::integral_constant<int, CUR ^ 1>(), 0);
             }
@@ -209,11 +210,20 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
             // waves drift out of phase and one wave's memory phase hides under another's MFMAs.
             __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e)
+            for (int e = 0; e < VEC; ++e) {
+                if (e == VEC / 2 && kg == KG - 2 && hand_over) {
+                    // LDS store of the next block's panel (requested one block ago) between two
+                    // halves of a cluster: the matrix core keeps running under it
+                    __builtin_amdgcn_sched_barrier(0);
+                    PA::store(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0]);
+                    PB::store(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
 #pragma unroll
                 for (int a = 0; a < CF::NBM; ++a)
 #pragma unroll
                     for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[fs][c][e], fa[fs][a][e]);   // C^T = B^T A^T
+            }
             __builtin_amdgcn_s_setprio(0);
         }
     };
