@@ -105,3 +105,19 @@ def workload_tensors(cfg: int, with_c: bool = False):
         dC = [w["ext"][c] for c in w["C"]]
         out.append(make_tensor(seed_for(seed_cfg, "C"), dC, w["dtype"]))
     return tuple(out)
+
+
+def lowrank_noise_tensor(seed: int, dims, core, noise: float = 0.05, dtype=np.float64) -> np.ndarray:
+    """Synthetic input for the Tucker application study (section V-C works on cubic tensors with a
+    10 x 10 x 10 core): a random core of size `core` with decaying entries, expanded by random
+    orthonormal factors to `dims`, plus uniform noise of relative size `noise`.  Column-major."""
+    rng = np.random.default_rng(seed)
+    G = rng.standard_normal(core)
+    for r, c in enumerate(core):                       # decaying weights: distinct, well-separated singular values
+        w = 1.0 / (1.0 + np.arange(c))
+        G = G * w.reshape([-1 if a == r else 1 for a in range(3)])
+    factors = [np.linalg.qr(rng.standard_normal((d, c)))[0] for d, c in zip(dims, core)]
+    T = np.einsum("ijk,mi,nj,pk->mnp", G, *factors)
+    T = T / np.sqrt(np.mean(T * T))
+    T = T + noise * rng.uniform(-1.0, 1.0, size=T.shape)
+    return np.asfortranarray(T.astype(dtype))
