@@ -1,4 +1,5 @@
-"""ctypes binding of libsbgemm.so: the same entry points as include/sbgemm.h, same names.
+"""ctypes binding of libsbgemm.so: the same entry points as include/sbgemm.h and include/sbtucker.h,
+same names.
 
 Only argument marshalling happens here; every step of the path (planning, kernel selection,
 kernels) runs inside the library.  torch is used for device memory and streams only.  There is
@@ -28,7 +29,8 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 
 __all__ = [n for n in dir() if n.startswith("SB_")] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
-    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_force_kernel", "sb_last_kernel"]
+    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_force_kernel", "sb_last_kernel",
+    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"]
 
 
 class sb_plan(ctypes.Structure):
@@ -86,6 +88,14 @@ def load():
     lib.sb_force_kernel.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
     lib.sb_last_kernel.argtypes = []
+    lib.sb_tucker_workspace.restype = ci
+    lib.sb_tucker_workspace.argtypes = [ci, i64, i64, i64, i64, i64, i64, ci, i64p]
+    lib.sb_tucker_hooi.restype = ci
+    lib.sb_tucker_hooi.argtypes = [ci, vp, i64, i64, i64, i64, i64, i64, ci, ci, vp, vp, vp, vp, vp, i64, vp]
+    lib.sb_sym_eig_workspace.restype = ci
+    lib.sb_sym_eig_workspace.argtypes = [ci, i64, i64p]
+    lib.sb_sym_eig.restype = ci
+    lib.sb_sym_eig.argtypes = [ci, i64, vp, vp, vp, ci, vp, i64, vp]
     _lib = lib
     return lib
 
@@ -219,3 +229,43 @@ def sb_force_kernel(kernel_id):
 
 def sb_last_kernel():
     return load().sb_last_kernel()
+
+
+def sb_tucker_workspace(dt, m, n, p, i, j, k, with_init=True, check=True):
+    """Bytes of device workspace for sb_tucker_hooi (see sbtucker.h).  Returns (status, bytes)."""
+    out = ctypes.c_int64(0)
+    rc = load().sb_tucker_workspace(_dtype_of(dt), m, n, p, i, j, k, int(bool(with_init)), ctypes.byref(out))
+    if check and rc != SB_OK:
+        raise SbError("sb_tucker_workspace", rc)
+    return rc, out.value
+
+
+def sb_tucker_hooi(T, dims, core, iterations, A, B, C, G, workspace, init=True, dt=None, stream=None, check=True):
+    """Tucker decomposition by HOOI on device tensors (see sbtucker.h: sb_tucker_hooi).  `workspace` is a
+    device buffer (torch tensor of any dtype) of at least sb_tucker_workspace(...) bytes."""
+    m, n, p = dims
+    i, j, k = core
+    nbytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else 0
+    rc = load().sb_tucker_hooi(_dtype_of(dt, T, A, B, C, G), _ptr(T), m, n, p, i, j, k, int(iterations), int(bool(init)),
+                               _ptr(A), _ptr(B), _ptr(C), _ptr(G), _ptr(workspace), nbytes, _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_tucker_hooi", rc)
+    return rc
+
+
+def sb_sym_eig_workspace(dt, n, check=True):
+    out = ctypes.c_int64(0)
+    rc = load().sb_sym_eig_workspace(_dtype_of(dt), n, ctypes.byref(out))
+    if check and rc != SB_OK:
+        raise SbError("sb_sym_eig_workspace", rc)
+    return rc, out.value
+
+
+def sb_sym_eig(n, S, V, lam, workspace, sweeps=0, dt=None, stream=None, check=True):
+    """Eigen-decomposition of a symmetric device matrix by Jacobi rotations (see sbtucker.h: sb_sym_eig)."""
+    nbytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else 0
+    rc = load().sb_sym_eig(_dtype_of(dt, S, V, lam), n, _ptr(S), _ptr(V), _ptr(lam), int(sweeps), _ptr(workspace), nbytes,
+                           _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_sym_eig", rc)
+    return rc

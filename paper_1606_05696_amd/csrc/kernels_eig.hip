@@ -1,0 +1,252 @@
+// Symmetric eigensolver for the Tucker decomposition (Algorithm 1, section II-C): the "leading left
+// singular vectors" of an unfolding are the leading eigenvectors of a Gram matrix, which this
+// file diagonalises with two-sided Jacobi rotations in the parallel (round-robin) ordering:
+// a step rotates n/2 disjoint index pairs (p,q) at once, A <- J^T A J, V <- V J, and n-1 steps
+// (a sweep) visit every pair once.  With all pairs of a step disjoint, the 2 x 2 block of A at
+// (pair P, pair Q) depends only on its own four elements and on the rotations of P and Q, so a
+// step is a fully parallel element-wise update.
+//
+// Two drivers share the arithmetic: one workgroup holding A and V in LDS for small matrices (the
+// 100 x 100 Gram matrices of the iteration), and one launch per step on ping-pong buffers in
+// global memory for larger ones (the initialisation).  Neither synchronises with the host: the
+// number of sweeps is fixed by the caller.
+#include "sb_internal.h"
+
+namespace {
+
+// round-robin tournament on ne (even) players: pair t of round r
+__device__ __forceinline__ void pair_of(int t, int round, int ne, int &p, int &q)
+{
+    const int mod = ne - 1;
+    if (t == 0) { p = ne - 1; q = round; }
+    else {
+        p = round + t; if (p >= mod) p -= mod;
+        q = round - t; if (q < 0) q += mod;
+    }
+}
+
+// Jacobi rotation J = [[c, s], [-s, c]] that annihilates the off-diagonal element of
+// [[app, apq], [apq, aqq]] under J^T . J; the smaller root of t^2 + 2 theta t - 1 = 0 keeps the
+// rotation angle below 45 degrees.
+template <typename T>
+__device__ __forceinline__ void rotation(T app, T aqq, T apq, T &c, T &s)
+{
+    if (apq == T(0)) { c = T(1); s = T(0); return; }
+    const T theta = (aqq - app) / (T(2) * apq);
+    const T t = (theta >= T(0) ? T(1) : T(-1)) / (fabs(theta) + sqrt(theta * theta + T(1)));
+    c = T(1) / sqrt(t * t + T(1));
+    s = t * c;
+}
+
+// Global-memory step: Ain/Vin -> Aout/Vout (ping-pong, so every thread sees the matrix as it was
+// before the step).  n is the matrix order, ne = n rounded up to even (the phantom index of an
+// odd matrix pairs with nothing).  Work items: (ne/2)^2 blocks of A, then n * ne/2 row pairs of V.
+template <typename T>
+__global__ __launch_bounds__(256) void jacobi_step_kernel(const T *__restrict__ Ain, T *__restrict__ Aout,
+                                                          const T *__restrict__ Vin, T *__restrict__ Vout, int n, int ne, int round)
+{
+    const int h = ne / 2;
+    const int64_t nA = (int64_t)h * h, total = nA + (int64_t)n * h;
+    for (int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; item < total; item += (int64_t)gridDim.x * blockDim.x) {
+        if (item < nA) {
+            const int P = (int)(item % h), Q = (int)(item / h);
+            int p1, q1, p2, q2;
+            pair_of(P, round, ne, p1, q1);
+            pair_of(Q, round, ne, p2, q2);
+            T cP = T(1), sP = T(0), cQ = T(1), sQ = T(0);
+            const bool vP = p1 < n && q1 < n, vQ = p2 < n && q2 < n;
+            if (vP) rotation(Ain[p1 + (int64_t)p1 * n], Ain[q1 + (int64_t)q1 * n], Ain[p1 + (int64_t)q1 * n], cP, sP);
+            if (vQ) rotation(Ain[p2 + (int64_t)p2 * n], Ain[q2 + (int64_t)q2 * n], Ain[p2 + (int64_t)q2 * n], cQ, sQ);
+            const bool rp = p1 < n, rq = q1 < n, cp = p2 < n, cq = q2 < n;
+            const T a = (rp && cp) ? Ain[p1 + (int64_t)p2 * n] : T(0), b = (rp && cq) ? Ain[p1 + (int64_t)q2 * n] : T(0);
+            const T c = (rq && cp) ? Ain[q1 + (int64_t)p2 * n] : T(0), d = (rq && cq) ? Ain[q1 + (int64_t)q2 * n] : T(0);
+            const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;        // J_P^T M
+            const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
+            if (rp && cp) Aout[p1 + (int64_t)p2 * n] = x00 * cQ - x01 * sQ;   // . J_Q
+            if (rp && cq) Aout[p1 + (int64_t)q2 * n] = x00 * sQ + x01 * cQ;
+            if (rq && cp) Aout[q1 + (int64_t)p2 * n] = x10 * cQ - x11 * sQ;
+            if (rq && cq) Aout[q1 + (int64_t)q2 * n] = x10 * sQ + x11 * cQ;
+        } else {
+            const int64_t it = item - nA;
+            const int row = (int)(it % n), Q = (int)(it / n);
+            int p2, q2;
+            pair_of(Q, round, ne, p2, q2);
+            const bool cp = p2 < n, cq = q2 < n;
+            T cQ = T(1), sQ = T(0);
+            if (cp && cq) rotation(Ain[p2 + (int64_t)p2 * n], Ain[q2 + (int64_t)q2 * n], Ain[p2 + (int64_t)q2 * n], cQ, sQ);
+            const T vp = cp ? Vin[row + (int64_t)p2 * n] : T(0), vq = cq ? Vin[row + (int64_t)q2 * n] : T(0);
+            if (cp) Vout[row + (int64_t)p2 * n] = vp * cQ - vq * sQ;
+            if (cq) Vout[row + (int64_t)q2 * n] = vp * sQ + vq * cQ;
+        }
+    }
+}
+
+template <typename T>
+__global__ void identity_kernel(T *V, int n)
+{
+    const int64_t total = (int64_t)n * n;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x)
+        V[e] = (e % n == e / n) ? T(1) : T(0);
+}
+
+// Small matrices: the whole iteration in one workgroup, A and V in LDS, updated in place
+// (rotations of a step are computed first, then every 2 x 2 block is rewritten by one thread).
+constexpr int LDS_THREADS = 1024;
+
+template <typename T>
+__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
+    T *As = (T *)raw, *Vs = As + (size_t)n * n, *cs = Vs + (size_t)n * n;       // cs: [h][2]
+    const int h = ne / 2, tid = threadIdx.x;
+    for (int e = tid; e < n * n; e += LDS_THREADS) {
+        As[e] = A[e];
+        Vs[e] = (e % n == e / n) ? T(1) : T(0);
+    }
+    __syncthreads();
+    const int nA = h * h, total = nA + n * h;
+    for (int sweep = 0; sweep < sweeps; ++sweep) {
+        for (int round = 0; round < ne - 1; ++round) {
+            if (tid < h) {
+                int p, q;
+                pair_of(tid, round, ne, p, q);
+                T c = T(1), s = T(0);
+                if (p < n && q < n) rotation(As[p + p * n], As[q + q * n], As[p + q * n], c, s);
+                cs[2 * tid] = c;
+                cs[2 * tid + 1] = s;
+            }
+            __syncthreads();
+            for (int item = tid; item < total; item += LDS_THREADS) {
+                if (item < nA) {
+                    const int P = item % h, Q = item / h;
+                    int p1, q1, p2, q2;
+                    pair_of(P, round, ne, p1, q1);
+                    pair_of(Q, round, ne, p2, q2);
+                    const T cP = cs[2 * P], sP = cs[2 * P + 1], cQ = cs[2 * Q], sQ = cs[2 * Q + 1];
+                    const bool rp = p1 < n, rq = q1 < n, cp = p2 < n, cq = q2 < n;
+                    const T a = (rp && cp) ? As[p1 + p2 * n] : T(0), b = (rp && cq) ? As[p1 + q2 * n] : T(0);
+                    const T c = (rq && cp) ? As[q1 + p2 * n] : T(0), d = (rq && cq) ? As[q1 + q2 * n] : T(0);
+                    const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;
+                    const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
+                    if (rp && cp) As[p1 + p2 * n] = x00 * cQ - x01 * sQ;
+                    if (rp && cq) As[p1 + q2 * n] = x00 * sQ + x01 * cQ;
+                    if (rq && cp) As[q1 + p2 * n] = x10 * cQ - x11 * sQ;
+                    if (rq && cq) As[q1 + q2 * n] = x10 * sQ + x11 * cQ;
+                } else {
+                    const int it = item - nA;
+                    const int row = it % n, Q = it / n;
+                    int p2, q2;
+                    pair_of(Q, round, ne, p2, q2);
+                    const bool cp = p2 < n, cq = q2 < n;
+                    const T cQ = cs[2 * Q], sQ = cs[2 * Q + 1];
+                    const T vp = cp ? Vs[row + p2 * n] : T(0), vq = cq ? Vs[row + q2 * n] : T(0);
+                    if (cp) Vs[row + p2 * n] = vp * cQ - vq * sQ;
+                    if (cq) Vs[row + q2 * n] = vp * sQ + vq * cQ;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int e = tid; e < n * n; e += LDS_THREADS) {
+        A[e] = As[e];
+        V[e] = Vs[e];
+    }
+}
+
+// Order the eigenvalues (the diagonal of the rotated matrix): rank[i] = number of eigenvalues that
+// come before lambda_i in descending order (ties by index); lam[rank] = lambda_i, sel[rank] = i.
+template <typename T>
+__global__ __launch_bounds__(256) void eig_order_kernel(const T *A, int n, T *lam, int *sel)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        const T li = A[i + (int64_t)i * n];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const T lj = A[j + (int64_t)j * n];
+            rank += (lj > li) || (lj == li && j < i);
+        }
+        lam[rank] = li;
+        sel[rank] = i;
+    }
+}
+
+// W[:, c] = V[:, sel[c]] * scale_c for the r leading eigenpairs; scale_c = 1 (scaled == 0) or
+// 1/sqrt(lambda_c), the factor that turns an eigenvector of Y^T Y into Y^T u (zero when the
+// eigenvalue is not safely positive: a rank-deficient matrix has no such singular vector).
+template <typename T>
+__global__ __launch_bounds__(256) void eig_gather_kernel(const T *V, int n, const int *sel, const T *lam, int r, T *W, int64_t ldw, int scaled, T floor_rel)
+{
+    const int64_t total = (int64_t)n * r;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+        const int row = (int)(e % n), c = (int)(e / n);
+        T scale = T(1);
+        if (scaled) scale = (lam[c] > floor_rel * lam[0] && lam[c] > T(0)) ? T(1) / sqrt(lam[c]) : T(0);
+        int col = sel[c];
+        if ((unsigned)col >= (unsigned)n) col = 0;         // NaN eigenvalues leave the order undefined; stay in bounds
+        W[row + c * ldw] = V[row + (int64_t)col * n] * scale;
+    }
+}
+
+template <typename T>
+size_t lds_need(int n, int ne) { return ((size_t)2 * n * n + ne) * sizeof(T); }
+
+template <typename T>
+hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweeps, hipStream_t stream, T **A_final, T **V_final)
+{
+    const int ne = n + (n & 1);
+    if (n == 1) {
+        identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
+        *A_final = A; *V_final = V;
+    } else if (lds_need<T>(n, ne) <= (size_t)160 * 1024) {
+        const size_t bytes = lds_need<T>(n, ne);
+        static bool configured = false;
+        if (!configured) {
+            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            configured = true;
+        }
+        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps);
+        *A_final = A; *V_final = V;
+    } else {
+        const int h = ne / 2;
+        const int64_t items = (int64_t)h * h + (int64_t)n * h;
+        const unsigned blocks = (unsigned)((items + 255) / 256 < 4096 ? (items + 255) / 256 : 4096);
+        identity_kernel<T><<<256, 256, 0, stream>>>(V, n);
+        T *ain = A, *aout = A2, *vin = V, *vout = V2;
+        for (int sweep = 0; sweep < sweeps; ++sweep)
+            for (int round = 0; round < ne - 1; ++round) {
+                jacobi_step_kernel<T><<<blocks, 256, 0, stream>>>(ain, aout, vin, vout, n, ne, round);
+                T *t = ain; ain = aout; aout = t;
+                t = vin; vin = vout; vout = t;
+            }
+        *A_final = ain; *V_final = vin;
+    }
+    eig_order_kernel<T><<<(n + 255) / 256, 256, 0, stream>>>(*A_final, n, lam, sel);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Eigen-decomposition of the symmetric n x n matrix in A (column-major, packed; destroyed).
+// A2, V, V2: n*n elements each; lam: n; sel: n ints.  On return *V_final (V or V2) holds the
+// eigenvectors as columns in rotation order, lam the eigenvalues in descending order and sel the
+// column of *V_final that belongs to each.
+hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, void *lam, int *sel, int sweeps,
+                      hipStream_t stream, void **A_final, void **V_final)
+{
+    if (dt == SB_F64) return eig_impl<double>(n, (double *)A, (double *)A2, (double *)V, (double *)V2, (double *)lam, sel, sweeps, stream, (double **)A_final, (double **)V_final);
+    if (dt == SB_F32) return eig_impl<float>(n, (float *)A, (float *)A2, (float *)V, (float *)V2, (float *)lam, sel, sweeps, stream, (float **)A_final, (float **)V_final);
+    return hipErrorInvalidValue;
+}
+
+// W (n x r, leading dimension ldw) = the r leading eigenvectors, optionally scaled by lambda^-1/2.
+hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw, int scaled, hipStream_t stream)
+{
+    const int64_t total = (int64_t)n * r;
+    const unsigned blocks = (unsigned)((total + 255) / 256 < 1024 ? (total + 255) / 256 : 1024);
+    if (total == 0) return hipSuccess;
+    if (dt == SB_F64) eig_gather_kernel<double><<<blocks, 256, 0, stream>>>((const double *)V, n, sel, (const double *)lam, r, (double *)W, ldw, scaled, 1e-24);
+    else if (dt == SB_F32) eig_gather_kernel<float><<<blocks, 256, 0, stream>>>((const float *)V, n, sel, (const float *)lam, r, (float *)W, ldw, scaled, 1e-10f);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}

@@ -1,0 +1,235 @@
+// Tucker decomposition by higher-order orthogonal iteration (Algorithm 1, section II-C) as a
+// host-side driver over the contraction entry points: every tensor product of the algorithm is
+// one or two single-index contractions through sb_contract, and the leading left singular
+// vectors of an unfolding come from the Gram matrix of its shorter side (sb_gemm), the Jacobi
+// eigensolver, and one more GEMM that maps the eigenvectors back.  Nothing synchronises with the
+// host; all intermediates live in the caller's workspace.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "../../include/sbtucker.h"
+#include "sb_internal.h"
+
+hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, void *lam, int *sel, int sweeps,
+                      hipStream_t stream, void **A_final, void **V_final);
+hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw,
+                         int scaled, hipStream_t stream);
+
+namespace {
+
+constexpr int64_t ALIGN = 256;
+int64_t esize(sb_dtype dt) { return dt == SB_F64 ? 8 : 4; }
+int64_t up(int64_t bytes) { return (bytes + ALIGN - 1) / ALIGN * ALIGN; }
+// cyclic Jacobi converges quadratically: random and Gram matrices of order 100-500 reach working
+// precision in 6 sweeps (fp64) or 4 (fp32); the defaults leave a margin
+int default_sweeps(sb_dtype dt, int64_t n) { return dt == SB_F64 ? (n > 128 ? 12 : 10) : (n > 128 ? 7 : 6); }
+
+// carve-out of the workspace; sizes in bytes, every block 256-byte aligned
+struct EigSpace {
+    int64_t nmax;
+    char *S, *S2, *V, *V2, *lam, *sel;
+    static int64_t bytes(sb_dtype dt, int64_t nmax)
+    {
+        const int64_t mat = up(nmax * nmax * esize(dt));
+        return 4 * mat + up(nmax * esize(dt)) + up(nmax * 4);
+    }
+    char *carve(sb_dtype dt, char *base, int64_t n)
+    {
+        nmax = n;
+        const int64_t mat = up(n * n * esize(dt));
+        S = base; S2 = S + mat; V = S2 + mat; V2 = V + mat;
+        lam = V2 + mat;
+        sel = lam + up(n * esize(dt));
+        return sel + up(n * 4);
+    }
+};
+
+struct Sizes {
+    int64_t m, n, p, i, j, k;
+    int64_t eig_loop() const { return std::max({std::min(m, j * k), std::min(n, i * k), std::min(p, i * j)}); }
+    int64_t eig_init() const { return std::max({m, n, p}); }
+    int64_t rmax() const { return std::max({i, j, k}); }
+    int64_t y_elems() const { return std::max({m * j * k, n * i * k, i * j * p}); }
+};
+
+int64_t tucker_bytes(sb_dtype dt, const Sizes &s, int with_init)
+{
+    const int64_t es = esize(dt);
+    const int64_t nmax = with_init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
+    return up(s.m * s.n * s.k * es) + up(s.i * s.n * s.p * es) + up(s.y_elems() * es) + up(nmax * s.rmax() * es) +
+           EigSpace::bytes(dt, nmax);
+}
+
+struct Ctx {
+    sb_dtype dt;
+    hipStream_t stream;
+    EigSpace eig;
+    char *W;          // nmax x rmax: selected (scaled) eigenvectors
+    int status;
+
+    bool ok() const { return status == SB_OK; }
+    void check(int rc) { if (status == SB_OK && rc != SB_OK) status = rc; }
+    void check_hip(hipError_t e) { if (status == SB_OK && e != hipSuccess) status = SB_ERR_LAUNCH + (int)e; }
+
+    void gemm(sb_op ta, sb_op tb, int64_t m, int64_t n, int64_t k, const void *A, int64_t lda, const void *B, int64_t ldb,
+              double beta, void *C, int64_t ldc)
+    {
+        if (!ok()) return;
+        check(sb_gemm(dt, ta, tb, m, n, k, 1.0, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, 1, stream));
+    }
+
+    void contract(const char *ma, const char *mb, const char *mc, const void *A, const int64_t *dA, const void *B,
+                  const int64_t *dB, void *C, const int64_t *dC)
+    {
+        if (!ok()) return;
+        check(sb_contract(dt, ma, mb, mc, 1.0, A, dA, nullptr, B, dB, nullptr, 0.0, C, dC, nullptr, SB_AUTO, stream));
+    }
+
+    // eigenvectors of the Gram matrix already in eig.S (order e): the r leading ones go to out
+    // (ld = ldo), scaled by lambda^-1/2 if `scaled`
+    void eig_leading(int64_t e, int64_t r, void *out, int64_t ldo, int scaled)
+    {
+        if (!ok()) return;
+        void *Af = nullptr, *Vf = nullptr;
+        check_hip(sb_eig_sym(dt, (int)e, eig.S, eig.S2, eig.V, eig.V2, eig.lam, (int *)eig.sel, default_sweeps(dt, e), stream, &Af, &Vf));
+        if (!ok()) return;
+        check_hip(sb_eig_gather(dt, (int)e, Vf, (const int *)eig.sel, eig.lam, (int)r, out, ldo, scaled, stream));
+    }
+
+    // U (rows x r) <- the r leading left singular vectors of the rows x R matrix Y.
+    // trans == 0: Y is stored column-major with leading dimension rows;
+    // trans == 1: its transpose X (R x rows, leading dimension R) is what is stored.
+    void leading_left(const void *Y, int64_t rows, int64_t R, int trans, int64_t r, void *U)
+    {
+        const int64_t ld = trans ? R : rows;
+        if (R <= rows) {                // Gram matrix of the short side: Q = Y^T Y, U = Y V_r Lambda_r^-1/2
+            if (!trans) gemm(SB_OP_T, SB_OP_N, R, R, rows, Y, ld, Y, ld, 0.0, eig.S, R);
+            else        gemm(SB_OP_N, SB_OP_T, R, R, rows, Y, ld, Y, ld, 0.0, eig.S, R);
+            eig_leading(R, r, W, R, 1);
+            if (!trans) gemm(SB_OP_N, SB_OP_N, rows, r, R, Y, ld, W, R, 0.0, U, rows);
+            else        gemm(SB_OP_T, SB_OP_N, rows, r, R, Y, ld, W, R, 0.0, U, rows);
+        } else {                        // S = Y Y^T: its eigenvectors are the left singular vectors
+            if (!trans) gemm(SB_OP_N, SB_OP_T, rows, rows, R, Y, ld, Y, ld, 0.0, eig.S, rows);
+            else        gemm(SB_OP_T, SB_OP_N, rows, rows, R, Y, ld, Y, ld, 0.0, eig.S, rows);
+            eig_leading(rows, r, U, rows, 0);
+        }
+    }
+};
+
+}  // namespace
+
+extern "C" int sb_tucker_workspace(sb_dtype dt, int64_t m, int64_t n, int64_t p, int64_t i, int64_t j, int64_t k,
+                                   int with_init, int64_t *bytes)
+{
+    if (dt != SB_F64 && dt != SB_F32) return -1;
+    if (m < 1) return -2;
+    if (n < 1) return -3;
+    if (p < 1) return -4;
+    if (i < 1 || i > m || i > j * k) return -5;
+    if (j < 1 || j > n || j > i * k) return -6;
+    if (k < 1 || k > p || k > i * j) return -7;
+    if (!bytes) return -9;
+    const Sizes s{m, n, p, i, j, k};
+    if (std::max(s.eig_loop(), with_init ? s.eig_init() : 0) > 4096) return -2;
+    *bytes = tucker_bytes(dt, s, with_init);
+    return SB_OK;
+}
+
+extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, int64_t p, int64_t i, int64_t j, int64_t k,
+                              int iterations, int init, void *A, void *B, void *C, void *G, void *workspace,
+                              int64_t workspace_bytes, void *stream)
+{
+    if (dt != SB_F64 && dt != SB_F32) return -1;
+    if (m < 1) return -3;
+    if (n < 1) return -4;
+    if (p < 1) return -5;
+    if (i < 1 || i > m || i > j * k) return -6;
+    if (j < 1 || j > n || j > i * k) return -7;
+    if (k < 1 || k > p || k > i * j) return -8;
+    int64_t need = 0;
+    if (sb_tucker_workspace(dt, m, n, p, i, j, k, init, &need) != SB_OK) return -3;      // an eigenproblem above 4096
+    if (!T) return -2;
+    if (iterations < 0) return -9;
+    if (!A) return -11;
+    if (!B) return -12;
+    if (!C) return -13;
+    if (!G) return -14;
+    if (!workspace || (uintptr_t)workspace % ALIGN) return -15;
+    if (workspace_bytes < need) return -16;
+
+    const Sizes s{m, n, p, i, j, k};
+    const int64_t es = esize(dt);
+    Ctx c;
+    c.dt = dt;
+    c.stream = (hipStream_t)stream;
+    c.status = SB_OK;
+    char *w = (char *)workspace;
+    char *W1 = w;  w += up(m * n * k * es);          // W1_mnk = T_mnp C_pk
+    char *Z = w;   w += up(i * n * p * es);          // Z_inp  = T_mnp A_mi
+    char *Y = w;   w += up(s.y_elems() * es);        // the Y of steps 4, 6, 8
+    const int64_t nmax = init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
+    c.W = w;       w += up(nmax * s.rmax() * es);
+    c.eig.carve(dt, w, nmax);
+
+    const int64_t dT[3] = {m, n, p}, dAf[2] = {m, i}, dBf[2] = {n, j}, dCf[2] = {p, k};
+    const int64_t dW1[3] = {m, n, k}, dZ[3] = {i, n, p}, dY1[3] = {m, j, k}, dY2[3] = {n, i, k}, dY3[3] = {i, j, p}, dG[3] = {i, j, k};
+
+    if (init) {
+        // step 2: leading eigenvectors of T_(r) T_(r)^T.  T_(1) is the m x (np) matrix T itself,
+        // T_(3)^T the (mn) x p matrix T itself; T_(2) T_(2)^T is the sum over p of T_p^T T_p.
+        c.gemm(SB_OP_N, SB_OP_T, m, m, n * p, T, m, T, m, 0.0, c.eig.S, m);
+        c.eig_leading(m, i, A, m, 0);
+        for (int64_t q = 0; q < p && c.ok(); ++q) {
+            const char *Tq = (const char *)T + q * m * n * es;
+            c.gemm(SB_OP_T, SB_OP_N, n, n, m, Tq, m, Tq, m, q ? 1.0 : 0.0, c.eig.S, n);
+        }
+        c.eig_leading(n, j, B, n, 0);
+        c.gemm(SB_OP_T, SB_OP_N, p, p, m * n, T, m * n, T, m * n, 0.0, c.eig.S, p);
+        c.eig_leading(p, k, C, p, 0);
+    }
+
+    for (int it = 0; it < iterations && c.ok(); ++it) {
+        c.contract("mnp", "pk", "mnk", T, dT, C, dCf, W1, dW1);          // step 4: Y_mjk = T_mnp B_nj C_pk
+        c.contract("mnk", "nj", "mjk", W1, dW1, B, dBf, Y, dY1);
+        c.leading_left(Y, m, j * k, 0, i, A);                            // step 5
+        c.contract("mnk", "mi", "nik", W1, dW1, A, dAf, Y, dY2);         // step 6 with mode n first: Y_(2) is a plain matrix
+        c.leading_left(Y, n, i * k, 0, j, B);                            // step 7
+        c.contract("mnp", "mi", "inp", T, dT, A, dAf, Z, dZ);            // step 8: Y_ijp = T_mnp B_nj A_mi
+        c.contract("inp", "nj", "ijp", Z, dZ, B, dBf, Y, dY3);
+        c.leading_left(Y, p, i * j, 1, k, C);                            // step 9: Y_(3) is the transpose of the (ij) x p matrix
+    }
+    c.contract("mnp", "mi", "inp", T, dT, A, dAf, Z, dZ);                // step 11: G_ijk = T_mnp A_mi B_nj C_pk
+    c.contract("inp", "nj", "ijp", Z, dZ, B, dBf, Y, dY3);
+    c.contract("ijp", "pk", "ijk", Y, dY3, C, dCf, G, dG);
+    return c.status;
+}
+
+extern "C" int sb_sym_eig_workspace(sb_dtype dt, int64_t n, int64_t *bytes)
+{
+    if (dt != SB_F64 && dt != SB_F32) return -1;
+    if (n < 1 || n > 4096) return -2;
+    if (!bytes) return -3;
+    *bytes = EigSpace::bytes(dt, n);
+    return SB_OK;
+}
+
+extern "C" int sb_sym_eig(sb_dtype dt, int64_t n, void *S, void *V, void *lambda, int sweeps, void *workspace,
+                          int64_t workspace_bytes, void *stream)
+{
+    int64_t need = 0;
+    const int rc = sb_sym_eig_workspace(dt, n, &need);
+    if (rc != SB_OK) return rc;
+    if (!S) return -3;
+    if (!V) return -4;
+    if (!lambda) return -5;
+    if (!workspace || (uintptr_t)workspace % ALIGN) return -7;
+    if (workspace_bytes < need) return -8;
+    EigSpace e;
+    e.carve(dt, (char *)workspace, n);
+    void *Af = nullptr, *Vf = nullptr;
+    hipError_t err = sb_eig_sym(dt, (int)n, S, e.S2, e.V, e.V2, lambda, (int *)e.sel, sweeps > 0 ? sweeps : default_sweeps(dt, n),
+                                (hipStream_t)stream, &Af, &Vf);
+    if (err == hipSuccess) err = sb_eig_gather(dt, (int)n, Vf, (const int *)e.sel, lambda, (int)n, V, n, 0, (hipStream_t)stream);
+    return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
+}

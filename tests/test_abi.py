@@ -11,15 +11,19 @@ FAKE = 0x10000      # never dereferenced: validation fails (or the problem is em
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "sbgemm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"^(?:int|const char \*)\s*(sb_\w+)\s*\(", text, flags=re.M)
+    names = []
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"^(?:int|const char \*)\s*(sb_\w+)\s*\(", text, flags=re.M)
+    return names
 
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch",
-                          "sb_status_string", "sb_force_kernel", "sb_last_kernel"}
+                          "sb_status_string", "sb_force_kernel", "sb_last_kernel", "sb_tucker_workspace",
+                          "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"}
     lib = binding.load()
     for n in names:
         assert getattr(lib, n) is not None
@@ -109,3 +113,22 @@ def test_status_strings():
 def test_force_kernel_rejects_unknown_ids():
     assert sb.sb_force_kernel(12) == -1
     assert sb.sb_force_kernel(sb.SB_KERNEL_AUTO) == sb.SB_OK
+
+
+def test_tucker_argument_validation_on_the_host():
+    hooi = lambda dt="f32", dims=(4, 4, 4), core=(2, 2, 2), its=1, T=FAKE, ws=FAKE - FAKE % 256, nbytes=1 << 30: \
+        binding.load().sb_tucker_hooi(binding.DTYPES[dt], T, *dims, *core, its, 1, FAKE, FAKE, FAKE, FAKE, ws, nbytes, None)
+    assert hooi(dt="bf16") == -1
+    assert hooi(T=None) == -2
+    assert hooi(dims=(0, 4, 4)) == -3 and hooi(dims=(4, 0, 4)) == -4 and hooi(dims=(4, 4, 0)) == -5
+    assert hooi(core=(5, 2, 2)) == -6 and hooi(core=(2, 5, 2)) == -7 and hooi(core=(2, 2, 5)) == -8
+    assert hooi(core=(1, 1, 2)) == -8                    # k may not exceed i*j
+    assert hooi(its=-1) == -9
+    assert hooi(ws=None) == -15 and hooi(ws=FAKE + 8) == -15 and hooi(nbytes=64) == -16
+    rc, need = sb.sb_tucker_workspace("f32", 256, 256, 256, 10, 10, 10, with_init=False)
+    assert rc == 0 and need % 256 == 0
+    # W1 (m n k), Z (i n p), Y, the selected eigenvectors, four 100 x 100 matrices, lambda, selection
+    assert need >= 4 * (256 * 256 * 10 + 10 * 256 * 256 + 256 * 100 + 100 * 10 + 4 * 100 * 100 + 100) + 4 * 100
+    assert sb.sb_tucker_workspace("f32", 256, 256, 256, 10, 10, 10, with_init=True)[1] >= need + 4 * 4 * (256 * 256 - 100 * 100)
+    assert sb.sb_sym_eig_workspace("f64", 100)[1] >= 4 * 8 * 100 * 100
+    assert sb.sb_sym_eig_workspace("f32", 5000, check=False)[0] == -2
