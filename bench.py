@@ -317,6 +317,44 @@ def run_sweeps(steps, warmup):
     return out
 
 
+def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128):
+    """The application study of section V-C: HOOI (Algorithm 1) on cubic n^3 tensors with a 10^3 core,
+    fp32, every contraction through sb_contract.  Reports time per iteration (steps 4-9: five
+    contractions and three Gram / eigensolver / back-multiplication rounds), the one-off
+    initialisation (step 2) and, at one size, the numpy oracle's time per iteration on the host."""
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    rows = []
+    for n in sizes:
+        T = inputs.lowrank_noise_tensor(61, [n, n, n], (core,) * 3, noise=0.05, dtype=np.float32)
+        tT = dev(T, "f32")
+        fac = [torch.zeros(n * core, dtype=torch.float32, device="cuda") for _ in range(3)]
+        tG = torch.zeros(core ** 3, dtype=torch.float32, device="cuda")
+        ws = torch.empty(sb.sb_tucker_workspace("f32", n, n, n, core, core, core)[1], dtype=torch.uint8, device="cuda")
+
+        def run(its, init):
+            sb.sb_tucker_hooi(tT, (n, n, n), (core,) * 3, its, fac[0], fac[1], fac[2], tG, ws, init=init, dt="f32")
+
+        run(2, True)                                   # warm-up (first-use set-up of every kernel)
+        _, t_init = time_steps(lambda: run(0, True), 3, 1)
+        _, t_loop = time_steps(lambda: run(iterations, False), 3, 1)
+        _, t_tail = time_steps(lambda: run(0, False), 3, 1)      # step 11 alone
+        row = dict(n=n, core=core, iterations_timed=iterations, ms_per_iteration=(t_loop - t_tail) / iterations,
+                   init_ms=t_init - t_tail, core_ms=t_tail,
+                   fit=float(torch.linalg.vector_norm(tG) / torch.linalg.vector_norm(tT)))
+        if n == oracle_n:
+            from oracle import tucker_oracle
+            T64 = T.astype(np.float64)
+            start = tucker_oracle.hosvd_init(T64, (core,) * 3)
+            t0 = time.perf_counter()
+            tucker_oracle.hooi(T64, (core,) * 3, 1, init=start)
+            row["cpu_oracle_ms_per_iteration"] = (time.perf_counter() - t0) * 1e3
+        rows.append(row)
+        del tT, ws
+    return dict(workload="Tucker/HOOI (Algorithm 1): cubic tensors, core %d^3, f32" % core, cases=rows)
+
+
 def cpu_baseline(cfg, tensors, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
     last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
@@ -396,6 +434,7 @@ def main():
             others.append(r)
         others.append(run_table2_cases(max(args.steps, 200), args.warmup))
         others.append(run_exceptional_cases(args.steps, args.warmup))
+        others.append(run_tucker())
         result["workloads"] = others
     print(json.dumps(result))
 

@@ -91,65 +91,87 @@ __global__ void identity_kernel(T *V, int n)
 
 // Small matrices: the whole iteration in one workgroup, A and V in LDS, updated in place
 // (rotations of a step are computed first, then every 2 x 2 block is rewritten by one thread).
+// One compute unit does all the arithmetic, so the step is kept short in instructions: an odd
+// matrix is padded with a zero row and column (its phantom index then rotates by the identity
+// without any test), the pairs and rotations of a step sit in a small LDS table, and the
+// (pair, pair) coordinates of a thread's work items advance by addition.  A sweep in which no
+// rotation angle exceeded rounding level ends the iteration early.
 constexpr int LDS_THREADS = 1024;
 
+// what a step needs to know about one pair: the two indices and the rotation; one LDS read
 template <typename T>
-__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps)
+struct __attribute__((aligned(16))) PairRec { int p, q; T c, s; };
+
+template <typename T>
+size_t jacobi_lds_bytes(int n)
+{
+    const size_t ne = n + (n & 1);
+    return 2 * ne * ne * sizeof(T) + 16 + (ne / 2) * sizeof(PairRec<T>);
+}
+
+template <typename T>
+__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps, T angle_tol)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
-    T *As = (T *)raw, *Vs = As + (size_t)n * n, *cs = Vs + (size_t)n * n;       // cs: [h][2]
     const int h = ne / 2, tid = threadIdx.x;
-    for (int e = tid; e < n * n; e += LDS_THREADS) {
-        As[e] = A[e];
-        Vs[e] = (e % n == e / n) ? T(1) : T(0);
+    T *As = (T *)raw;                    // ne x ne, leading dimension ne
+    T *Vs = As + ne * ne;                // ne x ne as well (a zero phantom row keeps row pairs aligned)
+    PairRec<T> *rec = (PairRec<T> *)(((uintptr_t)(Vs + ne * ne) + 15) & ~(uintptr_t)15);      // [h]
+    __shared__ int rotated;
+    for (int e = tid; e < ne * ne; e += LDS_THREADS) {
+        const int i = e % ne, j = e / ne;
+        As[e] = (i < n && j < n) ? A[i + j * n] : T(0);
     }
+    for (int e = tid; e < ne * ne; e += LDS_THREADS) Vs[e] = (e % ne == e / ne && e % ne < n) ? T(1) : T(0);
+    if (tid == 0) rotated = 0;
     __syncthreads();
-    const int nA = h * h, total = nA + n * h;
+    const int nA = h * h;
+    const int P0 = tid % h, Q0 = tid / h, dP = LDS_THREADS % h, dQ = LDS_THREADS / h;
+    typedef T T2 __attribute__((ext_vector_type(2)));
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         for (int round = 0; round < ne - 1; ++round) {
             if (tid < h) {
                 int p, q;
                 pair_of(tid, round, ne, p, q);
-                T c = T(1), s = T(0);
-                if (p < n && q < n) rotation(As[p + p * n], As[q + q * n], As[p + q * n], c, s);
-                cs[2 * tid] = c;
-                cs[2 * tid + 1] = s;
+                T c, s;
+                rotation(As[p + p * ne], As[q + q * ne], As[p + q * ne], c, s);      // phantom index: apq = 0 -> identity
+                PairRec<T> r;
+                r.p = p; r.q = q; r.c = c; r.s = s;
+                rec[tid] = r;
+                if (fabs(s) > angle_tol) rotated = 1;
             }
             __syncthreads();
-            for (int item = tid; item < total; item += LDS_THREADS) {
-                if (item < nA) {
-                    const int P = item % h, Q = item / h;
-                    int p1, q1, p2, q2;
-                    pair_of(P, round, ne, p1, q1);
-                    pair_of(Q, round, ne, p2, q2);
-                    const T cP = cs[2 * P], sP = cs[2 * P + 1], cQ = cs[2 * Q], sQ = cs[2 * Q + 1];
-                    const bool rp = p1 < n, rq = q1 < n, cp = p2 < n, cq = q2 < n;
-                    const T a = (rp && cp) ? As[p1 + p2 * n] : T(0), b = (rp && cq) ? As[p1 + q2 * n] : T(0);
-                    const T c = (rq && cp) ? As[q1 + p2 * n] : T(0), d = (rq && cq) ? As[q1 + q2 * n] : T(0);
-                    const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;
-                    const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
-                    if (rp && cp) As[p1 + p2 * n] = x00 * cQ - x01 * sQ;
-                    if (rp && cq) As[p1 + q2 * n] = x00 * sQ + x01 * cQ;
-                    if (rq && cp) As[q1 + p2 * n] = x10 * cQ - x11 * sQ;
-                    if (rq && cq) As[q1 + q2 * n] = x10 * sQ + x11 * cQ;
-                } else {
-                    const int it = item - nA;
-                    const int row = it % n, Q = it / n;
-                    int p2, q2;
-                    pair_of(Q, round, ne, p2, q2);
-                    const bool cp = p2 < n, cq = q2 < n;
-                    const T cQ = cs[2 * Q], sQ = cs[2 * Q + 1];
-                    const T vp = cp ? Vs[row + p2 * n] : T(0), vq = cq ? Vs[row + q2 * n] : T(0);
-                    if (cp) Vs[row + p2 * n] = vp * cQ - vq * sQ;
-                    if (cq) Vs[row + q2 * n] = vp * sQ + vq * cQ;
-                }
+            int P = P0, Q = Q0;
+            for (int item = tid; item < nA; item += LDS_THREADS) {
+                const PairRec<T> rP = rec[P], rQ = rec[Q];
+                const int p1 = rP.p, q1 = rP.q, p2 = rQ.p * ne, q2 = rQ.q * ne;
+                const T cP = rP.c, sP = rP.s, cQ = rQ.c, sQ = rQ.s;
+                const T a = As[p1 + p2], b = As[p1 + q2], c = As[q1 + p2], d = As[q1 + q2];
+                const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;        // J_P^T M
+                const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
+                As[p1 + p2] = x00 * cQ - x01 * sQ;                           // . J_Q
+                As[p1 + q2] = x00 * sQ + x01 * cQ;
+                As[q1 + p2] = x10 * cQ - x11 * sQ;
+                As[q1 + q2] = x10 * sQ + x11 * cQ;
+                // rows 2P and 2P+1 of V times J_Q: the same (P, Q) grid serves V, two rows at a time
+                T2 *vp = (T2 *)(Vs + 2 * P + rQ.p * ne), *vq = (T2 *)(Vs + 2 * P + rQ.q * ne);
+                const T2 up = *vp, uq = *vq;
+                *vp = up * cQ - uq * sQ;
+                *vq = up * sQ + uq * cQ;
+                P += dP; Q += dQ;
+                if (P >= h) { P -= h; ++Q; }
             }
             __syncthreads();
         }
+        const int any = rotated;
+        __syncthreads();
+        if (!any) break;                 // workgroup-uniform
+        if (tid == 0) rotated = 0;
+        __syncthreads();                 // the reset must not overtake the next sweep's first rotations
     }
     for (int e = tid; e < n * n; e += LDS_THREADS) {
-        A[e] = As[e];
-        V[e] = Vs[e];
+        A[e] = As[e % n + (e / n) * ne];
+        V[e] = Vs[e % n + (e / n) * ne];
     }
 }
 
@@ -188,24 +210,23 @@ __global__ __launch_bounds__(256) void eig_gather_kernel(const T *V, int n, cons
 }
 
 template <typename T>
-size_t lds_need(int n, int ne) { return ((size_t)2 * n * n + ne) * sizeof(T); }
-
-template <typename T>
 hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweeps, hipStream_t stream, T **A_final, T **V_final)
 {
     const int ne = n + (n & 1);
     if (n == 1) {
         identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
         *A_final = A; *V_final = V;
-    } else if (lds_need<T>(n, ne) <= (size_t)160 * 1024) {
-        const size_t bytes = lds_need<T>(n, ne);
+    } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 64) {       // 64 bytes stay for the static flag
+        const size_t bytes = jacobi_lds_bytes<T>(n);
         static bool configured = false;
         if (!configured) {
-            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);    // 64 bytes stay for the static flag
             if (e != hipSuccess) return e;
             configured = true;
         }
-        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps);
+        // rotations below a few units of rounding no longer change the result
+        const T angle_tol = sizeof(T) == 8 ? T(4e-16) : T(2e-7);
+        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps, angle_tol);
         *A_final = A; *V_final = V;
     } else {
         const int h = ne / 2;

@@ -22,7 +22,8 @@ constexpr int64_t ALIGN = 256;
 int64_t esize(sb_dtype dt) { return dt == SB_F64 ? 8 : 4; }
 int64_t up(int64_t bytes) { return (bytes + ALIGN - 1) / ALIGN * ALIGN; }
 // cyclic Jacobi converges quadratically: random and Gram matrices of order 100-500 reach working
-// precision in 6 sweeps (fp64) or 4 (fp32); the defaults leave a margin
+// precision in 6 sweeps (fp64) or 4 (fp32); the defaults leave a margin (the in-LDS solver stops
+// by itself once a sweep no longer rotates anything)
 int default_sweeps(sb_dtype dt, int64_t n) { return dt == SB_F64 ? (n > 128 ? 12 : 10) : (n > 128 ? 7 : 6); }
 
 // carve-out of the workspace; sizes in bytes, every block 256-byte aligned

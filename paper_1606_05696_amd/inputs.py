@@ -117,7 +117,9 @@ def lowrank_noise_tensor(seed: int, dims, core, noise: float = 0.05, dtype=np.fl
         w = 1.0 / (1.0 + np.arange(c))
         G = G * w.reshape([-1 if a == r else 1 for a in range(3)])
     factors = [np.linalg.qr(rng.standard_normal((d, c)))[0] for d, c in zip(dims, core)]
-    T = np.einsum("ijk,mi,nj,pk->mnp", G, *factors)
+    T = G                                              # mode products one at a time (T = G x1 F0 x2 F1 x3 F2)
+    for r, F in enumerate(factors):
+        T = np.moveaxis(np.tensordot(F, T, axes=(1, r)), 0, r)
     T = T / np.sqrt(np.mean(T * T))
     T = T + noise * rng.uniform(-1.0, 1.0, size=T.shape)
     return np.asfortranarray(T.astype(dtype))
