@@ -317,7 +317,7 @@ def run_sweeps(steps, warmup):
     return out
 
 
-def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128):
+def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128, with_oracle=True):
     """The application study of section V-C: HOOI (Algorithm 1) on cubic n^3 tensors with a 10^3 core,
     fp32, every contraction through sb_contract.  Reports time per iteration (steps 4-9: five
     contractions and three Gram / eigensolver / back-multiplication rounds), the one-off
@@ -343,7 +343,7 @@ def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128):
         row = dict(n=n, core=core, iterations_timed=iterations, ms_per_iteration=(t_loop - t_tail) / iterations,
                    init_ms=t_init - t_tail, core_ms=t_tail,
                    fit=float(torch.linalg.vector_norm(tG) / torch.linalg.vector_norm(tT)))
-        if n == oracle_n:
+        if with_oracle and n == oracle_n:
             from oracle import tucker_oracle
             T64 = T.astype(np.float64)
             start = tucker_oracle.hosvd_init(T64, (core,) * 3)
@@ -434,7 +434,7 @@ def main():
             others.append(r)
         others.append(run_table2_cases(max(args.steps, 200), args.warmup))
         others.append(run_exceptional_cases(args.steps, args.warmup))
-        others.append(run_tucker())
+        others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others
     print(json.dumps(result))
 
