@@ -345,10 +345,188 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbA
     }
 }
 
+// Streaming variant for problems made of whole tiles (m, n multiples of the tile, k a multiple of
+// 2*BK and at least 4*BK, aligned operands): the panel stream never drains at a tile boundary.
+// While the last k blocks of a tile are multiplied, the first panels of the workgroup's NEXT tile
+// are already being fetched and handed to LDS, so a new tile starts multiplying as soon as the old
+// tile's results are queued for storing; no memory latency is exposed between tiles.
+//   - The loads of the next tile's third panel are issued BEFORE the stores of the finished tile:
+//     gfx9 counts loads and stores in one in-order counter, so a wait for a load issued after the
+//     stores would also wait for every store.  With this order the first waits that include the
+//     stores come two k blocks into the new tile.
+//   - The body of a tile exists twice (first tile after the explicit priming, all later tiles in
+//     a loop), and beta != 0 is a kernel of its own: where two paths with different numbers of
+//     outstanding memory operations meet, the compiler must wait for the smaller count, which
+//     here would mean "until the previous tile's stores have drained".
+//   - The last tile of a workgroup prefetches its own first panels again (in bounds, never used).
+template <typename MFT, bool A_KC, bool B_KC, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
+{
+    typedef Config<MFT, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N, 2> CF;
+    typedef typename CF::MF MF;
+    typedef typename MF::T T;
+    typedef typename CF::PA PA;
+    typedef typename CF::PB PB;
+    constexpr int MI = MF::MI, VEC = MF::VEC, BM = CF::BM, BN = CF::BN, KG = BK / MF::KGROUP;
+    __shared__ __attribute__((aligned(16))) T As[2][PA::LDS_SIZE];
+    __shared__ __attribute__((aligned(16))) T Bs[2][PB::LDS_SIZE];
+
+    const int64_t ldA = A_KC ? g.rsA : g.csA;
+    const int64_t ldB = B_KC ? g.csB : g.rsB;
+    const int64_t stepA = (A_KC ? 1 : g.csA) * BK, stepB = (B_KC ? 1 : g.rsB) * BK;      // one panel along k
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
+    const T alpha = (T)g.alpha, beta = (T)g.beta;
+    const int64_t nkb = g.k / BK;
+
+    // same persistent, XCD-aware schedule as sbgemm_mfma_kernel
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t total = tiles * g.batch0 * g.batch1;
+    const int64_t nslots = (int64_t)gridDim.x / NXCD;
+    const int64_t xcd = blockIdx.x % NXCD, slot = blockIdx.x / NXCD;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t first = xcd * q8 + (xcd < r8 ? xcd : r8);
+    const int64_t last = first + q8 + (xcd < r8 ? 1 : 0);
+    int64_t logical = first + slot;
+    if (logical >= last) return;
+
+    typename PA::Vec ra[2][PA::NVEC];
+    typename PB::Vec rb[2][PB::NVEC];
+    T fa[2][CF::NBM][VEC], fb[2][CF::NBN][VEC];
+    typename MF::Acc acc[CF::NBM][CF::NBN];
+
+    // tile number -> operand pointers.  The walk over the tiles advances (batch, tile) by addition;
+    // 64-bit divisions at every tile boundary would sit right where the matrix cores wait.
+    struct Loc { const T *A, *B; T *C; };
+    auto locate = [&](int64_t b, int tile) {
+        int64_t b0 = b, b1 = 0;
+        if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
+        const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
+        const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
+        Loc l;
+        l.A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
+        l.B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
+        l.C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1] + i0 + j0 * g.ldc;
+        return l;
+    };
+    int64_t b = logical / tiles;
+    int tile = (int)(logical - b * tiles);
+    const int64_t dq = nslots / tiles;
+    const int dr = (int)(nslots - dq * tiles);
+    auto gload = [&](auto set, const T *pa, const T *pb) {
+        PA::template load<false>(ra[set], pa, ldA, 0, 0, true);
+        PB::template load<false>(rb[set], pb, ldB, 0, 0, true);
+    };
+    auto read_frags = [&](auto set, auto buf, int kg) {
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[set][a], As[buf], wm + a * MI, kg, lane);
+#pragma unroll
+        for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[set][c], Bs[buf], wn + c * MI, kg, lane);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    // One k block of the stream (CUR = parity of the block): optionally request the panel two
+    // blocks ahead into the staging set this block's panel came from, multiply, and hand the next
+    // block's panel to LDS in the middle of the second-to-last MFMA cluster.
+    auto block = [&](auto cur_c, auto load_c, const T *pa, const T *pb) {
+        constexpr int CUR = decltype(cur_c)::value;
+        if (decltype(load_c)::value) gload(std::integral_constant<int, CUR>(), pa, pb);
+#pragma unroll
+        for (int kg = 0; kg < KG; ++kg) {
+            const int fs = kg & 1;
+            if (kg + 1 < KG) {
+                if (fs == 0) read_frags(I1(), std::integral_constant<int, CUR>(), kg + 1);
+                else         read_frags(I0(), std::integral_constant<int, CUR>(), kg + 1);
+            } else {
+                __syncthreads();
+                read_frags(I0(), std::integral_constant<int, CUR ^ 1>(), 0);
+            }
+            __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                if (e == VEC / 2 && kg == KG - 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    PA::store(As[CUR ^ 1], ra[CUR ^ 1]);
+                    PB::store(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+                    for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[fs][c][e], fa[fs][a][e]);   // C^T = B^T A^T
+            }
+            __builtin_amdgcn_s_setprio(0);
+        }
+    };
+    // One tile.  On entry its panel 0 is in LDS buffer 0 with the first fragments read, panel 1 is
+    // in staging set 1 (in flight), panel 2 in staging set 0 (in flight).
+    auto run_tile = [&](const Loc &cur, const Loc &nxt) {
+        const T *A = cur.A, *B = cur.B, *An = nxt.A, *Bn = nxt.B;
+        T *C = cur.C;
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c)
+#pragma unroll
+                for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
+        block(I0(), std::false_type(), A, B);                             // panel 2 was requested before the previous stores
+        block(I1(), std::true_type(), A + 3 * stepA, B + 3 * stepB);
+        const T *pa = A + 4 * stepA, *pb = B + 4 * stepB;
+        for (int64_t kb = 2; kb < nkb; kb += 2) {
+            if (kb + 2 == nkb) { pa = An; pb = Bn; }                      // the stream moves on to the next tile
+            block(I0(), std::true_type(), pa, pb);
+            pa += stepA; pb += stepB;
+            block(I1(), std::true_type(), pa, pb);
+            pa += stepA; pb += stepB;
+        }
+        gload(I0(), pa, pb);                                              // next tile's panel 2, ahead of the stores below
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c) {
+                T *col = C + wm + a * MI + (lane % MI) + (int64_t)(wn + c * MI + MF::result_row_lane(lane)) * g.ldc;
+#pragma unroll
+                for (int r = 0; r < MF::NREG; ++r) {
+                    T *dst = col + MF::result_row_reg(r) * g.ldc;
+                    T v = alpha * acc[a][c][r];
+                    if (BETA) v += beta * *dst;
+                    *dst = v;
+                }
+            }
+    };
+
+    Loc cur = locate(b, tile);
+    {   // prime the stream with the first tile's panels 0, 1 and 2
+        gload(I0(), cur.A, cur.B);
+        gload(I1(), cur.A + stepA, cur.B + stepB);
+        PA::store(As[0], ra[0]);
+        PB::store(Bs[0], rb[0]);
+        __syncthreads();
+        read_frags(I0(), I0(), 0);
+        gload(I0(), cur.A + 2 * stepA, cur.B + 2 * stepB);
+    }
+    // one tile and the step to the workgroup's next one; the last tile names itself as successor
+    auto step = [&]() {
+        const bool more = logical + nslots < last;
+        int tile2 = tile + dr;
+        int64_t b2 = b + dq;
+        if (tile2 >= tiles) { tile2 -= (int)tiles; ++b2; }
+        const Loc nxt = more ? locate(b2, tile2) : cur;
+        run_tile(cur, nxt);
+        logical += nslots;
+        b = b2;
+        tile = tile2;
+        cur = nxt;
+        return more;
+    };
+    bool more = step();               // first tile: follows the priming above
+    while (more) more = step();       // later tiles: follow a finished tile
+}
+
 // Launch `kernel` with as many workgroups as can be resident at once (a multiple of the XCD
 // count), or fewer if there are fewer tiles.  The residency of a kernel is asked once per process.
-template <typename K>
-hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, int vec_ok)
+template <typename K, typename... Extra>
+hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, Extra... extra)
 {
     static int resident = 0;                   // one instance per kernel instantiation
     if (resident == 0) {
@@ -362,7 +540,7 @@ hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStr
     }
     int64_t grid = total_tiles < resident ? total_tiles : resident;
     grid = (grid + NXCD - 1) / NXCD * NXCD;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, vec_ok);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, extra...);
     return hipGetLastError();
 }
 
@@ -382,6 +560,17 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
                        aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
                        aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
+    // whole tiles, aligned operands, an even number (>= 4) of k blocks: the streaming kernel
+    if (vec_ok && a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK) {
+#define STREAM(AK, BKC)                                                                                                                  \
+    (a.beta == 0.0 ? launch_persistent(sbgemm_mfma_stream_kernel<T, AK, BKC, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn) \
+                   : launch_persistent(sbgemm_mfma_stream_kernel<T, AK, BKC, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn))
+        if (a_kc && b_kc)        return STREAM(true, true);
+        else if (a_kc && !b_kc)  return STREAM(true, false);
+        else if (!a_kc && b_kc)  return STREAM(false, true);
+        return STREAM(false, false);
+#undef STREAM
+    }
     if (a_kc && b_kc)        return launch_persistent(sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
     else if (a_kc && !b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
     else if (!a_kc && b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);

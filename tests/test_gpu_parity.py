@@ -387,3 +387,22 @@ def test_replays_inside_a_hip_graph():
         assert rel_fro(from_dev(tC, ref_c.shape), ref_c) <= TOL["f32"], rep
         assert rel_fro(from_dev(tD, [ext["k"], ext["n"], ext["p"]]), ref_d) <= 2 * TOL["f32"], rep
         tB.mul_(1.0)                         # eager work between replays
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
+def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
+    # whole 128 x 128 (or 64 x 64) tiles with k a multiple of 32: the streaming member of the MFMA
+    # family, whose panel stream runs across tile boundaries; shortest legal k, odd tile counts,
+    # more and fewer tiles than resident workgroups, beta = 0 and beta != 0 (separate kernels)
+    for m, n, k, batch in ((256, 384, 64, 5), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1)):
+        lda = (m if opA == "N" else k) + 4
+        ldb = (k if opB == "N" else n) + 8
+        ldc = m + 12
+        loa = lda * (k if opA == "N" else m) + 16
+        lob = ldb * (n if opB == "N" else k)
+        loc = ldc * n + 4
+        for alpha, beta in ((1.0, 0.0), (-0.5, 1.5)):
+            err, got, ref = run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta,
+                                        seed=m + n + k, kernel="mfma")
+            assert err <= TOL[dtype], (m, n, k, batch, alpha, beta, err)
