@@ -13,94 +13,104 @@ typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int TM = 64, TN = 64, KMAX = 128;
 constexpr int LD_KC = KMAX + 8;          // [row][k] layout, rows padded by 16 bytes
-constexpr int LD_MC = TM + 8;            // [k][row] layout
-constexpr int PANEL = (TM * LD_KC > KMAX * LD_MC) ? TM * LD_KC : KMAX * LD_MC;   // elements
-
-// MFMA operand of the 32 rows starting at row0 for k-step ks: lane l holds X[row0 + l%32][16 ks + 8 (l/32) .. +7]
-template <bool KC>
-__device__ __forceinline__ bf16x8 panel_fragment(const uint16_t *lds, int row0, int ks, int lane)
-{
-    const int row = row0 + (lane & 31);
-    const int k = ks * 16 + (lane >> 5) * 8;
-    u16x8 v;
-    if (KC) {
-        v = *(const u16x8 *)(lds + row * LD_KC + k);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = lds[(k + e) * LD_MC + row];
-    }
-    return __builtin_bit_cast(bf16x8, v);
-}
 
 // Two-level ("outer product") batch blocking: op(A) depends only on batch level 0 and op(B) only
 // on level 1, as in C_mn[p][q] = A_mk[p] B_nk[q] (section III-F).  The (p,q) batches then form a
-// grid in which every A_p meets every B_q, and a workgroup that takes a GP x GQ block of that grid
-// needs only GP + GQ panels for GP*GQ small GEMMs: the nested batch becomes a blocked computation
-// with the operand reuse of a large GEMM, although no operand is ever flattened or copied.
-// One workgroup of 16 waves: 4 + 4 whole-K panels in LDS (all eight fetched at once, which also
-// puts enough bytes in flight to cover memory latency), 16 GEMMs of up to 64 x 64 x 128.
-constexpr int GP = 4, GQ = 4, OT = 1024;
-constexpr int ONVEC = (GP + GQ) * TM * KMAX / 8 / OT;     // 16-byte vectors per lane for all panels (8)
+// grid in which every A_p meets every B_q, and a workgroup that takes a 2 x 2 block of that grid
+// needs only 2 + 2 panels for 4 small GEMMs: the nested batch becomes a blocked computation with
+// operand reuse, although no operand is ever flattened or copied.  Four waves, one GEMM of up to
+// 64 x 64 x 128 each; 68 KB of LDS, so two workgroups share a compute unit and one block's
+// stores drain to HBM while the next block's panels are being fetched.
+// Every panel is kept [row][k] in LDS, whatever the operand's orientation in memory, so that an
+// MFMA operand is always ONE 16-byte LDS read (a [k][row] panel needs eight 2-byte reads per
+// operand).  An operand with m (or n) contiguous is transposed on the
+// way in: a lane loads an 8 x 8 block (8 vectors of 8 rows, one per k), transposes it in registers
+// and writes 8 vectors of 8 k.  Those rows are 8 apart for neighbouring lanes, which a plain
+// layout would put on the same banks; the 16-byte chunk index of such a panel is therefore XORed
+// with (row / 8) % 8, on the write and on the read side.
+constexpr int GP2 = 2, GQ2 = 2, OT2 = 256;
+constexpr int PANEL2 = TM * LD_KC;                            // elements; [row][k], rows padded by 16 bytes
+constexpr int SPITCH2 = 68;                                   // staged column: 64 rows + 8 bytes
+constexpr int OUTER2_LDS = (GP2 + GQ2) * PANEL2;              // the staging area (4 x 64 x 68 elements) fits inside
 
-// Results leave through LDS: a wave parks its 32 x 64 x 2 block as bf16, column by column, and
-// writes it out as 16-byte vectors along the rows of C (64 two-byte stores per lane become 8).
-constexpr int SPITCH = 36;                        // elements per staged column: 32 rows + 8 bytes (bank spread)
-constexpr int STAGE = 2 * TN * SPITCH;            // per wave: two GEMMs x 64 columns
-constexpr int OUTER_LDS = ((GP + GQ) * PANEL > (OT / 64) * STAGE) ? (GP + GQ) * PANEL : (OT / 64) * STAGE;   // elements
-
-template <bool A_KC, bool B_KC, int KS>
-__global__ __launch_bounds__(OT) void sbgemm_outer_bf16_kernel(SbArgs g, int groups_p, int vec_store)
+// fill the two panels of one operand (X_{b0}, X_{b0+1}) with all 256 lanes
+template <bool KC>
+__device__ __forceinline__ void fill_two_panels(uint16_t *lds, const uint16_t *X, int64_t bs, int64_t b0, int64_t blim, int64_t ld,
+                                                int rows, int kk)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [GP + GQ][PANEL], later [wave][STAGE]
-    const int gp = (int)(blockIdx.x % groups_p), gq = (int)(blockIdx.x / groups_p);
-    const int64_t p0 = (int64_t)gp * GP, q0 = (int64_t)gq * GQ;
-    const int m = (int)g.m, n = (int)g.n, kk = (int)g.k;
-    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
-
-    // fill: panel j < GP is A_{p0+j}, panel GP + j is B_{q0+j}; indices past the end are clamped
-    // (their results are never stored)
-    {
-        u16x8 v[ONVEC];
+    const int tid = (int)threadIdx.x;
+    if (KC) {                       // k contiguous in memory: 2 x 1024 vectors, straight copy
+        u16x8 v[8];
 #pragma unroll
-        for (int i = 0; i < ONVEC; ++i) {
-            const int panel = i;                               // lane handles one vector slot of every panel
-            const int f = (int)threadIdx.x;
-            const bool is_a = panel < GP;
-            const bool kc = is_a ? A_KC : B_KC;
-            int row, k;
-            if (kc) { row = f / (KMAX / 8); k = (f % (KMAX / 8)) * 8; }
-            else    { k = f / (TM / 8); row = (f % (TM / 8)) * 8; }
-            const int rows = is_a ? m : n;
+        for (int i = 0; i < 8; ++i) {
+            const int panel = i / 4, f = tid + OT2 * (i % 4);
+            const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
+            int64_t b = b0 + panel;
+            if (b >= blim) b = blim - 1;
             const bool inside = row < rows && k < kk;
-            int64_t b = is_a ? p0 + panel : q0 + (panel - GP);
-            const int64_t lim = is_a ? g.batch0 : g.batch1;
-            if (b >= lim) b = lim - 1;
-            const uint16_t *base = is_a ? (const uint16_t *)g.A + b * g.bsA[0] : (const uint16_t *)g.B + b * g.bsB[1];
-            const int64_t ld = is_a ? ldA : ldB;
-            const int64_t off = kc ? (int64_t)row * ld + k : (int64_t)k * ld + row;
-            v[i] = *(const u16x8 *)(base + (inside ? off : 0));
+            v[i] = *(const u16x8 *)(X + b * bs + (inside ? (int64_t)row * ld + k : 0));
         }
 #pragma unroll
-        for (int i = 0; i < ONVEC; ++i) {
-            const int panel = i;
-            const int f = (int)threadIdx.x;
-            const bool is_a = panel < GP;
-            const bool kc = is_a ? A_KC : B_KC;
-            int row, k;
-            if (kc) { row = f / (KMAX / 8); k = (f % (KMAX / 8)) * 8; }
-            else    { k = f / (TM / 8); row = (f % (TM / 8)) * 8; }
-            const int rows = is_a ? m : n;
+        for (int i = 0; i < 8; ++i) {
+            const int panel = i / 4, f = tid + OT2 * (i % 4);
+            const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
             const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            uint16_t *dst = lds + panel * PANEL + (kc ? row * LD_KC + k : k * LD_MC + row);
-            *(u16x8 *)dst = (row < rows && k < kk) ? v[i] : z;
+            *(u16x8 *)(lds + panel * PANEL2 + row * LD_KC + k) = (row < rows && k < kk) ? v[i] : z;
+        }
+    } else {                        // rows contiguous in memory: one 8 x 8 block per lane, transposed in registers
+        const int panel = tid / 128, blk = tid % 128;
+        const int rg = blk % 8, kg = blk / 8;                  // rows 8 rg .. +7, k 8 kg .. +7
+        int64_t b = b0 + panel;
+        if (b >= blim) b = blim - 1;
+        const uint16_t *src = X + b * bs + rg * 8;
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int k = kg * 8 + i;
+            const bool inside = rg * 8 < rows && k < kk;
+            v[i] = *(const u32x4 *)(src + (inside ? (int64_t)k * ld : -(int64_t)(rg * 8)));
+            if (!inside) v[i] = u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {                          // row 8 rg + j: its 8 k as 4 words
+            u32x4 w;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned lo = v[2 * c][j / 2], hi = v[2 * c + 1][j / 2];
+                w[c] = (j % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
+            }
+            *(u32x4 *)(lds + panel * PANEL2 + (rg * 8 + j) * LD_KC + ((kg ^ rg) * 8)) = w;
         }
     }
+}
+
+// MFMA operand of the 32 rows starting at row0 for k-step ks; SWZ: the panel was written with the chunk swizzle
+template <bool SWZ>
+__device__ __forceinline__ bf16x8 panel2_fragment(const uint16_t *lds, int row0, int ks, int lane)
+{
+    const int row = row0 + (lane & 31);
+    int chunk = ks * 2 + (lane >> 5);
+    if (SWZ) chunk ^= (row >> 3) & 7;
+    return __builtin_bit_cast(bf16x8, *(const u16x8 *)(lds + row * LD_KC + chunk * 8));
+}
+
+template <bool A_KC, bool B_KC, int KS>
+__global__ __launch_bounds__(OT2) void sbgemm_outer2_bf16_kernel(SbArgs g, int groups_p, int vec_store)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [GP2 + GQ2][PANEL2], later [wave][64][SPITCH2]
+    const int gp = (int)(blockIdx.x % groups_p), gq = (int)(blockIdx.x / groups_p);
+    const int64_t p0 = (int64_t)gp * GP2, q0 = (int64_t)gq * GQ2;
+    const int m = (int)g.m, n = (int)g.n, kk = (int)g.k;
+
+    fill_two_panels<A_KC>(lds, (const uint16_t *)g.A, g.bsA[0], p0, g.batch0, A_KC ? g.rsA : g.csA, m, kk);
+    fill_two_panels<B_KC>(lds + GP2 * PANEL2, (const uint16_t *)g.B, g.bsB[1], q0, g.batch1, B_KC ? g.csB : g.rsB, n, kk);
     __syncthreads();
 
-    // wave w: A panel w/4, row block (w/2)%2, the two B panels 2*(w%2) and 2*(w%2)+1, both column blocks
+    // wave w: the whole 64 x 64 GEMM A_{p0 + w/2} B_{q0 + w%2}
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int pi = wave >> 2, rb = (wave >> 1) & 1, qh = wave & 1;
-    const uint16_t *la = lds + pi * PANEL;
+    const int pi = wave >> 1, qi = wave & 1;
+    const uint16_t *la = lds + pi * PANEL2, *lb = lds + (GP2 + qi) * PANEL2;
     f32x16 acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -110,80 +120,68 @@ __global__ __launch_bounds__(OT) void sbgemm_outer_bf16_kernel(SbArgs g, int gro
             for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 fa = panel_fragment<A_KC>(la, rb * 32, ks, lane);
+        bf16x8 fa[2], fb[2];
 #pragma unroll
-        for (int qq = 0; qq < 2; ++qq) {
-            const uint16_t *lb = lds + (GP + 2 * qh + qq) * PANEL;
+        for (int a = 0; a < 2; ++a) fa[a] = panel2_fragment<!A_KC>(la, a * 32, ks, lane);
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                const bf16x8 fb = panel_fragment<B_KC>(lb, cb * 32, ks, lane);
+        for (int c = 0; c < 2; ++c) fb[c] = panel2_fragment<!B_KC>(lb, c * 32, ks, lane);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
                 // result register r of lane l: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
-                acc[qq][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[qq][cb], 0, 0, 0);
-            }
-        }
+                acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[c], acc[a][c], 0, 0, 0);
     }
     __syncthreads();                 // every wave is done with the panels: the space becomes the staging area
 
     const float alpha = (float)g.alpha, beta = (float)g.beta;
-    const int64_t p = p0 + pi;
-    const int row0 = rb * 32;
-    uint16_t *st = lds + wave * STAGE;
-    uint16_t *Cp = (uint16_t *)g.C + p * g.bsC[0] + row0;
+    const int64_t p = p0 + pi, q = q0 + qi;
+    const bool live = p < g.batch0 && q < g.batch1;
+    uint16_t *st = lds + wave * (TN * SPITCH2);
+    uint16_t *Cq = (uint16_t *)g.C + (live ? p * g.bsC[0] + q * g.bsC[1] : 0);
+    typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int qq = 0; qq < 2; ++qq) {
-        const int64_t q = q0 + 2 * qh + qq;
-        const bool live = p < g.batch0 && q < g.batch1;
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            const int j = cb * 32 + (lane & 31);
+        for (int c = 0; c < 2; ++c) {
+            const int j = c * 32 + (lane & 31);
 #pragma unroll
             for (int gq4 = 0; gq4 < 4; ++gq4) {
-                const int i0 = 8 * gq4 + 4 * (lane >> 5);
+                const int i0 = a * 32 + 8 * gq4 + 4 * (lane >> 5);
                 float v[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = alpha * acc[qq][cb][4 * gq4 + e];
+                for (int e = 0; e < 4; ++e) v[e] = alpha * acc[a][c][4 * gq4 + e];
                 if (beta != 0.f && live && j < n) {
-                    const uint16_t *old = Cp + q * g.bsC[1] + (int64_t)j * g.ldc + i0;
+                    const uint16_t *old = Cq + (int64_t)j * g.ldc + i0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (row0 + i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
+                        if (i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
                 }
-                typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
                 u16x4 pk;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
-                *(u16x4 *)(st + (qq * TN + j) * SPITCH + i0) = pk;
+                *(u16x4 *)(st + j * SPITCH2 + i0) = pk;
             }
         }
-    }
     __syncthreads();
+    if (!live) return;
+    if (vec_store) {                 // m is a multiple of 8 and every column of C starts 16-byte aligned
+        const int seg = 8 * (lane & 7);
 #pragma unroll
-    for (int qq = 0; qq < 2; ++qq) {
-        const int64_t q = q0 + 2 * qh + qq;
-        if (!(p < g.batch0 && q < g.batch1)) continue;
-        uint16_t *Cq = Cp + q * g.bsC[1];
-        const uint16_t *sq = st + qq * TN * SPITCH;
-        if (vec_store) {             // m is a multiple of 8 and every column of C starts 16-byte aligned
-            typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
-            const int seg = 8 * (lane & 3);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int j = 16 * t + (lane >> 2);
-                const u16x4 lo = *(const u16x4 *)(sq + j * SPITCH + seg);
-                const u16x4 hi = *(const u16x4 *)(sq + j * SPITCH + seg + 4);
-                if (row0 + seg < m && j < n) {
-                    u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
-                }
+        for (int t = 0; t < 8; ++t) {
+            const int j = 8 * t + (lane >> 3);
+            const u16x4 lo = *(const u16x4 *)(st + j * SPITCH2 + seg);
+            const u16x4 hi = *(const u16x4 *)(st + j * SPITCH2 + seg + 4);
+            if (seg < m && j < n) {
+                u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
             }
-        } else {
-            const int i = lane & 31;
+        }
+    } else {
 #pragma unroll 4
-            for (int jj = 0; jj < TN; jj += 2) {
-                const int j = jj + (lane >> 5);
-                const uint16_t v = sq[j * SPITCH + i];
-                if (row0 + i < m && j < n) Cq[(int64_t)j * g.ldc + i] = v;
-            }
+        for (int j = 0; j < TN; ++j) {
+            const uint16_t v = st[j * SPITCH2 + lane];
+            if (lane < m && j < n) Cq[(int64_t)j * g.ldc + lane] = v;
         }
     }
 }
@@ -212,22 +210,22 @@ bool sb_panel_bf16_supports(const SbArgs &a)
 template <bool A_KC, bool B_KC>
 static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
 {
-    const int64_t groups_p = (a.batch0 + GP - 1) / GP, groups_q = (a.batch1 + GQ - 1) / GQ;
-    const size_t lds_bytes = (size_t)OUTER_LDS * sizeof(uint16_t);
     auto al8 = [](int64_t v) { return v % 8 == 0; };
     const int vec_store = (uintptr_t)a.C % 16 == 0 && al8(a.ldc) && al8(a.bsC[0]) && al8(a.bsC[1]) && al8(a.m);
-    dim3 grid((unsigned)(groups_p * groups_q)), block(OT);
     const int ks = (int)((a.k + 15) / 16);
+    const int64_t groups_p = (a.batch0 + GP2 - 1) / GP2, groups_q = (a.batch1 + GQ2 - 1) / GQ2;
+    const size_t lds_bytes = (size_t)OUTER2_LDS * sizeof(uint16_t);
+    dim3 grid((unsigned)(groups_p * groups_q)), block(OT2);
 #define SB_OUTER(KS_)                                                                                                  \
     do {                                                                                                                \
-        auto kern = sbgemm_outer_bf16_kernel<A_KC, B_KC, KS_>;                                                          \
+        auto kern = sbgemm_outer2_bf16_kernel<A_KC, B_KC, KS_>;                                                         \
         static bool configured = false;                                                                                 \
         if (!configured) {                                                                                              \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
             if (e != hipSuccess) return e;                                                                              \
             configured = true;                                                                                          \
         }                                                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p, vec_store);                               \
+        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p, vec_store);                          \
     } while (0)
     if (ks <= 2)      SB_OUTER(2);
     else if (ks <= 4) SB_OUTER(4);
@@ -240,7 +238,7 @@ static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
 static bool outer_applies(const SbArgs &a)
 {
     return a.batch0 >= 4 && a.batch1 >= 4 && a.bsA[1] == 0 && a.bsB[0] == 0 && a.bsA[0] != 0 && a.bsB[1] != 0 &&
-           a.batch0 * a.batch1 / (GP * GQ) < ((int64_t)1 << 30);
+           a.batch0 * a.batch1 / (GP2 * GQ2) < ((int64_t)1 << 30);
 }
 
 hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream)
