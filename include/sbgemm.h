@@ -173,6 +173,11 @@ int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char 
 int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
                    double beta, void *C, void *stream);
 
+/* Host only: the number of kernel launches sb_plan_launch issues for this plan.  A launch takes two
+ * batch levels; levels whose strides nest in all three tensors (adjacent modes of packed tensors)
+ * are merged first, the rest loops on the host as in Listing 2.  -1 for an invalid plan. */
+int64_t sb_plan_launches(const sb_plan *plan);
+
 /* Static text for a status code returned by any function above. */
 const char *sb_status_string(int status);
 

@@ -29,7 +29,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 
 __all__ = [n for n in dir() if n.startswith("SB_")] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
-    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_force_kernel", "sb_last_kernel",
+    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
     "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"]
 
 
@@ -82,6 +82,8 @@ def load():
     lib.sb_contract.argtypes = [ci, cp, cp, cp, dbl, vp, i64p, i64p, vp, i64p, i64p, dbl, vp, i64p, i64p, ci, vp]
     lib.sb_plan_launch.restype = ci
     lib.sb_plan_launch.argtypes = [ci, ctypes.POINTER(sb_plan), dbl, vp, vp, dbl, vp, vp]
+    lib.sb_plan_launches.restype = i64
+    lib.sb_plan_launches.argtypes = [ctypes.POINTER(sb_plan)]
     lib.sb_status_string.restype = cp
     lib.sb_status_string.argtypes = [ci]
     lib.sb_force_kernel.restype = ci
@@ -229,6 +231,11 @@ def sb_force_kernel(kernel_id):
 
 def sb_last_kernel():
     return load().sb_last_kernel()
+
+
+def sb_plan_launches(plan):
+    """Number of kernel launches sb_plan_launch issues for this plan (see sbgemm.h)."""
+    return load().sb_plan_launches(ctypes.byref(plan))
 
 
 def sb_tucker_workspace(dt, m, n, p, i, j, k, with_init=True, check=True):

@@ -107,6 +107,63 @@ extern "C" int sb_gemm(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64
     return -map[-rc];
 }
 
+namespace {
+
+// The batch levels of a plan as the launcher sees them.  Two levels whose strides nest in all
+// three tensors (stride_outer == stride_inner * count_inner, or both 0) are one level with the
+// product of the counts, so an N-level nest over adjacent modes of packed tensors still fits the
+// two levels a launch can take; what cannot be merged below two levels loops on the host (Listing 2).
+struct Levels {
+    int n;
+    int64_t count[SB_MAX_BATCH_LEVELS], sL[SB_MAX_BATCH_LEVELS], sR[SB_MAX_BATCH_LEVELS], sC[SB_MAX_BATCH_LEVELS];
+};
+
+Levels merged_levels(const sb_plan &plan)
+{
+    Levels lv;
+    lv.n = plan.nbatch;
+    for (int q = 0; q < lv.n; ++q) {
+        lv.count[q] = plan.batch[q];
+        lv.sL[q] = plan.strideL[q];
+        lv.sR[q] = plan.strideR[q];
+        lv.sC[q] = plan.strideC[q];
+    }
+    // level 0 of an extended operation is the operand's unit-stride mode and keeps its own slot
+    const int first = (plan.opL > SB_OP_T || plan.opR > SB_OP_T) ? 1 : 0;
+    bool changed = true;
+    while (changed) {
+        changed = false;
+        for (int a = first; a < lv.n && !changed; ++a)
+            for (int b = first; b < lv.n && !changed; ++b) {
+                if (a == b) continue;
+                const bool nests = lv.sL[b] == lv.sL[a] * lv.count[a] && lv.sR[b] == lv.sR[a] * lv.count[a] &&
+                                   lv.sC[b] == lv.sC[a] * lv.count[a];
+                if (!nests) continue;
+                lv.count[a] *= lv.count[b];                 // b runs outside a: one level with a's strides
+                for (int q = b; q + 1 < lv.n; ++q) {
+                    lv.count[q] = lv.count[q + 1];
+                    lv.sL[q] = lv.sL[q + 1];
+                    lv.sR[q] = lv.sR[q + 1];
+                    lv.sC[q] = lv.sC[q + 1];
+                }
+                --lv.n;
+                changed = true;
+            }
+    }
+    return lv;
+}
+
+}  // namespace
+
+extern "C" int64_t sb_plan_launches(const sb_plan *plan)
+{
+    if (!plan || plan->nbatch < 0 || plan->nbatch > SB_MAX_BATCH_LEVELS) return -1;
+    const Levels lv = merged_levels(*plan);
+    int64_t outer = 1;
+    for (int q = 2; q < lv.n; ++q) outer *= lv.count[q];
+    return outer;
+}
+
 extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
                               double beta, void *C, void *stream)
 {
@@ -116,25 +173,26 @@ extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, co
     const char *L = (const char *)(plan->left_is_B ? B : A);
     const char *R = (const char *)(plan->left_is_B ? A : B);
     char *Cb = (char *)C;
-    const int nb = plan->nbatch;
+    const Levels lv = merged_levels(*plan);
+    const int nb = lv.n;
     // levels 0 and 1 run inside the launch; an extended operand passes its stored-column stride
     // in place of the (implied, unit) level-0 batch stride
-    const int64_t b0 = nb > 0 ? plan->batch[0] : 1, b1 = nb > 1 ? plan->batch[1] : 1;
+    const int64_t b0 = nb > 0 ? lv.count[0] : 1, b1 = nb > 1 ? lv.count[1] : 1;
     const bool exL = plan->opL > SB_OP_T, exR = plan->opR > SB_OP_T;
-    const int64_t sL0 = exL ? plan->exL : (nb > 0 ? plan->strideL[0] : 0);
-    const int64_t sR0 = exR ? plan->exR : (nb > 0 ? plan->strideR[0] : 0);
-    const int64_t sC0 = nb > 0 ? plan->strideC[0] : 0;
-    const int64_t sL1 = nb > 1 ? plan->strideL[1] : 0, sR1 = nb > 1 ? plan->strideR[1] : 0, sC1 = nb > 1 ? plan->strideC[1] : 0;
+    const int64_t sL0 = exL ? plan->exL : (nb > 0 ? lv.sL[0] : 0);
+    const int64_t sR0 = exR ? plan->exR : (nb > 0 ? lv.sR[0] : 0);
+    const int64_t sC0 = nb > 0 ? lv.sC[0] : 0;
+    const int64_t sL1 = nb > 1 ? lv.sL[1] : 0, sR1 = nb > 1 ? lv.sR[1] : 0, sC1 = nb > 1 ? lv.sC[1] : 0;
     // deeper levels: an odometer of host-side launches (Listing 2)
     int64_t idx[SB_MAX_BATCH_LEVELS] = {0};
     int64_t outer = 1;
-    for (int q = 2; q < nb; ++q) outer *= plan->batch[q];
+    for (int q = 2; q < nb; ++q) outer *= lv.count[q];
     for (int64_t it = 0; it < outer; ++it) {
         int64_t oL = 0, oR = 0, oC = 0;
         for (int q = 2; q < nb; ++q) {
-            oL += idx[q] * plan->strideL[q];
-            oR += idx[q] * plan->strideR[q];
-            oC += idx[q] * plan->strideC[q];
+            oL += idx[q] * lv.sL[q];
+            oR += idx[q] * lv.sR[q];
+            oC += idx[q] * lv.sC[q];
         }
         int rc = sb_gemm2(dt, (sb_op)plan->opL, (sb_op)plan->opR, plan->m, plan->n, plan->k, alpha,
                           L ? L + oL * esz : nullptr, plan->ldL, sL0, sL1,
@@ -148,7 +206,7 @@ extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, co
             return -2;
         }
         for (int q = 2; q < nb; ++q) {
-            if (++idx[q] < plan->batch[q]) break;
+            if (++idx[q] < lv.count[q]) break;
             idx[q] = 0;
         }
     }

@@ -15,13 +15,13 @@ def declared_functions():
     for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names += re.findall(r"^(?:int|const char \*)\s*(sb_\w+)\s*\(", text, flags=re.M)
+        names += re.findall(r"^(?:int|int64_t|const char \*)\s*(sb_\w+)\s*\(", text, flags=re.M)
     return names
 
 
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
-    assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch",
+    assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch", "sb_plan_launches",
                           "sb_status_string", "sb_force_kernel", "sb_last_kernel", "sb_tucker_workspace",
                           "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"}
     lib = binding.load()

@@ -294,10 +294,12 @@ def test_bf16_output_rounding_is_nearest_even(kernel):
     assert np.array_equal(got, np.broadcast_to(want.reshape(batch, 1, m), got.shape))
 
 
-def test_three_level_nest_loops_on_the_host():
-    ext = dict(m=20, n=12, p=3, q=4, r=2, k=9)
-    err, text = contract_case("f32", "mpk", "knqr", "mnpqr", ext, strat="nested", seed=77)
-    assert err <= TOL["f32"], (text, err)
+def test_three_and_four_level_nests():
+    # batch levels that nest in every tensor are merged into one launch; the others loop on the host
+    ext = dict(m=20, n=12, p=3, q=4, r=2, s=3, k=9)
+    for ma, mb, mc in (("mpk", "knqr", "mnpqr"), ("mpk", "knqr", "mnqpr"), ("mpk", "knqrs", "mnpqrs"), ("kpm", "qnkr", "mrnpq")):
+        err, text = contract_case("f32", ma, mb, mc, ext, strat="nested", alpha=0.5, beta=-1.0, seed=77)
+        assert err <= TOL["f32"], (text, err)
 
 
 def test_extended_operations_directly():
