@@ -91,6 +91,30 @@ def time_steps(fn, steps, warmup):
     return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
 
 
+def measured_peaks(dtypes):
+    """What this device sustains, for pricing next to the published peaks: the matrix-core rate of a
+    pure-MFMA kernel per element type (sb_probe_mfma) and the rate of a 1 GiB device copy."""
+    import torch
+    import paper_1606_05696_amd as sb
+    out = {}
+    scratch = torch.empty(1 << 19, dtype=torch.float32, device="cuda")          # 2 MiB
+    for dt in dtypes:
+        flops = [0.0]
+
+        def probe():
+            flops[0] = sb.sb_probe_mfma(dt, 2048, scratch)[1]
+
+        _, ms = time_steps(probe, 5, 2)
+        out["mfma_%s_tflops" % dt] = flops[0] / ms / 1e9
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda")              # 1 GiB
+    dst = torch.empty_like(src)
+    _, ms = time_steps(lambda: dst.copy_(src), 5, 2)
+    out["hbm_copy_gbps"] = 2.0 * src.numel() * 4 / ms / 1e6                      # read + write
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 LLC_BYTES = 256 << 20      # Infinity Cache: working sets below this can be served without touching HBM
 
 
@@ -408,6 +432,10 @@ def main():
 
     head, tensors = run_workload(args.workload, args.steps, args.warmup, not args.no_torch_baseline)
     w = inputs.WORKLOADS[args.workload]
+    peaks = measured_peaks(sorted({v["dtype"] for v in inputs.WORKLOADS.values()}))
+    measured = peaks["mfma_%s_tflops" % w["dtype"]] if head["roofline"]["bound"] == "mfma" else peaks["hbm_copy_gbps"]
+    head["roofline"]["measured_peak"] = measured
+    head["roofline"]["frac_of_measured"] = head["roofline"]["achieved"] / measured
     result = {
         "metric": "GFLOP/s per contraction (StridedBatchedGemm path), 1 GPU",
         "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -417,6 +445,7 @@ def main():
                    "flops_per_step": head["flops"], "algorithmic_bytes_per_step": head["bytes"]},
         "roofline": head["roofline"],
     }
+    result["measured_peaks"] = peaks
     if not args.no_torch_baseline:
         result["baselines"] = {"conventional_same_gpu": head["torch_matmul"]}
     if not args.no_cpu_baseline:

@@ -189,6 +189,14 @@ enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
 
+/* Diagnostics for benchmarks: enqueue a kernel that only issues the MFMA instruction the kernels of
+ * element type dt are built on (4 independent accumulators per wave, 16 waves per compute unit),
+ * `iterations` rounds (a multiple of 16); *flops receives the floating-point operations it performs, so that
+ * flops / measured time is the matrix-core rate this device sustains.  scratch: device memory of at
+ * least 2 MiB that the kernel overwrites.
+ * Argument numbers: dt=1 iterations=2 scratch=3 scratch_bytes=4 stream=5 flops=6. */
+int sb_probe_mfma(sb_dtype dt, int iterations, void *scratch, int64_t scratch_bytes, void *stream, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 __all__ = [n for n in dir() if n.startswith("SB_")] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
-    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"]
+    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
 
 
 class sb_plan(ctypes.Structure):
@@ -90,6 +90,8 @@ def load():
     lib.sb_force_kernel.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
     lib.sb_last_kernel.argtypes = []
+    lib.sb_probe_mfma.restype = ci
+    lib.sb_probe_mfma.argtypes = [ci, ci, vp, i64, vp, ctypes.POINTER(dbl)]
     lib.sb_tucker_workspace.restype = ci
     lib.sb_tucker_workspace.argtypes = [ci, i64, i64, i64, i64, i64, i64, ci, i64p]
     lib.sb_tucker_hooi.restype = ci
@@ -236,6 +238,16 @@ def sb_last_kernel():
 def sb_plan_launches(plan):
     """Number of kernel launches sb_plan_launch issues for this plan (see sbgemm.h)."""
     return load().sb_plan_launches(ctypes.byref(plan))
+
+
+def sb_probe_mfma(dt, iterations, scratch, stream=None, check=True):
+    """Enqueue the pure-MFMA probe kernel (see sbgemm.h: sb_probe_mfma).  Returns (status, flops)."""
+    out = dbl_out = ctypes.c_double(0.0)
+    rc = load().sb_probe_mfma(_dtype_of(dt), int(iterations), _ptr(scratch), scratch.numel() * scratch.element_size(),
+                              _stream(stream), ctypes.byref(out))
+    if check and rc != SB_OK:
+        raise SbError("sb_probe_mfma", rc)
+    return rc, dbl_out.value
 
 
 def sb_tucker_workspace(dt, m, n, p, i, j, k, with_init=True, check=True):

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch", "sb_plan_launches",
                           "sb_status_string", "sb_force_kernel", "sb_last_kernel", "sb_tucker_workspace",
-                          "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig"}
+                          "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"}
     lib = binding.load()
     for n in names:
         assert getattr(lib, n) is not None
