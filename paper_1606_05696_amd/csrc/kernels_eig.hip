@@ -94,8 +94,8 @@ __global__ void identity_kernel(T *V, int n)
 // One compute unit does all the arithmetic, so the step is kept short in instructions: an odd
 // matrix is padded with a zero row and column (its phantom index then rotates by the identity
 // without any test), the pairs and rotations of a step sit in a small LDS table, and the
-// (pair, pair) coordinates of a thread's work items advance by addition.  A sweep in which no
-// rotation angle exceeded rounding level ends the iteration early.
+// (pair, pair) coordinates of a thread's work items advance by addition.  A sweep that rotated
+// nothing ends the iteration early.
 constexpr int LDS_THREADS = 1024;
 
 // what a step needs to know about one pair: the two indices and the rotation; one LDS read
@@ -110,7 +110,7 @@ size_t jacobi_lds_bytes(int n)
 }
 
 template <typename T>
-__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps, T angle_tol)
+__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps, T rel_tol)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
     const int h = ne / 2, tid = threadIdx.x;
@@ -125,6 +125,16 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
     for (int e = tid; e < ne * ne; e += LDS_THREADS) Vs[e] = (e % ne == e / ne && e % ne < n) ? T(1) : T(0);
     if (tid == 0) rotated = 0;
     __syncthreads();
+    // off-diagonal elements below rounding level of the largest diagonal element are left alone: they
+    // no longer move the eigenvalues, and among (nearly) equal eigenvalues they would rotate noise forever
+    __shared__ T tiny_s;
+    if (tid == 0) {
+        T big = T(0);
+        for (int i = 0; i < n; ++i) big = fmax(big, fabs(As[i + i * ne]));
+        tiny_s = rel_tol * big;
+    }
+    __syncthreads();
+    const T tiny = tiny_s;
     const int nA = h * h;
     const int P0 = tid % h, Q0 = tid / h, dP = LDS_THREADS % h, dQ = LDS_THREADS / h;
     typedef T T2 __attribute__((ext_vector_type(2)));
@@ -133,12 +143,15 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
             if (tid < h) {
                 int p, q;
                 pair_of(tid, round, ne, p, q);
-                T c, s;
-                rotation(As[p + p * ne], As[q + q * ne], As[p + q * ne], c, s);      // phantom index: apq = 0 -> identity
+                T c = T(1), s = T(0);
+                const T apq = As[p + q * ne];                                       // phantom index: apq = 0 -> identity
+                if (fabs(apq) > tiny) {
+                    rotation(As[p + p * ne], As[q + q * ne], apq, c, s);
+                    rotated = 1;
+                }
                 PairRec<T> r;
                 r.p = p; r.q = q; r.c = c; r.s = s;
                 rec[tid] = r;
-                if (fabs(s) > angle_tol) rotated = 1;
             }
             __syncthreads();
             int P = P0, Q = Q0;
@@ -220,13 +233,14 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweep
         const size_t bytes = jacobi_lds_bytes<T>(n);
         static bool configured = false;
         if (!configured) {
-            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);    // 64 bytes stay for the static flag
+            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);    // 64 bytes stay for the static variables
             if (e != hipSuccess) return e;
             configured = true;
         }
-        // rotations below a few units of rounding no longer change the result
-        const T angle_tol = sizeof(T) == 8 ? T(4e-16) : T(2e-7);
-        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps, angle_tol);
+        // 8 units of rounding of the largest diagonal element: rotating smaller elements only stirs rounding
+        // noise (each sweep creates as much as it removes), and a warm-started solve would never stop early
+        const T rel_tol = sizeof(T) == 8 ? T(1.8e-15) : T(9.6e-7);
+        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps, rel_tol);
         *A_final = A; *V_final = V;
     } else {
         const int h = ne / 2;

@@ -58,8 +58,9 @@ int64_t tucker_bytes(sb_dtype dt, const Sizes &s, int with_init)
 {
     const int64_t es = esize(dt);
     const int64_t nmax = with_init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
+    const int64_t loop = s.eig_loop();
     return up(s.m * s.n * s.k * es) + up(s.i * s.n * s.p * es) + up(s.y_elems() * es) + up(nmax * s.rmax() * es) +
-           EigSpace::bytes(dt, nmax);
+           EigSpace::bytes(dt, nmax) + 4 * up(loop * loop * es);       // + previous eigenvectors of each mode, one temporary
 }
 
 struct Ctx {
@@ -67,6 +68,10 @@ struct Ctx {
     hipStream_t stream;
     EigSpace eig;
     char *W;          // nmax x rmax: selected (scaled) eigenvectors
+    char *Vprev[3];   // eigenvectors found for each mode in the previous iteration
+    char *tmp;
+    bool have_prev[3];
+    int warm_runs[3];    // warm starts since the last cold solve of each mode
     int status;
 
     bool ok() const { return status == SB_OK; }
@@ -88,12 +93,34 @@ struct Ctx {
     }
 
     // eigenvectors of the Gram matrix already in eig.S (order e): the r leading ones go to out
-    // (ld = ldo), scaled by lambda^-1/2 if `scaled`
-    void eig_leading(int64_t e, int64_t r, void *out, int64_t ldo, int scaled)
+    // (ld = ldo), scaled by lambda^-1/2 if `scaled`.  mode >= 0: warm start.  From one HOOI iteration
+    // to the next the Gram matrix of a mode changes little, so it is first rotated by the previous
+    // iteration's eigenvectors (S' = V^T S V, nearly diagonal; the Jacobi solver then stops after a
+    // sweep or two) and the new eigenvectors are V V'.
+    void eig_leading(int mode, int64_t e, int64_t r, void *out, int64_t ldo, int scaled)
     {
         if (!ok()) return;
+        const int64_t es = esize(dt);
+        // the accumulated product V V' V'' ... drifts away from orthogonality by a rounding error per
+        // iteration; every 16th solve starts cold again
+        const bool warm = mode >= 0 && have_prev[mode] && warm_runs[mode] < 15;
+        if (warm) {
+            gemm(SB_OP_N, SB_OP_N, e, e, e, eig.S, e, Vprev[mode], e, 0.0, tmp, e);          // S V
+            gemm(SB_OP_T, SB_OP_N, e, e, e, Vprev[mode], e, tmp, e, 0.0, eig.S, e);          // V^T (S V)
+        }
         void *Af = nullptr, *Vf = nullptr;
         check_hip(sb_eig_sym(dt, (int)e, eig.S, eig.S2, eig.V, eig.V2, eig.lam, (int *)eig.sel, default_sweeps(dt, e), stream, &Af, &Vf));
+        if (!ok()) return;
+        if (warm) {
+            gemm(SB_OP_N, SB_OP_N, e, e, e, Vprev[mode], e, Vf, e, 0.0, tmp, e);             // V V'
+            std::swap(Vprev[mode], tmp);
+            Vf = Vprev[mode];
+            ++warm_runs[mode];
+        } else if (mode >= 0) {
+            check_hip(hipMemcpyAsync(Vprev[mode], Vf, e * e * es, hipMemcpyDeviceToDevice, stream));
+            have_prev[mode] = true;
+            warm_runs[mode] = 0;
+        }
         if (!ok()) return;
         check_hip(sb_eig_gather(dt, (int)e, Vf, (const int *)eig.sel, eig.lam, (int)r, out, ldo, scaled, stream));
     }
@@ -101,19 +128,19 @@ struct Ctx {
     // U (rows x r) <- the r leading left singular vectors of the rows x R matrix Y.
     // trans == 0: Y is stored column-major with leading dimension rows;
     // trans == 1: its transpose X (R x rows, leading dimension R) is what is stored.
-    void leading_left(const void *Y, int64_t rows, int64_t R, int trans, int64_t r, void *U)
+    void leading_left(int mode, const void *Y, int64_t rows, int64_t R, int trans, int64_t r, void *U)
     {
         const int64_t ld = trans ? R : rows;
         if (R <= rows) {                // Gram matrix of the short side: Q = Y^T Y, U = Y V_r Lambda_r^-1/2
             if (!trans) gemm(SB_OP_T, SB_OP_N, R, R, rows, Y, ld, Y, ld, 0.0, eig.S, R);
             else        gemm(SB_OP_N, SB_OP_T, R, R, rows, Y, ld, Y, ld, 0.0, eig.S, R);
-            eig_leading(R, r, W, R, 1);
+            eig_leading(mode, R, r, W, R, 1);
             if (!trans) gemm(SB_OP_N, SB_OP_N, rows, r, R, Y, ld, W, R, 0.0, U, rows);
             else        gemm(SB_OP_T, SB_OP_N, rows, r, R, Y, ld, W, R, 0.0, U, rows);
         } else {                        // S = Y Y^T: its eigenvectors are the left singular vectors
             if (!trans) gemm(SB_OP_N, SB_OP_T, rows, rows, R, Y, ld, Y, ld, 0.0, eig.S, rows);
             else        gemm(SB_OP_T, SB_OP_N, rows, rows, R, Y, ld, Y, ld, 0.0, eig.S, rows);
-            eig_leading(rows, r, U, rows, 0);
+            eig_leading(mode, rows, r, U, rows, 0);
         }
     }
 };
@@ -171,7 +198,14 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
     char *Y = w;   w += up(s.y_elems() * es);        // the Y of steps 4, 6, 8
     const int64_t nmax = init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
     c.W = w;       w += up(nmax * s.rmax() * es);
-    c.eig.carve(dt, w, nmax);
+    w = c.eig.carve(dt, w, nmax);
+    const int64_t loop = s.eig_loop();
+    for (int q = 0; q < 3; ++q) {
+        c.Vprev[q] = w;  w += up(loop * loop * es);
+        c.have_prev[q] = false;
+        c.warm_runs[q] = 0;
+    }
+    c.tmp = w;
 
     const int64_t dT[3] = {m, n, p}, dAf[2] = {m, i}, dBf[2] = {n, j}, dCf[2] = {p, k};
     const int64_t dW1[3] = {m, n, k}, dZ[3] = {i, n, p}, dY1[3] = {m, j, k}, dY2[3] = {n, i, k}, dY3[3] = {i, j, p}, dG[3] = {i, j, k};
@@ -180,25 +214,25 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
         // step 2: leading eigenvectors of T_(r) T_(r)^T.  T_(1) is the m x (np) matrix T itself,
         // T_(3)^T the (mn) x p matrix T itself; T_(2) T_(2)^T is the sum over p of T_p^T T_p.
         c.gemm(SB_OP_N, SB_OP_T, m, m, n * p, T, m, T, m, 0.0, c.eig.S, m);
-        c.eig_leading(m, i, A, m, 0);
+        c.eig_leading(-1, m, i, A, m, 0);
         for (int64_t q = 0; q < p && c.ok(); ++q) {
             const char *Tq = (const char *)T + q * m * n * es;
             c.gemm(SB_OP_T, SB_OP_N, n, n, m, Tq, m, Tq, m, q ? 1.0 : 0.0, c.eig.S, n);
         }
-        c.eig_leading(n, j, B, n, 0);
+        c.eig_leading(-1, n, j, B, n, 0);
         c.gemm(SB_OP_T, SB_OP_N, p, p, m * n, T, m * n, T, m * n, 0.0, c.eig.S, p);
-        c.eig_leading(p, k, C, p, 0);
+        c.eig_leading(-1, p, k, C, p, 0);
     }
 
     for (int it = 0; it < iterations && c.ok(); ++it) {
         c.contract("mnp", "pk", "mnk", T, dT, C, dCf, W1, dW1);          // step 4: Y_mjk = T_mnp B_nj C_pk
         c.contract("mnk", "nj", "mjk", W1, dW1, B, dBf, Y, dY1);
-        c.leading_left(Y, m, j * k, 0, i, A);                            // step 5
+        c.leading_left(0, Y, m, j * k, 0, i, A);                            // step 5
         c.contract("mnk", "mi", "nik", W1, dW1, A, dAf, Y, dY2);         // step 6 with mode n first: Y_(2) is a plain matrix
-        c.leading_left(Y, n, i * k, 0, j, B);                            // step 7
+        c.leading_left(1, Y, n, i * k, 0, j, B);                            // step 7
         c.contract("mnp", "mi", "inp", T, dT, A, dAf, Z, dZ);            // step 8: Y_ijp = T_mnp B_nj A_mi
         c.contract("inp", "nj", "ijp", Z, dZ, B, dBf, Y, dY3);
-        c.leading_left(Y, p, i * j, 1, k, C);                            // step 9: Y_(3) is the transpose of the (ij) x p matrix
+        c.leading_left(2, Y, p, i * j, 1, k, C);                            // step 9: Y_(3) is the transpose of the (ij) x p matrix
     }
     c.contract("mnp", "mi", "inp", T, dT, A, dAf, Z, dZ);                // step 11: G_ijk = T_mnp A_mi B_nj C_pk
     c.contract("inp", "nj", "ijp", Z, dZ, B, dBf, Y, dY3);
