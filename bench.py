@@ -34,7 +34,7 @@ BOUND = {1: "hbm", 3: "hbm", 40: "mfma", 41: "mfma", 5: "hbm"}
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same counters'
 # readings for a 1 GiB copy (profiles/bench_default_hbm_traffic.txt); measured offline, not in this run
 MIB = 1 << 20
-MEASURED_TRAFFIC = {41: int(1176.73 * MIB), 40: int(2563.44 * MIB), 3: int(128.14 * MIB), 5: int(41.17 * MIB),
+MEASURED_TRAFFIC = {41: int(1180.53 * MIB), 40: int(2568.34 * MIB), 3: int(128.14 * MIB), 5: int(41.16 * MIB),
                     1: int(0.65 * MIB)}
 
 
@@ -49,6 +49,7 @@ def parse_args():
     ap.add_argument("--no-torch-baseline", action="store_true")
     ap.add_argument("--sweeps", action="store_true",
                     help="instead of the other workloads, add the size sweeps (cubic tensors, n = 8 .. 512) to the line")
+    ap.add_argument("--no-tucker", action="store_true", help="skip the Tucker/HOOI timings (tens of thousands of small launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device copy of known size (to scale rocprofv3 byte counters)")
     return ap.parse_args()
@@ -463,7 +464,8 @@ def main():
             others.append(r)
         others.append(run_table2_cases(max(args.steps, 200), args.warmup))
         others.append(run_exceptional_cases(args.steps, args.warmup))
-        others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
+        if not args.no_tucker:
+            others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others
     print(json.dumps(result))
 
