@@ -231,11 +231,12 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweep
         *A_final = A; *V_final = V;
     } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 64) {       // 64 bytes stay for the static flag
         const size_t bytes = jacobi_lds_bytes<T>(n);
-        static bool configured = false;
-        if (!configured) {
+        static bool configured[SB_MAX_DEVICES] = {};
+        const int dev = sb_current_device();
+        if (!configured[dev]) {
             hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);    // 64 bytes stay for the static variables
             if (e != hipSuccess) return e;
-            configured = true;
+            configured[dev] = true;
         }
         // 8 units of rounding of the largest diagonal element: rotating smaller elements only stirs rounding
         // noise (each sweep creates as much as it removes), and a warm-started solve would never stop early

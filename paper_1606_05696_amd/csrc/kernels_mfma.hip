@@ -524,20 +524,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_ker
 }
 
 // Launch `kernel` with as many workgroups as can be resident at once (a multiple of the XCD
-// count), or fewer if there are fewer tiles.  The residency of a kernel is asked once per process.
+// count), or fewer if there are fewer tiles.  The residency of a kernel is asked once per device.
 template <typename K, typename... Extra>
 hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, Extra... extra)
 {
-    static int resident = 0;                   // one instance per kernel instantiation
-    if (resident == 0) {
-        int per_cu = 0, dev = 0, cus = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    static int resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
+    const int dev = sb_current_device();
+    if (resident_of[dev] == 0) {
+        int per_cu = 0, cus = 0;
+        hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, nthreads, 0);
         if (e != hipSuccess) return e;
         if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
-        resident = per_cu * cus;
+        resident_of[dev] = per_cu * cus;
     }
+    const int resident = resident_of[dev];
     int64_t grid = total_tiles < resident ? total_tiles : resident;
     grid = (grid + NXCD - 1) / NXCD * NXCD;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, extra...);

@@ -219,11 +219,12 @@ static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
 #define SB_OUTER(KS_)                                                                                                  \
     do {                                                                                                                \
         auto kern = sbgemm_outer2_bf16_kernel<A_KC, B_KC, KS_>;                                                         \
-        static bool configured = false;                                                                                 \
-        if (!configured) {                                                                                              \
+        static bool configured[SB_MAX_DEVICES] = {};                                                                    \
+        const int dev = sb_current_device();                                                                            \
+        if (!configured[dev]) {                                                                                         \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
             if (e != hipSuccess) return e;                                                                              \
-            configured = true;                                                                                          \
+            configured[dev] = true;                                                                                     \
         }                                                                                                               \
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p, vec_store);                          \
     } while (0)

@@ -36,3 +36,12 @@ bool sb_panel_bf16_supports(const SbArgs &a);
 hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream);
 bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a);       // extended op on the first operand (MFMA family)
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);
+
+// Set-up that HIP keeps per device (function attributes, occupancy) is cached per device ordinal.
+constexpr int SB_MAX_DEVICES = 64;
+inline int sb_current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SB_MAX_DEVICES) return 0;
+    return dev;
+}

@@ -408,3 +408,40 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
             err, got, ref = run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta,
                                         seed=m + n + k, kernel="mfma")
             assert err <= TOL[dtype], (m, n, k, batch, alpha, beta, err)
+
+
+def test_offsets_beyond_2_31_elements():
+    # tensors with more than 2^31 elements (8.7 GB each in fp32): 64-bit offsets in the tiny-matrix and
+    # the MFMA kernels, millions of batches.  B is a seeded vector of prime length repeated along memory,
+    # so the host can rebuild any column; sampled columns of C (the last ones, the ones around element
+    # 2^31, random ones) are compared with the oracle, and no element of C may be left unwritten.
+    import torch
+    L = 1000003
+    base = inputs.uniform_tensor(123, [L], np.float32)
+    base_dev = to_dev(base, "f32")
+    rng = np.random.default_rng(7)
+    for m, n, k, p in ((16, 16, 16, 8_500_000), (64, 64, 64, 530_000)):
+        total = k * n * p
+        assert total > 2 ** 31
+        tB = torch.empty(total, dtype=torch.float32, device="cuda")
+        chunk = 1 << 27
+        for s0 in range(0, total, chunk):
+            idx = torch.arange(s0, min(s0 + chunk, total), device="cuda") % L
+            tB[s0:s0 + idx.numel()] = base_dev[idx]
+        del idx
+        A = inputs.uniform_tensor(124, [m, k], np.float32)
+        tA = to_dev(A, "f32")
+        tC = torch.full((m * n * p,), float("nan"), dtype=torch.float32, device="cuda")
+        sb.sb_contract("mk", "knp", "mnp", 1.0, tA, [m, k], tB, [k, n, p], 0.0, tC, [m, n, p])
+        sync()
+        assert not bool(torch.isnan(tC).any())
+        edge = 2 ** 31 // (k * n)
+        for pp in [int(x) for x in rng.integers(0, p, 12)] + [p - 1, p - 2, edge - 1, edge, edge + 1, 0]:
+            for nn in (0, n - 1, int(rng.integers(0, n))):
+                off = k * nn + k * n * pp
+                col = base[(off + np.arange(k)) % L]
+                ref = oracle.contract("mk", A, "k", col, "m", wide=False)
+                got = tC[m * nn + m * n * pp: m * nn + m * n * pp + m].cpu().numpy().astype(np.float64)
+                assert rel_fro(got, ref) <= TOL["f32"], (m, pp, nn)
+        del tB, tC
+        torch.cuda.empty_cache()
