@@ -80,9 +80,14 @@ struct Panel {
         else    { k = f / (ROWS / VEC); row = (f % (ROWS / VEC)) * VEC; }
     }
 
-    // GUARD = false: the whole panel lies inside the matrix and every vector is 16-byte aligned.
-    // GUARD = true: rows_left / k_left say how much of the panel is inside (edge tiles, odd strides).
-    template <bool GUARD>
+    // GUARD = 0: the whole panel lies inside the matrix and every vector is 16-byte aligned.
+    // GUARD = 1: edge tile whose edges fall between vectors (aligned operands, the extent along the
+    //            contiguous dimension a multiple of the vector length): every lane still issues its
+    //            vector load, from a safe address when its vector lies outside, and zeroes it then;
+    //            no branch, so the loads stay countable and pipelined exactly as in an interior tile.
+    // GUARD = 2: rows_left / k_left say how much of the panel is inside, element by element (odd
+    //            extents, unaligned operands).
+    template <int GUARD>
     static __device__ __forceinline__ void load(Vec (&v)[NVEC], const T *p, int64_t ld, int64_t rows_left, int64_t k_left, bool vec_ok)
     {
 #pragma unroll
@@ -90,8 +95,14 @@ struct Panel {
             int row, k;
             coords((int)threadIdx.x + NT * q, row, k);
             const T *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
-            if (!GUARD) {
+            if (GUARD == 0) {
                 v[q] = *(const Vec *)src;
+                continue;
+            }
+            if (GUARD == 1) {
+                const bool in = row < rows_left && k < k_left;
+                v[q] = *(const Vec *)(in ? src : p);
+                if (!in) v[q] = Vec(T(0));
                 continue;
             }
             const bool inside = KC ? (row < rows_left && k + VEC <= k_left) : (row + VEC <= rows_left && k < k_left);
@@ -155,9 +166,10 @@ struct Config {
 //     MFMAs run (two fragment register sets).  The hand-over to the next block (LDS store of the
 //     staged panel, barrier, first fragment read of the new block) is placed BEFORE the last
 //     k-group's MFMAs of the current block, which then hide its latency.
-// GUARD selects bounds-checked scalar loads (edge tiles, unaligned operands) or plain 16-byte
+// GUARD selects bounds-checked scalar loads (odd extents, unaligned operands), masked vector loads
+// (edge tiles whose edges fall between vectors) or plain 16-byte
 // vector loads (interior tiles, branch-free).
-template <typename CF, typename T, bool GUARD>
+template <typename CF, typename T, int GUARD>
 __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::NBN], T (*As)[CF::PA::LDS_SIZE], T (*Bs)[CF::PB::LDS_SIZE],
                                         const T *A, const T *B, int64_t ldA, int64_t ldB, int64_t kstepA, int64_t kstepB,
                                         int64_t m_left, int64_t n_left, int64_t K, bool vec_ok, int wm, int wn, int lane, int BKc)
@@ -304,10 +316,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbA
 
         // workgroup-uniform: interior tile with aligned operands -> branch-free loop
         const bool interior = vec_ok && m_left >= BM && n_left >= BN && (g.k % BK == 0);
+        // edges that fall between 16-byte vectors: unconditional loads with masking
+        const bool vec_edges = vec_ok && (A_KC ? g.k % MF::VEC == 0 : g.m % MF::VEC == 0) && (B_KC ? g.k % MF::VEC == 0 : g.n % MF::VEC == 0);
         if (interior)
-            k_loop<CF, T, false>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
+            k_loop<CF, T, 0>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
+        else if (vec_edges)
+            k_loop<CF, T, 1>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
         else
-            k_loop<CF, T, true>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
+            k_loop<CF, T, 2>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
 
         // epilogue: lane = row of C within the block, result slot = column.  The four variants
         // (edge tile or not, beta or not) are chosen by workgroup-uniform branches so that the
