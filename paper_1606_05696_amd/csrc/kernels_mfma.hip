@@ -99,10 +99,9 @@ struct Panel {
                 v[q] = *(const Vec *)src;
                 continue;
             }
-            if (GUARD == 1) {
+            if (GUARD == 1) {          // the vector is zeroed when it goes to LDS: masking it here would wait for the load
                 const bool in = row < rows_left && k < k_left;
                 v[q] = *(const Vec *)(in ? src : p);
-                if (!in) v[q] = Vec(T(0));
                 continue;
             }
             const bool inside = KC ? (row < rows_left && k + VEC <= k_left) : (row + VEC <= rows_left && k < k_left);
@@ -118,14 +117,16 @@ struct Panel {
         }
     }
 
-    static __device__ __forceinline__ void store(T *lds, const Vec (&v)[NVEC])
+    // MASK: the panel was loaded with GUARD = 1; vectors outside the matrix become zeros here
+    template <bool MASK = false>
+    static __device__ __forceinline__ void store(T *lds, const Vec (&v)[NVEC], int64_t rows_left = 0, int64_t k_left = 0)
     {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
             coords((int)threadIdx.x + NT * q, row, k);
             T *dst = KC ? lds + row * LDS_LD + k : lds + k * LDS_LD + row;
-            *(Vec *)dst = v[q];
+            *(Vec *)dst = (!MASK || (row < rows_left && k < k_left)) ? v[q] : Vec(T(0));
         }
     }
 
@@ -227,8 +228,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
                     // LDS store of the next block's panel (requested one block ago) between two
                     // halves of a cluster: the matrix core keeps running under it
                     __builtin_amdgcn_sched_barrier(0);
-                    PA::store(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0]);
-                    PB::store(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0]);
+                    PA::template store<GUARD == 1>(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0], m_left, K - (kb + 1) * BK);
+                    PB::template store<GUARD == 1>(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0], n_left, K - (kb + 1) * BK);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -244,8 +245,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
 
     gload(I0(), 0);
     if (GD == 2 && nkb > 1) gload(std::integral_constant<int, GD - 1>(), 1);
-    PA::store(As[0], ra[0]);
-    PB::store(Bs[0], rb[0]);
+    PA::template store<GUARD == 1>(As[0], ra[0], m_left, K);
+    PB::template store<GUARD == 1>(Bs[0], rb[0], n_left, K);
     __syncthreads();
     read_frags(I0(), I0(), 0);
     int64_t kb = 0;
