@@ -10,6 +10,8 @@
 // tile: all PB batches share the same B panel, so the PB small products are one tall GEMM.
 // The transposition between "b contiguous" and "i contiguous" happens for free in the LDS
 // addressing of the MFMA fragments (lanes run along i, the panel is stored with b fastest).
+#include <type_traits>
+
 #include "sb_device.h"
 #include "sb_internal.h"
 
@@ -44,7 +46,7 @@ struct ExF64 {
 
 // PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK = 8 deep panels.
 template <typename MF, bool B_KC, int PB, int MB, int BN>
-__global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a)
+__global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a, int vec_b)
 {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
@@ -90,13 +92,18 @@ __global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles
 #pragma unroll
             for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
 
-    // A panel vector f: k = f / (MB * PB/VEC), i = (f / (PB/VEC)) % MB, b = (f % (PB/VEC)) * VEC
-    auto load_a = [&](Vec (&v)[NVA], int64_t k0) {
+    // A panel vector f: k = f / (MB * PB/VEC), i = (f / (PB/VEC)) % MB, b = (f % (PB/VEC)) * VEC.
+    // FAST: the whole brick lies inside the tensor and is 16-byte aligned (no tests, plain vector loads).
+    auto load_a = [&](auto fast_c, Vec (&v)[NVA], int64_t k0) {
 #pragma unroll
         for (int q = 0; q < NVA; ++q) {
             const int f = (int)threadIdx.x + ET * q;
             const int k = f / (MB * (PB / VEC)), i = (f / (PB / VEC)) % MB, b = (f % (PB / VEC)) * VEC;
             const T *src = A + b + (int64_t)i * g.rsA + (k0 + k) * g.csA;
+            if (decltype(fast_c)::value) {
+                v[q] = *(const Vec *)src;
+                continue;
+            }
             const bool row_ok = i < m_left && k0 + k < g.k;
             if (vec_a && row_ok && b + VEC <= b_left) {
                 v[q] = *(const Vec *)src;
@@ -114,14 +121,18 @@ __global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles
             *(Vec *)(lds + k * A_K + i * PBP + b) = v[q];
         }
     };
-    // B panel: one (guarded) vector per lane for the first BN*BK/VEC lanes
-    auto load_b = [&](Vec &v, int64_t k0) {
+    // B panel: one vector per lane for the first BN*BK/VEC lanes
+    auto load_b = [&](auto fast_c, Vec &v, int64_t k0) {
         const int f = threadIdx.x;
         if (f >= BN * BK / VEC) return;
         int col, k;
         if (B_KC) { col = f / (BK / VEC); k = (f % (BK / VEC)) * VEC; }
         else      { k = f / (BN / VEC); col = (f % (BN / VEC)) * VEC; }
         const T *src = B_KC ? B + (int64_t)col * ldB + (k0 + k) : B + (k0 + k) * kstepB + col;
+        if (decltype(fast_c)::value) {
+            v = *(const Vec *)src;
+            return;
+        }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             const bool ok = B_KC ? (col < n_left && k0 + k + e < g.k) : (col + e < n_left && k0 + k < g.k);
@@ -140,27 +151,14 @@ __global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles
     // tile row rho (0 .. BM-1) = (batch rho / MB, row rho % MB): lanes of an MFMA block run along i
     const int rho0 = wave * (BM / 4);
     const int kl = lane / MI;                          // lane group along k
-
-    Vec ra[NVA], rb;
     const int64_t nkb = (g.k + BK - 1) / BK;
-    load_a(ra, 0);
-    load_b(rb, 0);
-    store_a(As[0], ra);
-    store_b(Bs[0], rb);
-    __syncthreads();
-    for (int64_t kb = 0; kb < nkb; ++kb) {
-        const int cur = (int)(kb & 1);
-        const bool more = kb + 1 < nkb;
-        if (more) {
-            load_a(ra, (kb + 1) * BK);
-            load_b(rb, (kb + 1) * BK);
-        }
-        // one group of 8 k: lane group kl takes k = kl*VEC + e (VEC*KL = 8)
-        T fa[NBM][VEC], fb[NBN][VEC];
+
+    // MFMA operands of one panel (a group of 8 k: lane group kl takes k = kl*VEC + e)
+    auto read_frags = [&](T (&fa)[NBM][VEC], T (&fb)[NBN][VEC], int buf) {
 #pragma unroll
         for (int a = 0; a < NBM; ++a) {
             const int rho = rho0 + a * MI + (lane % MI);
-            const T *p = As[cur] + (rho % MB) * PBP + (rho / MB);
+            const T *p = As[buf] + (rho % MB) * PBP + (rho / MB);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) fa[a][e] = p[(kl * VEC + e) * A_K];
         }
@@ -168,26 +166,77 @@ __global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles
         for (int c = 0; c < NBN; ++c) {
             const int col = c * MI + (lane % MI);
             if (B_KC) {
-                Vec v = *(const Vec *)(Bs[cur] + col * B_LD + kl * VEC);
+                Vec v = *(const Vec *)(Bs[buf] + col * B_LD + kl * VEC);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) fb[c][e] = v[e];
             } else {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[cur][(kl * VEC + e) * B_LD + col];
+                for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[buf][(kl * VEC + e) * B_LD + col];
             }
         }
+    };
+
+    // The k loop, software-pipelined like the plain MFMA kernel: global loads run two panels ahead
+    // (two staging register sets), the LDS store of the next panel sits in the middle of the MFMA
+    // cluster, and the fragments of the next panel are read right after the barrier, before the
+    // second half of the current cluster's successor starts.  CUR = parity of the panel.
+    Vec ra[2][NVA], rb[2];
+    T fa[2][NBM][VEC], fb[2][NBN][VEC];
+    auto k_loop = [&](auto fast_c) {
+        auto block = [&](auto cur_c, auto steady_c, int64_t kb) {
+            constexpr int CUR = decltype(cur_c)::value;
+            constexpr bool STEADY = decltype(steady_c)::value;
+            if (STEADY || kb + 2 < nkb) {
+                load_a(fast_c, ra[CUR], (kb + 2) * BK);
+                load_b(fast_c, rb[CUR], (kb + 2) * BK);
+            }
+            const bool hand_over = STEADY || kb + 1 < nkb;
+            __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
+            for (int e = 0; e < VEC; ++e) {
+                if (e == VEC / 2 && hand_over) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    store_a(As[CUR ^ 1], ra[CUR ^ 1]);
+                    store_b(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
 #pragma unroll
-            for (int a = 0; a < NBM; ++a)
+                for (int a = 0; a < NBM; ++a)
 #pragma unroll
-                for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[c][e], fa[a][e]);     // C^T: lanes run along rows
-        if (more) {
-            store_a(As[cur ^ 1], ra);
-            store_b(Bs[cur ^ 1], rb);
+                    for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[CUR][c][e], fa[CUR][a][e]);     // C^T: lanes run along rows
+            }
+            __builtin_amdgcn_s_setprio(0);
+            if (hand_over) {
+                __syncthreads();
+                read_frags(fa[CUR ^ 1], fb[CUR ^ 1], CUR ^ 1);
+            }
+        };
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, 1> I1;
+        load_a(fast_c, ra[0], 0);
+        load_b(fast_c, rb[0], 0);
+        if (nkb > 1) {
+            load_a(fast_c, ra[1], BK);
+            load_b(fast_c, rb[1], BK);
         }
+        store_a(As[0], ra[0]);
+        store_b(Bs[0], rb[0]);
         __syncthreads();
-    }
+        read_frags(fa[0], fb[0], 0);
+        int64_t kb = 0;
+        for (; kb + 3 < nkb; kb += 2) {
+            block(I0(), std::true_type(), kb);
+            block(I1(), std::true_type(), kb + 1);
+        }
+        for (; kb < nkb; kb += 2) {
+            block(I0(), std::false_type(), kb);
+            if (kb + 1 < nkb) block(I1(), std::false_type(), kb + 1);
+        }
+    };
+    // workgroup-uniform choice
+    const bool fast = vec_a && vec_b && b_left >= PB && m_left >= MB && n_left >= BN && g.k % BK == 0;
+    if (fast) k_loop(std::true_type());
+    else      k_loop(std::false_type());
 
     // epilogue: lane = tile row rho = (batch, row); consecutive lanes are consecutive rows of one C_b
     const T alpha = (T)g.alpha, beta = (T)g.beta;
@@ -222,9 +271,10 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
     constexpr int VEC = MF::VEC;
     const int vec_a = ((uintptr_t)a.A % 16 == 0) && a.rsA % VEC == 0 && a.csA % VEC == 0 && a.bsA[1] % VEC == 0;
+    const int vec_b = ((uintptr_t)a.B % 16 == 0) && (a.rsB == 1 ? a.csB : a.rsB) % VEC == 0 && a.bsB[1] % VEC == 0;
     dim3 grid((unsigned)total), block(ET);
-    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a);
-    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a);
+    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
+    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
     return hipGetLastError();
 }
 
