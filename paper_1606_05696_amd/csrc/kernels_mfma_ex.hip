@@ -45,8 +45,12 @@ struct ExF64 {
 };
 
 // PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK = 8 deep panels.
+// The second launch bound (waves per SIMD the register allocation must leave room for) keeps two
+// fp64 workgroups on a compute unit; left alone the allocator gives the fp64 variant more than 256
+// registers and one workgroup per compute unit (35 instead of 54 TFLOP/s at 512^4).  The fp32 variant
+// fits three by itself and is left alone (any bound made it slower).
 template <typename MF, bool B_KC, int PB, int MB, int BN>
-__global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a, int vec_b)
+__global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a, int vec_b)
 {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
@@ -238,27 +242,40 @@ __global__ __launch_bounds__(ET) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles
     if (fast) k_loop(std::true_type());
     else      k_loop(std::false_type());
 
-    // epilogue: lane = tile row rho = (batch, row); consecutive lanes are consecutive rows of one C_b
+    // epilogue: lane = tile row rho = (batch, row); consecutive lanes are consecutive rows of one C_b.
+    // The variants (whole brick or not, beta or not) are chosen by workgroup-uniform branches so that
+    // the common one is a straight run of stores.
     const T alpha = (T)g.alpha, beta = (T)g.beta;
+    auto store_tile = [&](auto guard_c, auto beta_c) {
+        constexpr bool GUARD = decltype(guard_c)::value, BETA = decltype(beta_c)::value;
 #pragma unroll
-    for (int a = 0; a < NBM; ++a) {
-        const int rho = rho0 + a * MI + (lane % MI);
-        const int bl = rho / MB, il = rho % MB;
-        if (bl >= b_left || il >= m_left) continue;
-        T *Cb = (T *)g.C + (bb + bl) * g.bsC[0] + b1 * g.bsC[1] + (i0 + il);
+        for (int a = 0; a < NBM; ++a) {
+            const int rho = rho0 + a * MI + (lane % MI);
+            const int bl = rho / MB, il = rho % MB;
+            if (GUARD && (bl >= b_left || il >= m_left)) continue;
+            T *Cb = (T *)g.C + (bb + bl) * g.bsC[0] + b1 * g.bsC[1] + (i0 + il);
 #pragma unroll
-        for (int c = 0; c < NBN; ++c) {
-            const int64_t jl = j0 + c * MI + MF::row_lane(lane);
+            for (int c = 0; c < NBN; ++c) {
+                const int64_t jl = j0 + c * MI + MF::row_lane(lane);
+                T *col = Cb + jl * g.ldc;
 #pragma unroll
-            for (int r = 0; r < MF::NREG; ++r) {
-                const int64_t j = jl + MF::row_reg(r);
-                if (j >= g.n) continue;
-                T *dst = Cb + j * g.ldc;
-                T v = alpha * acc[a][c][r];
-                if (beta != T(0)) v += beta * *dst;
-                *dst = v;
+                for (int r = 0; r < MF::NREG; ++r) {
+                    if (GUARD && jl + MF::row_reg(r) >= g.n) continue;
+                    T *dst = col + MF::row_reg(r) * g.ldc;
+                    T v = alpha * acc[a][c][r];
+                    if (BETA) v += beta * *dst;
+                    *dst = v;
+                }
             }
         }
+    };
+    const bool whole = b_left >= PB && m_left >= MB && n_left >= BN;
+    if (whole) {
+        if (beta == T(0)) store_tile(std::false_type(), std::false_type());
+        else              store_tile(std::false_type(), std::true_type());
+    } else {
+        if (beta == T(0)) store_tile(std::true_type(), std::false_type());
+        else              store_tile(std::true_type(), std::true_type());
     }
 }
 
