@@ -260,8 +260,10 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     }
 }
 
+// Second launch bound: the 4-wave configurations must leave room for two workgroups per compute unit
+// (256 registers per lane); some operand orientations would otherwise take 290 and run alone.
 template <typename MFT, bool A_KC, bool B_KC, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 : 1) void sbgemm_mfma_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
 {
     typedef Config<MFT, A_KC, B_KC, BK, WM, WN, WAVES_M, WAVES_N, GD> CF;
     typedef typename CF::MF MF;
