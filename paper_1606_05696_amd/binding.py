@@ -113,20 +113,45 @@ def _ptr(x):
     return x.data_ptr()
 
 
+_TORCH_DTYPES = None
+
+
 def _dtype_of(dt, *tensors):
+    global _TORCH_DTYPES
     if dt is not None:
         return DTYPES[dt] if dt.__class__ is str else dt
-    import torch
-    table = {torch.float64: SB_F64, torch.float32: SB_F32, torch.bfloat16: SB_BF16}
-    kinds = {table[t.dtype] for t in tensors if hasattr(t, "dtype")}
-    if len(kinds) != 1:
-        raise TypeError("cannot infer one element type from the tensors; pass dt")
-    return kinds.pop()
+    if _TORCH_DTYPES is None:
+        import torch
+        _TORCH_DTYPES = {torch.float64: SB_F64, torch.float32: SB_F32, torch.bfloat16: SB_BF16}
+    kind = None
+    for t in tensors:
+        d = getattr(t, "dtype", None)
+        if d is None:
+            continue
+        if kind is None:
+            kind = d
+        elif d is not kind:
+            raise TypeError("the tensors have different element types; pass dt")
+    if kind is None or kind not in _TORCH_DTYPES:
+        raise TypeError("cannot infer the element type from the tensors; pass dt")
+    return _TORCH_DTYPES[kind]
 
 
-def _stream(stream):
+_RAW_STREAM = None
+
+
+def _stream(stream, ref=None):
+    """hipStream_t (as an integer) to launch on: the one given, else torch's current stream of the
+    device that holds `ref`.  torch.cuda.current_stream() builds a Stream object (2.6 us); the raw
+    getter behind it costs 0.1 us, which matters for contractions that are launch-bound."""
+    global _RAW_STREAM
     if stream is None:
         import torch
+        if _RAW_STREAM is None:
+            _RAW_STREAM = getattr(torch._C, "_cuda_getCurrentRawStream", False)
+        if _RAW_STREAM:
+            dev = ref.device.index if ref is not None and hasattr(ref, "device") else None
+            return _RAW_STREAM(torch.cuda.current_device() if dev is None else dev)
         return torch.cuda.current_stream().cuda_stream
     if stream.__class__ is int:
         return stream
@@ -177,7 +202,7 @@ def sb_gemm(transA, transB, m, n, k, alpha, A, lda, strideA, B, ldb, strideB, be
     """C_p = alpha*opA(A_p)*opB(B_p) + beta*C_p over device buffers (see sbgemm.h: sb_gemm)."""
     rc = load().sb_gemm(_dtype_of(dt, A, B, C), _op(transA), _op(transB), m, n, k, float(alpha),
                         _ptr(A), lda, strideA, _ptr(B), ldb, strideB, float(beta), _ptr(C), ldc, strideC,
-                        batch, _stream(stream))
+                        batch, _stream(stream, C))
     if check and rc != SB_OK:
         raise SbError("sb_gemm", rc)
     return rc
@@ -188,7 +213,7 @@ def sb_gemm2(transA, transB, m, n, k, alpha, A, lda, strideA0, strideA1, B, ldb,
     """Two batch levels in one launch (see sbgemm.h: sb_gemm2)."""
     rc = load().sb_gemm2(_dtype_of(dt, A, B, C), _op(transA), _op(transB), m, n, k, float(alpha),
                          _ptr(A), lda, strideA0, strideA1, _ptr(B), ldb, strideB0, strideB1,
-                         float(beta), _ptr(C), ldc, strideC0, strideC1, batch0, batch1, _stream(stream))
+                         float(beta), _ptr(C), ldc, strideC0, strideC1, batch0, batch1, _stream(stream, C))
     if check and rc != SB_OK:
         raise SbError("sb_gemm2", rc)
     return rc
@@ -212,7 +237,7 @@ def sb_contract(modesA, modesB, modesC, alpha, A, dimsA, B, dimsB, beta, C, dims
     rc = load().sb_contract(_dtype_of(dt, A, B, C), _b(modesA), _b(modesB), _b(modesC),
                             float(alpha), _ptr(A), _i64arr(dimsA), _i64arr(stridesA),
                             _ptr(B), _i64arr(dimsB), _i64arr(stridesB),
-                            float(beta), _ptr(C), _i64arr(dimsC), _i64arr(stridesC), _strat(strat), _stream(stream))
+                            float(beta), _ptr(C), _i64arr(dimsC), _i64arr(stridesC), _strat(strat), _stream(stream, C))
     if check and rc != SB_OK:
         raise SbError("sb_contract", rc)
     return rc
@@ -221,7 +246,7 @@ def sb_contract(modesA, modesB, modesC, alpha, A, dimsA, B, dimsB, beta, C, dims
 def sb_plan_launch(plan, alpha, A, B, beta, C, dt=None, stream=None, check=True):
     """Launch a plan made by sb_contract_plan (see sbgemm.h: sb_plan_launch)."""
     rc = load().sb_plan_launch(_dtype_of(dt, A, B, C), ctypes.byref(plan), float(alpha), _ptr(A), _ptr(B),
-                               float(beta), _ptr(C), _stream(stream))
+                               float(beta), _ptr(C), _stream(stream, C))
     if check and rc != SB_OK:
         raise SbError("sb_plan_launch", rc)
     return rc
@@ -266,7 +291,7 @@ def sb_tucker_hooi(T, dims, core, iterations, A, B, C, G, workspace, init=True, 
     i, j, k = core
     nbytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else 0
     rc = load().sb_tucker_hooi(_dtype_of(dt, T, A, B, C, G), _ptr(T), m, n, p, i, j, k, int(iterations), int(bool(init)),
-                               _ptr(A), _ptr(B), _ptr(C), _ptr(G), _ptr(workspace), nbytes, _stream(stream))
+                               _ptr(A), _ptr(B), _ptr(C), _ptr(G), _ptr(workspace), nbytes, _stream(stream, T))
     if check and rc != SB_OK:
         raise SbError("sb_tucker_hooi", rc)
     return rc
