@@ -615,12 +615,14 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a)
 {
     if (sb_mfma_exa_supports(dt, a)) return a.m >= 16 && a.n >= 16 && a.k >= 8;
-    if (a.m >= 32 && a.n >= 32 && a.k >= 16) return true;
+    // any k: with a short k the call is bound by writing C, and the MFMA kernel's stores of whole
+    // 128-byte runs beat the general kernel by 1.6x even at k = 1 (rank-1 updates)
+    if (a.m >= 32 && a.n >= 32) return true;
     // tall-and-skinny or short-and-wide (a factor matrix against a tensor unfolding): streaming the big
     // operand through the MFMA kernel's vector loads beats the general kernel although most of the
     // tile's columns (rows) are padding
     const int64_t lo = a.m < a.n ? a.m : a.n, hi = a.m < a.n ? a.n : a.m;
-    return lo >= 4 && hi >= 256 && a.k >= 16;
+    return lo >= 4 && hi >= 256;
 }
 
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
