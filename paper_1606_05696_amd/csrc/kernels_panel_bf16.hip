@@ -33,57 +33,72 @@ constexpr int PANEL2 = TM * LD_KC;                            // elements; [row]
 constexpr int SPITCH2 = 68;                                   // staged column: 64 rows + 8 bytes
 constexpr int OUTER2_LDS = (GP2 + GQ2) * PANEL2;              // the staging area (4 x 64 x 68 elements) fits inside
 
-// fill the two panels of one operand (X_{b0}, X_{b0+1}) with all 256 lanes
+// The two panels of one operand (X_{b0}, X_{b0+1}) on their way from memory to LDS, spread over all
+// 256 lanes: load() only issues the global loads (so that the panels of a later block can already be
+// in flight), store() writes them to LDS in [row][k] form.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 template <bool KC>
-__device__ __forceinline__ void fill_two_panels(uint16_t *lds, const uint16_t *X, int64_t bs, int64_t b0, int64_t blim, int64_t ld,
-                                                int rows, int kk)
-{
-    const int tid = (int)threadIdx.x;
-    if (KC) {                       // k contiguous in memory: 2 x 1024 vectors, straight copy
-        u16x8 v[8];
+struct TwoPanels {
+    u32x4 v[8];
+
+    __device__ __forceinline__ void load(const uint16_t *X, int64_t bs, int64_t b0, int64_t blim, int64_t ld, int rows, int kk)
+    {
+        const int tid = (int)threadIdx.x;
+        if (KC) {                       // k contiguous in memory: 2 x 1024 vectors, straight copy
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int panel = i / 4, f = tid + OT2 * (i % 4);
-            const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
+            for (int i = 0; i < 8; ++i) {
+                const int panel = i / 4, f = tid + OT2 * (i % 4);
+                const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
+                int64_t b = b0 + panel;
+                if (b >= blim) b = blim - 1;          // past the end: any valid panel, its results are never stored
+                const bool inside = row < rows && k < kk;
+                v[i] = *(const u32x4 *)(X + b * bs + (inside ? (int64_t)row * ld + k : 0));
+            }
+        } else {                        // rows contiguous in memory: one 8 x 8 block per lane (8 vectors of 8 rows)
+            const int panel = tid / 128, blk = tid % 128;
+            const int rg = blk % 8, kg = blk / 8;                  // rows 8 rg .. +7, k 8 kg .. +7
             int64_t b = b0 + panel;
             if (b >= blim) b = blim - 1;
-            const bool inside = row < rows && k < kk;
-            v[i] = *(const u16x8 *)(X + b * bs + (inside ? (int64_t)row * ld + k : 0));
-        }
+            const uint16_t *src = X + b * bs;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int panel = i / 4, f = tid + OT2 * (i % 4);
-            const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
-            const u16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-            *(u16x8 *)(lds + panel * PANEL2 + row * LD_KC + k) = (row < rows && k < kk) ? v[i] : z;
-        }
-    } else {                        // rows contiguous in memory: one 8 x 8 block per lane, transposed in registers
-        const int panel = tid / 128, blk = tid % 128;
-        const int rg = blk % 8, kg = blk / 8;                  // rows 8 rg .. +7, k 8 kg .. +7
-        int64_t b = b0 + panel;
-        if (b >= blim) b = blim - 1;
-        const uint16_t *src = X + b * bs + rg * 8;
-        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-        u32x4 v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int k = kg * 8 + i;
-            const bool inside = rg * 8 < rows && k < kk;
-            v[i] = *(const u32x4 *)(src + (inside ? (int64_t)k * ld : -(int64_t)(rg * 8)));
-            if (!inside) v[i] = u32x4{0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {                          // row 8 rg + j: its 8 k as 4 words
-            u32x4 w;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const unsigned lo = v[2 * c][j / 2], hi = v[2 * c + 1][j / 2];
-                w[c] = (j % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
+            for (int i = 0; i < 8; ++i) {
+                const int k = kg * 8 + i;
+                const bool inside = rg * 8 < rows && k < kk;
+                v[i] = *(const u32x4 *)(src + (inside ? (int64_t)k * ld + rg * 8 : 0));
             }
-            *(u32x4 *)(lds + panel * PANEL2 + (rg * 8 + j) * LD_KC + ((kg ^ rg) * 8)) = w;
         }
     }
-}
+
+    // vectors outside the matrix become zeros here (not after the load, which would wait for it)
+    __device__ __forceinline__ void store(uint16_t *lds, int rows, int kk) const
+    {
+        const int tid = (int)threadIdx.x;
+        const u32x4 z = {0, 0, 0, 0};
+        if (KC) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int panel = i / 4, f = tid + OT2 * (i % 4);
+                const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
+                *(u32x4 *)(lds + panel * PANEL2 + row * LD_KC + k) = (row < rows && k < kk) ? v[i] : z;
+            }
+        } else {                        // transposed in registers: row 8 rg + j gets its 8 k as 4 words
+            const int panel = tid / 128, blk = tid % 128;
+            const int rg = blk % 8, kg = blk / 8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                u32x4 w;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool in_lo = rg * 8 < rows && kg * 8 + 2 * c < kk, in_hi = rg * 8 < rows && kg * 8 + 2 * c + 1 < kk;
+                    const unsigned lo = in_lo ? v[2 * c][j / 2] : 0u, hi = in_hi ? v[2 * c + 1][j / 2] : 0u;
+                    w[c] = (j % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
+                }
+                *(u32x4 *)(lds + panel * PANEL2 + (rg * 8 + j) * LD_KC + ((kg ^ rg) * 8)) = w;
+            }
+        }
+    }
+};
 
 // MFMA operand of the 32 rows starting at row0 for k-step ks; SWZ: the panel was written with the chunk swizzle
 template <bool SWZ>
@@ -95,94 +110,119 @@ __device__ __forceinline__ bf16x8 panel2_fragment(const uint16_t *lds, int row0,
     return __builtin_bit_cast(bf16x8, *(const u16x8 *)(lds + row * LD_KC + chunk * 8));
 }
 
+// A workgroup takes TWO neighbouring 2 x 2 blocks (same A panels, the next two B panels).  The loads of
+// the second block's B panels are issued together with the first block's, so they are in flight
+// while the first block is multiplied and stored, and the first block's stores drain while the
+// second is multiplied: with one block per workgroup the grid ran as two rounds of workgroups whose
+// fetch, multiply and store phases (2.4 + 1.0 + 2.0 us, each a chain of latencies) simply added up.
 template <bool A_KC, bool B_KC, int KS>
 __global__ __launch_bounds__(OT2) void sbgemm_outer2_bf16_kernel(SbArgs g, int groups_p, int vec_store)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [GP2 + GQ2][PANEL2], later [wave][64][SPITCH2]
-    const int gp = (int)(blockIdx.x % groups_p), gq = (int)(blockIdx.x / groups_p);
-    const int64_t p0 = (int64_t)gp * GP2, q0 = (int64_t)gq * GQ2;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [A0 A1 | B0 B1]; the B half doubles as staging area
+    const int gp = (int)(blockIdx.x % groups_p), gq2 = (int)(blockIdx.x / groups_p);
+    const int64_t p0 = (int64_t)gp * GP2, q0 = (int64_t)gq2 * (2 * GQ2);
     const int m = (int)g.m, n = (int)g.n, kk = (int)g.k;
+    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
+    uint16_t *ldsB = lds + GP2 * PANEL2;
 
-    fill_two_panels<A_KC>(lds, (const uint16_t *)g.A, g.bsA[0], p0, g.batch0, A_KC ? g.rsA : g.csA, m, kk);
-    fill_two_panels<B_KC>(lds + GP2 * PANEL2, (const uint16_t *)g.B, g.bsB[1], q0, g.batch1, B_KC ? g.csB : g.rsB, n, kk);
+    TwoPanels<A_KC> pa;
+    TwoPanels<B_KC> pb, pb2;
+    pa.load((const uint16_t *)g.A, g.bsA[0], p0, g.batch0, ldA, m, kk);
+    pb.load((const uint16_t *)g.B, g.bsB[1], q0, g.batch1, ldB, n, kk);
+    pb2.load((const uint16_t *)g.B, g.bsB[1], q0 + GQ2, g.batch1, ldB, n, kk);      // clamped when there is no second block
+    pa.store(lds, m, kk);
+    pb.store(ldsB, n, kk);
     __syncthreads();
 
-    // wave w: the whole 64 x 64 GEMM A_{p0 + w/2} B_{q0 + w%2}
+    // wave w: the whole 64 x 64 GEMM A_{p0 + w/2} B_{q + w%2}
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int pi = wave >> 1, qi = wave & 1;
-    const uint16_t *la = lds + pi * PANEL2, *lb = lds + (GP2 + qi) * PANEL2;
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 fa[2], fb[2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a) fa[a] = panel2_fragment<!A_KC>(la, a * 32, ks, lane);
-#pragma unroll
-        for (int c = 0; c < 2; ++c) fb[c] = panel2_fragment<!B_KC>(lb, c * 32, ks, lane);
+    const uint16_t *la = lds + pi * PANEL2, *lb = ldsB + qi * PANEL2;
+    const float alpha = (float)g.alpha, beta = (float)g.beta;
+    const int64_t p = p0 + pi;
+    uint16_t *st = ldsB + wave * (TN * SPITCH2);
+    typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+    // multiply, park the results as bf16 in the B half (free once every wave has its products),
+    // write whole 128-byte lines of C
+    auto block = [&](int64_t q) {
+        f32x16 acc[2][2];
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
-                // result register r of lane l: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
-                acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[c], acc[a][c], 0, 0, 0);
-    }
-    __syncthreads();                 // every wave is done with the panels: the space becomes the staging area
-
-    const float alpha = (float)g.alpha, beta = (float)g.beta;
-    const int64_t p = p0 + pi, q = q0 + qi;
-    const bool live = p < g.batch0 && q < g.batch1;
-    uint16_t *st = lds + wave * (TN * SPITCH2);
-    uint16_t *Cq = (uint16_t *)g.C + (live ? p * g.bsC[0] + q * g.bsC[1] : 0);
-    typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            const int j = c * 32 + (lane & 31);
+        for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 fa[2], fb[2];
 #pragma unroll
-            for (int gq4 = 0; gq4 < 4; ++gq4) {
-                const int i0 = a * 32 + 8 * gq4 + 4 * (lane >> 5);
-                float v[4];
+            for (int a = 0; a < 2; ++a) fa[a] = panel2_fragment<!A_KC>(la, a * 32, ks, lane);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = alpha * acc[a][c][4 * gq4 + e];
-                if (beta != 0.f && live && j < n) {
-                    const uint16_t *old = Cq + (int64_t)j * g.ldc + i0;
+            for (int c = 0; c < 2; ++c) fb[c] = panel2_fragment<!B_KC>(lb, c * 32, ks, lane);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+                    // result register r of lane l: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[c], acc[a][c], 0, 0, 0);
+        }
+        __syncthreads();             // every wave is done with the B panels
+        const bool live = p < g.batch0 && q < g.batch1;
+        uint16_t *Cq = (uint16_t *)g.C + (live ? p * g.bsC[0] + q * g.bsC[1] : 0);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const int j = c * 32 + (lane & 31);
+#pragma unroll
+                for (int gq4 = 0; gq4 < 4; ++gq4) {
+                    const int i0 = a * 32 + 8 * gq4 + 4 * (lane >> 5);
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = alpha * acc[a][c][4 * gq4 + e];
+                    if (beta != 0.f && live && j < n) {
+                        const uint16_t *old = Cq + (int64_t)j * g.ldc + i0;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
+                    }
+                    u16x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
+                    *(u16x4 *)(st + j * SPITCH2 + i0) = pk;
                 }
-                u16x4 pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
-                *(u16x4 *)(st + j * SPITCH2 + i0) = pk;
             }
-        }
-    __syncthreads();
-    if (!live) return;
-    if (vec_store) {                 // m is a multiple of 8 and every column of C starts 16-byte aligned
-        const int seg = 8 * (lane & 7);
+        __syncthreads();
+        if (live) {
+            if (vec_store) {             // m is a multiple of 8 and every column of C starts 16-byte aligned
+                const int seg = 8 * (lane & 7);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int j = 8 * t + (lane >> 3);
-            const u16x4 lo = *(const u16x4 *)(st + j * SPITCH2 + seg);
-            const u16x4 hi = *(const u16x4 *)(st + j * SPITCH2 + seg + 4);
-            if (seg < m && j < n) {
-                u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
-            }
-        }
-    } else {
+                for (int t = 0; t < 8; ++t) {
+                    const int j = 8 * t + (lane >> 3);
+                    const u16x4 lo = *(const u16x4 *)(st + j * SPITCH2 + seg);
+                    const u16x4 hi = *(const u16x4 *)(st + j * SPITCH2 + seg + 4);
+                    if (seg < m && j < n) {
+                        u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
+                    }
+                }
+            } else {
 #pragma unroll 4
-        for (int j = 0; j < TN; ++j) {
-            const uint16_t v = st[j * SPITCH2 + lane];
-            if (lane < m && j < n) Cq[(int64_t)j * g.ldc + lane] = v;
+                for (int j = 0; j < TN; ++j) {
+                    const uint16_t v = st[j * SPITCH2 + lane];
+                    if (lane < m && j < n) Cq[(int64_t)j * g.ldc + lane] = v;
+                }
+            }
         }
+    };
+
+    block(q0 + qi);
+    if (q0 + GQ2 < g.batch1) {           // workgroup-uniform: the second block exists
+        __syncthreads();                 // the staged results of the first block have been read
+        pb2.store(ldsB, n, kk);
+        __syncthreads();
+        block(q0 + GQ2 + qi);
     }
 }
 
@@ -213,7 +253,7 @@ static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
     auto al8 = [](int64_t v) { return v % 8 == 0; };
     const int vec_store = (uintptr_t)a.C % 16 == 0 && al8(a.ldc) && al8(a.bsC[0]) && al8(a.bsC[1]) && al8(a.m);
     const int ks = (int)((a.k + 15) / 16);
-    const int64_t groups_p = (a.batch0 + GP2 - 1) / GP2, groups_q = (a.batch1 + GQ2 - 1) / GQ2;
+    const int64_t groups_p = (a.batch0 + GP2 - 1) / GP2, groups_q = (a.batch1 + 2 * GQ2 - 1) / (2 * GQ2);     // two blocks along q per workgroup
     const size_t lds_bytes = (size_t)OUTER2_LDS * sizeof(uint16_t);
     dim3 grid((unsigned)(groups_p * groups_q)), block(OT2);
 #define SB_OUTER(KS_)                                                                                                  \
