@@ -185,7 +185,7 @@ const char *sb_status_string(int status);
  * intended path ran).  sb_force_kernel(id) makes later calls use that family when it supports the
  * problem (SB_KERNEL_AUTO restores the selector); sb_last_kernel() is the family of the most
  * recent launch of this thread's process (-1 before any).  Neither is thread-safe. */
-enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2 };
+enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2, SB_KERNEL_THIN = 3 };
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
 

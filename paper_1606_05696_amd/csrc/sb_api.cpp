@@ -29,14 +29,17 @@ int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     int kernel = SB_KERNEL_GENERIC;
     if (g_force_kernel == SB_KERNEL_TINY && sb_tiny_supports(dt, a)) kernel = SB_KERNEL_TINY;
     else if (g_force_kernel == SB_KERNEL_MFMA && sb_mfma_supports(dt, a)) kernel = SB_KERNEL_MFMA;
+    else if (g_force_kernel == SB_KERNEL_THIN && sb_thin_supports(dt, a)) kernel = SB_KERNEL_THIN;
     else if (g_force_kernel == SB_KERNEL_AUTO) {
-        if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) kernel = SB_KERNEL_TINY;
+        if (sb_thin_supports(dt, a) && sb_thin_preferred(dt, a)) kernel = SB_KERNEL_THIN;
+        else if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) kernel = SB_KERNEL_TINY;
         else if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) kernel = SB_KERNEL_MFMA;
     }
     hipError_t err;
     switch (kernel) {
     case SB_KERNEL_TINY: err = sb_launch_tiny(dt, a, stream); break;
     case SB_KERNEL_MFMA: err = sb_launch_mfma(dt, a, stream); break;
+    case SB_KERNEL_THIN: err = sb_launch_thin(dt, a, stream); break;
     default:             err = sb_launch_generic(dt, a, stream); break;
     }
     g_last_kernel = kernel;
@@ -315,7 +318,7 @@ extern "C" const char *sb_status_string(int status)
 
 extern "C" int sb_force_kernel(int kernel_id)
 {
-    if (kernel_id < SB_KERNEL_AUTO || kernel_id > SB_KERNEL_MFMA) return -1;
+    if (kernel_id < SB_KERNEL_AUTO || kernel_id > SB_KERNEL_THIN) return -1;
     g_force_kernel = kernel_id;
     return SB_OK;
 }

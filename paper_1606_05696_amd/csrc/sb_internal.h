@@ -28,6 +28,10 @@ bool sb_tiny_supports(sb_dtype dt, const SbArgs &a);
 bool sb_tiny_preferred(sb_dtype dt, const SbArgs &a);
 hipError_t sb_launch_tiny(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 
+bool sb_thin_supports(sb_dtype dt, const SbArgs &a);            // m or n at most 4: level-2 kernels
+bool sb_thin_preferred(sb_dtype dt, const SbArgs &a);
+hipError_t sb_launch_thin(sb_dtype dt, const SbArgs &a, hipStream_t stream);
+
 bool sb_mfma_supports(sb_dtype dt, const SbArgs &a);
 bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a);
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream);

@@ -13,7 +13,8 @@ from paper_1606_05696_amd import inputs
 
 pytestmark = pytest.mark.gpu
 
-KERNELS = {"auto": sb.SB_KERNEL_AUTO, "generic": sb.SB_KERNEL_GENERIC, "tiny": sb.SB_KERNEL_TINY, "mfma": sb.SB_KERNEL_MFMA}
+KERNELS = {"auto": sb.SB_KERNEL_AUTO, "generic": sb.SB_KERNEL_GENERIC, "tiny": sb.SB_KERNEL_TINY, "mfma": sb.SB_KERNEL_MFMA,
+           "thin": sb.SB_KERNEL_THIN}
 
 
 @pytest.fixture(autouse=True)
@@ -69,7 +70,7 @@ def test_sb_gemm_ragged_tiles(dtype, opA, opB, kernel):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
-@pytest.mark.parametrize("kernel", ["auto", "generic", "tiny", "mfma"])
+@pytest.mark.parametrize("kernel", ["auto", "generic", "tiny", "mfma", "thin"])
 @pytest.mark.parametrize("m,n,k,batch", [(1, 1, 1, 1), (1, 9, 5, 4), (9, 1, 5, 4), (16, 16, 16, 1000), (8, 8, 8, 70001),
                                           (33, 17, 1, 3), (5, 6, 7, 2), (64, 64, 64, 5), (128, 128, 96, 2), (200, 130, 260, 2)])
 def test_sb_gemm_shapes(dtype, kernel, m, n, k, batch):
@@ -78,6 +79,43 @@ def test_sb_gemm_shapes(dtype, kernel, m, n, k, batch):
     assert err <= TOL[dtype], err
     err, got, ref = run_sb_gemm(dtype, "T", "N", m, n, k, batch, k, k, m, m * k, 0, m * n, -1.5, 1.0, 12, kernel)
     assert err <= TOL[dtype], err
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
+@pytest.mark.parametrize("thin", [1, 2, 3, 4])
+def test_sb_gemm_thin_shapes(dtype, opA, opB, thin):
+    # the BatchedGemv end: n (then m) is the thin extent, the other two are several tiles with ragged
+    # tails.  Packed and whole-vector extents take the 16-byte kernels, the padded odd ones the scalar
+    # kernels; a long k exercises the unrolled trips and their tail; the last two have enough rows
+    # for the widest loads, with sixteen and with four waves to a workgroup.
+    for m, n, k, batch, pad in [(1000, thin, 333, 3, 1), (thin, 1000, 333, 3, 1), (1024, thin, 520, 5, 0),
+                                (thin, 1024, 520, 5, 0), (8, thin, 4099, 2, 0), (thin, 24, 8192, 4, 0),
+                                (4096, thin, 136, 16, 0), (4096, thin, 96, 70, 0)]:
+        lda = (m if opA == "N" else k) + 3 * pad
+        ldb = (k if opB == "N" else n) + 5 * pad
+        ldc = m + 2 * pad
+        loa = lda * (k if opA == "N" else m) + 7 * pad
+        lob = ldb * (n if opB == "N" else k) + pad
+        loc = ldc * n + 11 * pad
+        err, got, ref = run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, 0.75, -0.5, 21,
+                                    "thin")
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN
+        assert err <= TOL[dtype], (m, n, k, err)
+        err, got, ref = run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, 1.0, 0.0, 22)
+        assert err <= TOL[dtype], (m, n, k, err)
+
+
+def test_thin_calls_take_the_thin_kernels():
+    # a batched matrix-vector product and a batched vector-matrix product, many 16-byte tiles: the
+    # selector sends both to the level-2 family, shared operand (stride 0) included
+    for m, n in [(4096, 1), (1, 4096), (2048, 3), (2, 2048)]:
+        err, got, ref = run_sb_gemm("f32", "N", "N", m, n, 256, 40, m, 256, m, 0, 256 * n, m * n, 1.0, 0.0, 31)
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN
+        assert err <= TOL["f32"], err
+        err, got, ref = run_sb_gemm("f64", "T", "T", m, n, 256, 40, 256, n, m, m * 256, 0, m * n, 1.0, 0.0, 32)
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN
+        assert err <= TOL["f64"], err
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
