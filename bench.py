@@ -273,7 +273,8 @@ def run_sweeps(steps, warmup):
     """Size sweeps over cubic tensors in fp32, the shapes of the paper's GPU plots (section IV):
     batches of n small GEMMs (n x n x n) against the vendor's strided-batched GEMM; case 1.1 in its
     three evaluations (flattened, batched in p, batched in n); the exceptional case 6.4 with the
-    extended operation, as batched matrix-vector products and by transposition + GEMM."""
+    extended operation, as batched matrix-vector products and by transposition + GEMM; n matrix-vector products of n x n matrices (the BatchedGemv end).
+    """
     import torch
     import paper_1606_05696_amd as sb
     from paper_1606_05696_amd import inputs
@@ -339,6 +340,31 @@ def run_sweeps(steps, warmup):
         row["extended_op_gflops"] = 2 * n ** 4 / row["extended_op_us"] / 1e3
         rows.append(row)
     out["case_6_4_exceptional"] = rows
+
+    rows = []
+    for n in sizes[2:] + [1024]:      # n matrix-vector products y_p = op(A_p) x_p with n x n matrices: level 2, HBM-bound
+        tA = dev(inputs.uniform_tensor(57, [n, n, n], np.float32), "f32")
+        tx = dev(inputs.uniform_tensor(58, [n, n], np.float32), "f32")
+        ty = torch.empty(n * n, dtype=torch.float32, device="cuda")
+        row = dict(n=n)
+        nbytes = 4 * (n ** 3 + 2 * n * n)
+        for name, op in (("gemv_n", "N"), ("gemv_t", "T")):
+            def ours():
+                sb.sb_gemm(op, "N", n, 1, n, 1.0, tA, n, n * n, tx, n, n, 0.0, ty, n, n, n, dt="f32")
+            _, t = time_steps(ours, reps(n), warmup)
+            row[name + "_us"] = t * 1e3
+            row[name + "_gbps"] = nbytes / t / 1e6
+            row[name + "_frac_of_hbm_peak"] = nbytes / t / 1e6 / PEAK["hbm"]
+            row[name + "_kernel_family"] = sb.sb_last_kernel()
+        a3, x3, y3 = tA.view(n, n, n), tx.view(n, 1, n), ty.view(n, 1, n)
+
+        def vendor():      # row-major views: y_p^T = x_p^T A_p^T
+            torch.bmm(x3, a3, out=y3)
+
+        _, t = time_steps(vendor, reps(n), warmup)
+        row["vendor_bmm_us"] = t * 1e3
+        rows.append(row)
+    out["batched_gemv_n_of_nxn"] = rows
     return out
 
 
