@@ -167,13 +167,13 @@ struct Config {
 //     MFMAs run (two fragment register sets).  The hand-over to the next block (LDS store of the
 //     staged panel, barrier, first fragment read of the new block) is placed BEFORE the last
 //     k-group's MFMAs of the current block, which then hide its latency.
-// GUARD selects bounds-checked scalar loads (odd extents, unaligned operands), masked vector loads
-// (edge tiles whose edges fall between vectors) or plain 16-byte
-// vector loads (interior tiles, branch-free).
-template <typename CF, typename T, int GUARD>
+// GA / GB select, per operand, bounds-checked scalar loads (odd extents, unaligned operands),
+// masked vector loads (edge tiles whose edges fall between vectors) or plain 16-byte vector loads
+// (interior tiles, branch-free): a ragged or unaligned operand does not slow the other one down.
+template <typename CF, typename T, int GA, int GB>
 __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::NBN], T (*As)[CF::PA::LDS_SIZE], T (*Bs)[CF::PB::LDS_SIZE],
                                         const T *A, const T *B, int64_t ldA, int64_t ldB, int64_t kstepA, int64_t kstepB,
-                                        int64_t m_left, int64_t n_left, int64_t K, bool vec_ok, int wm, int wn, int lane, int BKc)
+                                        int64_t m_left, int64_t n_left, int64_t K, bool vec_a, bool vec_b, int wm, int wn, int lane, int BKc)
 {
     typedef typename CF::MF MF;
     typedef typename CF::PA PA;
@@ -194,8 +194,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
     };
     auto gload = [&](auto set, int64_t kb) {
         const int64_t k0 = kb * BK;
-        PA::template load<GUARD>(ra[set], A + k0 * kstepA, ldA, m_left, K - k0, vec_ok);
-        PB::template load<GUARD>(rb[set], B + k0 * kstepB, ldB, n_left, K - k0, vec_ok);
+        PA::template load<GA>(ra[set], A + k0 * kstepA, ldA, m_left, K - k0, vec_a);
+        PB::template load<GB>(rb[set], B + k0 * kstepB, ldB, n_left, K - k0, vec_b);
     };
     // one k block; CUR (= kb & 1) is a compile-time constant so that every register array is
     // indexed statically.  STEADY = true is the steady state (block kb+2 exists): the prefetch
@@ -228,8 +228,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
                     // LDS store of the next block's panel (requested one block ago) between two
                     // halves of a cluster: the matrix core keeps running under it
                     __builtin_amdgcn_sched_barrier(0);
-                    PA::template store<GUARD == 1>(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0], m_left, K - (kb + 1) * BK);
-                    PB::template store<GUARD == 1>(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0], n_left, K - (kb + 1) * BK);
+                    PA::template store<GA == 1>(As[CUR ^ 1], ra[GD == 2 ? (CUR ^ 1) : 0], m_left, K - (kb + 1) * BK);
+                    PB::template store<GB == 1>(Bs[CUR ^ 1], rb[GD == 2 ? (CUR ^ 1) : 0], n_left, K - (kb + 1) * BK);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
@@ -245,8 +245,8 @@ __device__ __forceinline__ void k_loop(typename CF::MF::Acc (&acc)[CF::NBM][CF::
 
     gload(I0(), 0);
     if (GD == 2 && nkb > 1) gload(std::integral_constant<int, GD - 1>(), 1);
-    PA::template store<GUARD == 1>(As[0], ra[0], m_left, K);
-    PB::template store<GUARD == 1>(Bs[0], rb[0], n_left, K);
+    PA::template store<GA == 1>(As[0], ra[0], m_left, K);
+    PB::template store<GB == 1>(Bs[0], rb[0], n_left, K);
     __syncthreads();
     read_frags(I0(), I0(), 0);
     int64_t kb = 0;
@@ -317,16 +317,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 
 #pragma unroll
                 for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
 
-        // workgroup-uniform: interior tile with aligned operands -> branch-free loop
-        const bool interior = vec_ok && m_left >= BM && n_left >= BN && (g.k % BK == 0);
-        // edges that fall between 16-byte vectors: unconditional loads with masking
-        const bool vec_edges = vec_ok && (A_KC ? g.k % MF::VEC == 0 : g.m % MF::VEC == 0) && (B_KC ? g.k % MF::VEC == 0 : g.n % MF::VEC == 0);
-        if (interior)
-            k_loop<CF, T, 0>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
-        else if (vec_edges)
-            k_loop<CF, T, 1>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, true, wm, wn, lane, BK);
-        else
-            k_loop<CF, T, 2>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_ok, wm, wn, lane, BK);
+        // workgroup-uniform choices.  Interior tile with aligned operands: branch-free loop.
+        // Otherwise, per operand: if its panels' edges fall between 16-byte vectors (aligned, and the
+        // extent along its contiguous dimension whole vectors or not cut by this tile), masked
+        // unconditional vector loads; else element-wise guards.
+        const bool vec_a = vec_ok & 1, vec_b = vec_ok & 2;
+        const bool interior = vec_a && vec_b && m_left >= BM && n_left >= BN && (g.k % BK == 0);
+        const bool mask_a = vec_a && (A_KC ? g.k % MF::VEC == 0 : (m_left >= BM || g.m % MF::VEC == 0));
+        const bool mask_b = vec_b && (B_KC ? g.k % MF::VEC == 0 : (n_left >= BN || g.n % MF::VEC == 0));
+#define K_LOOP(GA, GB) k_loop<CF, T, GA, GB>(acc, As, Bs, A, B, ldA, ldB, kstepA, kstepB, m_left, n_left, g.k, vec_a, vec_b, wm, wn, lane, BK)
+        if (interior)               K_LOOP(0, 0);
+        else if (mask_a && mask_b)  K_LOOP(1, 1);
+        else if (mask_a)            K_LOOP(1, 2);
+        else if (mask_b)            K_LOOP(2, 1);
+        else                        K_LOOP(2, 2);
+#undef K_LOOP
 
         // epilogue: lane = row of C within the block, result slot = column.  The four variants
         // (edge tile or not, beta or not) are chosen by workgroup-uniform branches so that the
@@ -576,12 +581,13 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     constexpr int VEC = MFT::VEC;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
     auto aligned = [](int64_t v) { return v % VEC == 0; };
-    const int vec_ok = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
-                       aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
-                       aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    // per operand: every 16-byte vector of its panels is aligned (bit 0: A, bit 1: B)
+    const bool vec_a = ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]);
+    const bool vec_b = ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    const int vec_ok = (vec_a ? 1 : 0) | (vec_b ? 2 : 0);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
     // whole tiles, aligned operands, an even number (>= 4) of k blocks: the streaming kernel
-    if (vec_ok && a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK) {
+    if (vec_ok == 3 && a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK) {
 #define STREAM(AK, BKC)                                                                                                                  \
     (a.beta == 0.0 ? launch_persistent(sbgemm_mfma_stream_kernel<T, AK, BKC, false, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn) \
                    : launch_persistent(sbgemm_mfma_stream_kernel<T, AK, BKC, true, BK, WM, WN, WAVES_M, WAVES_N>, NT, total, stream, a, tm, tn))
@@ -630,9 +636,15 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     if (sb_mfma_exa_supports(dt, a)) return sb_launch_mfma_exa(dt, a, stream);
     switch (dt) {
     case SB_F32:
+        // a factor matrix against a tensor unfolding: bound by streaming the big operand, so the
+        // tile is long in that operand's direction (big panels in flight) and one MFMA block wide
+        if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
+        if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (a.m <= 64 || a.n <= 64) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
+        if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
+        if (a.m <= 32 && a.n >= 256) return launch<MfmaF64x16, 16, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (a.m <= 64 || a.n <= 64) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
         return launch<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);                                 // 128 x 128 tiles, 16 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
