@@ -94,8 +94,9 @@ __global__ void identity_kernel(T *V, int n)
 // One compute unit does all the arithmetic, so the step is kept short in instructions: an odd
 // matrix is padded with a zero row and column (its phantom index then rotates by the identity
 // without any test), the pairs and rotations of a step sit in a small LDS table, and the
-// (pair, pair) coordinates of a thread's work items advance by addition.  A sweep that rotated
-// nothing ends the iteration early.
+// (pair, pair) coordinates of a thread's work items advance by addition.  The iteration ends as
+// soon as no off-diagonal element exceeds the threshold, and a round without a rotation costs one
+// barrier only.
 constexpr int LDS_THREADS = 1024;
 
 // what a step needs to know about one pair: the two indices and the rotation; one LDS read
@@ -117,13 +118,14 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
     T *As = (T *)raw;                    // ne x ne, leading dimension ne
     T *Vs = As + ne * ne;                // ne x ne as well (a zero phantom row keeps row pairs aligned)
     PairRec<T> *rec = (PairRec<T> *)(((uintptr_t)(Vs + ne * ne) + 15) & ~(uintptr_t)15);      // [h]
-    __shared__ int rotated;
+    __shared__ int rotates[3];           // does any pair of the round rotate?  three flags take turns
+    __shared__ T wave_max[LDS_THREADS / 64];
     for (int e = tid; e < ne * ne; e += LDS_THREADS) {
         const int i = e % ne, j = e / ne;
         As[e] = (i < n && j < n) ? A[i + j * n] : T(0);
     }
     for (int e = tid; e < ne * ne; e += LDS_THREADS) Vs[e] = (e % ne == e / ne && e % ne < n) ? T(1) : T(0);
-    if (tid == 0) rotated = 0;
+    if (tid < 3) rotates[tid] = 0;
     __syncthreads();
     // off-diagonal elements below rounding level of the largest diagonal element are left alone: they
     // no longer move the eigenvalues, and among (nearly) equal eigenvalues they would rotate noise forever
@@ -139,7 +141,23 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
     const int P0 = tid % h, Q0 = tid / h, dP = LDS_THREADS % h, dQ = LDS_THREADS / h;
     typedef T T2 __attribute__((ext_vector_type(2)));
     for (int sweep = 0; sweep < sweeps; ++sweep) {
+        // Done when no off-diagonal element is above the threshold: one pass over the matrix instead
+        // of a sweep that finds nothing to rotate (a warm-started matrix often needs a single sweep).
+        T big = T(0);
+        for (int e = tid; e < ne * ne; e += LDS_THREADS)
+            if (e % ne != e / ne) big = fmax(big, fabs(As[e]));
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) big = fmax(big, __shfl_xor(big, off));
+        if ((tid & 63) == 0) wave_max[tid >> 6] = big;
+        __syncthreads();
+        big = wave_max[0];
+#pragma unroll
+        for (int w = 1; w < LDS_THREADS / 64; ++w) big = fmax(big, wave_max[w]);
+        __syncthreads();                 // wave_max is rewritten by the next sweep's pass
+        if (!(big > tiny)) break;        // workgroup-uniform
         for (int round = 0; round < ne - 1; ++round) {
+            const int flag = (sweep * (ne - 1) + round) % 3;
+            if (tid == 0) rotates[(flag + 1) % 3] = 0;      // the next round's flag; last read two rounds ago
             if (tid < h) {
                 int p, q;
                 pair_of(tid, round, ne, p, q);
@@ -147,13 +165,14 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
                 const T apq = As[p + q * ne];                                       // phantom index: apq = 0 -> identity
                 if (fabs(apq) > tiny) {
                     rotation(As[p + p * ne], As[q + q * ne], apq, c, s);
-                    rotated = 1;
+                    rotates[flag] = 1;
                 }
                 PairRec<T> r;
                 r.p = p; r.q = q; r.c = c; r.s = s;
                 rec[tid] = r;
             }
             __syncthreads();
+            if (!rotates[flag]) continue;        // workgroup-uniform: nothing moves in this round
             int P = P0, Q = Q0;
             for (int item = tid; item < nA; item += LDS_THREADS) {
                 const PairRec<T> rP = rec[P], rQ = rec[Q];
@@ -176,11 +195,6 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
             }
             __syncthreads();
         }
-        const int any = rotated;
-        __syncthreads();
-        if (!any) break;                 // workgroup-uniform
-        if (tid == 0) rotated = 0;
-        __syncthreads();                 // the reset must not overtake the next sweep's first rotations
     }
     for (int e = tid; e < n * n; e += LDS_THREADS) {
         A[e] = As[e % n + (e / n) * ne];
@@ -229,12 +243,12 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweep
     if (n == 1) {
         identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
         *A_final = A; *V_final = V;
-    } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 64) {       // 64 bytes stay for the static flag
+    } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 512) {      // 512 bytes stay for the static variables
         const size_t bytes = jacobi_lds_bytes<T>(n);
         static bool configured[SB_MAX_DEVICES] = {};
         const int dev = sb_current_device();
         if (!configured[dev]) {
-            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);    // 64 bytes stay for the static variables
+            hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
             if (e != hipSuccess) return e;
             configured[dev] = true;
         }
