@@ -621,14 +621,17 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a)
 {
     if (sb_mfma_exa_supports(dt, a)) return a.m >= 16 && a.n >= 16 && a.k >= 8;
-    // any k: with a short k the call is bound by writing C, and the MFMA kernel's stores of whole
-    // 128-byte runs beat the general kernel by 1.6x even at k = 1 (rank-1 updates)
+    // Nearly every N/T problem the thin and tiny kernels leave.
+    // m, n >= 32, any k: with a short k the call is bound by writing C, and the MFMA kernel's stores
+    // of whole 128-byte runs beat the general kernel by 1.6x even at k = 1 (rank-1 updates).
     if (a.m >= 32 && a.n >= 32) return true;
-    // tall-and-skinny or short-and-wide (a factor matrix against a tensor unfolding): streaming the big
-    // operand through the MFMA kernel's vector loads beats the general kernel although most of the
-    // tile's columns (rows) are padding
-    const int64_t lo = a.m < a.n ? a.m : a.n, hi = a.m < a.n ? a.n : a.m;
-    return lo >= 4 && hi >= 256;
+    // a factor matrix against a tensor unfolding: the long tiles stream the big operand
+    const int64_t hi = a.m < a.n ? a.n : a.m;
+    if (hi >= 256) return true;
+    // Smaller shapes, where most of a 64 x 64 tile is padding (m = 10, n = 100): the vector loads
+    // and the matrix core are still 1.1-2.2x (bf16: 1.3-3.5x) ahead of the general kernel's scalar
+    // loads and vector-ALU products unless k is short (k < 32: the general kernel is 1.2-1.5x ahead).
+    return dt == SB_BF16 || a.k >= 32;
 }
 
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)

@@ -128,8 +128,8 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
     u16x8 ra[PA::NVEC], rb[PB::NVEC];
     const int64_t nkb = (g.k + BK - 1) / BK;
     if (nkb > 0) {
-        PA::load(ra, A, ldA, m_left, g.k, vec_ok);
-        PB::load(rb, B, ldB, n_left, g.k, vec_ok);
+        PA::load(ra, A, ldA, m_left, g.k, vec_ok & 1);
+        PB::load(rb, B, ldB, n_left, g.k, vec_ok & 2);
         PA::store(As[0], ra);
         PB::store(Bs[0], rb);
     }
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
         const bool more = kb + 1 < nkb;
         if (more) {
             const int64_t k0 = (kb + 1) * BK;
-            PA::load(ra, A + k0 * kstepA, ldA, m_left, g.k - k0, vec_ok);
-            PB::load(rb, B + k0 * kstepB, ldB, n_left, g.k - k0, vec_ok);
+            PA::load(ra, A + k0 * kstepA, ldA, m_left, g.k - k0, vec_ok & 1);
+            PB::load(rb, B + k0 * kstepB, ldB, n_left, g.k - k0, vec_ok & 2);
         }
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -192,9 +192,10 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
     auto aligned = [](int64_t v) { return v % 8 == 0; };
-    const int vec_ok = ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.B % 16 == 0) &&
-                       aligned(a_kc ? a.rsA : a.csA) && aligned(b_kc ? a.csB : a.rsB) &&
-                       aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    // per operand: every 16-byte vector of its panels is aligned (bit 0: A, bit 1: B)
+    const bool vec_a = ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]);
+    const bool vec_b = ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    const int vec_ok = (vec_a ? 1 : 0) | (vec_b ? 2 : 0);
     dim3 grid((unsigned)total), block(NTHREADS);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
     if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<true, true, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);
