@@ -189,6 +189,14 @@ enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
 
+/* Host only: the kernel family the selector sends an sb_gemm problem to (sizes, operations and
+ * strides as for sb_gemm, all of m, n, k, batch at least 1; no pointers: the family depends on the
+ * shape only, alignment decides between variants inside a family).  Negative: -i = i-th argument
+ * invalid.  Ignores sb_force_kernel. */
+int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                     int64_t lda, int64_t strideA, int64_t ldb, int64_t strideB, int64_t ldc,
+                     int64_t strideC, int64_t batch);
+
 /* Diagnostics for benchmarks: enqueue a kernel that only issues the MFMA instruction the kernels of
  * element type dt are built on (4 independent accumulators per wave, 16 waves per compute unit),
  * `iterations` rounds (a multiple of 16); *flops receives the floating-point operations it performs, so that

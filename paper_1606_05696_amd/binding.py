@@ -30,7 +30,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 __all__ = [n for n in dir() if n.startswith("SB_")] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
-    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
+    "sb_select_kernel",    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
 
 
 class sb_plan(ctypes.Structure):
@@ -90,6 +90,8 @@ def load():
     lib.sb_force_kernel.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
     lib.sb_last_kernel.argtypes = []
+    lib.sb_select_kernel.restype = ci
+    lib.sb_select_kernel.argtypes = [ci, ci, ci, i64, i64, i64, i64, i64, i64, i64, i64, i64, i64]
     lib.sb_probe_mfma.restype = ci
     lib.sb_probe_mfma.argtypes = [ci, ci, vp, i64, vp, ctypes.POINTER(dbl)]
     lib.sb_tucker_workspace.restype = ci
@@ -258,6 +260,11 @@ def sb_force_kernel(kernel_id):
 
 def sb_last_kernel():
     return load().sb_last_kernel()
+
+
+def sb_select_kernel(dt, transA, transB, m, n, k, lda, strideA, ldb, strideB, ldc, strideC, batch):
+    return load().sb_select_kernel(_dtype_of(dt), _op(transA), _op(transB), m, n, k, lda, strideA, ldb, strideB,
+                                   ldc, strideC, batch)
 
 
 def sb_plan_launches(plan):

@@ -24,17 +24,23 @@ void op_strides(int op, int64_t ld, int64_t stride0, int64_t &rs, int64_t &cs, i
     }
 }
 
+// The selector: which kernel family runs a problem (host arithmetic on sizes and strides only).
+int choose(sb_dtype dt, const SbArgs &a, int forced)
+{
+    if (forced == SB_KERNEL_TINY && sb_tiny_supports(dt, a)) return SB_KERNEL_TINY;
+    if (forced == SB_KERNEL_MFMA && sb_mfma_supports(dt, a)) return SB_KERNEL_MFMA;
+    if (forced == SB_KERNEL_THIN && sb_thin_supports(dt, a)) return SB_KERNEL_THIN;
+    if (forced == SB_KERNEL_AUTO) {
+        if (sb_thin_supports(dt, a) && sb_thin_preferred(dt, a)) return SB_KERNEL_THIN;
+        if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) return SB_KERNEL_TINY;
+        if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) return SB_KERNEL_MFMA;
+    }
+    return SB_KERNEL_GENERIC;
+}
+
 int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
-    int kernel = SB_KERNEL_GENERIC;
-    if (g_force_kernel == SB_KERNEL_TINY && sb_tiny_supports(dt, a)) kernel = SB_KERNEL_TINY;
-    else if (g_force_kernel == SB_KERNEL_MFMA && sb_mfma_supports(dt, a)) kernel = SB_KERNEL_MFMA;
-    else if (g_force_kernel == SB_KERNEL_THIN && sb_thin_supports(dt, a)) kernel = SB_KERNEL_THIN;
-    else if (g_force_kernel == SB_KERNEL_AUTO) {
-        if (sb_thin_supports(dt, a) && sb_thin_preferred(dt, a)) kernel = SB_KERNEL_THIN;
-        else if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) kernel = SB_KERNEL_TINY;
-        else if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) kernel = SB_KERNEL_MFMA;
-    }
+    const int kernel = choose(dt, a, g_force_kernel);
     hipError_t err;
     switch (kernel) {
     case SB_KERNEL_TINY: err = sb_launch_tiny(dt, a, stream); break;
@@ -94,6 +100,32 @@ extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int6
     a.bsC[0] = strideC0;  a.bsC[1] = strideC1;
     a.batch0 = batch0;  a.batch1 = batch1;
     return run(dt, a, (hipStream_t)stream);
+}
+
+extern "C" int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                                int64_t lda, int64_t strideA, int64_t ldb, int64_t strideB, int64_t ldc,
+                                int64_t strideC, int64_t batch)
+{
+    if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
+    if (!valid_op(transA)) return -2;
+    if (!valid_op(transB)) return -3;
+    if (m < 1) return -4;
+    if (n < 1) return -5;
+    if (k < 1) return -6;
+    if (lda < 1 || strideA < 0) return -7;
+    if (ldb < 1 || strideB < 0) return -9;
+    if (ldc < m || strideC < 0) return -11;
+    if (batch < 1) return -13;
+    SbArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.m = m;  a.n = n;  a.k = k;
+    a.alpha = 1.0;
+    op_strides(transA, lda, strideA, a.rsA, a.csA, a.bsA[0]);
+    op_strides(transB, ldb, strideB, a.rsB, a.csB, a.bsB[0]);
+    a.ldc = ldc;
+    a.bsC[0] = strideC;
+    a.batch0 = batch;  a.batch1 = 1;
+    return choose(dt, a, SB_KERNEL_AUTO);
 }
 
 extern "C" int sb_gemm(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,

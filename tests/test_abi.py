@@ -22,7 +22,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert set(names) >= {"sb_gemm", "sb_gemm2", "sb_contract", "sb_contract_plan", "sb_plan_launch", "sb_plan_launches",
-                          "sb_status_string", "sb_force_kernel", "sb_last_kernel", "sb_tucker_workspace",
+                          "sb_status_string", "sb_force_kernel", "sb_last_kernel", "sb_select_kernel", "sb_tucker_workspace",
                           "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"}
     lib = binding.load()
     for n in names:
@@ -132,3 +132,39 @@ def test_tucker_argument_validation_on_the_host():
     assert sb.sb_tucker_workspace("f32", 256, 256, 256, 10, 10, 10, with_init=True)[1] >= need + 4 * 4 * (256 * 256 - 100 * 100)
     assert sb.sb_sym_eig_workspace("f64", 100)[1] >= 4 * 8 * 100 * 100
     assert sb.sb_sym_eig_workspace("f32", 5000, check=False)[0] == -2
+
+
+def test_kernel_selector():
+    """The selector is host arithmetic on shapes: each family gets the shapes it was built for."""
+    def fam(dt, opA, opB, m, n, k, batch=8):
+        lda = m if opA == "N" else k
+        ldb = k if opB == "N" else n
+        return sb.sb_select_kernel(dt, opA, opB, m, n, k, lda, m * k, ldb, k * n, m, m * n, batch)
+    G, TINY, MFMA, THIN = sb.SB_KERNEL_GENERIC, sb.SB_KERNEL_TINY, sb.SB_KERNEL_MFMA, sb.SB_KERNEL_THIN
+    for dt in ("f32", "f64"):
+        assert fam(dt, "T", "N", 512, 512, 512) == MFMA            # the large cube
+        assert fam(dt, "N", "N", 64, 64, 64) == MFMA               # the 36 cases at 64
+        assert fam(dt, "N", "N", 16, 16, 16, 65536) == TINY        # the tiny-batch regime
+        assert fam(dt, "N", "N", 32, 32, 32) == TINY
+        assert fam(dt, "N", "N", 4096, 1, 4096) == THIN            # matrix-vector
+        assert fam(dt, "N", "N", 1, 4096, 4096) == THIN            # vector-matrix
+        assert fam(dt, "T", "N", 2048, 4, 100) == THIN
+        assert fam(dt, "N", "N", 1, 1, 5) == TINY                  # short dot products stay with the small-matrix kernels
+        assert fam(dt, "N", "N", 32, 1, 4096) == THIN              # long ones do not
+        assert fam(dt, "T", "N", 16, 2, 512) == THIN               # rows contiguous along k
+        assert fam(dt, "N", "N", 262144, 10, 512, 1) == MFMA       # factor matrix against an unfolding
+        assert fam(dt, "N", "N", 100, 10, 100) == MFMA
+        assert fam(dt, "N", "N", 100, 10, 16) == G                 # short k, mostly padding: vector-ALU kernel
+        assert fam(dt, "N", "N", 33, 200, 1) == MFMA               # rank-1 updates: bound by writing C
+    assert fam("bf16", "N", "N", 16, 16, 16) == MFMA
+    assert fam("bf16", "N", "N", 100, 10, 16) == MFMA
+    assert fam("bf16", "N", "N", 4096, 3, 64) == THIN
+    # extended operations (section III-E): on the first operand the MFMA family, on the second the general kernel
+    # (with the second operand shared by the batches, as in the exceptional cases of Table II)
+    assert sb.sb_select_kernel("f32", sb.SB_OP_EX_N, "N", 64, 64, 64, 64, 4096, 64, 0, 64, 4096, 8) == MFMA
+    assert sb.sb_select_kernel("f32", "N", sb.SB_OP_EX_N, 64, 64, 64, 64, 4096, 64, 4096, 64, 4096, 8) == G
+    assert sb.sb_select_kernel("f32", sb.SB_OP_EX_T, "N", 64, 1, 64, 64, 4096, 64, 4096, 64, 4096, 8) == THIN
+    # argument checks
+    assert sb.sb_select_kernel(7, "N", "N", 4, 4, 4, 4, 16, 4, 16, 4, 16, 1) == -1
+    assert sb.sb_select_kernel("f32", "N", "N", 0, 4, 4, 4, 16, 4, 16, 4, 16, 1) == -4
+    assert sb.sb_select_kernel("f32", "N", "N", 4, 4, 4, 4, 16, 4, 16, 3, 16, 1) == -11
