@@ -368,6 +368,27 @@ def run_sweeps(steps, warmup):
     return out
 
 
+def run_batched_gemv(steps, warmup, n=512):
+    """n matrix-vector products y_p = op(A_p) x_p with n x n fp32 matrices, both layouts: the level-2 end
+    of the primitive (thin kernels), bound by reading the matrices once."""
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+    tA = dev(inputs.uniform_tensor(57, [n, n, n], np.float32), "f32")
+    tx = dev(inputs.uniform_tensor(58, [n, n], np.float32), "f32")
+    ty = torch.empty(n * n, dtype=torch.float32, device="cuda")
+    nbytes = 4 * (n ** 3 + 2 * n * n)
+    out = dict(workload="%d matrix-vector products of %d x %d, f32: y_[p] = op(A_[p]) x_[p]" % (n, n, n),
+               algorithmic_bytes=nbytes, cases=[])
+    for op in ("N", "T"):
+        def ours():
+            sb.sb_gemm(op, "N", n, 1, n, 1.0, tA, n, n * n, tx, n, n, 0.0, ty, n, n, n, dt="f32")
+        _, t = time_steps(ours, max(steps, 100), warmup)
+        out["cases"].append(dict(op=op, kernel_family=sb.sb_last_kernel(), us=t * 1e3, gbps=nbytes / t / 1e6,
+                                 frac_of_hbm_peak=nbytes / t / 1e6 / PEAK["hbm"]))
+    return out
+
+
 def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128, with_oracle=True):
     """The application study of section V-C: HOOI (Algorithm 1) on cubic n^3 tensors with a 10^3 core,
     fp32, every contraction through sb_contract.  Reports time per iteration (steps 4-9: five
@@ -490,6 +511,7 @@ def main():
             others.append(r)
         others.append(run_table2_cases(max(args.steps, 200), args.warmup))
         others.append(run_exceptional_cases(args.steps, args.warmup))
+        others.append(run_batched_gemv(args.steps, args.warmup))
         if not args.no_tucker:
             others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others

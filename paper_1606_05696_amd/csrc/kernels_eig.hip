@@ -275,7 +275,51 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweep
     return hipGetLastError();
 }
 
+// Sign convention for a factor matrix: every column is scaled by +-1 so that its entry of largest
+// magnitude (the first one among equals) is positive.  One workgroup per column.
+template <typename T>
+__global__ __launch_bounds__(256) void column_signs_kernel(T *U, int64_t rows, int64_t ld)
+{
+    __shared__ T best_v[256];
+    __shared__ int64_t best_i[256];
+    T *col = U + (int64_t)blockIdx.x * ld;
+    T bv = T(-1);
+    int64_t bi = 0;
+    for (int64_t i = threadIdx.x; i < rows; i += 256) {
+        const T a = fabs(col[i]);
+        if (a > bv) { bv = a; bi = i; }            // ascending i per thread: the first of equals stays
+    }
+    best_v[threadIdx.x] = bv;
+    best_i[threadIdx.x] = bi;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) {
+            const T ov = best_v[threadIdx.x + half];
+            const int64_t oi = best_i[threadIdx.x + half];
+            if (ov > best_v[threadIdx.x] || (ov == best_v[threadIdx.x] && oi < best_i[threadIdx.x])) {
+                best_v[threadIdx.x] = ov;
+                best_i[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    const bool flip = best_v[0] > T(0) && col[best_i[0]] < T(0);
+    __syncthreads();                               // everyone has read the pivot before anyone flips it
+    if (flip)
+        for (int64_t i = threadIdx.x; i < rows; i += 256) col[i] = -col[i];
+}
+
 }  // namespace
+
+// U (rows x r, leading dimension ld): columns scaled by +-1 to the sign convention above.
+hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_t ld, hipStream_t stream)
+{
+    if (rows <= 0 || r <= 0) return hipSuccess;
+    if (dt == SB_F64) column_signs_kernel<double><<<(unsigned)r, 256, 0, stream>>>((double *)U, rows, ld);
+    else if (dt == SB_F32) column_signs_kernel<float><<<(unsigned)r, 256, 0, stream>>>((float *)U, rows, ld);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
 
 // Eigen-decomposition of the symmetric n x n matrix in A (column-major, packed; destroyed).
 // A2, V, V2: n*n elements each; lam: n; sel: n ints.  On return *V_final (V or V2) holds the

@@ -15,6 +15,7 @@ hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, 
                       hipStream_t stream, void **A_final, void **V_final);
 hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw,
                          int scaled, hipStream_t stream);
+hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_t ld, hipStream_t stream);
 
 namespace {
 
@@ -79,10 +80,10 @@ struct Ctx {
     void check_hip(hipError_t e) { if (status == SB_OK && e != hipSuccess) status = SB_ERR_LAUNCH + (int)e; }
 
     void gemm(sb_op ta, sb_op tb, int64_t m, int64_t n, int64_t k, const void *A, int64_t lda, const void *B, int64_t ldb,
-              double beta, void *C, int64_t ldc)
+              double beta, void *C, int64_t ldc, double alpha = 1.0)
     {
         if (!ok()) return;
-        check(sb_gemm(dt, ta, tb, m, n, k, 1.0, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, 1, stream));
+        check(sb_gemm(dt, ta, tb, m, n, k, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, 1, stream));
     }
 
     void contract(const char *ma, const char *mb, const char *mc, const void *A, const int64_t *dA, const void *B,
@@ -101,9 +102,18 @@ struct Ctx {
     {
         if (!ok()) return;
         const int64_t es = esize(dt);
-        // the accumulated product V V' V'' ... drifts away from orthogonality by a rounding error per
-        // iteration; every 16th solve starts cold again
-        const bool warm = mode >= 0 && have_prev[mode] && warm_runs[mode] < 15;
+        // The accumulated product V V' V'' ... drifts away from orthogonality by a rounding error per
+        // iteration.  Every 16th solve first pulls it back with one Newton-Schulz step,
+        // V <- V (3 I - V^T V) / 2, which squares the distance from orthogonality (three small GEMMs
+        // instead of the five or so sweeps of a cold solve).
+        const bool warm = mode >= 0 && have_prev[mode];
+        if (warm && warm_runs[mode] >= 15) {
+            gemm(SB_OP_T, SB_OP_N, e, e, e, Vprev[mode], e, Vprev[mode], e, 0.0, eig.V2, e);          // V^T V (solver scratch, free until the solve)
+            check_hip(hipMemcpyAsync(tmp, Vprev[mode], e * e * es, hipMemcpyDeviceToDevice, stream));
+            gemm(SB_OP_N, SB_OP_N, e, e, e, Vprev[mode], e, eig.V2, e, 1.5, tmp, e, -0.5);            // 1.5 V - 0.5 V (V^T V)
+            std::swap(Vprev[mode], tmp);
+            warm_runs[mode] = 0;
+        }
         if (warm) {
             gemm(SB_OP_N, SB_OP_N, e, e, e, eig.S, e, Vprev[mode], e, 0.0, tmp, e);          // S V
             gemm(SB_OP_T, SB_OP_N, e, e, e, Vprev[mode], e, tmp, e, 0.0, eig.S, e);          // V^T (S V)
@@ -142,6 +152,11 @@ struct Ctx {
             else        gemm(SB_OP_T, SB_OP_N, rows, rows, R, Y, ld, Y, ld, 0.0, eig.S, rows);
             eig_leading(mode, rows, r, U, rows, 0);
         }
+        // Singular vectors are fixed up to sign, and the sign a Jacobi solve ends with depends on its
+        // path.  A fixed convention keeps each factor the same from one iteration to the next once
+        // its subspace has settled, so the other modes' Gram matrices (which live in the basis of
+        // these columns) stay put and their warm starts keep working.
+        if (ok()) check_hip(sb_column_signs(dt, U, rows, r, rows, stream));
     }
 };
 
