@@ -111,7 +111,7 @@ size_t jacobi_lds_bytes(int n)
 }
 
 template <typename T>
-__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int n, int ne, int sweeps, T rel_tol)
+__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, const T *V0, int n, int ne, int sweeps, T rel_tol)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
     const int h = ne / 2, tid = threadIdx.x;
@@ -124,7 +124,11 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, int
         const int i = e % ne, j = e / ne;
         As[e] = (i < n && j < n) ? A[i + j * n] : T(0);
     }
-    for (int e = tid; e < ne * ne; e += LDS_THREADS) Vs[e] = (e % ne == e / ne && e % ne < n) ? T(1) : T(0);
+    // the rotations accumulate onto V0 (the basis the matrix was rotated into beforehand) or onto I
+    for (int e = tid; e < ne * ne; e += LDS_THREADS) {
+        const int i = e % ne, j = e / ne;
+        Vs[e] = (i < n && j < n) ? (V0 ? V0[i + j * n] : (i == j ? T(1) : T(0))) : T(0);
+    }
     if (tid < 3) rotates[tid] = 0;
     __syncthreads();
     // off-diagonal elements below rounding level of the largest diagonal element are left alone: they
@@ -237,11 +241,12 @@ __global__ __launch_bounds__(256) void eig_gather_kernel(const T *V, int n, cons
 }
 
 template <typename T>
-hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweeps, hipStream_t stream, T **A_final, T **V_final)
+hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, const T *V0, T *lam, int *sel, int sweeps, hipStream_t stream, T **A_final, T **V_final)
 {
     const int ne = n + (n & 1);
     if (n == 1) {
-        identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
+        if (V0) { hipError_t e = hipMemcpyAsync(V, V0, sizeof(T), hipMemcpyDeviceToDevice, stream); if (e != hipSuccess) return e; }
+        else identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
         *A_final = A; *V_final = V;
     } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 512) {      // 512 bytes stay for the static variables
         const size_t bytes = jacobi_lds_bytes<T>(n);
@@ -255,13 +260,14 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, T *lam, int *sel, int sweep
         // 8 units of rounding of the largest diagonal element: rotating smaller elements only stirs rounding
         // noise (each sweep creates as much as it removes), and a warm-started solve would never stop early
         const T rel_tol = sizeof(T) == 8 ? T(1.8e-15) : T(9.6e-7);
-        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, n, ne, sweeps, rel_tol);
+        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, V0, n, ne, sweeps, rel_tol);
         *A_final = A; *V_final = V;
     } else {
         const int h = ne / 2;
         const int64_t items = (int64_t)h * h + (int64_t)n * h;
         const unsigned blocks = (unsigned)((items + 255) / 256 < 4096 ? (items + 255) / 256 : 4096);
-        identity_kernel<T><<<256, 256, 0, stream>>>(V, n);
+        if (V0) { hipError_t e = hipMemcpyAsync(V, V0, sizeof(T) * n * n, hipMemcpyDeviceToDevice, stream); if (e != hipSuccess) return e; }
+        else identity_kernel<T><<<256, 256, 0, stream>>>(V, n);
         T *ain = A, *aout = A2, *vin = V, *vout = V2;
         for (int sweep = 0; sweep < sweeps; ++sweep)
             for (int round = 0; round < ne - 1; ++round) {
@@ -324,12 +330,13 @@ hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_
 // Eigen-decomposition of the symmetric n x n matrix in A (column-major, packed; destroyed).
 // A2, V, V2: n*n elements each; lam: n; sel: n ints.  On return *V_final (V or V2) holds the
 // eigenvectors as columns in rotation order, lam the eigenvalues in descending order and sel the
-// column of *V_final that belongs to each.
-hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, void *lam, int *sel, int sweeps,
+// column of *V_final that belongs to each.  V0 (may be null; not V or V2): the rotations accumulate
+// onto this matrix instead of the identity, so for A = V0^T S V0 the result holds eigenvectors of S.
+hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, const void *V0, void *lam, int *sel, int sweeps,
                       hipStream_t stream, void **A_final, void **V_final)
 {
-    if (dt == SB_F64) return eig_impl<double>(n, (double *)A, (double *)A2, (double *)V, (double *)V2, (double *)lam, sel, sweeps, stream, (double **)A_final, (double **)V_final);
-    if (dt == SB_F32) return eig_impl<float>(n, (float *)A, (float *)A2, (float *)V, (float *)V2, (float *)lam, sel, sweeps, stream, (float **)A_final, (float **)V_final);
+    if (dt == SB_F64) return eig_impl<double>(n, (double *)A, (double *)A2, (double *)V, (double *)V2, (const double *)V0, (double *)lam, sel, sweeps, stream, (double **)A_final, (double **)V_final);
+    if (dt == SB_F32) return eig_impl<float>(n, (float *)A, (float *)A2, (float *)V, (float *)V2, (const float *)V0, (float *)lam, sel, sweeps, stream, (float **)A_final, (float **)V_final);
     return hipErrorInvalidValue;
 }
 

@@ -637,18 +637,22 @@ bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a)
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
     if (sb_mfma_exa_supports(dt, a)) return sb_launch_mfma_exa(dt, a, stream);
+    // a problem of few 128 x 128 tiles leaves most compute units idle: 64 x 64 tiles spread it over
+    // four times as many workgroups
+    const int64_t tiles128 = ((a.m + 127) / 128) * ((a.n + 127) / 128) * a.batch0 * a.batch1;
+    const bool few_tiles = tiles128 < 128;
     switch (dt) {
     case SB_F32:
         // a factor matrix against a tensor unfolding: bound by streaming the big operand, so the
         // tile is long in that operand's direction (big panels in flight) and one MFMA block wide
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (a.m <= 64 || a.n <= 64) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF64x16, 16, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (a.m <= 64 || a.n <= 64) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
+        if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
         return launch<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);                                 // 128 x 128 tiles, 16 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;

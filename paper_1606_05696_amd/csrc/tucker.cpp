@@ -11,7 +11,7 @@
 #include "../../include/sbtucker.h"
 #include "sb_internal.h"
 
-hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, void *lam, int *sel, int sweeps,
+hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, const void *V0, void *lam, int *sel, int sweeps,
                       hipStream_t stream, void **A_final, void **V_final);
 hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw,
                          int scaled, hipStream_t stream);
@@ -97,7 +97,7 @@ struct Ctx {
     // (ld = ldo), scaled by lambda^-1/2 if `scaled`.  mode >= 0: warm start.  From one HOOI iteration
     // to the next the Gram matrix of a mode changes little, so it is first rotated by the previous
     // iteration's eigenvectors (S' = V^T S V, nearly diagonal; the Jacobi solver then stops after a
-    // sweep or two) and the new eigenvectors are V V'.
+    // sweep or two) and the new eigenvectors are V V' (the solver multiplies its rotations onto V).
     void eig_leading(int mode, int64_t e, int64_t r, void *out, int64_t ldo, int scaled)
     {
         if (!ok()) return;
@@ -118,18 +118,15 @@ struct Ctx {
             gemm(SB_OP_N, SB_OP_N, e, e, e, eig.S, e, Vprev[mode], e, 0.0, tmp, e);          // S V
             gemm(SB_OP_T, SB_OP_N, e, e, e, Vprev[mode], e, tmp, e, 0.0, eig.S, e);          // V^T (S V)
         }
+        // warm: the solver's rotations accumulate onto the previous eigenvectors, so it returns V V' itself
         void *Af = nullptr, *Vf = nullptr;
-        check_hip(sb_eig_sym(dt, (int)e, eig.S, eig.S2, eig.V, eig.V2, eig.lam, (int *)eig.sel, default_sweeps(dt, e), stream, &Af, &Vf));
+        check_hip(sb_eig_sym(dt, (int)e, eig.S, eig.S2, eig.V, eig.V2, warm ? Vprev[mode] : nullptr, eig.lam, (int *)eig.sel,
+                             default_sweeps(dt, e), stream, &Af, &Vf));
         if (!ok()) return;
-        if (warm) {
-            gemm(SB_OP_N, SB_OP_N, e, e, e, Vprev[mode], e, Vf, e, 0.0, tmp, e);             // V V'
-            std::swap(Vprev[mode], tmp);
-            Vf = Vprev[mode];
-            ++warm_runs[mode];
-        } else if (mode >= 0) {
+        if (mode >= 0) {
             check_hip(hipMemcpyAsync(Vprev[mode], Vf, e * e * es, hipMemcpyDeviceToDevice, stream));
-            have_prev[mode] = true;
-            warm_runs[mode] = 0;
+            if (warm) ++warm_runs[mode];
+            else { have_prev[mode] = true; warm_runs[mode] = 0; }
         }
         if (!ok()) return;
         check_hip(sb_eig_gather(dt, (int)e, Vf, (const int *)eig.sel, eig.lam, (int)r, out, ldo, scaled, stream));
@@ -278,7 +275,7 @@ extern "C" int sb_sym_eig(sb_dtype dt, int64_t n, void *S, void *V, void *lambda
     EigSpace e;
     e.carve(dt, (char *)workspace, n);
     void *Af = nullptr, *Vf = nullptr;
-    hipError_t err = sb_eig_sym(dt, (int)n, S, e.S2, e.V, e.V2, lambda, (int *)e.sel, sweeps > 0 ? sweeps : default_sweeps(dt, n),
+    hipError_t err = sb_eig_sym(dt, (int)n, S, e.S2, e.V, e.V2, nullptr, lambda, (int *)e.sel, sweeps > 0 ? sweeps : default_sweeps(dt, n),
                                 (hipStream_t)stream, &Af, &Vf);
     if (err == hipSuccess) err = sb_eig_gather(dt, (int)n, Vf, (const int *)e.sel, lambda, (int)n, V, n, 0, (hipStream_t)stream);
     return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
