@@ -483,3 +483,44 @@ def test_offsets_beyond_2_31_elements():
                 assert rel_fro(got, ref) <= TOL["f32"], (m, pp, nn)
         del tB, tC
         torch.cuda.empty_cache()
+
+
+def test_thin_kernels_beyond_2_31_elements():
+    # one matrix of more than 2^31 elements (8.7 GB in fp32) times a vector, in both layouts: 64-bit
+    # offsets in the rows and the dots kernel.  The matrix is a seeded vector of prime length repeated
+    # along memory, so the host can rebuild any row; sampled entries of y (first, last, the ones whose
+    # row crosses element 2^31, random ones) are compared with the oracle, none may be left unwritten.
+    import torch
+    L = 1000003
+    base = inputs.uniform_tensor(125, [L], np.float32)
+    base_dev = to_dev(base, "f32")
+    rng = np.random.default_rng(8)
+    rows, k = 1 << 22, 520
+    total = rows * k
+    assert total > 2 ** 31
+    tA = torch.empty(total, dtype=torch.float32, device="cuda")
+    chunk = 1 << 27
+    for s0 in range(0, total, chunk):
+        idx = torch.arange(s0, min(s0 + chunk, total), device="cuda") % L
+        tA[s0:s0 + idx.numel()] = base_dev[idx]
+    del idx
+    x = inputs.uniform_tensor(126, [k], np.float32)
+    tx = to_dev(x, "f32")
+    for op in ("N", "T"):
+        ty = torch.full((rows,), float("nan"), dtype=torch.float32, device="cuda")
+        lda = rows if op == "N" else k
+        sb.sb_gemm(op, "N", rows, 1, k, 1.0, tA, lda, 0, tx, k, 0, 0.0, ty, rows, 0, 1, dt="f32")
+        sync()
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN
+        assert not bool(torch.isnan(ty).any())
+        edge = 2 ** 31 // k if op == "T" else 2 ** 31 % rows
+        sample = [int(v) for v in rng.integers(0, rows, 24)] + [0, 1, rows - 1, rows - 2] + \
+                 [e for e in (edge - 1, edge, edge + 1) if 0 <= e < rows]
+        l = np.arange(k)
+        M = np.stack([base[((i + l * rows) if op == "N" else (l + i * k)) % L] for i in sample])
+        ref = oracle.contract("mk", M, "k", x, "m", wide=False)
+        got = ty[torch.tensor(sample, device="cuda")].cpu().numpy().astype(np.float64)
+        assert rel_fro(got, ref) <= TOL["f32"], op
+        del ty
+    del tA
+    torch.cuda.empty_cache()
