@@ -11,6 +11,8 @@
 #include "sb_device.h"
 #include "sb_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -21,7 +23,7 @@ constexpr int NTHREADS = 256;
 constexpr int NXCD = 8;
 constexpr int BK = 32;          // two MFMA k-steps of 16 per panel
 
-template <bool KC, int ROWS>
+template <bool KC, int ROWS, int BK = 32>
 struct PanelBf16 {
     static constexpr int NVEC = ROWS * BK / 8 / NTHREADS;             // 16-byte vectors per lane
     static constexpr int LDS_LD = (KC ? BK : ROWS) + 8;               // padded by 16 bytes
@@ -51,6 +53,17 @@ struct PanelBf16 {
                     v[q][e] = ok ? src[e] : (uint16_t)0;
                 }
             }
+        }
+    }
+
+    // whole panel inside the matrix, every vector aligned: no branch, the loads stay countable
+    static __device__ __forceinline__ void load_plain(u16x8 (&v)[NVEC], const uint16_t *p, int64_t ld)
+    {
+#pragma unroll
+        for (int q = 0; q < NVEC; ++q) {
+            int row, k;
+            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            v[q] = *(const u16x8 *)(KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row);
         }
     }
 
@@ -182,6 +195,209 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
     }
 }
 
+// Streaming variant for problems made of whole 128 x 128 tiles with both operands k-contiguous
+// (A with T, B with N), aligned, k a multiple of 128: persistent workgroups walk over their tiles
+// and the panel stream (64 k per panel, two panels in flight in registers, LDS double buffer) never
+// drains at a tile boundary.  The schedule is the one of the fp32 / fp64 streaming kernel:
+//   - while the last panels of a tile are multiplied, the first panels of the workgroup's next tile
+//     are already requested, and the loads of its third panel are issued BEFORE the finished tile's
+//     stores (loads and stores share one in-order counter);
+//   - the LDS store of the next panel sits between the MFMAs of the second-to-last k-group, the
+//     barrier and the first fragment read of the new panel before the last k-group's MFMAs;
+//   - the tile body exists twice (first tile after the priming, later tiles in a loop) and
+//     beta != 0 is a kernel of its own, so that no two paths with different numbers of outstanding
+//     memory operations meet.
+// Every lambda is forced inline: a closure that is called holds the register arrays by address,
+// which would put them in scratch memory.
+// NBM x NBN: MFMA blocks per wave tile.  2 x 2 (128 x 128 workgroup tile, two workgroups per
+// compute unit) reads one LDS fragment per MFMA, which makes LDS bandwidth the limit at about two
+// thirds of the matrix peak; 4 x 4 (256 x 256 tile, 256 accumulator registers, one workgroup per
+// compute unit) reads half a fragment per MFMA.
+// SBK: k per panel (64 for 2 x 2; 32 for 4 x 4, whose staging registers must share 256 with the fragments).
+template <bool BETA, int NBM, int NBN, int SBK>
+__global__ __launch_bounds__(NTHREADS, NBM * NBN <= 4 ? 2 : 1) void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
+{
+    constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = 2 * WM, TN = 2 * WN;
+    typedef PanelBf16<true, TM, SBK> PA;
+    typedef PanelBf16<true, TN, SBK> PB;
+    constexpr int KG = SBK / 16;                 // MFMA k-steps per panel (even: two fragment sets alternate)
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
+
+    const int64_t ldA = g.rsA, ldB = g.csB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave & 1) * WM, wn = (wave >> 1) * WN;
+    const float alpha = (float)g.alpha, beta = (float)g.beta;
+    const int64_t nkb = g.k / SBK;
+
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t total = tiles * g.batch0 * g.batch1;
+    const int64_t nslots = (int64_t)gridDim.x / NXCD;           // the launcher makes gridDim.x a multiple of 8
+    const int64_t xcd = blockIdx.x % NXCD, slot = blockIdx.x / NXCD;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t first = xcd * q8 + (xcd < r8 ? xcd : r8);
+    const int64_t last = first + q8 + (xcd < r8 ? 1 : 0);
+    int64_t logical = first + slot;
+    if (logical >= last) return;
+
+    u16x8 ra[2][PA::NVEC], rb[2][PB::NVEC];
+    bf16x8 fa[2][NBM], fb[2][NBN];
+    f32x16 acc[NBM][NBN];
+
+    struct Loc { const uint16_t *A, *B; uint16_t *C; };
+    auto locate = [&](int64_t b, int tile) __attribute__((always_inline)) {
+        int64_t b0 = b, b1 = 0;
+        if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
+        const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
+        const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
+        Loc l;
+        l.A = (const uint16_t *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
+        l.B = (const uint16_t *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
+        l.C = (uint16_t *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1] + i0 + j0 * g.ldc;
+        return l;
+    };
+    int64_t b = logical / tiles;
+    int tile = (int)(logical - b * tiles);
+    const int64_t dq = nslots / tiles;
+    const int dr = (int)(nslots - dq * tiles);
+
+    auto gload = [&](auto set, const uint16_t *pa, const uint16_t *pb) __attribute__((always_inline)) {
+        PA::load_plain(ra[set], pa, ldA);
+        PB::load_plain(rb[set], pb, ldB);
+    };
+    auto read_frags = [&](auto set, auto buf, int kg) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < NBM; ++a) fa[set][a] = PA::fragment(As[buf], wm + a * 32, kg, lane);
+#pragma unroll
+        for (int c = 0; c < NBN; ++c) fb[set][c] = PB::fragment(Bs[buf], wn + c * 32, kg, lane);
+    };
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    auto block = [&](auto cur_c, auto load_c, const uint16_t *pa, const uint16_t *pb) __attribute__((always_inline)) {
+        constexpr int CUR = decltype(cur_c)::value;
+        if (decltype(load_c)::value) gload(std::integral_constant<int, CUR>(), pa, pb);
+#pragma unroll
+        for (int kg = 0; kg < KG; ++kg) {
+            const int fs = kg & 1;
+            if (kg + 1 < KG) {
+                if (fs == 0) read_frags(I1(), std::integral_constant<int, CUR>(), kg + 1);
+                else         read_frags(I0(), std::integral_constant<int, CUR>(), kg + 1);
+            } else {
+                __syncthreads();
+                read_frags(I0(), std::integral_constant<int, CUR ^ 1>(), 0);
+            }
+            __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+            for (int a = 0; a < NBM; ++a) {
+                if (a == NBM / 2 && kg == KG - 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    PA::store(As[CUR ^ 1], ra[CUR ^ 1]);
+                    PB::store(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int c = 0; c < NBN; ++c)     // C^T = B^T A^T: lanes run along rows of C
+                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[fs][c], fa[fs][a], acc[a][c], 0, 0, 0);
+            }
+            __builtin_amdgcn_s_setprio(0);
+        }
+    };
+    // One tile.  On entry its panel 0 is in LDS buffer 0 with the first fragments read, panel 1 is
+    // in staging set 1 (in flight), panel 2 in staging set 0 (in flight).
+    auto run_tile = [&](const Loc &cur, const Loc &nxt) __attribute__((always_inline)) {
+        const uint16_t *A = cur.A, *B = cur.B, *An = nxt.A, *Bn = nxt.B;
+        uint16_t *C = cur.C;
+#pragma unroll
+        for (int a = 0; a < NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < NBN; ++c)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+        block(I0(), std::false_type(), A, B);                             // panel 2 was requested before the previous stores
+        block(I1(), std::true_type(), A + 3 * SBK, B + 3 * SBK);
+        const uint16_t *pa = A + 4 * SBK, *pb = B + 4 * SBK;
+        for (int64_t kb = 2; kb < nkb; kb += 2) {
+            if (kb + 2 == nkb) { pa = An; pb = Bn; }                      // the stream moves on to the next tile
+            block(I0(), std::true_type(), pa, pb);
+            pa += SBK; pb += SBK;
+            block(I1(), std::true_type(), pa, pb);
+            pa += SBK; pb += SBK;
+        }
+        gload(I0(), pa, pb);                                              // next tile's panel 2, ahead of the stores below
+#pragma unroll
+        for (int a = 0; a < NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < NBN; ++c) {
+                uint16_t *col = C + wm + a * 32 + (lane & 31) + (int64_t)(wn + c * 32 + 4 * (lane >> 5)) * g.ldc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    uint16_t *dst = col + (8 * (r >> 2) + (r & 3)) * g.ldc;
+                    float v = alpha * acc[a][c][r];
+                    if (BETA) v += beta * sb_bf16_to_f32(*dst);
+                    *dst = sb_f32_to_bf16(v);
+                }
+            }
+    };
+
+    Loc cur = locate(b, tile);
+    {   // prime the stream with the first tile's panels 0, 1 and 2
+        gload(I0(), cur.A, cur.B);
+        gload(I1(), cur.A + SBK, cur.B + SBK);
+        PA::store(As[0], ra[0]);
+        PB::store(Bs[0], rb[0]);
+        __syncthreads();
+        read_frags(I0(), I0(), 0);
+        gload(I0(), cur.A + 2 * SBK, cur.B + 2 * SBK);
+    }
+    // one tile and the step to the workgroup's next one; the last tile names itself as successor
+    auto step = [&]() __attribute__((always_inline)) {
+        const bool more = logical + nslots < last;
+        int tile2 = tile + dr;
+        int64_t b2 = b + dq;
+        if (tile2 >= tiles) { tile2 -= (int)tiles; ++b2; }
+        const Loc nxt = more ? locate(b2, tile2) : cur;
+        run_tile(cur, nxt);
+        logical += nslots;
+        b = b2;
+        tile = tile2;
+        cur = nxt;
+        return more;
+    };
+    bool more = step();               // first tile: follows the priming above
+    while (more) more = step();       // later tiles: follow a finished tile
+}
+
+bool stream_applies(const SbArgs &a, int tile, int SBK)
+{
+    auto aligned = [](int64_t v) { return v % 8 == 0; };
+    return a.csA == 1 && a.rsB == 1 && a.m % tile == 0 && a.n % tile == 0 && a.k % (2 * SBK) == 0 && a.k >= 4 * SBK &&
+           (uintptr_t)a.A % 16 == 0 && (uintptr_t)a.B % 16 == 0 && aligned(a.rsA) && aligned(a.csB) &&
+           aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+}
+
+template <typename K>
+hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream)
+{
+    const int64_t tiles_m = a.m / tile, tiles_n = a.n / tile;
+    const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
+    if (total <= 0) return hipSuccess;
+    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    static int resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
+    const int dev = sb_current_device();
+    if (resident_of[dev] == 0) {
+        int per_cu = 0, cus = 0;
+        hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, NTHREADS, 0);
+        if (e != hipSuccess) return e;
+        if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
+        resident_of[dev] = per_cu * cus;
+    }
+    int64_t grid = total < resident_of[dev] ? total : resident_of[dev];
+    grid = (grid + NXCD - 1) / NXCD * NXCD;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, (int)tiles_m, (int)tiles_n);
+    return hipGetLastError();
+}
+
 template <int WT>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
@@ -211,6 +427,17 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
 {
     // many small GEMMs with short k: whole-K panels, batches pipelined inside persistent workgroups
     if (sb_panel_bf16_supports(a)) return sb_launch_panel_bf16(a, stream);
+    // whole 128 x 128 tiles, both operands k-contiguous: the streaming kernel
+    // (256 x 256 tiles when there are enough of them to fill the chip and k is long: measured 1.06-1.10x
+    // over the 128 x 128 tiles at k = 2048-4096, 0.87x at k = 512, where a tile ends too soon)
+    if (stream_applies(a, 256, 32) && a.k >= 1024 && (a.m / 256) * (a.n / 256) * a.batch0 * a.batch1 >= 256) {
+        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 4, 4, 32>, 256, a, stream);
+        return launch_stream(sbgemm_bf16_stream_kernel<true, 4, 4, 32>, 256, a, stream);
+    }
+    if (stream_applies(a, 128, 64)) {
+        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 2, 2, 64>, 128, a, stream);
+        return launch_stream(sbgemm_bf16_stream_kernel<true, 2, 2, 64>, 128, a, stream);
+    }
     // small matrices per batch: 64x64 tiles waste less and give more workgroups
     if (a.m <= 64 || a.n <= 64) return launch<32>(a, stream);
     return launch<64>(a, stream);

@@ -448,6 +448,28 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
             assert err <= TOL[dtype], (m, n, k, batch, alpha, beta, err)
 
 
+def test_sb_gemm_whole_tile_shapes_bf16():
+    # bf16 with both operands k-contiguous, whole 128 x 128 tiles, k a multiple of 128 (at least 256):
+    # the streaming bf16 kernel; shortest legal k, odd tile counts, more and fewer tiles than resident
+    # workgroups, beta = 0 and beta != 0 (separate kernels).  The neighbouring shapes (k = 320, an
+    # operand not k-contiguous) take the plain bf16 kernel and are checked the same way.  The last
+    # three have at least 256 tiles of 256 x 256 and k >= 1024: the variant with 128 x 128 wave tiles
+    # (k a multiple of 64).
+    for opA, opB, m, n, k, batch in (("T", "N", 256, 384, 256, 5), ("T", "N", 128, 128, 384, 3), ("T", "N", 128, 256, 1024, 1),
+                                     ("T", "N", 512, 256, 256, 131), ("T", "N", 128, 128, 320, 3), ("N", "N", 256, 128, 256, 2),
+                                     ("T", "N", 512, 768, 1024, 43), ("T", "N", 1024, 512, 1088, 37), ("T", "N", 256, 256, 2048, 300)):
+        lda = (m if opA == "N" else k) + 8
+        ldb = (k if opB == "N" else n) + 16
+        ldc = m + 12
+        loa = lda * (k if opA == "N" else m) + 16
+        lob = ldb * (n if opB == "N" else k)
+        loc = ldc * n + 4
+        for alpha, beta in ((1.0, 0.0), (-0.5, 1.5)):
+            err, got, ref = run_sb_gemm("bf16", opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta,
+                                        seed=m + n + k, kernel="mfma")
+            assert err <= TOL["bf16"], (opA, opB, m, n, k, batch, alpha, beta, err)
+
+
 def test_offsets_beyond_2_31_elements():
     # tensors with more than 2^31 elements (8.7 GB each in fp32): 64-bit offsets in the tiny-matrix and
     # the MFMA kernels, millions of batches.  B is a seeded vector of prime length repeated along memory,
