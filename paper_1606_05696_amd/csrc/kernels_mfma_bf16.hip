@@ -23,10 +23,21 @@ constexpr int NTHREADS = 256;
 constexpr int NXCD = 8;
 constexpr int BK = 32;          // two MFMA k-steps of 16 per panel
 
-template <bool KC, int ROWS, int BK = 32>
+// SWZ (k-contiguous panels only): rows are stored unpadded and the 16-byte chunk c of row r sits at
+// chunk c ^ f(r), f(r) = (r / rows-per-256-bytes) mod chunks-per-row.  Sixteen lanes that write
+// consecutive chunks then cover 256 contiguous bytes, and sixteen lanes that read the same chunk
+// of consecutive rows (an MFMA fragment) hit sixteen different bank groups: neither conflicts.
+// (With padding the reads are conflict-free but a store wraps onto the banks of the row 3 above.)
+template <bool KC, int ROWS, int BK = 32, bool SWZ = false>
 struct PanelBf16 {
+    static_assert(!SWZ || KC, "the swizzle is for k-contiguous panels");
     static constexpr int NVEC = ROWS * BK / 8 / NTHREADS;             // 16-byte vectors per lane
-    static constexpr int LDS_LD = (KC ? BK : ROWS) + 8;               // padded by 16 bytes
+    static constexpr int LDS_LD = SWZ ? BK : (KC ? BK : ROWS) + 8;    // padded by 16 bytes unless swizzled
+    static constexpr int CPR = BK / 8;                                // 16-byte chunks per row
+    static __device__ __forceinline__ int swizzled(int row, int k)   // k a multiple of 8
+    {
+        return SWZ ? (((k >> 3) ^ ((row / (16 / CPR)) & (CPR - 1))) << 3) : k;
+    }
     static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
     static_assert(ROWS * BK % (8 * NTHREADS) == 0, "panel must split evenly over the lanes");
 
@@ -73,7 +84,7 @@ struct PanelBf16 {
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
             coords((int)threadIdx.x + NTHREADS * q, row, k);
-            uint16_t *dst = KC ? lds + row * LDS_LD + k : lds + k * LDS_LD + row;
+            uint16_t *dst = KC ? lds + row * LDS_LD + swizzled(row, k) : lds + k * LDS_LD + row;
             *(u16x8 *)dst = v[q];
         }
     }
@@ -85,7 +96,7 @@ struct PanelBf16 {
         const int k = ks * 16 + (lane >> 5) * 8;
         u16x8 v;
         if (KC) {
-            v = *(const u16x8 *)(lds + row * LDS_LD + k);
+            v = *(const u16x8 *)(lds + row * LDS_LD + swizzled(row, k));
         } else {
 #pragma unroll
             for (int e = 0; e < 8; ++e) v[e] = lds[(k + e) * LDS_LD + row];
@@ -218,8 +229,8 @@ template <bool BETA, int NBM, int NBN, int SBK>
 __global__ __launch_bounds__(NTHREADS, NBM * NBN <= 4 ? 2 : 1) void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
     constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = 2 * WM, TN = 2 * WN;
-    typedef PanelBf16<true, TM, SBK> PA;
-    typedef PanelBf16<true, TN, SBK> PB;
+    typedef PanelBf16<true, TM, SBK, true> PA;
+    typedef PanelBf16<true, TN, SBK, true> PB;
     constexpr int KG = SBK / 16;                 // MFMA k-steps per panel (even: two fragment sets alternate)
     __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
