@@ -70,8 +70,21 @@ struct Panel {
     typedef typename MF::Vec Vec;
     static constexpr int VEC = MF::VEC;
     static constexpr int NVEC = ROWS * BK / VEC / NT;                  // 16-byte vectors per lane
-    static constexpr int LDS_LD = (KC ? BK : ROWS) + VEC;              // padded by 16 bytes
+    // k-contiguous panels are stored unpadded, the 16-byte chunk c of row r at chunk c ^ f(r) with
+    // f(r) = (r / rows-per-256-bytes) mod chunks-per-row: sixteen lanes that store consecutive chunks
+    // cover 256 contiguous bytes, sixteen lanes that read the same chunk of consecutive rows (an
+    // MFMA fragment) hit sixteen different groups of four banks, so neither conflicts.  (Padded
+    // rows keep the reads apart but let a store wrap onto the banks of the row three above: a third
+    // of the LDS cycles of the 128 x 128 kernels were bank conflicts.)  Row-contiguous panels keep
+    // the padding.
+    static constexpr int CPR = BK / VEC;                               // chunks per row
+    static_assert(!KC || (CPR <= 16 && (CPR & (CPR - 1)) == 0), "chunks per row: a power of two up to 16");
+    static constexpr int LDS_LD = KC ? BK : ROWS + VEC;
     static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
+    static __device__ __forceinline__ int swizzled(int row, int k)     // k a multiple of VEC
+    {
+        return ((k / VEC) ^ ((row / (16 / CPR)) & (CPR - 1))) * VEC;
+    }
     static_assert(ROWS * BK % (VEC * NT) == 0, "panel must split evenly over the lanes");
 
     static __device__ __forceinline__ void coords(int f, int &row, int &k)
@@ -125,7 +138,7 @@ struct Panel {
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
             coords((int)threadIdx.x + NT * q, row, k);
-            T *dst = KC ? lds + row * LDS_LD + k : lds + k * LDS_LD + row;
+            T *dst = KC ? lds + row * LDS_LD + swizzled(row, k) : lds + k * LDS_LD + row;
             *(Vec *)dst = (!MASK || (row < rows_left && k < k_left)) ? v[q] : Vec(T(0));
         }
     }
@@ -137,7 +150,7 @@ struct Panel {
         const int row = row0 + (lane % MI);
         const int k = kg * MF::KGROUP + (lane / MI) * VEC;
         if (KC) {
-            Vec v = *(const Vec *)(lds + row * LDS_LD + k);
+            Vec v = *(const Vec *)(lds + row * LDS_LD + swizzled(row, k));
 #pragma unroll
             for (int e = 0; e < VEC; ++e) frag[e] = v[e];
         } else {
