@@ -390,6 +390,20 @@ def test_general_orders_sampled():
             assert err <= TOL["f32"], (ma, mb, mc, strat, text, err)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_vector_operands(dtype):
+    # the level-2 and level-1 rows of Table I through sb_contract: matrix-vector products in both
+    # storage orders, tensor-vector products batched over the last mode, flattened, and with the
+    # extended operation (batch over the first mode);
+    # large enough for several workgroups of the thin kernels, with ragged extents
+    ext = dict(m=1030, n=6, p=37, k=531)
+    for i, (ma, mb, mc) in enumerate([("mk", "k", "m"), ("km", "k", "m"), ("mkp", "k", "mp"), ("kmp", "k", "mp"),
+                                      ("pkm", "k", "mp"), ("k", "km", "m")]):
+        err, text = contract_case(dtype, ma, mb, mc, ext, alpha=1.5, beta=-0.25, seed=500 + i)
+        assert err <= TOL[dtype], (ma, mb, mc, text, err)
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN, (ma, mb, mc, text)
+
+
 def test_replays_inside_a_hip_graph():
     # the library allocates nothing and never synchronises, so a sequence of contractions can be
     # captured once and replayed; every replay is checked, with eager work between the replays
