@@ -44,17 +44,21 @@ struct ExF64 {
     static constexpr int row_reg(int r) { return 4 * r; }
 };
 
-// PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK = 8 deep panels.
+// PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK deep panels (8: one group of
+// MFMA fragments per panel; 16: two, so that a barrier comes only every 32 MFMAs of a wave).
 // The second launch bound (waves per SIMD the register allocation must leave room for) keeps two
 // fp64 workgroups on a compute unit; left alone the allocator gives the fp64 variant more than 256
 // registers and one workgroup per compute unit (35 instead of 54 TFLOP/s at 512^4).  The fp32 variant
-// fits three by itself and is left alone (any bound made it slower).
-template <typename MF, bool B_KC, int PB, int MB, int BN>
+// with 16-deep panels takes 212-232 registers by itself, two workgroups per compute unit, and is
+// left alone: bounded to three it spills inside the k loop (0.50 instead of 0.70 of the peak), and
+// with 8-deep panels three fit but a barrier every 16 MFMAs costs more (0.67).
+template <typename MF, bool B_KC, int PB, int MB, int BN, int BK>
 __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a, int vec_b)
 {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
-    constexpr int MI = MF::MI, VEC = MF::VEC, BK = 8;
+    constexpr int MI = MF::MI, VEC = MF::VEC, KG = BK / 8;     // KG groups of 8 k per panel
+    static_assert(KG == 1 || KG == 2, "one or two fragment groups per panel");
     constexpr int BM = PB * MB;                       // tile rows = (batch, row) pairs
     constexpr int PBP = PB + 16 / (int)sizeof(T);     // b-run padded by 16 bytes: lanes that differ in i hit different banks
     constexpr int A_K = MB * PBP;                     // elements per k slab of the A panel: [k][i][b]
@@ -158,24 +162,25 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     const int64_t nkb = (g.k + BK - 1) / BK;
 
     // MFMA operands of one panel (a group of 8 k: lane group kl takes k = kl*VEC + e)
-    auto read_frags = [&](T (&fa)[NBM][VEC], T (&fb)[NBN][VEC], int buf) {
+    auto read_frags = [&](T (&fa)[NBM][VEC], T (&fb)[NBN][VEC], int buf, int kg = 0) {
+        const int k = kg * 8 + kl * VEC;
 #pragma unroll
         for (int a = 0; a < NBM; ++a) {
             const int rho = rho0 + a * MI + (lane % MI);
             const T *p = As[buf] + (rho % MB) * PBP + (rho / MB);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) fa[a][e] = p[(kl * VEC + e) * A_K];
+            for (int e = 0; e < VEC; ++e) fa[a][e] = p[(k + e) * A_K];
         }
 #pragma unroll
         for (int c = 0; c < NBN; ++c) {
             const int col = c * MI + (lane % MI);
             if (B_KC) {
-                Vec v = *(const Vec *)(Bs[buf] + col * B_LD + kl * VEC);
+                Vec v = *(const Vec *)(Bs[buf] + col * B_LD + k);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) fb[c][e] = v[e];
             } else {
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[buf][(kl * VEC + e) * B_LD + col];
+                for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[buf][(k + e) * B_LD + col];
             }
         }
     };
@@ -195,6 +200,41 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
                 load_b(fast_c, rb[CUR], (kb + 2) * BK);
             }
             const bool hand_over = STEADY || kb + 1 < nkb;
+            if (KG == 2) {
+                // Two fragment groups per panel, fragment sets alternate by group: group 1 is read
+                // while group 0 is multiplied (with the LDS store of the next panel in the middle
+                // of that cluster); the barrier and the next panel's group 0 come before group 1's
+                // MFMAs, which then cover both.
+                read_frags(fa[1], fb[1], CUR, 1);
+                __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    if (e == VEC / 2 && hand_over) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        store_a(As[CUR ^ 1], ra[CUR ^ 1]);
+                        store_b(Bs[CUR ^ 1], rb[CUR ^ 1]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int a = 0; a < NBM; ++a)
+#pragma unroll
+                        for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[0][c][e], fa[0][a][e]);
+                }
+                __builtin_amdgcn_s_setprio(0);
+                if (hand_over) {
+                    __syncthreads();
+                    read_frags(fa[0], fb[0], CUR ^ 1, 0);
+                }
+                __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                    for (int a = 0; a < NBM; ++a)
+#pragma unroll
+                        for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[1][c][e], fa[1][a][e]);
+                __builtin_amdgcn_s_setprio(0);
+                return;
+            }
             __builtin_amdgcn_s_setprio(2);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
@@ -279,7 +319,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     }
 }
 
-template <typename MF, int PB, int MB, int BN>
+template <typename MF, int PB, int MB, int BN, int BK>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
     const int64_t tiles_b = (a.batch0 + PB - 1) / PB, tiles_i = (a.m + MB - 1) / MB, tiles_n = (a.n + BN - 1) / BN;
@@ -290,8 +330,8 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int vec_a = ((uintptr_t)a.A % 16 == 0) && a.rsA % VEC == 0 && a.csA % VEC == 0 && a.bsA[1] % VEC == 0;
     const int vec_b = ((uintptr_t)a.B % 16 == 0) && (a.rsB == 1 ? a.csB : a.rsB) % VEC == 0 && a.bsB[1] % VEC == 0;
     dim3 grid((unsigned)total), block(ET);
-    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
-    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
+    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
+    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
     return hipGetLastError();
 }
 
@@ -311,7 +351,7 @@ bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
 
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
-    if (dt == SB_F32) return launch<ExF32, 16, 16, 64>(a, stream);     // 16 batches x 16 rows x 64 columns per tile
-    if (dt == SB_F64) return launch<ExF64, 16, 16, 32>(a, stream);
+    if (dt == SB_F32) return launch<ExF32, 16, 16, 64, 16>(a, stream);     // 16 batches x 16 rows x 64 columns per tile, 16 k per panel
+    if (dt == SB_F64) return launch<ExF64, 16, 16, 32, 8>(a, stream);
     return hipErrorInvalidValue;
 }
