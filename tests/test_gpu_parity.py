@@ -106,6 +106,32 @@ def test_sb_gemm_thin_shapes(dtype, opA, opB, thin):
         assert err <= TOL[dtype], (m, n, k, err)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_thin_blas_conventions(dtype):
+    # thin shapes with alpha == 0 (operands full of NaN are not read), k == 0, and beta == 0 over a C
+    # full of NaN (not read either)
+    m, n, k, batch = 300, 2, 40, 3
+    rng = np.random.default_rng(9)
+    a = quantise(rng.uniform(-1, 1, m * k * batch), dtype)
+    b = quantise(rng.uniform(-1, 1, k * n), dtype)
+    c0 = quantise(rng.uniform(-1, 1, m * n * batch), dtype)
+    dA, dB = to_dev(a, dtype), to_dev(b, dtype)
+    dNaN = to_dev(np.full(m * k * batch, np.nan), dtype)
+    dC = to_dev(c0, dtype)
+    sb.sb_gemm("N", "N", m, n, k, 0.0, dNaN, m, m * k, dNaN, k, 0, 0.5, dC, m, m * n, batch, dt=dtype)
+    assert sb.sb_last_kernel() == sb.SB_KERNEL_THIN
+    assert rel_fro(from_dev(dC), 0.5 * c0) <= TOL[dtype]
+    dC = to_dev(c0, dtype)
+    sb.sb_gemm("N", "N", m, n, 0, 1.0, dA, m, 0, dB, 1, 0, 0.0, dC, m, m * n, batch, dt=dtype)
+    assert np.array_equal(from_dev(dC), np.zeros(m * n * batch))
+    dC = to_dev(np.full(m * n * batch, np.nan), dtype)
+    sb.sb_gemm("N", "N", m, n, k, 1.0, dA, m, m * k, dB, k, 0, 0.0, dC, m, m * n, batch, dt=dtype)
+    ref = oracle.sb_gemm("N", "N", m, n, k, 1.0, a, m, m * k, b, k, 0, 0.0, np.zeros_like(c0), m, m * n, batch)
+    got = from_dev(dC)
+    assert np.isfinite(got).all() and rel_fro(got, ref) <= TOL[dtype]
+    sync()
+
+
 def test_thin_calls_take_the_thin_kernels():
     # a batched matrix-vector product and a batched vector-matrix product, many 16-byte tiles: the
     # selector sends both to the level-2 family, shared operand (stride 0) included
