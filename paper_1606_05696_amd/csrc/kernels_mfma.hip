@@ -582,7 +582,9 @@ hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStr
     return hipGetLastError();
 }
 
-template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD = 2>
+// STREAM_ONLY: the caller has checked that the problem is made of whole tiles (stream_applies), so
+// only the streaming kernels of this configuration are instantiated.
+template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N, int GD = 2, bool STREAM_ONLY = false>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
     typedef MFT T;
@@ -610,10 +612,26 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
         return STREAM(false, false);
 #undef STREAM
     }
+    if constexpr (STREAM_ONLY) return hipErrorInvalidValue;
+    else {
     if (a_kc && b_kc)        return launch_persistent(sbgemm_mfma_kernel<T, true, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
     else if (a_kc && !b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, true, false, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
     else if (!a_kc && b_kc)  return launch_persistent(sbgemm_mfma_kernel<T, false, true, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
     return launch_persistent(sbgemm_mfma_kernel<T, false, false, BK, WM, WN, WAVES_M, WAVES_N, GD>, NT, total, stream, a, tm, tn, vec_ok);
+    }
+}
+
+// Whole BM x BN tiles, aligned operands, an even number (>= 4) of BK-deep k blocks: what the
+// streaming kernels need (the same test as inside launch()).
+template <typename MFT>
+bool stream_applies(const SbArgs &a, int BM, int BN, int BK)
+{
+    constexpr int VEC = MFT::VEC;
+    const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
+    auto aligned = [](int64_t v) { return v % VEC == 0; };
+    return ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]) &&
+           ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]) &&
+           a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK;
 }
 
 }  // namespace
@@ -661,6 +679,10 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        // whole 128 x 256 tiles, at least one per compute unit: eight waves of 64 x 64 (fewer panel
+        // loads per flop and fewer, longer tiles: 2-3 % over the 128 x 128 tiles at 512^4)
+        if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && (a.m / 128) * (a.n / 256) * a.batch0 * a.batch1 >= 256)
+            return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
