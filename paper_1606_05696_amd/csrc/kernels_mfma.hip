@@ -679,8 +679,11 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
-        // whole 128 x 256 tiles, at least one per compute unit: eight waves of 64 x 64 (fewer panel
-        // loads per flop and fewer, longer tiles: 2-3 % over the 128 x 128 tiles at 512^4)
+        // whole 256 x 256 or 128 x 256 tiles, at least one per compute unit: eight waves of 128 x 64
+        // or 64 x 64 (fewer panel loads per flop and fewer, longer tiles: 2-3 % and 4-5 % over the
+        // 128 x 128 tiles at 512^4)
+        if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && (a.m / 256) * (a.n / 256) * a.batch0 * a.batch1 >= 256)
+            return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
         if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && (a.m / 128) * (a.n / 256) * a.batch0 * a.batch1 >= 256)
             return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
