@@ -34,7 +34,7 @@ BOUND = {1: "hbm", 3: "hbm", 40: "mfma", 41: "mfma", 5: "hbm"}
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same counters'
 # readings for a 1 GiB copy (profiles/bench_default_hbm_traffic.txt); measured offline, not in this run
 MIB = 1 << 20
-MEASURED_TRAFFIC = {41: int(1177.88 * MIB), 40: int(2567.97 * MIB), 3: int(128.14 * MIB), 5: int(41.29 * MIB),
+MEASURED_TRAFFIC = {41: int(1127.02 * MIB), 40: int(2564.64 * MIB), 3: int(128.14 * MIB), 5: int(41.29 * MIB),
                     1: int(0.65 * MIB)}
 
 
