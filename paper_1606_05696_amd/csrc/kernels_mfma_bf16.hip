@@ -28,10 +28,10 @@ constexpr int BK = 32;          // two MFMA k-steps of 16 per panel
 // consecutive chunks then cover 256 contiguous bytes, and sixteen lanes that read the same chunk
 // of consecutive rows (an MFMA fragment) hit sixteen different bank groups: neither conflicts.
 // (With padding the reads are conflict-free but a store wraps onto the banks of the row 3 above.)
-template <bool KC, int ROWS, int BK = 32, bool SWZ = false>
+template <bool KC, int ROWS, int BK = 32, bool SWZ = false, int NT = NTHREADS>
 struct PanelBf16 {
     static_assert(!SWZ || KC, "the swizzle is for k-contiguous panels");
-    static constexpr int NVEC = ROWS * BK / 8 / NTHREADS;             // 16-byte vectors per lane
+    static constexpr int NVEC = ROWS * BK / 8 / NT;             // 16-byte vectors per lane
     static constexpr int LDS_LD = SWZ ? BK : (KC ? BK : ROWS) + 8;    // padded by 16 bytes unless swizzled
     static constexpr int CPR = BK / 8;                                // 16-byte chunks per row
     static __device__ __forceinline__ int swizzled(int row, int k)   // k a multiple of 8
@@ -39,7 +39,7 @@ struct PanelBf16 {
         return SWZ ? (((k >> 3) ^ ((row / (16 / CPR)) & (CPR - 1))) << 3) : k;
     }
     static constexpr int LDS_SIZE = (KC ? ROWS : BK) * LDS_LD;
-    static_assert(ROWS * BK % (8 * NTHREADS) == 0, "panel must split evenly over the lanes");
+    static_assert(ROWS * BK % (8 * NT) == 0, "panel must split evenly over the lanes");
 
     static __device__ __forceinline__ void coords(int f, int &row, int &k)
     {
@@ -52,7 +52,7 @@ struct PanelBf16 {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
-            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            coords((int)threadIdx.x + NT * q, row, k);
             const uint16_t *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
             const bool inside = KC ? (row < rows_left && k + 8 <= k_left) : (row + 8 <= rows_left && k < k_left);
             if (vec_ok && inside) {
@@ -73,7 +73,7 @@ struct PanelBf16 {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
-            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            coords((int)threadIdx.x + NT * q, row, k);
             v[q] = *(const u16x8 *)(KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row);
         }
     }
@@ -83,7 +83,7 @@ struct PanelBf16 {
 #pragma unroll
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
-            coords((int)threadIdx.x + NTHREADS * q, row, k);
+            coords((int)threadIdx.x + NT * q, row, k);
             uint16_t *dst = KC ? lds + row * LDS_LD + swizzled(row, k) : lds + k * LDS_LD + row;
             *(u16x8 *)dst = v[q];
         }
@@ -220,24 +220,27 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
 //     memory operations meet.
 // Every lambda is forced inline: a closure that is called holds the register arrays by address,
 // which would put them in scratch memory.
-// NBM x NBN: MFMA blocks per wave tile.  2 x 2 (128 x 128 workgroup tile, two workgroups per
-// compute unit) reads one LDS fragment per MFMA, which makes LDS bandwidth the limit at about two
-// thirds of the matrix peak; 4 x 4 (256 x 256 tile, 256 accumulator registers, one workgroup per
-// compute unit) reads half a fragment per MFMA.
-// SBK: k per panel (64 for 2 x 2; 32 for 4 x 4, whose staging registers must share 256 with the fragments).
-template <bool BETA, int NBM, int NBN, int SBK>
-__global__ __launch_bounds__(NTHREADS, NBM * NBN <= 4 ? 2 : 1) void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
+// NBM x NBN: MFMA blocks per wave tile, WAVES_M x WAVES_N waves.  2 x 2 blocks on 2 x 2 waves (128 x 128
+// workgroup tile, two workgroups per compute unit) read one LDS fragment per MFMA, which makes LDS
+// bandwidth the limit at about two thirds of the matrix peak; 4 x 2 blocks on 2 x 4 waves (256 x 256
+// tile, one workgroup of 512 lanes per compute unit, still two waves per SIMD) read three quarters
+// of a fragment per MFMA and half the panel bytes per flop.  (4 x 4 blocks on 2 x 2 waves, with 256
+// accumulator registers and one wave per SIMD, were slower: nothing hides a wave's own stalls.)
+// SBK: k per panel (64 for 2 x 2 blocks; 32 for 4 x 2, whose staging registers must share 256 with 128 accumulators).
+template <bool BETA, int NBM, int NBN, int SBK, int WAVES_M = 2, int WAVES_N = 2>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (NBM * NBN <= 4 && WAVES_M * WAVES_N == 4) ? 2 : 1)
+void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
-    constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = 2 * WM, TN = 2 * WN;
-    typedef PanelBf16<true, TM, SBK, true> PA;
-    typedef PanelBf16<true, TN, SBK, true> PB;
+    constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = WAVES_M * WM, TN = WAVES_N * WN, NT = 64 * WAVES_M * WAVES_N;
+    typedef PanelBf16<true, TM, SBK, true, NT> PA;
+    typedef PanelBf16<true, TN, SBK, true, NT> PB;
     constexpr int KG = SBK / 16;                 // MFMA k-steps per panel (even: two fragment sets alternate)
     __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
 
     const int64_t ldA = g.rsA, ldB = g.csB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave & 1) * WM, wn = (wave >> 1) * WN;
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
     const float alpha = (float)g.alpha, beta = (float)g.beta;
     const int64_t nkb = g.k / SBK;
 
@@ -387,7 +390,7 @@ bool stream_applies(const SbArgs &a, int tile, int SBK)
 }
 
 template <typename K>
-hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream)
+hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream, int nthreads = NTHREADS)
 {
     const int64_t tiles_m = a.m / tile, tiles_n = a.n / tile;
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
@@ -398,14 +401,14 @@ hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream
     if (resident_of[dev] == 0) {
         int per_cu = 0, cus = 0;
         hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, NTHREADS, 0);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, nthreads, 0);
         if (e != hipSuccess) return e;
         if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
         resident_of[dev] = per_cu * cus;
     }
     int64_t grid = total < resident_of[dev] ? total : resident_of[dev];
     grid = (grid + NXCD - 1) / NXCD * NXCD;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NTHREADS), 0, stream, a, (int)tiles_m, (int)tiles_n);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, (int)tiles_m, (int)tiles_n);
     return hipGetLastError();
 }
 
@@ -441,9 +444,10 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
     // whole 128 x 128 tiles, both operands k-contiguous: the streaming kernel
     // (256 x 256 tiles when there are enough of them to fill the chip and k is long: measured 1.06-1.10x
     // over the 128 x 128 tiles at k = 2048-4096, 0.87x at k = 512, where a tile ends too soon)
-    if (stream_applies(a, 256, 32) && a.k >= 1024 && (a.m / 256) * (a.n / 256) * a.batch0 * a.batch1 >= 256) {
-        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 4, 4, 32>, 256, a, stream);
-        return launch_stream(sbgemm_bf16_stream_kernel<true, 4, 4, 32>, 256, a, stream);
+    // (256 x 256 tiles on eight waves when there are enough of them to fill the chip)
+    if (stream_applies(a, 256, 32) && (a.m / 256) * (a.n / 256) * a.batch0 * a.batch1 >= 256) {
+        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 4, 2, 32, 2, 4>, 256, a, stream, 512);
+        return launch_stream(sbgemm_bf16_stream_kernel<true, 4, 2, 32, 2, 4>, 256, a, stream, 512);
     }
     if (stream_applies(a, 128, 64)) {
         if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 2, 2, 64>, 128, a, stream);

@@ -495,11 +495,10 @@ def test_sb_gemm_whole_tile_shapes_bf16():
     # the streaming bf16 kernel; shortest legal k, odd tile counts, more and fewer tiles than resident
     # workgroups, beta = 0 and beta != 0 (separate kernels).  The neighbouring shapes (k = 320, an
     # operand not k-contiguous) take the plain bf16 kernel and are checked the same way.  The last
-    # three have at least 256 tiles of 256 x 256 and k >= 1024: the variant with 128 x 128 wave tiles
-    # (k a multiple of 64).
+    # three have at least 256 tiles of 256 x 256: the eight-wave variant (k a multiple of 64).
     for opA, opB, m, n, k, batch in (("T", "N", 256, 384, 256, 5), ("T", "N", 128, 128, 384, 3), ("T", "N", 128, 256, 1024, 1),
                                      ("T", "N", 512, 256, 256, 131), ("T", "N", 128, 128, 320, 3), ("N", "N", 256, 128, 256, 2),
-                                     ("T", "N", 512, 768, 1024, 43), ("T", "N", 1024, 512, 1088, 37), ("T", "N", 256, 256, 2048, 300)):
+                                     ("T", "N", 512, 768, 128, 43), ("T", "N", 1024, 512, 1088, 37), ("T", "N", 256, 256, 192, 300)):
         lda = (m if opA == "N" else k) + 8
         ldb = (k if opB == "N" else n) + 16
         ldc = m + 12
