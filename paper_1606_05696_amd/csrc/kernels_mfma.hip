@@ -636,6 +636,15 @@ bool stream_applies(const SbArgs &a, int BM, int BN, int BK)
 
 }  // namespace
 
+// How evenly `tiles` equal tiles fill `slots` persistent workgroups that each take ceil or floor of
+// tiles / slots of them: useful work over occupied time, 1 when every workgroup gets the same number.
+double sb_slot_fill(int64_t tiles, int64_t slots)
+{
+    if (tiles <= 0) return 0.0;
+    const int64_t rounds = (tiles + slots - 1) / slots;
+    return (double)tiles / (double)(rounds * slots);
+}
+
 // N and T operands only: one of the two strides of each operand must be 1.
 bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
 {
@@ -679,13 +688,17 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
-        // whole 256 x 256 or 128 x 256 tiles, at least one per compute unit: eight waves of 128 x 64
-        // or 64 x 64 (fewer panel loads per flop and fewer, longer tiles: 2-3 % and 4-5 % over the
-        // 128 x 128 tiles at 512^4)
-        if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && (a.m / 256) * (a.n / 256) * a.batch0 * a.batch1 >= 256)
-            return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
-        if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && (a.m / 128) * (a.n / 256) * a.batch0 * a.batch1 >= 256)
-            return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
+        // whole 256 x 256 or 128 x 256 tiles: eight waves of 128 x 64 or 64 x 64 (fewer panel loads per
+        // flop and fewer, longer tiles: 4-5 % and 2-3 % over the 128 x 128 tiles at 512^4), unless the
+        // bigger tiles would fill the chip's workgroup slots less evenly than that gain
+        {
+            const int64_t batch = a.batch0 * a.batch1;
+            const double fill128 = sb_slot_fill(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 512);
+            if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && sb_slot_fill((a.m / 256) * (a.n / 256) * batch, 256) * 1.04 >= fill128)
+                return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
+            if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_slot_fill((a.m / 128) * (a.n / 256) * batch, 256) * 1.02 >= fill128)
+                return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
+        }
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves

@@ -475,9 +475,9 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
     # whole 128 x 128 (or 64 x 64) tiles with k a multiple of 32: the streaming member of the MFMA
     # family, whose panel stream runs across tile boundaries; shortest legal k, odd tile counts,
     # more and fewer tiles than resident workgroups, beta = 0 and beta != 0 (separate kernels)
-    # the last three have at least 256 tiles of 128 x 256 or 256 x 256: the eight-wave fp32 configurations
-    for m, n, k, batch in ((256, 384, 64, 5), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1),
-                           (256, 512, 96, 140), (128, 256, 160, 300), (384, 256, 64, 260)):
+    # the last five fill the chip with 128 x 256 (three) or 256 x 256 tiles (two): the eight-wave fp32 configurations
+    for m, n, k, batch in ((256, 384, 64, 5), (256, 384, 64, 30), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1),
+                           (256, 512, 96, 140), (128, 256, 160, 300), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128)):
         lda = (m if opA == "N" else k) + 4
         ldb = (k if opB == "N" else n) + 8
         ldc = m + 12
@@ -495,10 +495,10 @@ def test_sb_gemm_whole_tile_shapes_bf16():
     # the streaming bf16 kernel; shortest legal k, odd tile counts, more and fewer tiles than resident
     # workgroups, beta = 0 and beta != 0 (separate kernels).  The neighbouring shapes (k = 320, an
     # operand not k-contiguous) take the plain bf16 kernel and are checked the same way.  The last
-    # three have at least 256 tiles of 256 x 256: the eight-wave variant (k a multiple of 64).
+    # three fill the chip with 256 x 256 tiles: the eight-wave variant (k a multiple of 64).
     for opA, opB, m, n, k, batch in (("T", "N", 256, 384, 256, 5), ("T", "N", 128, 128, 384, 3), ("T", "N", 128, 256, 1024, 1),
                                      ("T", "N", 512, 256, 256, 131), ("T", "N", 128, 128, 320, 3), ("N", "N", 256, 128, 256, 2),
-                                     ("T", "N", 512, 768, 128, 43), ("T", "N", 1024, 512, 1088, 37), ("T", "N", 256, 256, 192, 300)):
+                                     ("T", "N", 512, 768, 128, 128), ("T", "N", 1024, 512, 1088, 32), ("T", "N", 256, 256, 192, 256)):
         lda = (m if opA == "N" else k) + 8
         ldb = (k if opB == "N" else n) + 16
         ldc = m + 12
