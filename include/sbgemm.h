@@ -191,7 +191,7 @@ int sb_last_kernel(void);
 
 /* Host only: the kernel family the selector sends an sb_gemm problem to (sizes, operations and
  * strides as for sb_gemm, all of m, n, k, batch at least 1; no pointers: the family depends on the
- * shape only, alignment decides between variants inside a family).  Negative: -i = i-th argument
+ * shape only; no alignment beyond that of the elements is ever required of the operands).  Negative: -i = i-th argument
  * invalid.  Ignores sb_force_kernel. */
 int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
                      int64_t lda, int64_t strideA, int64_t ldb, int64_t strideB, int64_t ldc,

@@ -37,6 +37,7 @@ struct MfmaF32x32 {
     static constexpr int MI = 32, VEC = 4, NREG = 16, KGROUP = 8;
     typedef f32x16 Acc;
     typedef float Vec __attribute__((ext_vector_type(4)));
+    typedef float VecU __attribute__((ext_vector_type(4), aligned(4)));       // a vector at any element address
     static __device__ __forceinline__ void mma(Acc &c, float first, float second)
     {
         c = __builtin_amdgcn_mfma_f32_32x32x2f32(first, second, c, 0, 0, 0);
@@ -51,6 +52,7 @@ struct MfmaF64x16 {
     static constexpr int MI = 16, VEC = 2, NREG = 4, KGROUP = 8;
     typedef f64x4 Acc;
     typedef double Vec __attribute__((ext_vector_type(2)));
+    typedef double VecU __attribute__((ext_vector_type(2), aligned(8)));
     static __device__ __forceinline__ void mma(Acc &c, double first, double second)
     {
         c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0);
@@ -68,6 +70,7 @@ template <typename MF, bool KC, int ROWS, int BK, int NT>
 struct Panel {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
+    typedef typename MF::VecU VecU;      // global loads: gfx950 reads a 16-byte vector at any element-aligned address
     static constexpr int VEC = MF::VEC;
     static constexpr int NVEC = ROWS * BK / VEC / NT;                  // 16-byte vectors per lane
     // k-contiguous panels are stored unpadded, the 16-byte chunk c of row r at chunk c ^ f(r) with
@@ -109,17 +112,17 @@ struct Panel {
             coords((int)threadIdx.x + NT * q, row, k);
             const T *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
             if (GUARD == 0) {
-                v[q] = *(const Vec *)src;
+                v[q] = *(const VecU *)src;
                 continue;
             }
             if (GUARD == 1) {          // the vector is zeroed when it goes to LDS: masking it here would wait for the load
                 const bool in = row < rows_left && k < k_left;
-                v[q] = *(const Vec *)(in ? src : p);
+                v[q] = *(const VecU *)(in ? src : p);
                 continue;
             }
             const bool inside = KC ? (row < rows_left && k + VEC <= k_left) : (row + VEC <= rows_left && k < k_left);
             if (vec_ok && inside) {
-                v[q] = *(const Vec *)src;
+                v[q] = *(const VecU *)src;
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
@@ -593,13 +596,11 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    constexpr int VEC = MFT::VEC;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
-    auto aligned = [](int64_t v) { return v % VEC == 0; };
-    // per operand: every 16-byte vector of its panels is aligned (bit 0: A, bit 1: B)
-    const bool vec_a = ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]);
-    const bool vec_b = ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
-    const int vec_ok = (vec_a ? 1 : 0) | (vec_b ? 2 : 0);
+    // per operand (bit 0: A, bit 1: B): its panels may be read as 16-byte vectors.  The hardware
+    // reads such a vector at any element-aligned address, so leading dimensions and offsets need
+    // not be multiples of the vector length.
+    const int vec_ok = 3;
     const int tm = (int)tiles_m, tn = (int)tiles_n;
     // whole tiles, aligned operands, an even number (>= 4) of k blocks: the streaming kernel
     if (vec_ok == 3 && a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK) {
@@ -621,17 +622,12 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     }
 }
 
-// Whole BM x BN tiles, aligned operands, an even number (>= 4) of BK-deep k blocks: what the
+// Whole BM x BN tiles and an even number (>= 4) of BK-deep k blocks: what the
 // streaming kernels need (the same test as inside launch()).
 template <typename MFT>
 bool stream_applies(const SbArgs &a, int BM, int BN, int BK)
 {
-    constexpr int VEC = MFT::VEC;
-    const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
-    auto aligned = [](int64_t v) { return v % VEC == 0; };
-    return ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]) &&
-           ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]) &&
-           a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK;
+    return a.m % BM == 0 && a.n % BN == 0 && a.k % (2 * BK) == 0 && a.k >= 4 * BK;
 }
 
 }  // namespace

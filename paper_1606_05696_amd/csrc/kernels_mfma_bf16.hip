@@ -18,6 +18,7 @@ namespace {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x8u __attribute__((ext_vector_type(8), aligned(2)));      // global loads: any element address
 
 constexpr int NTHREADS = 256;
 constexpr int NXCD = 8;
@@ -56,7 +57,7 @@ struct PanelBf16 {
             const uint16_t *src = KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row;
             const bool inside = KC ? (row < rows_left && k + 8 <= k_left) : (row + 8 <= rows_left && k < k_left);
             if (vec_ok && inside) {
-                v[q] = *(const u16x8 *)src;
+                v[q] = *(const u16x8u *)src;
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
@@ -74,7 +75,7 @@ struct PanelBf16 {
         for (int q = 0; q < NVEC; ++q) {
             int row, k;
             coords((int)threadIdx.x + NT * q, row, k);
-            v[q] = *(const u16x8 *)(KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row);
+            v[q] = *(const u16x8u *)(KC ? p + (int64_t)row * ld + k : p + (int64_t)k * ld + row);
         }
     }
 
@@ -383,10 +384,7 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
 
 bool stream_applies(const SbArgs &a, int tile, int SBK)
 {
-    auto aligned = [](int64_t v) { return v % 8 == 0; };
-    return a.csA == 1 && a.rsB == 1 && a.m % tile == 0 && a.n % tile == 0 && a.k % (2 * SBK) == 0 && a.k >= 4 * SBK &&
-           (uintptr_t)a.A % 16 == 0 && (uintptr_t)a.B % 16 == 0 && aligned(a.rsA) && aligned(a.csB) &&
-           aligned(a.bsA[0]) && aligned(a.bsA[1]) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
+    return a.csA == 1 && a.rsB == 1 && a.m % tile == 0 && a.n % tile == 0 && a.k % (2 * SBK) == 0 && a.k >= 4 * SBK;
 }
 
 template <typename K>
@@ -421,11 +419,9 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
-    auto aligned = [](int64_t v) { return v % 8 == 0; };
-    // per operand: every 16-byte vector of its panels is aligned (bit 0: A, bit 1: B)
-    const bool vec_a = ((uintptr_t)a.A % 16 == 0) && aligned(a_kc ? a.rsA : a.csA) && aligned(a.bsA[0]) && aligned(a.bsA[1]);
-    const bool vec_b = ((uintptr_t)a.B % 16 == 0) && aligned(b_kc ? a.csB : a.rsB) && aligned(a.bsB[0]) && aligned(a.bsB[1]);
-    const int vec_ok = (vec_a ? 1 : 0) | (vec_b ? 2 : 0);
+    // per operand (bit 0: A, bit 1: B): 16-byte vector loads; the hardware reads them at any
+    // element-aligned address, so no leading dimension or offset has to be a multiple of 8
+    const int vec_ok = 3;
     dim3 grid((unsigned)total), block(NTHREADS);
     const int tm = (int)tiles_m, tn = (int)tiles_n;
     if (a_kc && b_kc)        hipLaunchKernelGGL((sbgemm_mfma_bf16_kernel<true, true, WT>), grid, block, 0, stream, a, tm, tn, vec_ok);

@@ -29,6 +29,7 @@ struct ExF32 {
     typedef float T;
     typedef f32x16 Acc;
     typedef float Vec __attribute__((ext_vector_type(4)));
+    typedef float VecU __attribute__((ext_vector_type(4), aligned(4)));       // global loads: any element address
     static constexpr int MI = 32, VEC = 4, NREG = 16;       // 64/MI lane groups along k, VEC k each: 8 k per fragment
     static __device__ __forceinline__ void mma(Acc &c, float first, float second) { c = __builtin_amdgcn_mfma_f32_32x32x2f32(first, second, c, 0, 0, 0); }
     static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 5); }
@@ -38,6 +39,7 @@ struct ExF64 {
     typedef double T;
     typedef f64x4 Acc;
     typedef double Vec __attribute__((ext_vector_type(2)));
+    typedef double VecU __attribute__((ext_vector_type(2), aligned(8)));
     static constexpr int MI = 16, VEC = 2, NREG = 4;
     static __device__ __forceinline__ void mma(Acc &c, double first, double second) { c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0); }
     static __device__ __forceinline__ int row_lane(int lane) { return lane >> 4; }
@@ -57,6 +59,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
 {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
+    typedef typename MF::VecU VecU;
     constexpr int MI = MF::MI, VEC = MF::VEC, KG = BK / 8;     // KG groups of 8 k per panel
     static_assert(KG == 1 || KG == 2, "one or two fragment groups per panel");
     constexpr int BM = PB * MB;                       // tile rows = (batch, row) pairs
@@ -109,12 +112,12 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
             const int k = f / (MB * (PB / VEC)), i = (f / (PB / VEC)) % MB, b = (f % (PB / VEC)) * VEC;
             const T *src = A + b + (int64_t)i * g.rsA + (k0 + k) * g.csA;
             if (decltype(fast_c)::value) {
-                v[q] = *(const Vec *)src;
+                v[q] = *(const VecU *)src;
                 continue;
             }
             const bool row_ok = i < m_left && k0 + k < g.k;
             if (vec_a && row_ok && b + VEC <= b_left) {
-                v[q] = *(const Vec *)src;
+                v[q] = *(const VecU *)src;
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[q][e] = (row_ok && b + e < b_left) ? src[e] : T(0);
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
         else      { k = f / (BN / VEC); col = (f % (BN / VEC)) * VEC; }
         const T *src = B_KC ? B + (int64_t)col * ldB + (k0 + k) : B + (k0 + k) * kstepB + col;
         if (decltype(fast_c)::value) {
-            v = *(const Vec *)src;
+            v = *(const VecU *)src;
             return;
         }
 #pragma unroll
@@ -326,9 +329,8 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int64_t total = tiles_b * tiles_i * tiles_n * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    constexpr int VEC = MF::VEC;
-    const int vec_a = ((uintptr_t)a.A % 16 == 0) && a.rsA % VEC == 0 && a.csA % VEC == 0 && a.bsA[1] % VEC == 0;
-    const int vec_b = ((uintptr_t)a.B % 16 == 0) && (a.rsB == 1 ? a.csB : a.rsB) % VEC == 0 && a.bsB[1] % VEC == 0;
+    // 16-byte vector loads need no alignment beyond the element's: the hardware reads them anywhere
+    const int vec_a = 1, vec_b = 1;
     dim3 grid((unsigned)total), block(ET);
     if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
     else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);

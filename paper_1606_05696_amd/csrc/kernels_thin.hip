@@ -17,14 +17,20 @@
 //                 lanes owns 4 rows, each lane accumulates its share of the 4 dot products, and
 //                 a butterfly over the group finishes them.
 // VEC > 1 variants read M (and, in the dots kernel, X) as 16-byte (or, bf16 only, 4-byte) vectors;
-// they need the fast stride to be 1 and every other stride, the extent along the vector and the
-// base address to be whole vectors.  VEC = 1 variants take anything.
+// they need the fast stride to be 1 and the extent along the vector to be whole vectors (the
+// hardware reads a vector at any element-aligned address, so neither the other strides nor the
+// base address matter).  VEC = 1 variants take anything.
 #include "sb_device.h"
 #include "sb_internal.h"
 
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// global loads of 16 (4) bytes at any address that is aligned for the element: the hardware takes them
+typedef uint32_t u32x4a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4a8 __attribute__((ext_vector_type(4), aligned(8)));
+typedef uint32_t u32x4a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef uint32_t u32a2 __attribute__((aligned(2)));
 
 struct Thin {
     const void *M, *X;
@@ -48,7 +54,7 @@ template <typename T, typename Acc> struct Pack<T, Acc, 1> {
 };
 template <> struct Pack<float, float, 4> {
     typedef u32x4 Raw;
-    static __device__ __forceinline__ Raw load(const float *p) { return *(const u32x4 *)p; }
+    static __device__ __forceinline__ Raw load(const float *p) { return *(const u32x4a4 *)p; }
     static __device__ __forceinline__ void unpack(const Raw &r, float (&v)[4])
     {
 #pragma unroll
@@ -57,7 +63,7 @@ template <> struct Pack<float, float, 4> {
 };
 template <> struct Pack<double, double, 2> {
     typedef u32x4 Raw;
-    static __device__ __forceinline__ Raw load(const double *p) { return *(const u32x4 *)p; }
+    static __device__ __forceinline__ Raw load(const double *p) { return *(const u32x4a8 *)p; }
     static __device__ __forceinline__ void unpack(const Raw &r, double (&v)[2])
     {
         v[0] = __hiloint2double((int)r[1], (int)r[0]);
@@ -66,7 +72,7 @@ template <> struct Pack<double, double, 2> {
 };
 template <> struct Pack<sb_bf16, float, 8> {
     typedef u32x4 Raw;
-    static __device__ __forceinline__ Raw load(const sb_bf16 *p) { return *(const u32x4 *)p; }
+    static __device__ __forceinline__ Raw load(const sb_bf16 *p) { return *(const u32x4a2 *)p; }
     static __device__ __forceinline__ void unpack(const Raw &r, float (&v)[8])
     {
 #pragma unroll
@@ -79,7 +85,7 @@ template <> struct Pack<sb_bf16, float, 8> {
 
 template <> struct Pack<sb_bf16, float, 2> {
     typedef uint32_t Raw;
-    static __device__ __forceinline__ Raw load(const sb_bf16 *p) { return *(const uint32_t *)p; }
+    static __device__ __forceinline__ Raw load(const sb_bf16 *p) { return *(const u32a2 *)p; }
     static __device__ __forceinline__ void unpack(const Raw &r, float (&v)[2])
     {
         v[0] = __uint_as_float(r << 16);
@@ -294,7 +300,6 @@ __global__ __launch_bounds__(THIN_THREADS) void thin_dots_kernel(Thin g, int64_t
 
 // ---------------------------------------------------------------------------------------------
 bool whole_vectors(int64_t x, int vec) { return x % vec == 0; }
-bool aligned_to(const void *p, size_t bytes) { return ((uintptr_t)p & (bytes - 1)) == 0; }
 
 Thin thin_view(const SbArgs &a)
 {
@@ -352,16 +357,13 @@ hipError_t launch_nv(const Thin &t, hipStream_t stream)
 {
     constexpr int VEC = VecOf<T>::value, MID = VecOf<T>::dword;
     const int64_t batch = t.batch0 * t.batch1;
-    auto m_whole = [&](int vec) {
-        return whole_vectors(t.bsM[0], vec) && whole_vectors(t.bsM[1], vec) && aligned_to(t.M, vec * sizeof(T));
-    };
     // lanes along the rows of M unless its columns are the contiguous direction
     const bool rows = t.K <= 1 || (t.R > 1 && t.rsM <= t.csM);
     if (rows) {
         // The widest loads that still leave a workgroup for every compute unit; when the loads
         // in flight are few even so, sixteen waves each split l instead of four.
         auto usable = [&](int vec) {
-            return vec == 1 || (t.rsM == 1 && whole_vectors(t.R, vec) && whole_vectors(t.csM, vec) && m_whole(vec));
+            return vec == 1 || (t.rsM == 1 && whole_vectors(t.R, vec));
         };
         auto groups = [&](int vec) { return (t.R + 64 * vec - 1) / (64 * vec) * batch; };
         const int vec = usable(VEC) && groups(VEC) >= 256 ? VEC : (usable(MID) && groups(MID) >= 256 ? MID : 1);
@@ -374,9 +376,7 @@ hipError_t launch_nv(const Thin &t, hipStream_t stream)
         if (vec == MID) return launch_rows<T, Acc, NV, MID>(t, many_waves, stream);
         return launch_rows<T, Acc, NV, 1>(t, many_waves, stream);
     }
-    const bool vec = t.csM == 1 && t.sxl == 1 && whole_vectors(t.K, VEC) && whole_vectors(t.rsM, VEC) && m_whole(VEC) &&
-                     whole_vectors(t.sxv, VEC) && whole_vectors(t.bsX[0], VEC) && whole_vectors(t.bsX[1], VEC) &&
-                     aligned_to(t.X, VEC * sizeof(T));
+    const bool vec = t.csM == 1 && t.sxl == 1 && whole_vectors(t.K, VEC);
     // rows of at most 32 loads per lane group go four groups to a wave
     const bool short_rows = t.K <= 32 * (vec ? VEC : 1);
     const int64_t tile_rows = short_rows ? 64 : 16;
