@@ -24,6 +24,9 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
+// global accesses: the hardware reads and writes these at any element-aligned address
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef double f64x4u __attribute__((ext_vector_type(4), aligned(8)));
 
 template <typename T> struct TinyMfma;
 
@@ -31,6 +34,7 @@ template <typename T> struct TinyMfma;
 template <> struct TinyMfma<float> {
     typedef f32x4 Acc;
     typedef f32x4 Vec4;
+    typedef f32x4u Vec4U;
     static constexpr bool SWAP = false;     // lane = column of C, slots = 4 consecutive rows
     static __device__ __forceinline__ void mma(Acc &c, float first, float second)
     {
@@ -42,6 +46,7 @@ template <> struct TinyMfma<float> {
 template <> struct TinyMfma<double> {
     typedef f64x4 Acc;
     typedef f64x4 Vec4;
+    typedef f64x4u Vec4U;
     static constexpr bool SWAP = true;      // computes C^T: lane = row of C, slots = columns h, h+4, ..
     static __device__ __forceinline__ void mma(Acc &c, double first, double second)
     {
@@ -61,7 +66,7 @@ __device__ __forceinline__ void load_frag(T (&f)[4], const T *p, int64_t ld, int
     if (KC) {
         const T *src = p + (int64_t)rc * ld + k0;
         if (vec_ok && rc < rc_count && k0 + 4 <= kcount) {
-            Vec4 v = *(const Vec4 *)src;
+            Vec4 v = *(const typename TinyMfma<T>::Vec4U *)src;
 #pragma unroll
             for (int e = 0; e < 4; ++e) f[e] = v[e];
         } else {
@@ -166,11 +171,11 @@ __global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int
 #pragma unroll
                             for (int r = 0; r < 4; ++r) v[r] = alpha * acc[u][a][c][r];
                             if (beta != T(0)) {
-                                typename MF::Vec4 old = *(const typename MF::Vec4 *)dst;
+                                typename MF::Vec4 old = *(const typename MF::Vec4U *)dst;
 #pragma unroll
                                 for (int r = 0; r < 4; ++r) v[r] += beta * old[r];
                             }
-                            *(typename MF::Vec4 *)dst = v;
+                            *(typename MF::Vec4U *)dst = v;
                         } else {
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
@@ -205,13 +210,8 @@ hipError_t launch3(const SbArgs &a, hipStream_t stream)
     const int64_t total = a.batch0 * a.batch1;
     constexpr int U = (TM * TN == 1) ? 4 : (TM * TN == 2 ? 2 : 1);
     const bool hoist = (a.bsA[0] == 0 || a.batch0 == 1) && (a.bsA[1] == 0 || a.batch1 == 1) && a.k <= 16;
-    // vector accesses need 16-byte (fp32) / 32-byte (fp64) alignment of every address they touch
-    const int64_t V = 4;
-    const uintptr_t bytes = V * sizeof(T);
-    auto al = [&](int64_t v) { return v % V == 0; };
-    const int vec_a = A_KC && (uintptr_t)a.A % bytes == 0 && al(a.rsA) && al(a.bsA[0]) && al(a.bsA[1]);
-    const int vec_b = B_KC && (uintptr_t)a.B % bytes == 0 && al(a.csB) && al(a.bsB[0]) && al(a.bsB[1]);
-    const int vec_c = (uintptr_t)a.C % bytes == 0 && al(a.ldc) && al(a.bsC[0]) && al(a.bsC[1]);
+    // vector accesses need no alignment beyond the element's (leading dimensions and offsets may be odd)
+    const int vec_a = A_KC, vec_b = B_KC, vec_c = 1;
     // enough workgroups to fill the chip several waves deep, no more than the work needs
     int64_t groups = (total + (int64_t)WAVES * U - 1) / ((int64_t)WAVES * U);
     const int64_t cap = 256 * 8;
