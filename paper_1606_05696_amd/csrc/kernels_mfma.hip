@@ -677,13 +677,18 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     // four times as many workgroups
     const int64_t tiles128 = ((a.m + 127) / 128) * ((a.n + 127) / 128) * a.batch0 * a.batch1;
     const bool few_tiles = tiles128 < 128;
+    // and so do extents just above a multiple of 128 (300 x 300: 128 x 128 tiles compute 1.64 times
+    // the result's area, 64 x 64 tiles 1.14 times)
+    auto padded = [](int64_t x, int64_t t) { return (x + t - 1) / t * t; };
+    const bool much_padding = (double)(padded(a.m, 128) * padded(a.n, 128)) > 1.15 * (double)(padded(a.m, 64) * padded(a.n, 64));
+    const bool small_tiles = a.m <= 64 || a.n <= 64 || few_tiles || much_padding;
     switch (dt) {
     case SB_F32:
         // a factor matrix against a tensor unfolding: bound by streaming the big operand, so the
         // tile is long in that operand's direction (big panels in flight) and one MFMA block wide
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        if (small_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
         // whole 256 x 256 or 128 x 256 tiles: eight waves of 128 x 64 or 64 x 64 (fewer panel loads per
         // flop and fewer, longer tiles: 4-5 % and 2-3 % over the 128 x 128 tiles at 512^4), unless the
         // bigger tiles would fill the chip's workgroup slots less evenly than that gain
@@ -699,7 +704,7 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     case SB_F64:
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF64x16, 16, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (a.m <= 64 || a.n <= 64 || few_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
+        if (small_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
         return launch<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);                                 // 128 x 128 tiles, 16 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;
