@@ -632,13 +632,14 @@ bool stream_applies(const SbArgs &a, int BM, int BN, int BK)
 
 }  // namespace
 
-// How evenly `tiles` equal tiles fill `slots` persistent workgroups that each take ceil or floor of
-// tiles / slots of them: useful work over occupied time, 1 when every workgroup gets the same number.
-double sb_slot_fill(int64_t tiles, int64_t slots)
+// Estimated run time of a problem cut into `tiles` equal tiles, in units of one 128 x 128 tile on a
+// compute unit of its own: the busiest of the 256 compute units gets ceil(tiles / 256) tiles (two
+// workgroups that share a unit take turns on its matrix core, so they count like one after the
+// other), each `area` times a 128 x 128 tile and `gain` times faster per flop.
+double sb_tile_time(int64_t tiles, double area, double gain)
 {
-    if (tiles <= 0) return 0.0;
-    const int64_t rounds = (tiles + slots - 1) / slots;
-    return (double)tiles / (double)(rounds * slots);
+    const int64_t units = 256;
+    return (double)((tiles + units - 1) / units) * area / gain;
 }
 
 // N and T operands only: one of the two strides of each operand must be 1.
@@ -691,13 +692,13 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         if (small_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
         // whole 256 x 256 or 128 x 256 tiles: eight waves of 128 x 64 or 64 x 64 (fewer panel loads per
         // flop and fewer, longer tiles: 4-5 % and 2-3 % over the 128 x 128 tiles at 512^4), unless the
-        // bigger tiles would fill the chip's workgroup slots less evenly than that gain
+        // bigger tiles would leave compute units idle (few tiles, or a last round that is mostly empty)
         {
             const int64_t batch = a.batch0 * a.batch1;
-            const double fill128 = sb_slot_fill(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 512);
-            if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && sb_slot_fill((a.m / 256) * (a.n / 256) * batch, 256) * 1.04 >= fill128)
+            const double t128 = sb_tile_time(tiles128, 1.0, 1.0);
+            if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.04) <= t128)
                 return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
-            if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_slot_fill((a.m / 128) * (a.n / 256) * batch, 256) * 1.02 >= fill128)
+            if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_tile_time((a.m / 128) * (a.n / 256) * batch, 2.0, 1.02) <= t128)
                 return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
         }
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles

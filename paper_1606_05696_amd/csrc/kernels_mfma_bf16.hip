@@ -440,11 +440,11 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
     // whole 128 x 128 tiles, both operands k-contiguous: the streaming kernel
     // (256 x 256 tiles when there are enough of them to fill the chip and k is long: measured 1.06-1.10x
     // over the 128 x 128 tiles at k = 2048-4096, 0.87x at k = 512, where a tile ends too soon)
-    // (256 x 256 tiles on eight waves, 1.15-1.3x faster per flop, unless they would fill the chip's
-    // workgroup slots that much less evenly than 128 x 128 tiles)
+    // (256 x 256 tiles on eight waves, 1.15-1.3x faster per flop, unless they would leave compute
+    // units idle: few tiles, or a last round that is mostly empty)
     const int64_t batch = a.batch0 * a.batch1;
-    if (stream_applies(a, 256, 32) && sb_slot_fill((a.m / 256) * (a.n / 256) * batch, 256) * 1.15 >=
-                                          sb_slot_fill(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 512)) {
+    if (stream_applies(a, 256, 32) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.15) <=
+                                          sb_tile_time(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 1.0, 1.0)) {
         if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 4, 2, 32, 2, 4>, 256, a, stream, 512);
         return launch_stream(sbgemm_bf16_stream_kernel<true, 4, 2, 32, 2, 4>, 256, a, stream, 512);
     }

@@ -41,9 +41,9 @@ hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream);
 bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a);       // extended op on the first operand (MFMA family)
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 
-// How evenly `tiles` equal tiles fill `slots` persistent workgroups (1 = every workgroup gets the same
-// number of tiles): the launchers weigh it against what a bigger tile gains.
-double sb_slot_fill(int64_t tiles, int64_t slots);
+// Estimated run time of `tiles` equal tiles (area and speed relative to a 128 x 128 tile) on the chip's
+// 256 compute units: the launchers use it to choose between tile sizes.
+double sb_tile_time(int64_t tiles, double area, double gain);
 
 // Set-up that HIP keeps per device (function attributes, occupancy) is cached per device ordinal.
 constexpr int SB_MAX_DEVICES = 64;

@@ -475,9 +475,10 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
     # whole 128 x 128 (or 64 x 64) tiles with k a multiple of 32: the streaming member of the MFMA
     # family, whose panel stream runs across tile boundaries; shortest legal k, odd tile counts,
     # more and fewer tiles than resident workgroups, beta = 0 and beta != 0 (separate kernels)
-    # the last five fill the chip with 128 x 256 (three) or 256 x 256 tiles (two): the eight-wave fp32 configurations
+    # of the last five, two fill the chip with 128 x 256 tiles and two with 256 x 256 tiles (the eight-wave fp32
+    # configurations); the one between them would leave a round mostly empty with either and stays on 128 x 128
     for m, n, k, batch in ((256, 384, 64, 5), (256, 384, 64, 30), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1),
-                           (256, 512, 96, 140), (128, 256, 160, 300), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128)):
+                           (384, 512, 96, 128), (128, 256, 160, 512), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128)):
         lda = (m if opA == "N" else k) + 4
         ldb = (k if opB == "N" else n) + 8
         ldc = m + 12
