@@ -43,8 +43,12 @@ __device__ __forceinline__ void rotation(T app, T aqq, T apq, T &c, T &s)
 // odd matrix pairs with nothing).  Work items: (ne/2)^2 blocks of A, then n * ne/2 row pairs of V.
 template <typename T>
 __global__ __launch_bounds__(256) void jacobi_step_kernel(const T *__restrict__ Ain, T *__restrict__ Aout,
-                                                          const T *__restrict__ Vin, T *__restrict__ Vout, int n, int ne, int round)
+                                                          const T *__restrict__ Vin, T *__restrict__ Vout, int n, int ne, int round,
+                                                          int64_t stride)
 {
+    // several problems of the same order at a fixed stride: blockIdx.y picks one
+    Ain += blockIdx.y * stride; Aout += blockIdx.y * stride;
+    Vin += blockIdx.y * stride; Vout += blockIdx.y * stride;
     const int h = ne / 2;
     const int64_t nA = (int64_t)h * h, total = nA + (int64_t)n * h;
     for (int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; item < total; item += (int64_t)gridDim.x * blockDim.x) {
@@ -82,8 +86,9 @@ __global__ __launch_bounds__(256) void jacobi_step_kernel(const T *__restrict__ 
 }
 
 template <typename T>
-__global__ void identity_kernel(T *V, int n)
+__global__ void identity_kernel(T *V, int n, int64_t stride = 0)
 {
+    V += blockIdx.y * stride;
     const int64_t total = (int64_t)n * n;
     for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x)
         V[e] = (e % n == e / n) ? T(1) : T(0);
@@ -111,8 +116,12 @@ size_t jacobi_lds_bytes(int n)
 }
 
 template <typename T>
-__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, const T *V0, int n, int ne, int sweeps, T rel_tol)
+__global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, const T *V0, int n, int ne, int sweeps, T rel_tol, int64_t stride)
 {
+    // several problems of the same order at a fixed stride: one workgroup each
+    A += blockIdx.x * stride;
+    V += blockIdx.x * stride;
+    if (V0) V0 += blockIdx.x * stride;
     extern __shared__ __attribute__((aligned(16))) unsigned char raw[];
     const int h = ne / 2, tid = threadIdx.x;
     T *As = (T *)raw;                    // ne x ne, leading dimension ne
@@ -209,8 +218,11 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
 // Order the eigenvalues (the diagonal of the rotated matrix): rank[i] = number of eigenvalues that
 // come before lambda_i in descending order (ties by index); lam[rank] = lambda_i, sel[rank] = i.
 template <typename T>
-__global__ __launch_bounds__(256) void eig_order_kernel(const T *A, int n, T *lam, int *sel)
+__global__ __launch_bounds__(256) void eig_order_kernel(const T *A, int n, T *lam, int *sel, int64_t stride, int64_t stride_sel)
 {
+    A += blockIdx.y * stride;
+    lam += blockIdx.y * stride;
+    sel += blockIdx.y * stride_sel;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
         const T li = A[i + (int64_t)i * n];
         int rank = 0;
@@ -241,9 +253,12 @@ __global__ __launch_bounds__(256) void eig_gather_kernel(const T *V, int n, cons
 }
 
 template <typename T>
-hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, const T *V0, T *lam, int *sel, int sweeps, hipStream_t stream, T **A_final, T **V_final)
+hipError_t eig_impl(int n, int count, int64_t stride_bytes, T *A, T *A2, T *V, T *V2, const T *V0, T *lam, int *sel, int sweeps,
+                    hipStream_t stream, T **A_final, T **V_final)
 {
     const int ne = n + (n & 1);
+    const int64_t stride = stride_bytes / (int64_t)sizeof(T), stride_sel = stride_bytes / (int64_t)sizeof(int);
+    if (count < 1 || (count > 1 && (V0 || n == 1))) return hipErrorInvalidValue;      // batches start from the identity
     if (n == 1) {
         if (V0) { hipError_t e = hipMemcpyAsync(V, V0, sizeof(T), hipMemcpyDeviceToDevice, stream); if (e != hipSuccess) return e; }
         else identity_kernel<T><<<1, 64, 0, stream>>>(V, 1);
@@ -260,24 +275,24 @@ hipError_t eig_impl(int n, T *A, T *A2, T *V, T *V2, const T *V0, T *lam, int *s
         // 8 units of rounding of the largest diagonal element: rotating smaller elements only stirs rounding
         // noise (each sweep creates as much as it removes), and a warm-started solve would never stop early
         const T rel_tol = sizeof(T) == 8 ? T(1.8e-15) : T(9.6e-7);
-        jacobi_lds_kernel<T><<<1, LDS_THREADS, bytes, stream>>>(A, V, V0, n, ne, sweeps, rel_tol);
+        jacobi_lds_kernel<T><<<count, LDS_THREADS, bytes, stream>>>(A, V, V0, n, ne, sweeps, rel_tol, stride);
         *A_final = A; *V_final = V;
     } else {
         const int h = ne / 2;
         const int64_t items = (int64_t)h * h + (int64_t)n * h;
         const unsigned blocks = (unsigned)((items + 255) / 256 < 4096 ? (items + 255) / 256 : 4096);
         if (V0) { hipError_t e = hipMemcpyAsync(V, V0, sizeof(T) * n * n, hipMemcpyDeviceToDevice, stream); if (e != hipSuccess) return e; }
-        else identity_kernel<T><<<256, 256, 0, stream>>>(V, n);
+        else identity_kernel<T><<<dim3(256, count), 256, 0, stream>>>(V, n, stride);
         T *ain = A, *aout = A2, *vin = V, *vout = V2;
         for (int sweep = 0; sweep < sweeps; ++sweep)
             for (int round = 0; round < ne - 1; ++round) {
-                jacobi_step_kernel<T><<<blocks, 256, 0, stream>>>(ain, aout, vin, vout, n, ne, round);
+                jacobi_step_kernel<T><<<dim3(blocks, count), 256, 0, stream>>>(ain, aout, vin, vout, n, ne, round, stride);
                 T *t = ain; ain = aout; aout = t;
                 t = vin; vin = vout; vout = t;
             }
         *A_final = ain; *V_final = vin;
     }
-    eig_order_kernel<T><<<(n + 255) / 256, 256, 0, stream>>>(*A_final, n, lam, sel);
+    eig_order_kernel<T><<<dim3((n + 255) / 256, count), 256, 0, stream>>>(*A_final, n, lam, sel, stride, stride_sel);
     return hipGetLastError();
 }
 
@@ -332,11 +347,13 @@ hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_
 // eigenvectors as columns in rotation order, lam the eigenvalues in descending order and sel the
 // column of *V_final that belongs to each.  V0 (may be null; not V or V2): the rotations accumulate
 // onto this matrix instead of the identity, so for A = V0^T S V0 the result holds eigenvectors of S.
-hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, const void *V0, void *lam, int *sel, int sweeps,
-                      hipStream_t stream, void **A_final, void **V_final)
+// count > 1: that many independent problems of the same order, every array of problem q lying
+// q * stride_bytes after problem 0's (a multiple of 8); they share each launch, V0 must be null.
+hipError_t sb_eig_sym(sb_dtype dt, int n, int count, int64_t stride_bytes, void *A, void *A2, void *V, void *V2, const void *V0,
+                      void *lam, int *sel, int sweeps, hipStream_t stream, void **A_final, void **V_final)
 {
-    if (dt == SB_F64) return eig_impl<double>(n, (double *)A, (double *)A2, (double *)V, (double *)V2, (const double *)V0, (double *)lam, sel, sweeps, stream, (double **)A_final, (double **)V_final);
-    if (dt == SB_F32) return eig_impl<float>(n, (float *)A, (float *)A2, (float *)V, (float *)V2, (const float *)V0, (float *)lam, sel, sweeps, stream, (float **)A_final, (float **)V_final);
+    if (dt == SB_F64) return eig_impl<double>(n, count, stride_bytes, (double *)A, (double *)A2, (double *)V, (double *)V2, (const double *)V0, (double *)lam, sel, sweeps, stream, (double **)A_final, (double **)V_final);
+    if (dt == SB_F32) return eig_impl<float>(n, count, stride_bytes, (float *)A, (float *)A2, (float *)V, (float *)V2, (const float *)V0, (float *)lam, sel, sweeps, stream, (float **)A_final, (float **)V_final);
     return hipErrorInvalidValue;
 }
 

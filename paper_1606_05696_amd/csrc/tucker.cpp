@@ -11,7 +11,7 @@
 #include "../../include/sbtucker.h"
 #include "sb_internal.h"
 
-hipError_t sb_eig_sym(sb_dtype dt, int n, void *A, void *A2, void *V, void *V2, const void *V0, void *lam, int *sel, int sweeps,
+hipError_t sb_eig_sym(sb_dtype dt, int n, int count, int64_t stride_bytes, void *A, void *A2, void *V, void *V2, const void *V0, void *lam, int *sel, int sweeps,
                       hipStream_t stream, void **A_final, void **V_final);
 hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw,
                          int scaled, hipStream_t stream);
@@ -51,6 +51,8 @@ struct Sizes {
     int64_t m, n, p, i, j, k;
     int64_t eig_loop() const { return std::max({std::min(m, j * k), std::min(n, i * k), std::min(p, i * j)}); }
     int64_t eig_init() const { return std::max({m, n, p}); }
+    // the three eigenproblems of the initialisation have the same order and are solved together
+    bool init_batched() const { return m == n && n == p && m > 1; }
     int64_t rmax() const { return std::max({i, j, k}); }
     int64_t y_elems() const { return std::max({m * j * k, n * i * k, i * j * p}); }
 };
@@ -61,7 +63,8 @@ int64_t tucker_bytes(sb_dtype dt, const Sizes &s, int with_init)
     const int64_t nmax = with_init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
     const int64_t loop = s.eig_loop();
     return up(s.m * s.n * s.k * es) + up(s.i * s.n * s.p * es) + up(s.y_elems() * es) + up(nmax * s.rmax() * es) +
-           EigSpace::bytes(dt, nmax) + 4 * up(loop * loop * es);       // + previous eigenvectors of each mode, one temporary
+           EigSpace::bytes(dt, nmax) * (with_init && s.init_batched() ? 3 : 1) +
+           4 * up(loop * loop * es);       // + previous eigenvectors of each mode, one temporary
 }
 
 struct Ctx {
@@ -120,7 +123,7 @@ struct Ctx {
         }
         // warm: the solver's rotations accumulate onto the previous eigenvectors, so it returns V V' itself
         void *Af = nullptr, *Vf = nullptr;
-        check_hip(sb_eig_sym(dt, (int)e, eig.S, eig.S2, eig.V, eig.V2, warm ? Vprev[mode] : nullptr, eig.lam, (int *)eig.sel,
+        check_hip(sb_eig_sym(dt, (int)e, 1, 0, eig.S, eig.S2, eig.V, eig.V2, warm ? Vprev[mode] : nullptr, eig.lam, (int *)eig.sel,
                              default_sweeps(dt, e), stream, &Af, &Vf));
         if (!ok()) return;
         if (mode >= 0) {
@@ -211,6 +214,8 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
     const int64_t nmax = init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
     c.W = w;       w += up(nmax * s.rmax() * es);
     w = c.eig.carve(dt, w, nmax);
+    const int64_t eig_bytes = EigSpace::bytes(dt, nmax);             // the same layout twice more for a batched initialisation
+    if (init && s.init_batched()) w += 2 * eig_bytes;
     const int64_t loop = s.eig_loop();
     for (int q = 0; q < 3; ++q) {
         c.Vprev[q] = w;  w += up(loop * loop * es);
@@ -225,15 +230,29 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
     if (init) {
         // step 2: leading eigenvectors of T_(r) T_(r)^T.  T_(1) is the m x (np) matrix T itself,
         // T_(3)^T the (mn) x p matrix T itself; T_(2) T_(2)^T is the sum over p of T_p^T T_p.
+        // A cubic tensor gives three problems of one order: they share every launch of the solver
+        // (one workgroup each in LDS, or one grid row each in the multi-launch version).
+        const bool batched = s.init_batched();
+        char *S1 = batched ? c.eig.S + eig_bytes : c.eig.S, *S2 = batched ? c.eig.S + 2 * eig_bytes : c.eig.S;
         c.gemm(SB_OP_N, SB_OP_T, m, m, n * p, T, m, T, m, 0.0, c.eig.S, m);
-        c.eig_leading(-1, m, i, A, m, 0);
+        if (!batched) c.eig_leading(-1, m, i, A, m, 0);
         for (int64_t q = 0; q < p && c.ok(); ++q) {
             const char *Tq = (const char *)T + q * m * n * es;
-            c.gemm(SB_OP_T, SB_OP_N, n, n, m, Tq, m, Tq, m, q ? 1.0 : 0.0, c.eig.S, n);
+            c.gemm(SB_OP_T, SB_OP_N, n, n, m, Tq, m, Tq, m, q ? 1.0 : 0.0, S1, n);
         }
-        c.eig_leading(-1, n, j, B, n, 0);
-        c.gemm(SB_OP_T, SB_OP_N, p, p, m * n, T, m * n, T, m * n, 0.0, c.eig.S, p);
-        c.eig_leading(-1, p, k, C, p, 0);
+        if (!batched) c.eig_leading(-1, n, j, B, n, 0);
+        c.gemm(SB_OP_T, SB_OP_N, p, p, m * n, T, m * n, T, m * n, 0.0, S2, p);
+        if (!batched) c.eig_leading(-1, p, k, C, p, 0);
+        if (batched && c.ok()) {
+            void *Af = nullptr, *Vf = nullptr;
+            c.check_hip(sb_eig_sym(dt, (int)m, 3, eig_bytes, c.eig.S, c.eig.S2, c.eig.V, c.eig.V2, nullptr, c.eig.lam, (int *)c.eig.sel,
+                                   default_sweeps(dt, m), c.stream, &Af, &Vf));
+            void *out[3] = {A, B, C};
+            const int64_t r[3] = {i, j, k};
+            for (int q = 0; q < 3 && c.ok(); ++q)
+                c.check_hip(sb_eig_gather(dt, (int)m, (const char *)Vf + q * eig_bytes, (const int *)(c.eig.sel + q * eig_bytes),
+                                          c.eig.lam + q * eig_bytes, (int)r[q], out[q], m, 0, c.stream));
+        }
     }
 
     for (int it = 0; it < iterations && c.ok(); ++it) {
@@ -275,7 +294,7 @@ extern "C" int sb_sym_eig(sb_dtype dt, int64_t n, void *S, void *V, void *lambda
     EigSpace e;
     e.carve(dt, (char *)workspace, n);
     void *Af = nullptr, *Vf = nullptr;
-    hipError_t err = sb_eig_sym(dt, (int)n, S, e.S2, e.V, e.V2, nullptr, lambda, (int *)e.sel, sweeps > 0 ? sweeps : default_sweeps(dt, n),
+    hipError_t err = sb_eig_sym(dt, (int)n, 1, 0, S, e.S2, e.V, e.V2, nullptr, lambda, (int *)e.sel, sweeps > 0 ? sweeps : default_sweeps(dt, n),
                                 (hipStream_t)stream, &Af, &Vf);
     if (err == hipSuccess) err = sb_eig_gather(dt, (int)n, Vf, (const int *)e.sel, lambda, (int)n, V, n, 0, (hipStream_t)stream);
     return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
