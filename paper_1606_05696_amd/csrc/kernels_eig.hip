@@ -342,6 +342,28 @@ hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_
     return hipGetLastError();
 }
 
+// S[e] = sum over c < count of P[c * elems + e]: the partial Gram matrices of a sum that was split
+// to fill the chip are added up in a fixed order (no atomics, so the result is reproducible).
+template <typename T>
+__global__ __launch_bounds__(256) void sum_slices_kernel(const T *__restrict__ P, T *__restrict__ S, int64_t elems, int count)
+{
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < elems; e += (int64_t)gridDim.x * blockDim.x) {
+        T acc = P[e];
+        for (int c = 1; c < count; ++c) acc += P[(int64_t)c * elems + e];
+        S[e] = acc;
+    }
+}
+
+hipError_t sb_sum_slices(sb_dtype dt, const void *P, void *S, int64_t elems, int count, hipStream_t stream)
+{
+    if (elems <= 0 || count < 1) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((elems + 255) / 256 < 2048 ? (elems + 255) / 256 : 2048);
+    if (dt == SB_F64) sum_slices_kernel<double><<<blocks, 256, 0, stream>>>((const double *)P, (double *)S, elems, count);
+    else if (dt == SB_F32) sum_slices_kernel<float><<<blocks, 256, 0, stream>>>((const float *)P, (float *)S, elems, count);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 // Eigen-decomposition of the symmetric n x n matrix in A (column-major, packed; destroyed).
 // A2, V, V2: n*n elements each; lam: n; sel: n ints.  On return *V_final (V or V2) holds the
 // eigenvectors as columns in rotation order, lam the eigenvalues in descending order and sel the

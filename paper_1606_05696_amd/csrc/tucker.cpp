@@ -16,6 +16,7 @@ hipError_t sb_eig_sym(sb_dtype dt, int n, int count, int64_t stride_bytes, void 
 hipError_t sb_eig_gather(sb_dtype dt, int n, const void *V, const int *sel, const void *lam, int r, void *W, int64_t ldw,
                          int scaled, hipStream_t stream);
 hipError_t sb_column_signs(sb_dtype dt, void *U, int64_t rows, int64_t r, int64_t ld, hipStream_t stream);
+hipError_t sb_sum_slices(sb_dtype dt, const void *P, void *S, int64_t elems, int count, hipStream_t stream);
 
 namespace {
 
@@ -47,6 +48,20 @@ struct EigSpace {
     }
 };
 
+// A Gram matrix of order e is a sum over `slices` slices of the tensor.  Its e x e result has few
+// tiles, far fewer than the chip has compute units unless e is in the thousands, so the sum is split
+// into this many partial sums (a divisor of `slices`, at most 16) that one batched call computes
+// side by side and a small kernel adds up.  1: no split.
+int64_t gram_parts(int64_t e, int64_t slices)
+{
+    const int64_t tiles = ((e + 127) / 128) * ((e + 127) / 128);
+    const int64_t want = std::min<int64_t>(16, 256 / tiles);
+    int64_t parts = 1;
+    for (int64_t d = 2; d <= want && d <= slices; ++d)
+        if (slices % d == 0) parts = d;
+    return parts;
+}
+
 struct Sizes {
     int64_t m, n, p, i, j, k;
     int64_t eig_loop() const { return std::max({std::min(m, j * k), std::min(n, i * k), std::min(p, i * j)}); }
@@ -54,6 +69,11 @@ struct Sizes {
     // the three eigenproblems of the initialisation have the same order and are solved together
     bool init_batched() const { return m == n && n == p && m > 1; }
     int64_t rmax() const { return std::max({i, j, k}); }
+    // elements of the partial Gram matrices of the initialisation (mode 1 and 2 sum over p, mode 3 over n)
+    int64_t gram_elems() const
+    {
+        return std::max({gram_parts(m, p) * m * m, gram_parts(n, p) * n * n, gram_parts(p, n) * p * p});
+    }
     int64_t y_elems() const { return std::max({m * j * k, n * i * k, i * j * p}); }
 };
 
@@ -63,7 +83,7 @@ int64_t tucker_bytes(sb_dtype dt, const Sizes &s, int with_init)
     const int64_t nmax = with_init ? std::max(s.eig_loop(), s.eig_init()) : s.eig_loop();
     const int64_t loop = s.eig_loop();
     return up(s.m * s.n * s.k * es) + up(s.i * s.n * s.p * es) + up(s.y_elems() * es) + up(nmax * s.rmax() * es) +
-           EigSpace::bytes(dt, nmax) * (with_init && s.init_batched() ? 3 : 1) +
+           EigSpace::bytes(dt, nmax) * (with_init && s.init_batched() ? 3 : 1) + (with_init ? up(s.gram_elems() * es) : 0) +
            4 * up(loop * loop * es);       // + previous eigenvectors of each mode, one temporary
 }
 
@@ -74,6 +94,7 @@ struct Ctx {
     char *W;          // nmax x rmax: selected (scaled) eigenvectors
     char *Vprev[3];   // eigenvectors found for each mode in the previous iteration
     char *tmp;
+    char *partial;    // partial Gram matrices of the initialisation
     bool have_prev[3];
     int warm_runs[3];    // warm starts since the last cold solve of each mode
     int status;
@@ -87,6 +108,25 @@ struct Ctx {
     {
         if (!ok()) return;
         check(sb_gemm(dt, ta, tb, m, n, k, alpha, A, lda, 0, B, ldb, 0, beta, C, ldc, 0, 1, stream));
+    }
+
+    // S (e x e) = sum over q < slices of op(X_q) op(X_q)^T with X_q = X + q * step elements, each term
+    // a GEMM (ta, tb) with inner extent kk and leading dimension ld.  `merge`: consecutive slices
+    // continue one another along the inner index, so a run of them is one GEMM with a longer k.
+    void gram(sb_op ta, sb_op tb, int64_t e, int64_t kk, bool merge, const void *X, int64_t ld, int64_t slices, int64_t step, void *S)
+    {
+        if (!ok()) return;
+        const int64_t es = esize(dt), parts = gram_parts(e, slices), per = slices / parts;
+        void *out = parts > 1 ? (void *)partial : S;
+        if (merge) {
+            check(sb_gemm(dt, ta, tb, e, e, kk * per, 1.0, X, ld, per * step, X, ld, per * step, 0.0, out, e, e * e, parts, stream));
+        } else {
+            for (int64_t t = 0; t < per && ok(); ++t) {        // partial sum g takes slices g * per + t
+                const char *Xt = (const char *)X + t * step * es;
+                check(sb_gemm(dt, ta, tb, e, e, kk, 1.0, Xt, ld, per * step, Xt, ld, per * step, t ? 1.0 : 0.0, out, e, e * e, parts, stream));
+            }
+        }
+        if (parts > 1 && ok()) check_hip(sb_sum_slices(dt, partial, S, e * e, (int)parts, stream));
     }
 
     void contract(const char *ma, const char *mb, const char *mc, const void *A, const int64_t *dA, const void *B,
@@ -222,7 +262,8 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
         c.have_prev[q] = false;
         c.warm_runs[q] = 0;
     }
-    c.tmp = w;
+    c.tmp = w;       w += up(loop * loop * es);
+    c.partial = w;
 
     const int64_t dT[3] = {m, n, p}, dAf[2] = {m, i}, dBf[2] = {n, j}, dCf[2] = {p, k};
     const int64_t dW1[3] = {m, n, k}, dZ[3] = {i, n, p}, dY1[3] = {m, j, k}, dY2[3] = {n, i, k}, dY3[3] = {i, j, p}, dG[3] = {i, j, k};
@@ -234,14 +275,13 @@ extern "C" int sb_tucker_hooi(sb_dtype dt, const void *T, int64_t m, int64_t n, 
         // (one workgroup each in LDS, or one grid row each in the multi-launch version).
         const bool batched = s.init_batched();
         char *S1 = batched ? c.eig.S + eig_bytes : c.eig.S, *S2 = batched ? c.eig.S + 2 * eig_bytes : c.eig.S;
-        c.gemm(SB_OP_N, SB_OP_T, m, m, n * p, T, m, T, m, 0.0, c.eig.S, m);
+        // Each Gram matrix is a sum over slices: frontal slices T_q (m x n) for modes 1 and 2,
+        // the row blocks of T_(3)^T that belong to one value of n for mode 3.
+        c.gram(SB_OP_N, SB_OP_T, m, n, true, T, m, p, m * n, c.eig.S);
         if (!batched) c.eig_leading(-1, m, i, A, m, 0);
-        for (int64_t q = 0; q < p && c.ok(); ++q) {
-            const char *Tq = (const char *)T + q * m * n * es;
-            c.gemm(SB_OP_T, SB_OP_N, n, n, m, Tq, m, Tq, m, q ? 1.0 : 0.0, S1, n);
-        }
+        c.gram(SB_OP_T, SB_OP_N, n, m, false, T, m, p, m * n, S1);
         if (!batched) c.eig_leading(-1, n, j, B, n, 0);
-        c.gemm(SB_OP_T, SB_OP_N, p, p, m * n, T, m * n, T, m * n, 0.0, S2, p);
+        c.gram(SB_OP_T, SB_OP_N, p, m, true, T, m * n, n, m, S2);
         if (!batched) c.eig_leading(-1, p, k, C, p, 0);
         if (batched && c.ok()) {
             void *Af = nullptr, *Vf = nullptr;
