@@ -85,6 +85,65 @@ __global__ __launch_bounds__(256) void jacobi_step_kernel(const T *__restrict__ 
     }
 }
 
+// The same step for an even order with the matrix kept in tournament order: the pairs of every
+// round are the neighbours (2P, 2P+1) of the stored matrix, and the step writes each row and column
+// of A (each column of V) where the next round wants it.  Index 0 stays; the others walk round the
+// cycle 1 -> 2 -> 4 -> ... -> n-2 -> n-1 -> n-3 -> ... -> 3 -> 1, so that the neighbours are the
+// indices opposite one another on a circle of n-1 places (the circle method: every pair meets once
+// in n-1 rounds, after which every index is back where it started, so whole sweeps leave the
+// matrix in its original order).  Reads are pairs of neighbours along a column, contiguous across
+// the lanes of a wave; the walk moves a row by two places at most, so the writes of a wave still
+// fill whole cache lines.  Grid: x covers the row pairs, y = column pair, z = 2 * problem + (0: A, 1: V).
+__device__ __forceinline__ int next_place(int e, int n)
+{
+    if (e == 0) return 0;
+    if (e & 1) return e == 1 ? 2 : e - 2;
+    return e + 2 <= n - 2 ? e + 2 : n - 1;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void jacobi_step_even_kernel(const T *__restrict__ Ain, T *__restrict__ Aout,
+                                                               const T *__restrict__ Vin, T *__restrict__ Vout, int n, int64_t stride)
+{
+    typedef T T2 __attribute__((ext_vector_type(2), aligned(sizeof(T))));      // any element-aligned address
+    const int problem = blockIdx.z >> 1;
+    const bool is_v = blockIdx.z & 1;
+    Ain += problem * stride;
+    const int h = n / 2, Q = blockIdx.y, P = blockIdx.x * blockDim.x + threadIdx.x;
+    if (P >= h) return;
+    const int64_t col0 = (int64_t)(2 * Q) * n, col1 = col0 + n;
+    // the rotation of column pair Q (the same for the whole workgroup)
+    T cQ, sQ;
+    {
+        const T2 d1 = *(const T2 *)(Ain + 2 * Q + col1);                   // (a_pq, a_qq)
+        rotation(Ain[2 * Q + col0], d1.y, d1.x, cQ, sQ);
+    }
+    const int64_t out0 = (int64_t)next_place(2 * Q, n) * n, out1 = (int64_t)next_place(2 * Q + 1, n) * n;
+    if (is_v) {
+        // rows 2P, 2P+1 of V times J_Q; rows of V stay where they are
+        Vin += problem * stride; Vout += problem * stride;
+        const T2 vp = *(const T2 *)(Vin + 2 * P + col0), vq = *(const T2 *)(Vin + 2 * P + col1);
+        *(T2 *)(Vout + 2 * P + out0) = vp * cQ - vq * sQ;
+        *(T2 *)(Vout + 2 * P + out1) = vp * sQ + vq * cQ;
+        return;
+    }
+    Aout += problem * stride;
+    T cP, sP;
+    {
+        const int64_t dcol = (int64_t)(2 * P) * n;
+        const T2 d1 = *(const T2 *)(Ain + 2 * P + dcol + n);
+        rotation(Ain[2 * P + dcol], d1.y, d1.x, cP, sP);
+    }
+    const T2 m0 = *(const T2 *)(Ain + 2 * P + col0), m1 = *(const T2 *)(Ain + 2 * P + col1);   // (a, c), (b, d)
+    const T x00 = cP * m0.x - sP * m0.y, x01 = cP * m1.x - sP * m1.y;        // J_P^T M
+    const T x10 = sP * m0.x + cP * m0.y, x11 = sP * m1.x + cP * m1.y;
+    const int r0 = next_place(2 * P, n), r1 = next_place(2 * P + 1, n);
+    Aout[r0 + out0] = x00 * cQ - x01 * sQ;                                   // . J_Q
+    Aout[r0 + out1] = x00 * sQ + x01 * cQ;
+    Aout[r1 + out0] = x10 * cQ - x11 * sQ;
+    Aout[r1 + out1] = x10 * sQ + x11 * cQ;
+}
+
 template <typename T>
 __global__ void identity_kernel(T *V, int n, int64_t stride = 0)
 {
@@ -284,9 +343,15 @@ hipError_t eig_impl(int n, int count, int64_t stride_bytes, T *A, T *A2, T *V, T
         if (V0) { hipError_t e = hipMemcpyAsync(V, V0, sizeof(T) * n * n, hipMemcpyDeviceToDevice, stream); if (e != hipSuccess) return e; }
         else identity_kernel<T><<<dim3(256, count), 256, 0, stream>>>(V, n, stride);
         T *ain = A, *aout = A2, *vin = V, *vout = V2;
+        // an even order takes the step that keeps the matrix in tournament order (n/2 <= 65535 column pairs:
+        // any order that fits an int-indexed matrix)
+        const bool even = n == ne && h <= 65535;
+        const unsigned even_threads = (unsigned)(h < 256 ? (h + 63) / 64 * 64 : 256);
+        const dim3 even_grid((unsigned)((h + even_threads - 1) / even_threads), (unsigned)h, (unsigned)(2 * count));
         for (int sweep = 0; sweep < sweeps; ++sweep)
             for (int round = 0; round < ne - 1; ++round) {
-                jacobi_step_kernel<T><<<dim3(blocks, count), 256, 0, stream>>>(ain, aout, vin, vout, n, ne, round, stride);
+                if (even) jacobi_step_even_kernel<T><<<even_grid, even_threads, 0, stream>>>(ain, aout, vin, vout, n, stride);
+                else jacobi_step_kernel<T><<<dim3(blocks, count), 256, 0, stream>>>(ain, aout, vin, vout, n, ne, round, stride);
                 T *t = ain; ain = aout; aout = t;
                 t = vin; vin = vout; vout = t;
             }

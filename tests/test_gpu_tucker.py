@@ -29,7 +29,7 @@ def workspace(nbytes):
 
 
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
-@pytest.mark.parametrize("n", [1, 2, 7, 64, 100, 101, 150, 257])
+@pytest.mark.parametrize("n", [1, 2, 7, 64, 100, 101, 150, 256, 257])
 def test_symmetric_eigensolver(dtype, n):
     X = inputs.uniform_tensor(400 + n, [2 * n + 3, n])
     X = X * (1.0 / (1.0 + np.arange(n)))             # Gram matrix with a decaying spectrum, as in the iteration
