@@ -81,7 +81,10 @@ def compare(dtype, T, core, iterations, got, ref):
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("dims,core,iterations", [((40, 36, 44), (4, 3, 5), 0), ((40, 36, 44), (4, 3, 5), 3),
                                                   ((9, 8, 7), (3, 4, 2), 2), ((150, 20, 33), (6, 5, 4), 2),
-                                                  ((64, 64, 64), (10, 10, 10), 4), ((48, 40, 36), (5, 4, 6), 40)])
+                                                  ((64, 64, 64), (10, 10, 10), 4), ((48, 40, 36), (5, 4, 6), 40),
+                                                  # prime extents: Gram matrices in one piece; a cube beyond
+                                                  # LDS: three eigenproblems share the multi-launch solver
+                                                  ((24, 17, 19), (3, 3, 3), 2), ((150, 150, 150), (5, 5, 5), 1)])
 def test_hooi_matches_the_oracle(dtype, dims, core, iterations):
     T = inputs.lowrank_noise_tensor(700 + dims[0], list(dims), core, noise=0.05, dtype=NP_DTYPE[dtype]).astype(np.float64)
     ref = tk.hooi(T, core, iterations)
