@@ -38,6 +38,19 @@ __device__ __forceinline__ void rotation(T app, T aqq, T apq, T &c, T &s)
     s = t * c;
 }
 
+// The same rotation from the hardware's reciprocal, square root and reciprocal square root (1 ulp
+// each) for the in-LDS solver, where one wave computes a round's rotations while fifteen wait for it:
+// an inexact angle leaves a remainder far below the threshold, and c^2 + s^2 = c^2 (1 + t^2) is off
+// by 2 ulp at most, the same order as the rounding of the exact formula.
+__device__ __forceinline__ void rotation_quick(float app, float aqq, float apq, float &c, float &s)
+{
+    const float theta = (aqq - app) * __builtin_amdgcn_rcpf(2.0f * apq);
+    const float t = copysignf(__builtin_amdgcn_rcpf(fabsf(theta) + __builtin_amdgcn_sqrtf(theta * theta + 1.0f)), theta);
+    c = __builtin_amdgcn_rsqf(t * t + 1.0f);
+    s = t * c;
+}
+__device__ __forceinline__ void rotation_quick(double app, double aqq, double apq, double &c, double &s) { rotation(app, aqq, apq, c, s); }
+
 // Global-memory step: Ain/Vin -> Aout/Vout (ping-pong, so every thread sees the matrix as it was
 // before the step).  n is the matrix order, ne = n rounded up to even (the phantom index of an
 // odd matrix pairs with nothing).  Work items: (ne/2)^2 blocks of A, then n * ne/2 row pairs of V.
@@ -235,8 +248,9 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 pair_of(tid, round, ne, p, q);
                 T c = T(1), s = T(0);
                 const T apq = As[p + q * ne];                                       // phantom index: apq = 0 -> identity
+                const T app = As[p + p * ne], aqq = As[q + q * ne];                 // read with apq: one LDS latency, not two
                 if (fabs(apq) > tiny) {
-                    rotation(As[p + p * ne], As[q + q * ne], apq, c, s);
+                    rotation_quick(app, aqq, apq, c, s);
                     rotates[flag] = 1;
                 }
                 PairRec<T> r;
