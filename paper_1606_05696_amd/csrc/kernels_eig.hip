@@ -184,7 +184,7 @@ template <typename T>
 size_t jacobi_lds_bytes(int n)
 {
     const size_t ne = n + (n & 1);
-    return 2 * ne * ne * sizeof(T) + 16 + (ne / 2) * sizeof(PairRec<T>);
+    return 2 * ne * ne * sizeof(T) + 16 + (ne / 2) * (sizeof(PairRec<T>) + sizeof(int));
 }
 
 template <typename T>
@@ -199,7 +199,8 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
     T *As = (T *)raw;                    // ne x ne, leading dimension ne
     T *Vs = As + ne * ne;                // ne x ne as well (a zero phantom row keeps row pairs aligned)
     PairRec<T> *rec = (PairRec<T> *)(((uintptr_t)(Vs + ne * ne) + 15) & ~(uintptr_t)15);      // [h]
-    __shared__ int rotates[3];           // does any pair of the round rotate?  three flags take turns
+    int *list = (int *)(rec + h);        // [h] the pairs that rotate in this round, in any order
+    __shared__ int rotates[3];           // how many pairs of the round rotate?  three counters take turns
     __shared__ T wave_max[LDS_THREADS / 64];
     for (int e = tid; e < ne * ne; e += LDS_THREADS) {
         const int i = e % ne, j = e / ne;
@@ -251,33 +252,62 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 const T app = As[p + p * ne], aqq = As[q + q * ne];                 // read with apq: one LDS latency, not two
                 if (fabs(apq) > tiny) {
                     rotation_quick(app, aqq, apq, c, s);
-                    rotates[flag] = 1;
+                    if (s != T(0)) list[atomicAdd(&rotates[flag], 1)] = tid;        // on the list <=> s != 0
+                    else c = T(1);
                 }
                 PairRec<T> r;
                 r.p = p; r.q = q; r.c = c; r.s = s;
                 rec[tid] = r;
             }
             __syncthreads();
-            if (!rotates[flag]) continue;        // workgroup-uniform: nothing moves in this round
-            int P = P0, Q = Q0;
-            for (int item = tid; item < nA; item += LDS_THREADS) {
+            const int k = rotates[flag];
+            if (k == 0) continue;                // workgroup-uniform: nothing moves in this round
+            // block (P, Q) of A: J_P^T . J_Q
+            auto update_a = [&](int P, int Q) __attribute__((always_inline)) {
                 const PairRec<T> rP = rec[P], rQ = rec[Q];
                 const int p1 = rP.p, q1 = rP.q, p2 = rQ.p * ne, q2 = rQ.q * ne;
                 const T cP = rP.c, sP = rP.s, cQ = rQ.c, sQ = rQ.s;
                 const T a = As[p1 + p2], b = As[p1 + q2], c = As[q1 + p2], d = As[q1 + q2];
-                const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;        // J_P^T M
+                const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;
                 const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
-                As[p1 + p2] = x00 * cQ - x01 * sQ;                           // . J_Q
+                As[p1 + p2] = x00 * cQ - x01 * sQ;
                 As[p1 + q2] = x00 * sQ + x01 * cQ;
                 As[q1 + p2] = x10 * cQ - x11 * sQ;
                 As[q1 + q2] = x10 * sQ + x11 * cQ;
-                // rows 2P and 2P+1 of V times J_Q: the same (P, Q) grid serves V, two rows at a time
-                T2 *vp = (T2 *)(Vs + 2 * P + rQ.p * ne), *vq = (T2 *)(Vs + 2 * P + rQ.q * ne);
+            };
+            // rows 2R and 2R+1 of V times J_Q
+            auto update_v = [&](int R, int Q) __attribute__((always_inline)) {
+                const PairRec<T> rQ = rec[Q];
+                T2 *vp = (T2 *)(Vs + 2 * R + rQ.p * ne), *vq = (T2 *)(Vs + 2 * R + rQ.q * ne);
                 const T2 up = *vp, uq = *vq;
-                *vp = up * cQ - uq * sQ;
-                *vq = up * sQ + uq * cQ;
-                P += dP; Q += dQ;
-                if (P >= h) { P -= h; ++Q; }
+                *vp = up * rQ.c - uq * rQ.s;
+                *vq = up * rQ.s + uq * rQ.c;
+            };
+            if (8 * k > h) {
+                // most blocks change: the whole (P, Q) grid, which serves V as well (row pair P, column pair Q)
+                int P = P0, Q = Q0;
+                for (int item = tid; item < nA; item += LDS_THREADS) {
+                    update_a(P, Q);
+                    update_v(P, Q);
+                    P += dP; Q += dQ;
+                    if (P >= h) { P -= h; ++Q; }
+                }
+            } else {
+                // Few pairs rotate (the later sweeps of a warm start): only the block rows and block
+                // columns of A and the column pairs of V that belong to a listed pair change.  Three
+                // families of k * h items on a grid of h x 3k: blocks (listed, any), blocks (any that
+                // does not rotate, listed) -- a rotating row pair is in the first family already --
+                // and V's (row pair, listed).
+                int J = P0, I = Q0;
+                for (int item = tid; item < 3 * k * h; item += LDS_THREADS) {
+                    const int fam = (I >= k) + (I >= 2 * k);
+                    const int L = list[I - fam * k];
+                    if (fam == 0) update_a(L, J);
+                    else if (fam == 1) { if (rec[J].s == T(0)) update_a(J, L); }
+                    else update_v(J, L);
+                    J += dP; I += dQ;
+                    if (J >= h) { J -= h; ++I; }
+                }
             }
             __syncthreads();
         }
