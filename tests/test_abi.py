@@ -146,6 +146,8 @@ def test_kernel_selector():
         assert fam(dt, "N", "N", 64, 64, 64) == MFMA               # the 36 cases at 64
         assert fam(dt, "N", "N", 16, 16, 16, 65536) == TINY        # the tiny-batch regime
         assert fam(dt, "N", "N", 32, 32, 32) == TINY
+        assert fam(dt, "N", "N", 10, 10, 512, 512) == MFMA         # few small problems with a long k: the tiled kernels prefetch
+        assert fam(dt, "N", "N", 10, 10, 512, 4096) == TINY        # many of them: one wavefront each
         assert fam(dt, "N", "N", 4096, 1, 4096) == THIN            # matrix-vector
         assert fam(dt, "N", "N", 1, 4096, 4096) == THIN            # vector-matrix
         assert fam(dt, "T", "N", 2048, 4, 100) == THIN
