@@ -263,9 +263,9 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
             const int k = rotates[flag];
             if (k == 0) continue;                // workgroup-uniform: nothing moves in this round
             // block (P, Q) of A: J_P^T . J_Q
-            auto update_a = [&](int P, int Q) __attribute__((always_inline)) {
-                const PairRec<T> rP = rec[P], rQ = rec[Q];
-                const int p1 = rP.p, q1 = rP.q, p2 = rQ.p * ne, q2 = rQ.q * ne;
+            // (the kernel is bound by vector-instruction issue: 24-bit multiplies run at full rate, 32-bit ones at a quarter)
+            auto update_a = [&](const PairRec<T> &rP, const PairRec<T> &rQ) __attribute__((always_inline)) {
+                const int p1 = rP.p, q1 = rP.q, p2 = __mul24(rQ.p, ne), q2 = __mul24(rQ.q, ne);
                 const T cP = rP.c, sP = rP.s, cQ = rQ.c, sQ = rQ.s;
                 const T a = As[p1 + p2], b = As[p1 + q2], c = As[q1 + p2], d = As[q1 + q2];
                 const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;
@@ -276,9 +276,8 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 As[q1 + q2] = x10 * sQ + x11 * cQ;
             };
             // rows 2R and 2R+1 of V times J_Q
-            auto update_v = [&](int R, int Q) __attribute__((always_inline)) {
-                const PairRec<T> rQ = rec[Q];
-                T2 *vp = (T2 *)(Vs + 2 * R + rQ.p * ne), *vq = (T2 *)(Vs + 2 * R + rQ.q * ne);
+            auto update_v = [&](int R, const PairRec<T> &rQ) __attribute__((always_inline)) {
+                T2 *vp = (T2 *)(Vs + 2 * R + __mul24(rQ.p, ne)), *vq = (T2 *)(Vs + 2 * R + __mul24(rQ.q, ne));
                 const T2 up = *vp, uq = *vq;
                 *vp = up * rQ.c - uq * rQ.s;
                 *vq = up * rQ.s + uq * rQ.c;
@@ -287,8 +286,9 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 // most blocks change: the whole (P, Q) grid, which serves V as well (row pair P, column pair Q)
                 int P = P0, Q = Q0;
                 for (int item = tid; item < nA; item += LDS_THREADS) {
-                    update_a(P, Q);
-                    update_v(P, Q);
+                    const PairRec<T> rP = rec[P], rQ = rec[Q];
+                    update_a(rP, rQ);
+                    update_v(P, rQ);
                     P += dP; Q += dQ;
                     if (P >= h) { P -= h; ++Q; }
                 }
@@ -302,9 +302,10 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 for (int item = tid; item < 3 * k * h; item += LDS_THREADS) {
                     const int fam = (I >= k) + (I >= 2 * k);
                     const int L = list[I - fam * k];
-                    if (fam == 0) update_a(L, J);
-                    else if (fam == 1) { if (rec[J].s == T(0)) update_a(J, L); }
-                    else update_v(J, L);
+                    const PairRec<T> rL = rec[L], rJ = rec[J];
+                    if (fam == 0) update_a(rL, rJ);
+                    else if (fam == 1) { if (rJ.s == T(0)) update_a(rJ, rL); }
+                    else update_v(J, rL);
                     J += dP; I += dQ;
                     if (J >= h) { J -= h; ++I; }
                 }
