@@ -198,7 +198,9 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
     const int h = ne / 2, tid = threadIdx.x;
     T *As = (T *)raw;                    // ne x ne, leading dimension ne
     T *Vs = As + ne * ne;                // ne x ne as well (a zero phantom row keeps row pairs aligned)
-    PairRec<T> *rec = (PairRec<T> *)(((uintptr_t)(Vs + ne * ne) + 15) & ~(uintptr_t)15);      // [h]
+    // [h], 16-byte aligned; an offset from the array keeps the pointer in the LDS address space
+    // (through an integer it would become a generic pointer, read with the slower flat loads)
+    PairRec<T> *rec = (PairRec<T> *)(raw + ((2 * (size_t)ne * ne * sizeof(T) + 15) & ~(size_t)15));
     int *list = (int *)(rec + h);        // [h] the pairs that rotate in this round, in any order
     __shared__ int rotates[3];           // how many pairs of the round rotate?  three counters take turns
     __shared__ T wave_max[LDS_THREADS / 64];
@@ -286,9 +288,22 @@ __global__ __launch_bounds__(LDS_THREADS) void jacobi_lds_kernel(T *A, T *V, con
                 // most blocks change: the whole (P, Q) grid, which serves V as well (row pair P, column pair Q)
                 int P = P0, Q = Q0;
                 for (int item = tid; item < nA; item += LDS_THREADS) {
+                    // every read of the item before its first write: a write might alias any later read
+                    // for all the compiler knows, and each read waited for is an LDS latency
                     const PairRec<T> rP = rec[P], rQ = rec[Q];
-                    update_a(rP, rQ);
-                    update_v(P, rQ);
+                    const int p1 = rP.p, q1 = rP.q, p2 = __mul24(rQ.p, ne), q2 = __mul24(rQ.q, ne);
+                    const T cP = rP.c, sP = rP.s, cQ = rQ.c, sQ = rQ.s;
+                    T2 *vp = (T2 *)(Vs + 2 * P + p2), *vq = (T2 *)(Vs + 2 * P + q2);
+                    const T a = As[p1 + p2], b = As[p1 + q2], c = As[q1 + p2], d = As[q1 + q2];
+                    const T2 up = *vp, uq = *vq;
+                    const T x00 = cP * a - sP * c, x01 = cP * b - sP * d;
+                    const T x10 = sP * a + cP * c, x11 = sP * b + cP * d;
+                    As[p1 + p2] = x00 * cQ - x01 * sQ;
+                    As[p1 + q2] = x00 * sQ + x01 * cQ;
+                    As[q1 + p2] = x10 * cQ - x11 * sQ;
+                    As[q1 + q2] = x10 * sQ + x11 * cQ;
+                    *vp = up * cQ - uq * sQ;
+                    *vq = up * sQ + uq * cQ;
                     P += dP; Q += dQ;
                     if (P >= h) { P -= h; ++Q; }
                 }
