@@ -81,7 +81,9 @@ __device__ __forceinline__ void load_frag(T (&f)[4], const T *p, int64_t ld, int
 }
 
 // TM x TN MFMA blocks of 16 x 16 per C_p; U batches in flight per wave.
-template <typename T, int TM, int TN, bool A_KC, bool B_KC, bool HOIST_A, int U>
+// PIPE (k > 16): the operands of the next 16 k are requested before the current ones are multiplied,
+// two steps in flight instead of one; without it a wavefront's time is one memory latency per step.
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, bool HOIST_A, int U, bool PIPE>
 __global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int vec_a, int vec_b, int vec_c)
 {
     typedef TinyMfma<T> MF;
@@ -125,33 +127,72 @@ __global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int
 #pragma unroll
                     for (int r = 0; r < 4; ++r) acc[u][a][c][r] = T(0);
         }
-        for (int64_t k0 = 0; k0 < g.k; k0 += 16) {
-            T fa[U][TM][4], fb[U][TN][4];
+        if constexpr (PIPE) {
+            T fa[2][U][TM][4], fb[2][U][TN][4];
+            // a step beyond k loads nothing and yields zeros
+            auto load_step = [&](int s, int64_t k0) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!live[u]) continue;                 // wave-uniform
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;                 // wave-uniform
 #pragma unroll
-                for (int c = 0; c < TN; ++c)
-                    load_frag<T, B_KC>(fb[u][c], Bp[u], ldB, c * 16 + c16, n, k0 + 4 * h, g.k, vec_b);
-                if (!HOIST_A) {
+                    for (int c = 0; c < TN; ++c)
+                        load_frag<T, B_KC>(fb[s][u][c], Bp[u], ldB, c * 16 + c16, n, k0 + 4 * h, g.k, vec_b);
 #pragma unroll
                     for (int a = 0; a < TM; ++a)
-                        load_frag<T, A_KC>(fa[u][a], Ap[u], ldA, a * 16 + c16, m, k0 + 4 * h, g.k, vec_a);
+                        load_frag<T, A_KC>(fa[s][u][a], Ap[u], ldA, a * 16 + c16, m, k0 + 4 * h, g.k, vec_a);
                 }
+            };
+            auto mma_step = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int a = 0; a < TM; ++a)
+#pragma unroll
+                            for (int c = 0; c < TN; ++c) {
+                                if (MF::SWAP) MF::mma(acc[u][a][c], fb[s][u][c][e], fa[s][u][a][e]);
+                                else          MF::mma(acc[u][a][c], fa[s][u][a][e], fb[s][u][c][e]);
+                            }
+                }
+            };
+            load_step(0, 0);
+            for (int64_t k0 = 0; k0 < g.k; k0 += 32) {
+                load_step(1, k0 + 16);
+                mma_step(0);
+                load_step(0, k0 + 32);
+                mma_step(1);
             }
+        } else {
+            for (int64_t k0 = 0; k0 < g.k; k0 += 16) {
+                T fa[U][TM][4], fb[U][TN][4];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (!live[u]) continue;
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;                 // wave-uniform
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                    for (int c = 0; c < TN; ++c)
+                        load_frag<T, B_KC>(fb[u][c], Bp[u], ldB, c * 16 + c16, n, k0 + 4 * h, g.k, vec_b);
+                    if (!HOIST_A) {
 #pragma unroll
-                    for (int a = 0; a < TM; ++a)
+                        for (int a = 0; a < TM; ++a)
+                            load_frag<T, A_KC>(fa[u][a], Ap[u], ldA, a * 16 + c16, m, k0 + 4 * h, g.k, vec_a);
+                    }
+                }
 #pragma unroll
-                        for (int c = 0; c < TN; ++c) {
-                            const T av = HOIST_A ? fa_shared[a][e] : fa[u][a][e];
-                            if (MF::SWAP) MF::mma(acc[u][a][c], fb[u][c][e], av);
-                            else          MF::mma(acc[u][a][c], av, fb[u][c][e]);
-                        }
+                for (int u = 0; u < U; ++u) {
+                    if (!live[u]) continue;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int a = 0; a < TM; ++a)
+#pragma unroll
+                            for (int c = 0; c < TN; ++c) {
+                                const T av = HOIST_A ? fa_shared[a][e] : fa[u][a][e];
+                                if (MF::SWAP) MF::mma(acc[u][a][c], fb[u][c][e], av);
+                                else          MF::mma(acc[u][a][c], av, fb[u][c][e]);
+                            }
+                }
             }
         }
 #pragma unroll
@@ -218,8 +259,9 @@ hipError_t launch3(const SbArgs &a, hipStream_t stream)
     if (groups > cap) groups = cap;
     if (groups < 1) return hipSuccess;
     dim3 grid((unsigned)groups), block(TINY_THREADS);
-    if (hoist) hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, true, U>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
-    else       hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    if (hoist)         hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, true, U, false>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    else if (a.k > 16) hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U, true>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    else               hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U, false>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
     return hipGetLastError();
 }
 
@@ -255,10 +297,11 @@ bool sb_tiny_supports(sb_dtype dt, const SbArgs &a)
 }
 
 // One wavefront walks the whole k of its problem, a chain of memory latencies that grows with k
-// (about 0.07 us per k at any batch size).  With few problems and a long k the tiled kernels, which
-// prefetch along k, are faster although they pad the small matrices to their tiles.  Measured at
-// m = n = 10, k = 512, fp32: 512 problems 39 us here against 29 us tiled, 64 problems 38 against 19;
-// at 4096 problems this kernel wins, 45 against 184 us.  At m = n = 32 the two meet near k = 512.
+// (about 0.07 us per k at any batch size, two steps of 16 in flight).  With few problems and a long k
+// the tiled kernels, whose prefetch runs further ahead, are faster although they pad the small
+// matrices to their tiles.  Measured at m = n = 10, k = 512, fp32: 512 problems 36 us here against
+// 28 us tiled, 64 problems 38 against 19 (before the second step in flight); at 4096 problems this
+// kernel wins, 40 against 184 us.  At m = n = 32 the two meet near k = 2048.
 bool sb_tiny_preferred(sb_dtype dt, const SbArgs &a)
 {
     const bool few = a.batch0 * a.batch1 <= 512;
