@@ -390,7 +390,7 @@ def run_batched_gemv(steps, warmup, n=512):
 
 
 def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128, with_oracle=True):
-    """The application study of section V-C: HOOI (Algorithm 1) on cubic n^3 tensors with a 10^3 core,
+    """The application study of section IV-C: HOOI (Algorithm 1) on cubic n^3 tensors with a 10^3 core,
     fp32, every contraction through sb_contract.  Reports time per iteration (steps 4-9: five
     contractions and three Gram / eigensolver / back-multiplication rounds), the one-off
     initialisation (step 2) and, at one size, the numpy oracle's time per iteration on the host."""

@@ -80,8 +80,10 @@ enum {
  * ("stride between matrices of the batch").
  *   - strideA or strideB may be 0 (the operand is shared by all batches, Listing 2).
  *   - strideC may be smaller than ldc*n (batches interleaved inside one tensor, as in the
- *     C_m[n]p evaluations of Table II), but two batches must not share an element:
- *     strideC == 0 with batch > 1 is rejected (-17).
+ *     C_m[n]p evaluations of Table II), but two batches must not share an element: strideC == 0
+ *     with batch > 1 is rejected (-17), and so is any C whose rows, columns and batches, sorted by
+ *     stride, do not each step over everything the smaller strides span (the argument named is
+ *     the stride that is too small: -16 for ldc, -17 for strideC).
  *   - ld >= max(1, stored rows) is required for SB_OP_N / SB_OP_T operands and for C.
  *   - For SB_OP_EX_* see sb_op.
  * Argument numbers for the error code: dt=1 transA=2 transB=3 m=4 n=5 k=6 alpha=7 A=8 lda=9
@@ -98,7 +100,7 @@ int sb_gemm(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64
  *     X_{p,q} = X + p*strideX0 + q*strideX1,   p < batch0,  q < batch1.
  * Equivalent to `for q: sb_gemm(..., A + q*strideA1, ..., batch0)`.  For an SB_OP_EX_* operand
  * strideX0 is the stored-column stride (see sb_op) and its level-0 batch stride is 1.
- * Distinct (p,q) must address disjoint C_pq.
+ * Distinct (p,q) must address disjoint C_pq (checked as for sb_gemm: -18 ldc, -19 strideC0, -20 strideC1).
  * Argument numbers: dt=1 transA=2 transB=3 m=4 n=5 k=6 alpha=7 A=8 lda=9 strideA0=10 strideA1=11
  * B=12 ldb=13 strideB0=14 strideB1=15 beta=16 C=17 ldc=18 strideC0=19 strideC1=20 batch0=21
  * batch1=22 stream=23.
@@ -167,6 +169,12 @@ int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char 
                 double beta, void *C, const int64_t *dimsC, const int64_t *stridesC,
                 sb_strategy strat, void *stream);
 
+/* sb_contract keeps the plans of the calling thread's eight most recent distinct contractions
+ * (mode strings, extents, strides and strategy all equal: pointers and scalars may differ) and
+ * skips the planner when one of them comes again.  sb_plan_cache_enable(0) switches that off for
+ * the calling thread (benchmarks that want the planner inside the timed call), (1) on again. */
+int sb_plan_cache_enable(int on);
+
 /* Launch a plan produced by sb_contract_plan on the tensors it was planned for (device pointers
  * A, B, C of the ORIGINAL contraction; the plan knows which one feeds which GEMM slot).
  * Argument numbers: dt=1 plan=2 alpha=3 A=4 B=5 beta=6 C=7 stream=8. */
@@ -182,9 +190,15 @@ int64_t sb_plan_launches(const sb_plan *plan);
 const char *sb_status_string(int status);
 
 /* Kernel families behind sb_gemm (diagnostics: tests and the benchmark use these to make sure the
- * intended path ran).  sb_force_kernel(id) makes later calls use that family when it supports the
- * problem (SB_KERNEL_AUTO restores the selector); sb_last_kernel() is the family of the most
- * recent launch of this thread's process (-1 before any).  Neither is thread-safe. */
+ * intended path ran).  sb_force_kernel(id) makes later calls OF THE CALLING THREAD use that family
+ * whenever it takes the problem (SB_KERNEL_AUTO restores the selector); sb_last_kernel() is the
+ * family of the calling thread's most recent launch (-1 before any).  Both are per host thread.
+ * What each family takes when forced (anything else falls to SB_KERNEL_GENERIC):
+ *   SB_KERNEL_GENERIC  every problem the entry points accept;
+ *   SB_KERNEL_THIN     1 <= min(m, n) <= 4, any operation and element type;
+ *   SB_KERNEL_TINY     SB_F64 / SB_F32, m <= 32 and n <= 32, k >= 1, operations N / T;
+ *   SB_KERNEL_MFMA     k >= 1, operations N / T in every element type; an extended operation on the
+ *                      first operand in SB_F64 / SB_F32 when m >= 8, n >= 16 and batch0 >= 8. */
 enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2, SB_KERNEL_THIN = 3 };
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
@@ -192,7 +206,8 @@ int sb_last_kernel(void);
 /* Host only: the kernel family the selector sends an sb_gemm problem to (sizes, operations and
  * strides as for sb_gemm, all of m, n, k, batch at least 1; no pointers: the family depends on the
  * shape only; no alignment beyond that of the elements is ever required of the operands).  Negative: -i = i-th argument
- * invalid.  Ignores sb_force_kernel. */
+ * invalid (C is checked as in sb_gemm: -11 ldc, -12 strideC).  Ignores sb_force_kernel.
+ * Argument numbers: dt=1 transA=2 transB=3 m=4 n=5 k=6 lda=7 strideA=8 ldb=9 strideB=10 ldc=11 strideC=12 batch=13. */
 int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
                      int64_t lda, int64_t strideA, int64_t ldb, int64_t strideB, int64_t ldc,
                      int64_t strideC, int64_t batch);

@@ -1,7 +1,7 @@
 /*
  * sbtucker.h - C ABI of the Tucker decomposition by higher-order orthogonal iteration (HOOI),
  * the application study of "Tensor Contractions with Extended BLAS Kernels on CPU and GPU"
- * (section II-C, Algorithm 1; measured in section V-C), built on the contraction entry points of
+ * (section II-C, Algorithm 1; measured in section IV-C), built on the contraction entry points of
  * sbgemm.h.  Conventions (column-major device tensors, sizes in elements, stream as void*,
  * status codes, nothing allocated or synchronised by the library) are those of sbgemm.h.
  *

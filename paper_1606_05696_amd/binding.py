@@ -30,7 +30,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 __all__ = [n for n in dir() if n.startswith("SB_")] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
-    "sb_select_kernel",    "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
+    "sb_select_kernel", "sb_plan_cache_enable", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
 
 
 class sb_plan(ctypes.Structure):
@@ -88,6 +88,8 @@ def load():
     lib.sb_status_string.argtypes = [ci]
     lib.sb_force_kernel.restype = ci
     lib.sb_force_kernel.argtypes = [ci]
+    lib.sb_plan_cache_enable.restype = ci
+    lib.sb_plan_cache_enable.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
     lib.sb_last_kernel.argtypes = []
     lib.sb_select_kernel.restype = ci
@@ -262,6 +264,10 @@ def sb_last_kernel():
     return load().sb_last_kernel()
 
 
+def sb_plan_cache_enable(on):
+    return load().sb_plan_cache_enable(int(bool(on)))
+
+
 def sb_select_kernel(dt, transA, transB, m, n, k, lda, strideA, ldb, strideB, ldc, strideC, batch):
     return load().sb_select_kernel(_dtype_of(dt), _op(transA), _op(transB), m, n, k, lda, strideA, ldb, strideB,
                                    ldc, strideC, batch)
@@ -320,3 +326,4 @@ def sb_sym_eig(n, S, V, lam, workspace, sweeps=0, dt=None, stream=None, check=Tr
     if check and rc != SB_OK:
         raise SbError("sb_sym_eig", rc)
     return rc
+

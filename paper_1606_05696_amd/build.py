@@ -30,11 +30,26 @@ def _compile(src: str, verbose: bool) -> str:
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every source and link libsbgemm.so; returns its path.  Always recompiles."""
+def _stale(src: str) -> bool:
+    """True if the object of `src` is missing or older than the source or any header."""
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    if not os.path.exists(obj):
+        return True
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, h) for h in os.listdir(CSRC) if h.endswith(".h")]
+    inc = os.path.join(os.path.dirname(PKG), "include")
+    deps += [os.path.join(inc, h) for h in os.listdir(inc)]
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def build(verbose: bool = False, only_changed: bool = False) -> str:
+    """Compile every source and link libsbgemm.so; returns its path.  Recompiles everything unless
+    only_changed is set (a developer's shortcut: sources newer than their objects, or all of them
+    after a header changed)."""
     os.makedirs(OBJ, exist_ok=True)
+    todo = [s for s in SOURCES if not only_changed or _stale(s)]
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
-        objs = list(pool.map(lambda s: _compile(s, verbose), SOURCES))
+        list(pool.map(lambda s: _compile(s, verbose), todo))
+    objs = [os.path.join(OBJ, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs
     if verbose:
@@ -45,4 +60,4 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, only_changed="--changed" in sys.argv))

@@ -12,6 +12,8 @@
 // number of sweeps is fixed by the caller.
 #include "sb_internal.h"
 
+#include <atomic>
+
 namespace {
 
 // round-robin tournament on ne (even) players: pair t of round r
@@ -384,7 +386,7 @@ hipError_t eig_impl(int n, int count, int64_t stride_bytes, T *A, T *A2, T *V, T
         *A_final = A; *V_final = V;
     } else if (jacobi_lds_bytes<T>(n) <= (size_t)160 * 1024 - 512) {      // 512 bytes stay for the static variables
         const size_t bytes = jacobi_lds_bytes<T>(n);
-        static bool configured[SB_MAX_DEVICES] = {};
+        static std::atomic<bool> configured[SB_MAX_DEVICES] = {};
         const int dev = sb_current_device();
         if (!configured[dev]) {
             hipError_t e = hipFuncSetAttribute((const void *)jacobi_lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);

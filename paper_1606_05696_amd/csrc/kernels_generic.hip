@@ -102,8 +102,8 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int64_t tiles_m = (a.m + GM - 1) / GM, tiles_n = (a.n + GN - 1) / GN;
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
-    // the x dimension of a grid holds at most 2^31-1 workgroups: spill into y
-    const int64_t maxx = 1 << 30;
+    // the x dimension of a grid holds fewer than 2^32 lanes: spill into y
+    const int64_t maxx = sb_max_grid_x(256);
     const int64_t gx = total < maxx ? total : maxx;
     const int64_t gy = (total + gx - 1) / gx;
     if (gy > 65535) return hipErrorInvalidConfiguration;

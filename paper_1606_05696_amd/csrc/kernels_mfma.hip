@@ -20,6 +20,8 @@
 // read feeds several consecutive MFMAs; the sum over k does not depend on that order.
 #include "sb_device.h"
 #include "sb_internal.h"
+
+#include <atomic>
 #include <type_traits>
 
 namespace {
@@ -568,7 +570,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_ker
 template <typename K, typename... Extra>
 hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, Extra... extra)
 {
-    static int resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
+    static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
     const int dev = sb_current_device();
     if (resident_of[dev] == 0) {
         int per_cu = 0, cus = 0;
@@ -652,7 +654,10 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a)
     if (!a_ok || !b_ok) return false;
     // a k-contiguous operand with a single row or a single k is also "row contiguous": either view works
     const int64_t tiles = ((a.m + 63) / 64) * ((a.n + 63) / 64);       // smallest tile used below
-    return tiles * a.batch0 * a.batch1 < ((int64_t)1 << 31);
+    // fp32 / fp64 run persistent workgroups (32-bit tile counters); the plain bf16 kernel takes one
+    // workgroup per tile in a one-dimensional grid
+    const int64_t most = dt == SB_BF16 ? sb_max_grid_x(256) : ((int64_t)1 << 31) - 1;
+    return tiles * a.batch0 * a.batch1 <= most;
 }
 
 bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a)

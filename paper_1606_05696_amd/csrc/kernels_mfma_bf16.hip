@@ -11,6 +11,8 @@
 #include "sb_device.h"
 #include "sb_internal.h"
 
+#include <atomic>
+
 #include <type_traits>
 
 namespace {
@@ -394,7 +396,7 @@ hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    static int resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
+    static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
     const int dev = sb_current_device();
     if (resident_of[dev] == 0) {
         int per_cu = 0, cus = 0;
@@ -404,7 +406,8 @@ hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream
         if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
         resident_of[dev] = per_cu * cus;
     }
-    int64_t grid = total < resident_of[dev] ? total : resident_of[dev];
+    const int64_t resident = resident_of[dev];
+    int64_t grid = total < resident ? total : resident;
     grid = (grid + NXCD - 1) / NXCD * NXCD;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, (int)tiles_m, (int)tiles_n);
     return hipGetLastError();
@@ -417,7 +420,7 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int64_t tiles_m = (a.m + BM - 1) / BM, tiles_n = (a.n + BN - 1) / BN;
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
-    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    if (total > sb_max_grid_x(NTHREADS)) return hipErrorInvalidConfiguration;     // sb_mfma_supports keeps such problems away
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
     // per operand (bit 0: A, bit 1: B): 16-byte vector loads; the hardware reads them at any
     // element-aligned address, so no leading dimension or offset has to be a multiple of 8

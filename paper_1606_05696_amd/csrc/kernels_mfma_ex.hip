@@ -328,7 +328,7 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     const int64_t tiles_b = (a.batch0 + PB - 1) / PB, tiles_i = (a.m + MB - 1) / MB, tiles_n = (a.n + BN - 1) / BN;
     const int64_t total = tiles_b * tiles_i * tiles_n * a.batch1;
     if (total <= 0) return hipSuccess;
-    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    if (total > sb_max_grid_x(ET)) return hipErrorInvalidConfiguration;           // sb_mfma_exa_supports keeps such problems away
     // 16-byte vector loads need no alignment beyond the element's: the hardware reads them anywhere
     const int vec_a = 1, vec_b = 1;
     dim3 grid((unsigned)total), block(ET);
@@ -348,6 +348,9 @@ bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
     if (a.bsA[0] != 1 || a.rsA == 1 || a.csA == 1) return false;
     if (a.bsB[0] != 0) return false;
     if (a.rsB != 1 && a.csB != 1) return false;
+    // one workgroup per tile of at least 16 batches x 16 rows x 32 columns, in a one-dimensional grid
+    const int64_t tiles = ((a.batch0 + 15) / 16) * ((a.m + 15) / 16) * ((a.n + 31) / 32) * a.batch1;
+    if (tiles > sb_max_grid_x(ET)) return false;
     return a.m >= 8 && a.n >= 16;
 }
 

@@ -4,6 +4,8 @@
 #include "sb_device.h"
 #include "sb_internal.h"
 
+#include <atomic>
+
 
 namespace {
 
@@ -259,7 +261,7 @@ static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
 #define SB_OUTER(KS_)                                                                                                  \
     do {                                                                                                                \
         auto kern = sbgemm_outer2_bf16_kernel<A_KC, B_KC, KS_>;                                                         \
-        static bool configured[SB_MAX_DEVICES] = {};                                                                    \
+        static std::atomic<bool> configured[SB_MAX_DEVICES] = {};                                                                    \
         const int dev = sb_current_device();                                                                            \
         if (!configured[dev]) {                                                                                         \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \

@@ -40,6 +40,7 @@ struct Thin {
     int64_t rsM, csM, sxl, sxv, syr, syv;
     int64_t bsM[2], bsX[2], bsY[2];
     int64_t batch0, batch1;
+    int64_t xspan;            // elements from X to one past the last element of X any batch entry reads
     double alpha, beta;
 };
 
@@ -113,13 +114,16 @@ __device__ __forceinline__ bool thin_locate(const Thin &g, int64_t tiles_r, int6
 }
 
 // An element at an address that is the same in every lane, read through the scalar unit.  The
-// scalar unit reads whole dwords, so a bf16 element comes out of the aligned dword around it; that
-// dword lies in the same page as the element, so the read cannot leave the mapping.
-template <typename T, typename Acc> __device__ __forceinline__ Acc uniform_load(const T *p) { return sb_load<T, Acc>(p); }
-template <> __device__ __forceinline__ float uniform_load<sb_bf16, float>(const sb_bf16 *p)
+// scalar unit reads whole dwords, so a bf16 element comes out of the aligned dword around it --
+// unless that dword sticks out of the caller's X ([lo, hi): its first or last element on an odd
+// boundary), in which case the element alone is read with a 2-byte load.
+template <typename T, typename Acc> __device__ __forceinline__ Acc uniform_load(const T *p, const T *, const T *) { return sb_load<T, Acc>(p); }
+template <> __device__ __forceinline__ float uniform_load<sb_bf16, float>(const sb_bf16 *p, const sb_bf16 *lo, const sb_bf16 *hi)
 {
     const uint32_t odd = (uint32_t)((uintptr_t)p >> 1) & 1u;      // upper half of its dword?
-    const uint32_t w = *(const uint32_t *)(p - odd);              // pointer arithmetic keeps the address space
+    const sb_bf16 *q = p - odd;                                   // pointer arithmetic keeps the address space
+    if (q < lo || q + 2 > hi) return sb_load<sb_bf16, float>(p);
+    const uint32_t w = *(const uint32_t *)q;
     return __uint_as_float(odd ? (w & 0xffff0000u) : (w << 16));
 }
 
@@ -169,7 +173,7 @@ __global__ __launch_bounds__(64 * WAVES) void thin_rows_kernel(Thin g, int64_t t
         P::unpack(raw, mv);
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            const Acc xv = uniform_load<T, Acc>(X + l * g.sxl + xoff[v] * g.sxv);
+            const Acc xv = uniform_load<T, Acc>(X + l * g.sxl + xoff[v] * g.sxv, (const T *)g.X, (const T *)g.X + g.xspan);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[v][e] += mv[e] * xv;
         }
@@ -328,6 +332,7 @@ Thin thin_view(const SbArgs &a)
     if (t.nv == 1) t.sxv = 0;
     if (t.batch0 == 1) t.bsM[0] = t.bsX[0] = t.bsY[0] = 0;
     if (t.batch1 == 1) t.bsM[1] = t.bsX[1] = t.bsY[1] = 0;
+    t.xspan = t.K < 1 ? 0 : 1 + (t.K - 1) * t.sxl + (t.nv - 1) * t.sxv + (t.batch0 - 1) * t.bsX[0] + (t.batch1 - 1) * t.bsX[1];
     return t;
 }
 
@@ -336,7 +341,7 @@ hipError_t launch_grid(Kernel kernel, const Thin &t, int64_t tiles_r, int thread
 {
     const int64_t total = tiles_r * t.batch0 * t.batch1;
     if (total <= 0) return hipSuccess;
-    const int64_t maxx = 1 << 30;
+    const int64_t maxx = sb_max_grid_x(threads);
     const int64_t gx = total < maxx ? total : maxx;
     const int64_t gy = (total + gx - 1) / gx;
     if (gy > 65535) return hipErrorInvalidConfiguration;

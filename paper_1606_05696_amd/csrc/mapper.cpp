@@ -9,21 +9,77 @@
 //      mode of each operand, rule 1 (no batching of an operand's unit-stride mode unless an
 //      extended operation of section III-E is allowed), rules 2 and 3 for flattening.
 // Table II is not stored anywhere: stage 3 applied to the 36 order-2 x order-3 cases yields it.
+//
+// Nothing here touches the heap: a contraction has at most 3 * SB_MAX_MODES indices, so every list
+// is a fixed-capacity array on the stack and the notation is rendered into a character buffer.
+// Planning a launch-bound contraction then costs a fraction of a microsecond.
 #include "../../include/sbgemm.h"
 
 #include <algorithm>
 #include <cstring>
-#include <string>
-#include <vector>
 
 namespace {
 
 enum { TA = 0, TB = 1, TC = 2 };
+constexpr int MAX_IDX = 3 * SB_MAX_MODES;       // distinct indices of one contraction
+constexpr int MAX_GROUPS = 3 * SB_MAX_MODES / 2; // flattened runs (each has at least two members)
+
+// Fixed-capacity list with the few std::vector members the planner uses.  Capacities are chosen so
+// that no input that passes parse_modes can overflow them; push_back beyond capacity is dropped.
+template <typename T, int N>
+struct Vec {
+    T v[N];
+    int n = 0;
+    Vec() {}
+    Vec(int count, const T &x) : n(count < N ? count : N) { for (int i = 0; i < n; ++i) v[i] = x; }
+    void push_back(const T &x) { if (n < N) v[n++] = x; }
+    int size() const { return n; }
+    bool empty() const { return n == 0; }
+    void clear() { n = 0; }
+    void assign(int count, const T &x) { n = count < N ? count : N; for (int i = 0; i < n; ++i) v[i] = x; }
+    T &operator[](int i) { return v[i]; }
+    const T &operator[](int i) const { return v[i]; }
+    T &back() { return v[n - 1]; }
+    const T &back() const { return v[n - 1]; }
+    T *begin() { return v; }
+    T *end() { return v + n; }
+    const T *begin() const { return v; }
+    const T *end() const { return v + n; }
+    bool operator==(const Vec &o) const
+    {
+        if (n != o.n) return false;
+        for (int i = 0; i < n; ++i)
+            if (!(v[i] == o.v[i])) return false;
+        return true;
+    }
+};
+
+typedef Vec<int, SB_MAX_MODES> Run;             // positions or index ids of one flattened run / one tensor's modes
+typedef Vec<Run, MAX_GROUPS> Runs;
+typedef Vec<bool, MAX_IDX> Flags;
+
+// stable insertion sort (std::stable_sort may allocate a merge buffer)
+template <typename T, typename Less>
+void stable_sort_small(T *first, T *last, Less less)
+{
+    for (T *i = first; i != last; ++i)
+        for (T *j = i; j != first && less(*j, *(j - 1)); --j) std::swap(*j, *(j - 1));
+}
+
+// bounded character buffer for the notation
+struct Text {
+    char c[192];
+    int n = 0;
+    Text() { c[0] = 0; }
+    Text &operator+=(char ch) { if (n + 1 < (int)sizeof(c)) { c[n++] = ch; c[n] = 0; } return *this; }
+    Text &operator+=(const char *s) { while (*s) *this += *s++; return *this; }
+    Text &operator+=(const Text &t) { return *this += t.c; }
+};
 
 struct ParsedTensor {
-    std::vector<char> label;
-    std::vector<bool> batched;
-    std::vector<std::vector<int>> groups;   // positions (within this tensor) of flattened runs
+    Vec<char, SB_MAX_MODES + 1> label;      // one spare slot so that "too many modes" is seen
+    Vec<bool, SB_MAX_MODES + 1> batched;
+    Runs groups;                            // positions (within this tensor) of flattened runs
     bool annotated = false;
 };
 
@@ -36,15 +92,15 @@ struct Index {
 };
 
 struct Problem {
-    std::vector<Index> idx;
+    Vec<Index, MAX_IDX> idx;
     int order[3];
-    std::vector<int> modes[3];   // index ids in stored order
+    Run modes[3];                // index ids in stored order
     int k;                       // id of the contracted index
 };
 
 // A free mode of the evaluation after flattening: one index or a run of flattened indices.
 struct SMode {
-    std::vector<int> mem;   // index ids, first (fastest) member first
+    Run mem;                // index ids, first (fastest) member first
     int64_t ext;
     int64_t sOwner, sC;     // stride of the first member in the owning input tensor and in C
     int owner;
@@ -61,14 +117,16 @@ int parse_modes(const char *s, ParsedTensor &t)
     while (i < n) {
         char c = s[i];
         if (is_letter(c)) {
+            if (t.label.size() >= SB_MAX_MODES) return SB_ERR_MODES;
             t.label.push_back(c);
             t.batched.push_back(false);
             ++i;
         } else if (c == '[' || c == '(') {
             char close = (c == '[') ? ']' : ')';
             size_t j = i + 1;
-            std::vector<int> run;
+            Run run;
             while (j < n && is_letter(s[j])) {
+                if (t.label.size() >= SB_MAX_MODES) return SB_ERR_MODES;
                 run.push_back((int)t.label.size());
                 t.label.push_back(s[j]);
                 t.batched.push_back(c == '[');
@@ -83,17 +141,16 @@ int parse_modes(const char *s, ParsedTensor &t)
             return SB_ERR_MODES;
         }
     }
-    if (t.label.size() > SB_MAX_MODES) return SB_ERR_MODES;
-    for (size_t a = 0; a < t.label.size(); ++a)
-        for (size_t b = 0; b < a; ++b)
+    for (int a = 0; a < t.label.size(); ++a)
+        for (int b = 0; b < a; ++b)
             if (t.label[a] == t.label[b]) return SB_ERR_MODES;
     return SB_OK;
 }
 
 int find_index(const Problem &P, char label)
 {
-    for (size_t i = 0; i < P.idx.size(); ++i)
-        if (P.idx[i].label == label) return (int)i;
+    for (int i = 0; i < P.idx.size(); ++i)
+        if (P.idx[i].label == label) return i;
     return -1;
 }
 
@@ -135,7 +192,7 @@ int build_problem(const ParsedTensor pt[3], const int64_t *dims[3], const int64_
     // eq. (1): C's indices are those in exactly one of A, B; the ones in both are contracted.
     P.k = -1;
     int ncontracted = 0;
-    for (size_t i = 0; i < P.idx.size(); ++i) {
+    for (int i = 0; i < P.idx.size(); ++i) {
         Index &ix = P.idx[i];
         bool a = ix.pos[TA] >= 0, b = ix.pos[TB] >= 0, c = ix.pos[TC] >= 0;
         if (a && b) {
@@ -152,11 +209,11 @@ int build_problem(const ParsedTensor pt[3], const int64_t *dims[3], const int64_
     if (ncontracted != 1) return SB_ERR_CONTRACTION;   // single-index contractions only
     // The output must not alias itself: sorted by stride, every mode of C has to step over the
     // whole extent of the previous one (padding allowed).
-    std::vector<int> byStride;
+    Run byStride;
     for (int j = 0; j < P.order[TC]; ++j)
         if (P.idx[P.modes[TC][j]].ext > 1) byStride.push_back(P.modes[TC][j]);
-    std::stable_sort(byStride.begin(), byStride.end(), [&](int x, int y) { return P.idx[x].s[TC] < P.idx[y].s[TC]; });
-    for (size_t j = 1; j < byStride.size(); ++j) {
+    stable_sort_small(byStride.begin(), byStride.end(), [&](int x, int y) { return P.idx[x].s[TC] < P.idx[y].s[TC]; });
+    for (int j = 1; j < byStride.size(); ++j) {
         const Index &lo = P.idx[byStride[j - 1]], &hi = P.idx[byStride[j]];
         if (hi.s[TC] < lo.s[TC] * lo.ext) return SB_ERR_STRIDE;
     }
@@ -174,13 +231,14 @@ bool can_flatten_pair(const Problem &P, int a, int b)
 }
 
 // Free modes of the evaluation in C's order, given the batched flags and the flattened runs.
-int make_smodes(const Problem &P, const std::vector<bool> &batched,
-                const std::vector<std::vector<int>> &groups, std::vector<SMode> &out)
+typedef Vec<SMode, SB_MAX_MODES> SModes;
+
+int make_smodes(const Problem &P, const Flags &batched, const Runs &groups, SModes &out)
 {
-    std::vector<int> group_of(P.idx.size(), -1);
-    for (size_t g = 0; g < groups.size(); ++g) {
-        const std::vector<int> &run = groups[g];
-        for (size_t j = 0; j < run.size(); ++j) {
+    Vec<int, MAX_IDX> group_of(P.idx.size(), -1);
+    for (int g = 0; g < groups.size(); ++g) {
+        const Run &run = groups[g];
+        for (int j = 0; j < run.size(); ++j) {
             if (run[j] == P.k || group_of[run[j]] >= 0 || batched[run[j]]) return SB_ERR_ILLEGAL_EVAL;
             group_of[run[j]] = (int)g;
             if (j > 0 && !can_flatten_pair(P, run[j - 1], run[j])) return SB_ERR_ILLEGAL_EVAL;
@@ -194,7 +252,7 @@ int make_smodes(const Problem &P, const std::vector<bool> &batched,
         SMode m;
         if (g >= 0) m.mem = groups[g]; else m.mem.push_back(id);
         m.ext = 1;
-        for (size_t q = 0; q < m.mem.size(); ++q) m.ext *= P.idx[m.mem[q]].ext;
+        for (int q = 0; q < m.mem.size(); ++q) m.ext *= P.idx[m.mem[q]].ext;
         const Index &first = P.idx[m.mem[0]];
         m.owner = first.owner;
         m.sOwner = first.s[first.owner];
@@ -233,19 +291,20 @@ int lower_operand(int64_t rows, int64_t cols, int64_t rs, int64_t cs, Operand &o
     return SB_OK;
 }
 
-std::string render_tensor(const Problem &P, int t, char name, const std::vector<SMode> &sm)
+Text render_tensor(const Problem &P, int t, char name, const SModes &sm)
 {
-    std::string s(1, name);
+    Text s;
+    s += name;
     s += '_';
-    const std::vector<int> &modes = P.modes[t];
-    for (size_t j = 0; j < modes.size();) {
+    const Run &modes = P.modes[t];
+    for (int j = 0; j < modes.size();) {
         int id = modes[j];
         const SMode *hit = nullptr;
-        for (size_t q = 0; q < sm.size(); ++q)
+        for (int q = 0; q < sm.size(); ++q)
             if (sm[q].mem[0] == id) hit = &sm[q];
         if (hit && hit->mem.size() > 1) {
             s += '(';
-            for (size_t q = 0; q < hit->mem.size(); ++q) s += P.idx[hit->mem[q]].label;
+            for (int q = 0; q < hit->mem.size(); ++q) s += P.idx[hit->mem[q]].label;
             s += ')';
             j += hit->mem.size();
         } else if (hit && hit->batched) {
@@ -262,10 +321,10 @@ std::string render_tensor(const Problem &P, int t, char name, const std::vector<
 }
 
 // Stage 3: lower an evaluation (free modes with batched flags) to StridedBatchedGemm arguments.
-int lower(const Problem &P, const std::vector<SMode> &sm, bool allow_ex, sb_plan *out)
+int lower(const Problem &P, const SModes &sm, bool allow_ex, sb_plan *out)
 {
-    std::vector<int> fr, bt;
-    for (size_t i = 0; i < sm.size(); ++i) (sm[i].batched ? bt : fr).push_back((int)i);
+    Run fr, bt;
+    for (int i = 0; i < sm.size(); ++i) (sm[i].batched ? bt : fr).push_back(i);
     if (fr.size() > 2) return SB_ERR_ILLEGAL_EVAL;
     int r = -1, c = -1;
     if (fr.size() == 2) {
@@ -296,7 +355,7 @@ int lower(const Problem &P, const std::vector<SMode> &sm, bool allow_ex, sb_plan
     if (oL.needs_ex || oR.needs_ex) {
         if (!allow_ex) return SB_ERR_ILLEGAL_EVAL;
         int X = oL.needs_ex ? L : R;
-        for (size_t q = 0; q < bt.size(); ++q)
+        for (int q = 0; q < bt.size(); ++q)
             if (sm[bt[q]].owner == X && sm[bt[q]].sOwner == 1) ex_mode = bt[q];
         if (ex_mode < 0) return SB_ERR_ILLEGAL_EVAL;
         // stored matrix = the operand's two remaining modes in stored order (section III-E)
@@ -316,8 +375,8 @@ int lower(const Problem &P, const std::vector<SMode> &sm, bool allow_ex, sb_plan
     if (bt.size() > SB_MAX_BATCH_LEVELS) return SB_ERR_ILLEGAL_EVAL;
     // Batch levels: the extended-operation mode must be level 0; otherwise the mode with the
     // largest extent goes innermost (section IV-D, priority 2), ties to the earlier mode of C.
-    std::vector<int> lv(bt);
-    std::stable_sort(lv.begin(), lv.end(), [&](int x, int y) {
+    Run lv(bt);
+    stable_sort_small(lv.begin(), lv.end(), [&](int x, int y) {
         if ((x == ex_mode) != (y == ex_mode)) return x == ex_mode;
         if (sm[x].ext != sm[y].ext) return sm[x].ext > sm[y].ext;
         return sm[x].posC < sm[y].posC;
@@ -330,7 +389,7 @@ int lower(const Problem &P, const std::vector<SMode> &sm, bool allow_ex, sb_plan
     out->ldL = oL.ld;  out->ldR = oR.ld;  out->ldC = ldC;
     out->exL = oL.ex;  out->exR = oR.ex;
     out->exceptional = (ex_mode >= 0);
-    for (size_t q = 0; q < lv.size(); ++q) {
+    for (int q = 0; q < lv.size(); ++q) {
         const SMode &b = sm[lv[q]];
         if (b.sC == 0 && b.ext > 1) return SB_ERR_STRIDE;
         if (b.sC == 1 && b.ext > 1) out->exceptional = 1;   // C's first mode batched: a matrix-vector form
@@ -341,28 +400,29 @@ int lower(const Problem &P, const std::vector<SMode> &sm, bool allow_ex, sb_plan
     }
     // the evaluation in the paper's notation
     char nameL = (L == TA) ? 'A' : 'B', nameR = (R == TA) ? 'A' : 'B';
-    std::string lhs = render_tensor(P, TC, 'C', sm);
-    std::string tl = render_tensor(P, L, nameL, sm), tr = render_tensor(P, R, nameR, sm);
-    std::string text;
+    const Text lhs = render_tensor(P, TC, 'C', sm);
+    const Text tl = render_tensor(P, L, nameL, sm), tr = render_tensor(P, R, nameR, sm);
+    Text text;
     if (r < 0 && c >= 0) {
         // row-vector times matrix: written as the matrix-vector product it is (Table II, kernel 2
         // of the exceptional rows): the matrix first, transposed relative to the GEMM's view of it
         bool t = (oR.op == SB_OP_N || oR.op == SB_OP_EX_N);
-        text = lhs + " = " + tr + (t ? "^T " : " ") + tl;
+        text += lhs;  text += " = ";  text += tr;  text += (t ? "^T " : " ");  text += tl;
     } else {
         bool tL = (oL.op == SB_OP_T || oL.op == SB_OP_EX_T) && r >= 0;
         bool tR = (oR.op == SB_OP_T || oR.op == SB_OP_EX_T) && c >= 0;
-        text = lhs + " = " + tl + (tL ? "^T " : " ") + tr + (tR ? "^T" : "");
+        text += lhs;  text += " = ";  text += tl;  text += (tL ? "^T " : " ");  text += tr;  text += (tR ? "^T" : "");
     }
-    std::strncpy(out->notation, text.c_str(), sizeof(out->notation) - 1);
+    static_assert(sizeof(text.c) == sizeof(out->notation), "the notation buffer");
+    std::memcpy(out->notation, text.c, sizeof(out->notation));
     return SB_OK;
 }
 
 // Maximal runs of modes that rules 2 and 3 allow to be flattened.
-std::vector<std::vector<int>> flatten_candidates(const Problem &P)
+Runs flatten_candidates(const Problem &P)
 {
-    std::vector<std::vector<int>> groups;
-    std::vector<int> run;
+    Runs groups;
+    Run run;
     for (int j = 0; j < P.order[TC]; ++j) {
         int id = P.modes[TC][j];
         if (!run.empty() && can_flatten_pair(P, run.back(), id)) {
@@ -379,22 +439,22 @@ std::vector<std::vector<int>> flatten_candidates(const Problem &P)
 // Pick the GEMM's column mode among the second operand's free modes (largest extent first, ties
 // to the earlier mode of C: Algorithm 2 chooses the GEMM mode by maximum dimension), batch
 // every other free mode, and keep the first choice that lowers.
-int choose_columns(const Problem &P, const std::vector<std::vector<int>> &groups, bool allow_ex, sb_plan *out)
+int choose_columns(const Problem &P, const Runs &groups, bool allow_ex, sb_plan *out)
 {
-    std::vector<bool> none(P.idx.size(), false);
-    std::vector<SMode> sm;
+    Flags none(P.idx.size(), false);
+    SModes sm;
     int rc = make_smodes(P, none, groups, sm);
     if (rc) return rc;
     if (sm.empty()) return lower(P, sm, allow_ex, out);
     int L = sm[0].owner;                    // sm[0] holds C's first mode: the row mode
-    std::vector<int> cand;
-    for (size_t i = 1; i < sm.size(); ++i)
-        if (sm[i].owner != L) cand.push_back((int)i);
-    std::stable_sort(cand.begin(), cand.end(), [&](int x, int y) { return sm[x].ext > sm[y].ext; });
+    Run cand;
+    for (int i = 1; i < sm.size(); ++i)
+        if (sm[i].owner != L) cand.push_back(i);
+    stable_sort_small(cand.begin(), cand.end(), [&](int x, int y) { return sm[x].ext > sm[y].ext; });
     if (cand.empty()) cand.push_back(-1);   // second operand is a vector: one-column GEMM
     int last = SB_ERR_ILLEGAL_EVAL;
-    for (size_t q = 0; q < cand.size(); ++q) {
-        for (size_t i = 1; i < sm.size(); ++i) sm[i].batched = ((int)i != cand[q]);
+    for (int q = 0; q < cand.size(); ++q) {
+        for (int i = 1; i < sm.size(); ++i) sm[i].batched = (i != cand[q]);
         sm[0].batched = false;
         last = lower(P, sm, allow_ex, out);
         if (last == SB_OK) return SB_OK;
@@ -405,23 +465,23 @@ int choose_columns(const Problem &P, const std::vector<std::vector<int>> &groups
 // Batched matrix-vector evaluation: C's row mode is batched too, one free mode stays.
 int choose_level2(const Problem &P, sb_plan *out)
 {
-    std::vector<bool> none(P.idx.size(), false);
-    std::vector<std::vector<int>> nogroups;
-    std::vector<SMode> sm;
+    Flags none(P.idx.size(), false);
+    Runs nogroups;
+    SModes sm;
     int rc = make_smodes(P, none, nogroups, sm);
     if (rc) return rc;
     if (sm.size() < 2) return lower(P, sm, false, out);
     int L = sm[0].owner;
-    std::vector<int> cand;
-    for (size_t i = 1; i < sm.size(); ++i) cand.push_back((int)i);
+    Run cand;
+    for (int i = 1; i < sm.size(); ++i) cand.push_back(i);
     // the matrix comes from the tensor that holds C's first mode when it can (Table II), largest extent first
-    std::stable_sort(cand.begin(), cand.end(), [&](int x, int y) {
+    stable_sort_small(cand.begin(), cand.end(), [&](int x, int y) {
         if ((sm[x].owner == L) != (sm[y].owner == L)) return sm[x].owner == L;
         return sm[x].ext > sm[y].ext;
     });
     int last = SB_ERR_ILLEGAL_EVAL;
-    for (size_t q = 0; q < cand.size(); ++q) {
-        for (size_t i = 0; i < sm.size(); ++i) sm[i].batched = ((int)i != cand[q]);
+    for (int q = 0; q < cand.size(); ++q) {
+        for (int i = 0; i < sm.size(); ++i) sm[i].batched = (i != cand[q]);
         last = lower(P, sm, false, out);
         if (last == SB_OK) { out->exceptional = 1; return SB_OK; }
     }
@@ -430,18 +490,18 @@ int choose_level2(const Problem &P, sb_plan *out)
 
 int plan_from_annotations(const Problem &P, const ParsedTensor pt[3], sb_plan *out)
 {
-    std::vector<bool> batched(P.idx.size(), false);
-    std::vector<std::vector<int>> groups;
+    Flags batched(P.idx.size(), false);
+    Runs groups;
     for (int t = 0; t < 3; ++t) {
-        for (size_t j = 0; j < pt[t].label.size(); ++j)
+        for (int j = 0; j < pt[t].label.size(); ++j)
             if (pt[t].batched[j]) batched[P.modes[t][j]] = true;
-        for (size_t g = 0; g < pt[t].groups.size(); ++g) {
-            std::vector<int> run;
-            for (size_t j = 0; j < pt[t].groups[g].size(); ++j) run.push_back(P.modes[t][pt[t].groups[g][j]]);
+        for (int g = 0; g < pt[t].groups.size(); ++g) {
+            Run run;
+            for (int j = 0; j < pt[t].groups[g].size(); ++j) run.push_back(P.modes[t][pt[t].groups[g][j]]);
             bool seen = false;
-            for (size_t h = 0; h < groups.size(); ++h) {
+            for (int h = 0; h < groups.size(); ++h) {
                 if (groups[h] == run) { seen = true; break; }
-                for (size_t j = 0; j < run.size(); ++j)      // overlapping but different: rule 3
+                for (int j = 0; j < run.size(); ++j)      // overlapping but different: rule 3
                     if (std::find(groups[h].begin(), groups[h].end(), run[j]) != groups[h].end())
                         return SB_ERR_ILLEGAL_EVAL;
             }
@@ -449,7 +509,7 @@ int plan_from_annotations(const Problem &P, const ParsedTensor pt[3], sb_plan *o
         }
     }
     if (batched[P.k]) return SB_ERR_ILLEGAL_EVAL;
-    std::vector<SMode> sm;
+    SModes sm;
     int rc = make_smodes(P, batched, groups, sm);
     if (rc) return rc;
     return lower(P, sm, true, out);
@@ -483,12 +543,12 @@ int plan_impl(const char *modesA, const char *modesB, const char *modesC,
         if (strat != SB_AUTO) return -10;
         rc = plan_from_annotations(P, pt, out);
     } else {
-        std::vector<std::vector<int>> nogroups;
+        Runs nogroups;
         switch (strat) {
         case SB_AUTO: {
             // priority 1: flatten whenever possible; then the largest GEMM, batching the rest;
             // extended operations only when no plain evaluation exists (section III-E)
-            std::vector<std::vector<int>> groups = flatten_candidates(P);
+            const Runs groups = flatten_candidates(P);
             rc = choose_columns(P, groups, false, out);
             if (rc == SB_ERR_ILLEGAL_EVAL) rc = choose_columns(P, groups, true, out);
             if (rc == SB_ERR_ILLEGAL_EVAL) rc = choose_level2(P, out);
@@ -504,12 +564,12 @@ int plan_impl(const char *modesA, const char *modesB, const char *modesC,
             break;
         case SB_BATCH_LAST:
         case SB_BATCH_MID: {
-            std::vector<bool> batched(P.idx.size(), false);
+            Flags batched(P.idx.size(), false);
             int nC = P.order[TC];
             int col = (strat == SB_BATCH_LAST) ? 1 : nC - 1;
             for (int j = 1; j < nC; ++j)
                 if (j != col) batched[P.modes[TC][j]] = true;
-            std::vector<SMode> sm;
+            SModes sm;
             rc = make_smodes(P, batched, nogroups, sm);
             if (rc == SB_OK) rc = lower(P, sm, true, out);
             break;

@@ -7,8 +7,9 @@
 
 namespace {
 
-int g_force_kernel = SB_KERNEL_AUTO;
-int g_last_kernel = -1;
+// diagnostics state is per host thread: a thread pins and reads the family of its own calls
+thread_local int g_force_kernel = SB_KERNEL_AUTO;
+thread_local int g_last_kernel = -1;
 
 bool valid_op(int op) { return op >= SB_OP_N && op <= SB_OP_EX_T; }
 bool is_ex(int op) { return op == SB_OP_EX_N || op == SB_OP_EX_T; }
@@ -36,6 +37,26 @@ int choose(sb_dtype dt, const SbArgs &a, int forced)
         if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) return SB_KERNEL_MFMA;
     }
     return SB_KERNEL_GENERIC;
+}
+
+// No two (i, j, p, q) may address the same element of C.  Sufficient test: sorted by stride, each of
+// the four directions (rows, columns, two batch levels) steps over everything the smaller ones span.
+// Batches interleaved inside one tensor (C_m[n]p: batch stride below ldc) pass.  Returns 0 if C is
+// fine, else which stride is too small: 1 = ldc, 2 = level-0 batch stride, 3 = level-1 batch stride.
+int c_overlap(int64_t m, int64_t n, int64_t ldc, int64_t stride0, int64_t batch0, int64_t stride1, int64_t batch1)
+{
+    struct Dir { int64_t stride, extent; int which; } d[4] = {{1, m, 1}, {ldc, n, 1}, {stride0, batch0, 2}, {stride1, batch1, 3}};
+    int nd = 0;
+    for (int q = 0; q < 4; ++q)
+        if (d[q].extent > 1) d[nd++] = d[q];
+    for (int a = 1; a < nd; ++a)
+        for (int b = a; b > 0 && d[b].stride < d[b - 1].stride; --b) std::swap(d[b], d[b - 1]);
+    int64_t span = 0;                      // largest offset reachable with the directions seen so far
+    for (int q = 0; q < nd; ++q) {
+        if (q > 0 && d[q].stride <= span) return d[q].which;
+        span += (d[q].extent - 1) * d[q].stride;
+    }
+    return 0;
 }
 
 int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
@@ -86,6 +107,12 @@ extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int6
     if (ldc < std::max<int64_t>(1, m)) return -18;
     if (strideC0 < 0 || (strideC0 == 0 && batch0 > 1)) return -19;
     if (strideC1 < 0 || (strideC1 == 0 && batch1 > 1)) return -20;
+    switch (c_overlap(m, n, ldc, strideC0, batch0, strideC1, batch1)) {
+    case 1: return -18;
+    case 2: return -19;
+    case 3: return -20;
+    default: break;
+    }
 
     SbArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -114,8 +141,14 @@ extern "C" int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t
     if (k < 1) return -6;
     if (lda < 1 || strideA < 0) return -7;
     if (ldb < 1 || strideB < 0) return -9;
-    if (ldc < m || strideC < 0) return -11;
+    if (ldc < m) return -11;
+    if (strideC < 0 || (strideC == 0 && batch > 1)) return -12;
     if (batch < 1) return -13;
+    switch (c_overlap(m, n, ldc, strideC, batch, 0, 1)) {
+    case 1: return -11;
+    case 2: return -12;
+    default: break;
+    }
     SbArgs a;
     std::memset(&a, 0, sizeof(a));
     a.m = m;  a.n = n;  a.k = k;
@@ -282,14 +315,39 @@ bool fill_key(PlanKey &k, const char *const modes[3], const int64_t *const dims[
     return true;
 }
 
+// A small per-thread cache of recent plans: an iteration such as HOOI cycles through half a dozen
+// contractions, each of which finds its plan again as long as every planning input is identical.
 struct PlanCache {
-    bool valid = false;
-    PlanKey key;
-    sb_plan plan;
+    static constexpr int ENTRIES = 8;
+    bool valid[ENTRIES] = {};
+    PlanKey key[ENTRIES];
+    sb_plan plan[ENTRIES];
+    int next = 0;                          // round-robin replacement
+
+    const sb_plan *find(const PlanKey &k) const
+    {
+        for (int e = 0; e < ENTRIES; ++e)
+            if (valid[e] && std::memcmp(&key[e], &k, sizeof(k)) == 0) return &plan[e];
+        return nullptr;
+    }
+    void insert(const PlanKey &k, const sb_plan &p)
+    {
+        std::memcpy(&key[next], &k, sizeof(k));      // byte copy: the keys are compared as bytes, padding included
+        plan[next] = p;
+        valid[next] = true;
+        next = (next + 1) % ENTRIES;
+    }
 };
 thread_local PlanCache g_plan_cache;
+thread_local bool g_plan_cache_enabled = true;
 
 }  // namespace
+
+extern "C" int sb_plan_cache_enable(int on)
+{
+    g_plan_cache_enabled = on != 0;
+    return SB_OK;
+}
 
 extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, const char *modesC,
                            double alpha, const void *A, const int64_t *dimsA, const int64_t *stridesA,
@@ -298,24 +356,20 @@ extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, 
                            sb_strategy strat, void *stream)
 {
     if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
-    sb_plan plan;
-    int rc;
+    sb_plan planned;
+    const sb_plan *plan = nullptr;
+    int rc = SB_OK;
     const char *const modes[3] = {modesA, modesB, modesC};
     const int64_t *const dims[3] = {dimsA, dimsB, dimsC};
     const int64_t *const strides[3] = {stridesA, stridesB, stridesC};
     PlanKey key;
-    const bool keyed = fill_key(key, modes, dims, strides, (int)strat);
+    const bool keyed = g_plan_cache_enabled && fill_key(key, modes, dims, strides, (int)strat);
     PlanCache &cache = g_plan_cache;
-    if (keyed && cache.valid && std::memcmp(&cache.key, &key, sizeof(key)) == 0) {
-        plan = cache.plan;
-        rc = SB_OK;
-    } else {
-        rc = sb_contract_plan(modesA, modesB, modesC, dimsA, stridesA, dimsB, stridesB, dimsC, stridesC, strat, &plan);
-        if (rc == SB_OK && keyed) {
-            cache.key = key;
-            cache.plan = plan;
-            cache.valid = true;
-        }
+    if (keyed) plan = cache.find(key);
+    if (!plan) {
+        rc = sb_contract_plan(modesA, modesB, modesC, dimsA, stridesA, dimsB, stridesB, dimsC, stridesC, strat, &planned);
+        if (rc == SB_OK && keyed) cache.insert(key, planned);
+        plan = &planned;
     }
     if (rc < 0) {
         // planner argument numbers -> sb_contract argument numbers
@@ -323,7 +377,7 @@ extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, 
         return -map[-rc];
     }
     if (rc != SB_OK) return rc;
-    rc = sb_plan_launch(dt, &plan, alpha, A, B, beta, C, stream);
+    rc = sb_plan_launch(dt, plan, alpha, A, B, beta, C, stream);
     if (rc < 0) {
         static const int map[9] = {0, 1, 16, 5, 6, 9, 12, 13, 17};
         return -map[-rc];

@@ -45,7 +45,13 @@ hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 // 256 compute units: the launchers use it to choose between tile sizes.
 double sb_tile_time(int64_t tiles, double area, double gain);
 
-// Set-up that HIP keeps per device (function attributes, occupancy) is cached per device ordinal.
+// A launch may not have more than 2^32 - 1 work-items along x: the most workgroups of `threads`
+// lanes a one-dimensional grid can hold.  Launchers that take one workgroup per tile either spill
+// into y beyond it or leave larger problems to another family.
+inline int64_t sb_max_grid_x(int threads) { return (int64_t)0xFFFFFFFFll / threads; }
+
+// Set-up that HIP keeps per device (function attributes, occupancy) is cached per device ordinal in
+// std::atomic tables: two host threads that race on a first use both compute the same value.
 constexpr int SB_MAX_DEVICES = 64;
 inline int sb_current_device()
 {

@@ -108,7 +108,7 @@ def workload_tensors(cfg: int, with_c: bool = False):
 
 
 def lowrank_noise_tensor(seed: int, dims, core, noise: float = 0.05, dtype=np.float64) -> np.ndarray:
-    """Synthetic input for the Tucker application study (section V-C works on cubic tensors with a
+    """Synthetic input for the Tucker application study (section IV-C works on cubic tensors with a
     10 x 10 x 10 core): a random core of size `core` with decaying entries, expanded by random
     orthonormal factors to `dims`, plus uniform noise of relative size `noise`.  Column-major."""
     rng = np.random.default_rng(seed)

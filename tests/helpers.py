@@ -126,3 +126,53 @@ def rel_fro(got, ref):
     ref = np.asarray(ref, dtype=np.float64).ravel()
     den = np.linalg.norm(ref)
     return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
+
+
+# Element-wise bound.  A relative Frobenius norm over millions of outputs lets a handful of wrong
+# elements through (at bf16's 2e-2 even a whole wrong tile), so every comparison also bounds each
+# element by what the arithmetic can do.  The device computes v = alpha * sum_k a b + beta * c in the
+# accumulation type (unit roundoff u: 2^-24 for f32 and bf16, 2^-53 for f64) in some order, then
+# stores it (bf16: one more rounding to nearest even, relative 2^-8: 8 significant bits).  Any order of K products, K
+# additions and the alpha / beta arithmetic obeys the standard running-error bound
+#     |v - exact| <= (K + 4) u (|alpha| sum_k |a||b| + |beta||c|)  <=  (K + 4) u (|alpha| K amax bmax + |beta||c|),
+# and |stored - v| <= u_out |v|.  The reference is exact to 2^-53 or better, which the bound absorbs.
+ACC_UNIT = {"f64": 2.0 ** -53, "f32": 2.0 ** -24, "bf16": 2.0 ** -24}
+OUT_UNIT = {"f64": 0.0, "f32": 0.0, "bf16": 2.0 ** -8}
+
+
+def elementwise_bound(ref, dtype, K, amax, bmax, alpha=1.0, beta=0.0, c_old=None):
+    """Largest |got - ref| the arithmetic allows, per element of `ref` (an array of its shape)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    mag = abs(alpha) * max(K, 0) * float(amax) * float(bmax) * np.ones_like(ref)
+    if beta != 0.0 and c_old is not None:
+        mag = mag + abs(beta) * np.abs(np.asarray(c_old, dtype=np.float64).reshape(ref.shape))
+    acc = (max(K, 0) + 4) * ACC_UNIT[dtype] * mag
+    return OUT_UNIT[dtype] * (np.abs(ref) + acc) + acc
+
+
+def assert_close(got, ref, dtype, K, amax, bmax, alpha=1.0, beta=0.0, c_old=None, what=""):
+    """The two gates of every GPU comparison: relative Frobenius error within TOL[dtype] and every
+    element within elementwise_bound().  Returns the relative Frobenius error."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all(), ("non-finite output", what)
+    err = rel_fro(got, ref)
+    assert err <= TOL[dtype], ("relative Frobenius error", err, what)
+    excess = np.abs(got - ref) - elementwise_bound(ref, dtype, K, amax, bmax, alpha, beta, c_old)
+    if excess.size and excess.max() > 0:
+        at = np.unravel_index(int(np.argmax(excess)), excess.shape)
+        raise AssertionError("element %s: got %r, reference %r, %d elements beyond the element-wise bound (%s)"
+                             % (at, got[at], ref[at], int((excess > 0).sum()), what))
+    return err
+
+
+def gemm_window_mask(size, m, n, ldc, loc, batch):
+    """Boolean mask over a flat C buffer: True where one of the batch's m x n windows lies."""
+    mask = np.zeros(size, dtype=bool)
+    if m and n and batch:
+        i = np.arange(m, dtype=np.int64)[:, None, None]
+        j = np.arange(n, dtype=np.int64)[None, :, None]
+        p = np.arange(batch, dtype=np.int64)[None, None, :]
+        mask[(i + j * ldc + p * loc).ravel()] = True
+    return mask

@@ -59,6 +59,11 @@ def test_sb_gemm_argument_validation():
     assert gemm(strideC=0) == -17                 # batches of C would coincide
     assert gemm(strideC=-4) == -17
     assert gemm(batch=-1) == -18
+    # batches of C that overlap without coinciding: 4 x 5 windows (20 elements) only 19 or 7 apart
+    assert gemm(strideC=19) == -17
+    assert gemm(strideC=7) == -17
+    assert gemm(ldc=6, strideC=25) == -17          # columns 6 apart: a batch spans 28 elements
+    assert gemm(m=1, n=5, ldc=3, strideC=2, batch=3) == -16      # sorted by stride, ldc is the one that is too small
     assert gemm(transA="EX_N", strideA=0) == -10  # extended op: the stride argument is a column stride
     # quick returns: nothing to do, nothing launched
     assert gemm(m=0) == sb.SB_OK
@@ -80,6 +85,8 @@ def test_sb_gemm2_argument_validation():
     assert g2(b0=-1) == -21
     assert g2(b1=-1) == -22
     assert g2(ldc=2) == -18
+    assert g2(sC0=19) == -19                       # level-0 batches overlap
+    assert g2(sC1=59) == -20                       # level-1 batches overlap (three level-0 batches span 60)
     assert g2(b1=0) == sb.SB_OK
 
 
@@ -170,3 +177,19 @@ def test_kernel_selector():
     assert sb.sb_select_kernel(7, "N", "N", 4, 4, 4, 4, 16, 4, 16, 4, 16, 1) == -1
     assert sb.sb_select_kernel("f32", "N", "N", 0, 4, 4, 4, 16, 4, 16, 4, 16, 1) == -4
     assert sb.sb_select_kernel("f32", "N", "N", 4, 4, 4, 4, 16, 4, 16, 3, 16, 1) == -11
+
+
+def test_interleaved_batches_of_c_are_accepted_and_overlapping_ones_rejected():
+    # sb_select_kernel validates C exactly as sb_gemm does and launches nothing.
+    # C_m[n]p (Table II): m x p matrices with ldc = m*n, one per n, m apart -- legal although the
+    # batch stride is far below ldc * columns
+    m, n, p = 64, 48, 40
+    sel = lambda ldc, sc, batch, rows=m, cols=p: sb.sb_select_kernel("f32", "N", "N", rows, cols, 16, rows, 0, 16, 16 * cols,
+                                                                      ldc, sc, batch)
+    assert sel(m * n, m, n) >= 0
+    assert sel((m + 1) * n + 5, m + 1, n) >= 0         # padded: still disjoint
+    assert sel(m * n, m - 1, n) == -12                 # neighbouring batches share a row
+    assert sel(m * n - 1, m, n) == -11                 # the last batch runs into the next column
+    assert sel(m, m * p, n) >= 0 and sel(m, m * p - 1, n) == -12      # packed batches, one element short
+    assert sel(m, 0, 1) >= 0                           # one batch: its stride does not matter
+    assert sel(m, 0, 2) == -12
