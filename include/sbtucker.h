@@ -58,6 +58,19 @@ int sb_sym_eig_workspace(sb_dtype dt, int64_t n, int64_t *bytes);
 int sb_sym_eig(sb_dtype dt, int64_t n, void *S, void *V, void *lambda, int sweeps,
                void *workspace, int64_t workspace_bytes, void *stream);
 
+/*
+ * sb_sym_eig for callers that cannot allocate device memory or pass a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as sb_sym_eig, same kernels; the workspace is a device array inside the library
+ * (about 2 MiB per GPU, held until the process ends), so the order is limited to
+ * n <= SB_SYM_EIG_STATIC_MAX_N (-2 beyond).  The call allocates and frees nothing.  Every call on
+ * one GPU uses that GPU's array: calls that overlap in time on one GPU (two streams, two threads)
+ * race and must be serialised by the caller; calls on one stream are ordered by the stream.
+ * Argument numbers: dt=1 n=2 S=3 V=4 lambda=5 sweeps=6 stream=7.
+ */
+#define SB_SYM_EIG_STATIC_MAX_N 256
+int sb_sym_eig_static(sb_dtype dt, int64_t n, void *S, void *V, void *lambda, int sweeps, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

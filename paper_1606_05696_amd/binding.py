@@ -27,10 +27,11 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
               "batch_mid": SB_BATCH_MID, "nested": SB_NESTED, "level2": SB_LEVEL2}
 
 
-__all__ = [n for n in dir() if n.startswith("SB_")] + [
+__all__ = [n for n in dir() if n.startswith("SB_")] + ["SB_SYM_EIG_STATIC_MAX_N"] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
-    "sb_select_kernel", "sb_plan_cache_enable", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_probe_mfma"]
+    "sb_select_kernel", "sb_plan_cache_enable", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_sym_eig_static",
+    "sb_probe_mfma"]
 
 
 class sb_plan(ctypes.Structure):
@@ -104,6 +105,8 @@ def load():
     lib.sb_sym_eig_workspace.argtypes = [ci, i64, i64p]
     lib.sb_sym_eig.restype = ci
     lib.sb_sym_eig.argtypes = [ci, i64, vp, vp, vp, ci, vp, i64, vp]
+    lib.sb_sym_eig_static.restype = ci
+    lib.sb_sym_eig_static.argtypes = [ci, i64, vp, vp, vp, ci, vp]
     _lib = lib
     return lib
 
@@ -327,3 +330,13 @@ def sb_sym_eig(n, S, V, lam, workspace, sweeps=0, dt=None, stream=None, check=Tr
         raise SbError("sb_sym_eig", rc)
     return rc
 
+
+SB_SYM_EIG_STATIC_MAX_N = 256
+
+
+def sb_sym_eig_static(n, S, V, lam, sweeps=0, dt=None, stream=None, check=True):
+    """sb_sym_eig with the library's own fixed workspace (see sbtucker.h: sb_sym_eig_static): allocates nothing."""
+    rc = load().sb_sym_eig_static(_dtype_of(dt, S, V, lam), n, _ptr(S), _ptr(V), _ptr(lam), int(sweeps), _stream(stream))
+    if check and rc != SB_OK:
+        raise SbError("sb_sym_eig_static", rc)
+    return rc

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "../../include/sbtucker.h"
 #include "sb_internal.h"
@@ -338,4 +339,58 @@ extern "C" int sb_sym_eig(sb_dtype dt, int64_t n, void *S, void *V, void *lambda
                                 (hipStream_t)stream, &Af, &Vf);
     if (err == hipSuccess) err = sb_eig_gather(dt, (int)n, Vf, (const int *)e.sel, lambda, (int)n, V, n, 0, (hipStream_t)stream);
     return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
+}
+
+// ---------------------------------------------------------------------------------------------
+// sb_sym_eig for callers that cannot allocate: the solver's workspace (Jacobi ping-pong copies of
+// the matrix and of the eigenvectors, the eigenvalue order) lives in a file-scope device array.
+// The array's name is only a host-side handle; the device address is looked up once per device
+// with hipGetSymbolAddress and everything below uses that address.
+namespace {
+
+constexpr int64_t STATIC_EIG_MAX_N = SB_SYM_EIG_STATIC_MAX_N;
+// EigSpace::bytes(SB_F64, 256): four 256 x 256 fp64 matrices + eigenvalues + order, each block 256-byte aligned
+constexpr int64_t STATIC_EIG_BYTES = 4 * (STATIC_EIG_MAX_N * STATIC_EIG_MAX_N * 8) + STATIC_EIG_MAX_N * 8 + STATIC_EIG_MAX_N * 4;
+static_assert(STATIC_EIG_MAX_N * STATIC_EIG_MAX_N * 8 % ALIGN == 0 && STATIC_EIG_MAX_N * 4 % ALIGN == 0, "blocks stay aligned");
+
+static __device__ __align__(256) unsigned char scratch[STATIC_EIG_BYTES];
+
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[SB_MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device (null + error code on failure)
+hipError_t scratch_address(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= SB_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" int sb_sym_eig_static(sb_dtype dt, int64_t n, void *S, void *V, void *lambda, int sweeps, void *stream)
+{
+    if (dt != SB_F64 && dt != SB_F32) return -1;
+    if (n < 1 || n > STATIC_EIG_MAX_N) return -2;
+    if (!S) return -3;
+    if (!V) return -4;
+    if (!lambda) return -5;
+    if (EigSpace::bytes(dt, n) > STATIC_EIG_BYTES) return -2;
+    void *base = nullptr;
+    hipError_t err = scratch_address(&base);
+    if (err != hipSuccess) return SB_ERR_LAUNCH + (int)err;
+    // nothing in the workspace has to start at zero: the solver writes V (identity), the ping-pong
+    // copies and the order before it reads them, so the previous call's contents are harmless
+    return sb_sym_eig(dt, n, S, V, lambda, sweeps, base, STATIC_EIG_BYTES, stream);
 }
