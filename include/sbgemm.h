@@ -198,8 +198,13 @@ const char *sb_status_string(int status);
  *   SB_KERNEL_THIN     1 <= min(m, n) <= 4, any operation and element type;
  *   SB_KERNEL_TINY     SB_F64 / SB_F32, m <= 32 and n <= 32, k >= 1, operations N / T;
  *   SB_KERNEL_MFMA     k >= 1, operations N / T in every element type; an extended operation on the
- *                      first operand in SB_F64 / SB_F32 when m >= 8, n >= 16 and batch0 >= 8. */
-enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2, SB_KERNEL_THIN = 3 };
+ *                      first operand in SB_F64 / SB_F32 when m >= 8, n >= 16 and batch0 >= 8;
+ *   SB_KERNEL_PANEL    SB_BF16 with 1 <= k <= 128, operations N / T (whole-k operand panels in LDS: the
+ *                      selector takes it when C has at least 4 x 4 blocks of 64 x 64 -- counting, on
+ *                      each side, the batch levels that move only that side's operand -- and at least
+ *                      128 blocks of 256 x 256; smaller problems run on SB_KERNEL_MFMA's 64 x 64 tiles,
+ *                      which fetch an operand panel per 64 x 64 block instead of per four). */
+enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2, SB_KERNEL_THIN = 3, SB_KERNEL_PANEL = 4 };
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
 

@@ -17,7 +17,7 @@ SB_AUTO, SB_FLATTEN, SB_BATCH_LAST, SB_BATCH_MID, SB_NESTED, SB_LEVEL2 = 0, 1, 2
 SB_OK = 0
 SB_ERR_MODES, SB_ERR_CONTRACTION, SB_ERR_EXTENT, SB_ERR_STRIDE, SB_ERR_ILLEGAL_EVAL, SB_ERR_NO_DEVICE_CODE = 1, 2, 3, 4, 5, 6
 SB_ERR_LAUNCH = 1000
-SB_KERNEL_AUTO, SB_KERNEL_GENERIC, SB_KERNEL_TINY, SB_KERNEL_MFMA, SB_KERNEL_THIN = -1, 0, 1, 2, 3
+SB_KERNEL_AUTO, SB_KERNEL_GENERIC, SB_KERNEL_TINY, SB_KERNEL_MFMA, SB_KERNEL_THIN, SB_KERNEL_PANEL = -1, 0, 1, 2, 3, 4
 SB_MAX_MODES = 8
 SB_MAX_BATCH_LEVELS = 8
 

@@ -438,8 +438,6 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
 
 hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
 {
-    // many small GEMMs with short k: whole-K panels, batches pipelined inside persistent workgroups
-    if (sb_panel_bf16_supports(a)) return sb_launch_panel_bf16(a, stream);
     // whole 128 x 128 tiles, both operands k-contiguous: the streaming kernel
     // (256 x 256 tiles when there are enough of them to fill the chip and k is long: measured 1.06-1.10x
     // over the 128 x 128 tiles at k = 2048-4096, 0.87x at k = 512, where a tile ends too soon)

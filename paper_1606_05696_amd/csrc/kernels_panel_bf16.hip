@@ -1,102 +1,234 @@
-// Whole-K panel kernel for nests of small bf16 GEMMs (m, n <= 64, k <= 128) whose two batch
-// levels each move one operand: the batch loops take part in the tiling (section III-D argues a
-// strided batch interface allows exactly this; section III-F, Listing 2 is the nested case).
+// Whole-K panel-grid kernel for bf16 products with a short inner extent (k <= 128).
+//
+// With k this short the product is bound by writing C, not by the matrix cores: every operand
+// panel (64 rows x k, k x 64 columns) fits LDS whole, and the job is to keep the stores flowing.
+// The kernel sees C as a GRID of 64 x 64 blocks C[r][c] = Apanel[r] * Bpanel[c] in which the row
+// panel r does not depend on c and the column panel c does not depend on r.  A row panel is a run of
+// up to 64 rows of one op(A) matrix, a column panel a run of up to 64 columns of one op(B) matrix;
+// the panel index of a side counts, mixed radix, the 64-wide pieces of the flat extent and every
+// batch level that moves this side's operand only.  That one picture holds
+//   - the nested batch  C_m[p]n[q] = A_m[p]k B_kn[q]   (section III-F, Listing 2): rows = p, columns = q,
+//   - its flattened GEMM  C_(mp)(nq) = A_(mp)k B_k(nq)  (priority 1 of section IV-D): rows and columns
+//     are 64-wide pieces of the flat extents,
+//   - the partly flattened forms  C_(mp)n[q]  and  C_m[p](nq),
+// so all evaluations of such a contraction run through the same code at the same speed: "the batch
+// loop takes part in the tiling" (section III-D).  Batch levels that move both operands (or
+// neither) are an outer index z: independent grids.
+//
+// A workgroup of eight waves takes a block of 4 x 4 panels (256 x 256 outputs): 4 + 4 panels are
+// fetched for 16 small products, so the nest gets the operand reuse of a tiled GEMM although
+// nothing is flattened or copied.  Wave w owns row panel w % 4 and the left or right 32 columns of
+// every column panel; its A fragments (64 rows x k) stay in registers for all four column panels,
+// so a product reads only its B fragments from LDS (the matrix cores would otherwise wait for LDS:
+// 32 KB of fragment reads per 64 x 64 x 128 product against 1024 matrix-core cycles).
+// All 16 operand loads of a lane are issued at once; the A panels are handed to LDS first, then
+// the first column panel, and the other three while the first product runs.  Results leave through a
+// per-wave staging area in LDS (the A region, free once the fragments are in registers) as whole
+// 128-byte lines of C; a wave's stores drain while the next product runs, and no workgroup-wide
+// barrier separates the products.
+// Every panel is kept [row][k] in LDS, whatever the operand's orientation in memory, so that an
+// MFMA operand is ONE 16-byte LDS read.  An operand with m (or n) contiguous in memory is transposed
+// on the way in: a lane loads an 8 x 8 block (8 vectors of 8 rows, one per k), transposes it in
+// registers and writes 8 vectors of 8 k; the 16-byte chunk index of such a panel is XORed with
+// (row / 8) % 8 on the write and on the read side, which keeps those writes off the same banks.
+// Vector accesses need no alignment beyond the element's (the hardware reads and writes 16 bytes
+// at any element address).  RAGGED instantiations handle extents that are not whole vectors with
+// guarded element accesses; the others keep every load unconditional so that the hand-over to LDS
+// can wait for exactly the loads it needs.
 #include "sb_device.h"
 #include "sb_internal.h"
 
 #include <atomic>
-
+#include <type_traits>
 
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
-
-constexpr int TM = 64, TN = 64, KMAX = 128;
-constexpr int LD_KC = KMAX + 8;          // [row][k] layout, rows padded by 16 bytes
-
-// Two-level ("outer product") batch blocking: op(A) depends only on batch level 0 and op(B) only
-// on level 1, as in C_mn[p][q] = A_mk[p] B_nk[q] (section III-F).  The (p,q) batches then form a
-// grid in which every A_p meets every B_q, and a workgroup that takes a 2 x 2 block of that grid
-// needs only 2 + 2 panels for 4 small GEMMs: the nested batch becomes a blocked computation with
-// operand reuse, although no operand is ever flattened or copied.  Four waves, one GEMM of up to
-// 64 x 64 x 128 each; 68 KB of LDS, so two workgroups share a compute unit and one block's
-// stores drain to HBM while the next block's panels are being fetched.
-// Every panel is kept [row][k] in LDS, whatever the operand's orientation in memory, so that an
-// MFMA operand is always ONE 16-byte LDS read (a [k][row] panel needs eight 2-byte reads per
-// operand).  An operand with m (or n) contiguous is transposed on the
-// way in: a lane loads an 8 x 8 block (8 vectors of 8 rows, one per k), transposes it in registers
-// and writes 8 vectors of 8 k.  Those rows are 8 apart for neighbouring lanes, which a plain
-// layout would put on the same banks; the 16-byte chunk index of such a panel is therefore XORed
-// with (row / 8) % 8, on the write and on the read side.
-constexpr int GP2 = 2, GQ2 = 2, OT2 = 256;
-constexpr int PANEL2 = TM * LD_KC;                            // elements; [row][k], rows padded by 16 bytes
-constexpr int SPITCH2 = 68;                                   // staged column: 64 rows + 8 bytes
-constexpr int OUTER2_LDS = (GP2 + GQ2) * PANEL2;              // the staging area (4 x 64 x 68 elements) fits inside
-
-// The two panels of one operand (X_{b0}, X_{b0+1}) on their way from memory to LDS, spread over all
-// 256 lanes: load() only issues the global loads (so that the panels of a later block can already be
-// in flight), store() writes them to LDS in [row][k] form.
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4u __attribute__((ext_vector_type(4), aligned(2)));      // global access at any element address
 
-template <bool KC>
-struct TwoPanels {
+// how a result vector goes to C (a plain 16-byte store at any element address)
+#ifndef SB_PANEL_STORE
+#define SB_PANEL_STORE(ptr, value) (*(ptr) = (value))
+#endif
+
+constexpr int TM = 64, KMAX = 128;
+constexpr int LD_KC = KMAX + 8;           // [row][k] layout, rows padded by 16 bytes
+constexpr int PANEL = TM * LD_KC;         // elements of one panel in LDS
+constexpr int BR = 4, BC = 4;             // panels per workgroup block
+constexpr int NT = 512;                   // eight waves
+constexpr int SPITCH = 68;                // staged column: 64 rows + 8 bytes
+constexpr int LDS_ELEMS = (BR + BC) * PANEL;
+static_assert(8 * 32 * SPITCH <= BR * PANEL, "the staging areas of the eight waves fit the A region");
+
+// Division of a number below 2^31 by a divisor fixed on the host: one multiply-high, one add, one
+// shift (Granlund and Montgomery's round-up method; with n < 2^31 the add cannot overflow).  The
+// decode of a workgroup's block would otherwise spend a microsecond in emulated integer divisions
+// before the first load is issued.
+struct FastDiv {
+    uint32_t mul, shift;
+};
+__device__ __forceinline__ unsigned fdiv(unsigned n, FastDiv d) { return (__umulhi(n, d.mul) + n) >> d.shift; }
+
+// One side of the panel grid: rows of C (operand A) or columns of C (operand B).
+struct Side {
+    int32_t nf, n1, n2;        // 64-wide pieces of the flat extent; counts of up to two batch levels of this side
+    FastDiv dnf, dn1;
+    int32_t full, last;        // rows (columns) in a piece of the flat extent: every one but the last / the last
+    int64_t sf, s1, s2;        // element strides in the operand: between pieces, per batch level
+    int64_t cf, c1, c2;        // the same in C
+    uint32_t ld;               // operand: stride between rows (k contiguous) or between k (rows contiguous), below 2^31
+};
+
+struct PanelArgs {
+    const uint16_t *A, *B;
+    uint16_t *C;
+    Side row, col;
+    int32_t R, Cn;             // row panels, column panels
+    int32_t nrb, ncb;          // blocks of 4 along each side
+    int32_t nsc;               // super-tiles (4 x 8 blocks) along the columns
+    int32_t per_z;             // block slots per outer index (super-tiles are padded)
+    int32_t z0, z1;            // outer batch levels
+    FastDiv dper_z, dnsc, dz0;
+    int64_t zA[2], zB[2], zC[2];
+    int64_t ldc;
+    int32_t k;
+    float alpha, beta;
+};
+
+struct Loc {
+    int64_t off, offC;         // element offsets of the panel in its operand and in C
+    int32_t ext;               // rows (columns) of the panel
+};
+
+// panel idx of a side (the last valid one if idx is beyond `count`).  For an index that differs from
+// wave to wave: indexing the arrays below with it would move them from registers to scratch memory.
+__device__ __forceinline__ Loc locate1(const Side &s, int idx, int count)
+{
+    if (idx >= count) idx = count - 1;
+    const unsigned t = fdiv((unsigned)idx, s.dnf), f = (unsigned)idx - t * (unsigned)s.nf;
+    const unsigned l2 = fdiv(t, s.dn1), l1 = t - l2 * (unsigned)s.n1;
+    Loc r;
+    r.off = (int64_t)f * s.sf + (int64_t)l1 * s.s1 + (int64_t)l2 * s.s2;
+    r.offC = (int64_t)f * s.cf + (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
+    r.ext = (int)f == s.nf - 1 ? s.last : s.full;
+    return r;
+}
+
+// the four consecutive panels idx0 .. idx0+3 of a side; beyond `count` the last valid one is repeated
+// (its data is loaded again and never stored).  One decode, then a mixed-radix odometer.
+__device__ __forceinline__ void locate4(const Side &s, int idx0, int count, Loc (&out)[4])
+{
+    const unsigned t = fdiv((unsigned)idx0, s.dnf);
+    unsigned f = (unsigned)idx0 - t * (unsigned)s.nf;
+    unsigned l2 = fdiv(t, s.dn1), l1 = t - l2 * (unsigned)s.n1;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (i > 0 && idx0 + i < count) {
+            if (++f == (unsigned)s.nf) {
+                f = 0;
+                if (++l1 == (unsigned)s.n1) { l1 = 0; ++l2; }
+            }
+        }
+        out[i].off = (int64_t)f * s.sf + (int64_t)l1 * s.s1 + (int64_t)l2 * s.s2;
+        out[i].offC = (int64_t)f * s.cf + (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
+        out[i].ext = (int)f == s.nf - 1 ? s.last : s.full;
+    }
+}
+
+// The four panels of one side on their way from memory to LDS, spread over all 512 lanes: load() only
+// issues the global loads, store<P0, P1>() hands the panels P0 .. P1-1 to LDS in [row][k] form.
+//   KC (k contiguous in memory): 4 x 1024 vectors, straight copy; vector i of a lane belongs to panel i / 2.
+//   otherwise (rows contiguous): one 8 x 8 block per lane (8 vectors of 8 rows), transposed in registers;
+//     a lane's block belongs to panel tid / 128, so the four panels can only be stored together.
+template <bool KC, bool RAGGED>
+struct FourPanels {
     u32x4 v[8];
 
-    __device__ __forceinline__ void load(const uint16_t *X, int64_t bs, int64_t b0, int64_t blim, int64_t ld, int rows, int kk)
+    static __device__ __forceinline__ u32x4 guarded(const uint16_t *src, int n_ok)      // first n_ok elements, zeros after
+    {
+        uint16_t e[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) e[q] = q < n_ok ? src[q] : (uint16_t)0;
+        u32x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) w[c] = (unsigned)e[2 * c] | ((unsigned)e[2 * c + 1] << 16);
+        return w;
+    }
+
+    // loc: the four panels; mine: the panel of this lane's 8 x 8 block (rows-contiguous operands)
+    __device__ __forceinline__ void load(const uint16_t *X, const Loc (&loc)[4], const Loc &mine, uint32_t ld, int kk)
     {
         const int tid = (int)threadIdx.x;
-        if (KC) {                       // k contiguous in memory: 2 x 1024 vectors, straight copy
+        if (KC) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int panel = i / 4, f = tid + OT2 * (i % 4);
+                const int panel = i / 2, f = tid + NT * (i % 2);
                 const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
-                int64_t b = b0 + panel;
-                if (b >= blim) b = blim - 1;          // past the end: any valid panel, its results are never stored
-                const bool inside = row < rows && k < kk;
-                v[i] = *(const u32x4 *)(X + b * bs + (inside ? (int64_t)row * ld + k : 0));
+                const uint16_t *base = X + loc[panel].off;
+                if (RAGGED) {
+                    const int n_ok = row < loc[panel].ext ? kk - k : 0;
+                    if (n_ok >= 8) v[i] = *(const u32x4u *)(base + (uint64_t)((uint32_t)row * (uint64_t)ld + k));
+                    else if (n_ok > 0) v[i] = guarded(base + (uint64_t)((uint32_t)row * (uint64_t)ld + k), n_ok);
+                    else v[i] = u32x4{0, 0, 0, 0};
+                } else {            // a vector outside the panel reads the panel's first one instead; store() drops it
+                    const bool inside = row < loc[panel].ext && k < kk;
+                    v[i] = *(const u32x4u *)(base + (inside ? (uint64_t)((uint32_t)row * (uint64_t)ld + k) : 0));
+                }
             }
-        } else {                        // rows contiguous in memory: one 8 x 8 block per lane (8 vectors of 8 rows)
-            const int panel = tid / 128, blk = tid % 128;
+        } else {
+            const int blk = tid % 128;
             const int rg = blk % 8, kg = blk / 8;                  // rows 8 rg .. +7, k 8 kg .. +7
-            int64_t b = b0 + panel;
-            if (b >= blim) b = blim - 1;
-            const uint16_t *src = X + b * bs;
+            const uint16_t *base = X + mine.off;
+            const int ext = mine.ext;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int k = kg * 8 + i;
-                const bool inside = rg * 8 < rows && k < kk;
-                v[i] = *(const u32x4 *)(src + (inside ? (int64_t)k * ld + rg * 8 : 0));
+                if (RAGGED) {
+                    const int n_ok = k < kk ? ext - rg * 8 : 0;
+                    if (n_ok >= 8) v[i] = *(const u32x4u *)(base + (uint64_t)((uint32_t)k * (uint64_t)ld + rg * 8));
+                    else if (n_ok > 0) v[i] = guarded(base + (uint64_t)((uint32_t)k * (uint64_t)ld + rg * 8), n_ok);
+                    else v[i] = u32x4{0, 0, 0, 0};
+                } else {
+                    const bool inside = rg * 8 < ext && k < kk;
+                    v[i] = *(const u32x4u *)(base + (inside ? (uint64_t)((uint32_t)k * (uint64_t)ld + rg * 8) : 0));
+                }
             }
         }
     }
 
     // vectors outside the matrix become zeros here (not after the load, which would wait for it)
-    __device__ __forceinline__ void store(uint16_t *lds, int rows, int kk) const
+    template <int P0, int P1>
+    __device__ __forceinline__ void store(uint16_t *lds, const Loc (&loc)[4], const Loc &mine, int kk) const
     {
         const int tid = (int)threadIdx.x;
         const u32x4 z = {0, 0, 0, 0};
         if (KC) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int panel = i / 4, f = tid + OT2 * (i % 4);
+            for (int i = 2 * P0; i < 2 * P1; ++i) {
+                const int panel = i / 2, f = tid + NT * (i % 2);
                 const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
-                *(u32x4 *)(lds + panel * PANEL2 + row * LD_KC + k) = (row < rows && k < kk) ? v[i] : z;
+                const bool inside = RAGGED || (row < loc[panel].ext && k < kk);      // RAGGED: load() already put the zeros in
+                *(u32x4 *)(lds + panel * PANEL + row * LD_KC + k) = inside ? v[i] : z;
             }
-        } else {                        // transposed in registers: row 8 rg + j gets its 8 k as 4 words
+        } else if (P0 == 0) {               // transposed in registers: row 8 rg + j gets its 8 k as 4 words
             const int panel = tid / 128, blk = tid % 128;
             const int rg = blk % 8, kg = blk / 8;
+            const int ext = mine.ext;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 u32x4 w;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const bool in_lo = rg * 8 < rows && kg * 8 + 2 * c < kk, in_hi = rg * 8 < rows && kg * 8 + 2 * c + 1 < kk;
+                    const bool in_lo = RAGGED || (rg * 8 < ext && kg * 8 + 2 * c < kk);
+                    const bool in_hi = RAGGED || (rg * 8 < ext && kg * 8 + 2 * c + 1 < kk);
                     const unsigned lo = in_lo ? v[2 * c][j / 2] : 0u, hi = in_hi ? v[2 * c + 1][j / 2] : 0u;
                     w[c] = (j % 2 == 0) ? ((lo & 0xffffu) | (hi << 16)) : ((lo >> 16) | (hi & 0xffff0000u));
                 }
-                *(u32x4 *)(lds + panel * PANEL2 + (rg * 8 + j) * LD_KC + ((kg ^ rg) * 8)) = w;
+                *(u32x4 *)(lds + panel * PANEL + (rg * 8 + j) * LD_KC + ((kg ^ rg) * 8)) = w;
             }
         }
     }
@@ -104,7 +236,7 @@ struct TwoPanels {
 
 // MFMA operand of the 32 rows starting at row0 for k-step ks; SWZ: the panel was written with the chunk swizzle
 template <bool SWZ>
-__device__ __forceinline__ bf16x8 panel2_fragment(const uint16_t *lds, int row0, int ks, int lane)
+__device__ __forceinline__ bf16x8 panel_fragment(const uint16_t *lds, int row0, int ks, int lane)
 {
     const int row = row0 + (lane & 31);
     int chunk = ks * 2 + (lane >> 5);
@@ -112,183 +244,327 @@ __device__ __forceinline__ bf16x8 panel2_fragment(const uint16_t *lds, int row0,
     return __builtin_bit_cast(bf16x8, *(const u16x8 *)(lds + row * LD_KC + chunk * 8));
 }
 
-// A workgroup takes TWO neighbouring 2 x 2 blocks (same A panels, the next two B panels).  The loads of
-// the second block's B panels are issued together with the first block's, so they are in flight
-// while the first block is multiplied and stored, and the first block's stores drain while the
-// second is multiplied: with one block per workgroup the grid ran as two rounds of workgroups whose
-// fetch, multiply and store phases (2.4 + 1.0 + 2.0 us, each a chain of latencies) simply added up.
-template <bool A_KC, bool B_KC, int KS>
-__global__ __launch_bounds__(OT2) void sbgemm_outer2_bf16_kernel(SbArgs g, int groups_p, int vec_store)
+template <bool A_KC, bool B_KC, int KS, bool RAGGED>
+__global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs g)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [A0 A1 | B0 B1]; the B half doubles as staging area
-    const int gp = (int)(blockIdx.x % groups_p), gq2 = (int)(blockIdx.x / groups_p);
-    const int64_t p0 = (int64_t)gp * GP2, q0 = (int64_t)gq2 * (2 * GQ2);
-    const int m = (int)g.m, n = (int)g.n, kk = (int)g.k;
-    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
-    uint16_t *ldsB = lds + GP2 * PANEL2;
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [A0 .. A3 | B0 .. B3]; the A region becomes the staging area
+    uint16_t *ldsA = lds, *ldsB = lds + BR * PANEL;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    TwoPanels<A_KC> pa;
-    TwoPanels<B_KC> pb, pb2;
-    pa.load((const uint16_t *)g.A, g.bsA[0], p0, g.batch0, ldA, m, kk);
-    pb.load((const uint16_t *)g.B, g.bsB[1], q0, g.batch1, ldB, n, kk);
-    pb2.load((const uint16_t *)g.B, g.bsB[1], q0 + GQ2, g.batch1, ldB, n, kk);      // clamped when there is no second block
-    pa.store(lds, m, kk);
-    pb.store(ldsB, n, kk);
+    // Workgroup -> block.  The hardware deals consecutive workgroup ids to the 8 XCDs in turn; renumber
+    // so that each XCD owns a contiguous range of slots, and order the slots in super-tiles of 4 x 8
+    // blocks so that such a range is a compact rectangle of the grid: an XCD's L2 then holds few
+    // different panels (16 row and 32 column panels per super-tile).
+    const unsigned total = gridDim.x, bid = blockIdx.x;
+    const unsigned q8 = total >> 3, r8 = total & 7, xcd = bid & 7, slot = bid >> 3;
+    const unsigned logical = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+    const unsigned z = fdiv(logical, g.dper_z), within = logical - z * (unsigned)g.per_z;
+    const unsigned stile = within >> 5, in = within & 31;
+    const unsigned srow = fdiv(stile, g.dnsc), scol = stile - srow * (unsigned)g.nsc;
+    const int rb = (int)(srow * 4 + (in & 3)), cb = (int)(scol * 8 + (in >> 2));
+    if (rb >= g.nrb || cb >= g.ncb) return;                 // padding slot of a ragged super-tile (whole workgroup)
+    const unsigned zi1 = fdiv(z, g.dz0), zi0 = z - zi1 * (unsigned)g.z0;
+    const int kk = g.k;
+
+    // the loads go out as early as possible: row side, its loads, column side, its loads
+    Loc rl[4], cl[4];
+    Loc ra = {0, 0, 0}, ca = {0, 0, 0};          // rows-contiguous operands: the panel this lane's 8 x 8 block belongs to
+    FourPanels<A_KC, RAGGED> pa;
+    FourPanels<B_KC, RAGGED> pb;
+    locate4(g.row, rb * BR, g.R, rl);
+    if (!A_KC) ra = locate1(g.row, rb * BR + tid / 128, g.R);
+    pa.load(g.A + (int64_t)zi0 * g.zA[0] + (int64_t)zi1 * g.zA[1], rl, ra, g.row.ld, kk);
+    locate4(g.col, cb * BC, g.Cn, cl);
+    if (!B_KC) ca = locate1(g.col, cb * BC + tid / 128, g.Cn);
+    pb.load(g.B + (int64_t)zi0 * g.zB[0] + (int64_t)zi1 * g.zB[1], cl, ca, g.col.ld, kk);
+
+    // wave w: row panel w % 4, columns 32 (w / 4) .. +31 of every column panel
+    const int pi = wave & 3, half = wave >> 2;
+    const float alpha = g.alpha, beta = g.beta;
+    const bool row_live = rb * BR + pi < g.R;
+    const Loc my_row = locate1(g.row, rb * BR + pi, g.R);
+    const int rows = my_row.ext;
+    uint16_t *Crow = g.C + (int64_t)zi0 * g.zC[0] + (int64_t)zi1 * g.zC[1] + my_row.offC;
+    uint16_t *st = ldsA + wave * (32 * SPITCH);
+
+    pa.template store<0, 4>(ldsA, rl, ra, kk);
     __syncthreads();
+    bf16x8 fa[2][KS];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) fa[a][ks] = panel_fragment<!A_KC>(ldsA + pi * PANEL, a * 32, ks, lane);
+    pb.template store<0, 1>(ldsB, cl, ca, kk);
+    __syncthreads();             // first column panel in LDS; every wave holds its A fragments: the A region is free
 
-    // wave w: the whole 64 x 64 GEMM A_{p0 + w/2} B_{q + w%2}
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int pi = wave >> 1, qi = wave & 1;
-    const uint16_t *la = lds + pi * PANEL2, *lb = ldsB + qi * PANEL2;
-    const float alpha = (float)g.alpha, beta = (float)g.beta;
-    const int64_t p = p0 + pi;
-    uint16_t *st = ldsB + wave * (TN * SPITCH2);
-    typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
-
-    // multiply, park the results as bf16 in the B half (free once every wave has its products),
-    // write whole 128-byte lines of C
-    auto block = [&](int64_t q) {
-        f32x16 acc[2][2];
+    // result register r of lane l of an MFMA: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
+    auto clear = [&](f32x16 (&acc)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int r = 0; r < 16; ++r) acc[a][r] = 0.f;
+    };
+    auto read_b = [&](bf16x8 (&fb)[KS], int s) __attribute__((always_inline)) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
+        for (int ks = 0; ks < KS; ++ks) fb[ks] = panel_fragment<!B_KC>(ldsB + s * PANEL, half * 32, ks, lane);
+    };
+    auto mfma_step = [&](f32x16 (&acc)[2], const bf16x8 (&fb)[KS], int ks) __attribute__((always_inline)) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 fa[2], fb[2];
+        for (int a = 0; a < 2; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][ks], fb[ks], acc[a], 0, 0, 0);
+    };
+    // One eighth of the finished product s (4 rows x 32 columns per half wave) scaled, rounded to bf16
+    // and parked in the wave's staging area.  WITH_BETA: plus beta times the old C.
+    auto stage_part = [&](const f32x16 (&acc)[2], int s, int part, auto with_beta) __attribute__((always_inline)) {
+        const int a = part >> 2, g4 = part & 3, j = lane & 31;
+        const int i0 = a * 32 + 8 * g4 + 4 * (lane >> 5);
+        float v[4];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) fa[a] = panel2_fragment<!A_KC>(la, a * 32, ks, lane);
+        for (int e = 0; e < 4; ++e) v[e] = alpha * acc[a][4 * g4 + e];
+        if (decltype(with_beta)::value) {
+            const bool live = row_live && cb * BC + s < g.Cn;
+            if (live && j < cl[s].ext - half * 32) {
+                const uint16_t *old = Crow + cl[s].offC + (int64_t)(half * 32 + j) * g.ldc + i0;
 #pragma unroll
-            for (int c = 0; c < 2; ++c) fb[c] = panel2_fragment<!B_KC>(lb, c * 32, ks, lane);
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-                    // result register r of lane l: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[c], acc[a][c], 0, 0, 0);
-        }
-        __syncthreads();             // every wave is done with the B panels
-        const bool live = p < g.batch0 && q < g.batch1;
-        uint16_t *Cq = (uint16_t *)g.C + (live ? p * g.bsC[0] + q * g.bsC[1] : 0);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const int j = c * 32 + (lane & 31);
-#pragma unroll
-                for (int gq4 = 0; gq4 < 4; ++gq4) {
-                    const int i0 = a * 32 + 8 * gq4 + 4 * (lane >> 5);
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = alpha * acc[a][c][4 * gq4 + e];
-                    if (beta != 0.f && live && j < n) {
-                        const uint16_t *old = Cq + (int64_t)j * g.ldc + i0;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (i0 + e < m) v[e] += beta * sb_bf16_to_f32(old[e]);
-                    }
-                    u16x4 pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
-                    *(u16x4 *)(st + j * SPITCH2 + i0) = pk;
-                }
+                for (int e = 0; e < 4; ++e)
+                    if (i0 + e < rows) v[e] += beta * sb_bf16_to_f32(old[e]);
             }
-        __syncthreads();
+        }
+        u16x4 pk;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
+        *(u16x4 *)(st + j * SPITCH + i0) = pk;
+    };
+    // the staged 64 x 32 block goes to C as whole 128-byte lines
+    auto write_block = [&](int s) __attribute__((always_inline)) {
+        // the wave's own LDS accesses execute in order; the fences keep the compiler from moving them
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const bool live = row_live && cb * BC + s < g.Cn;
+        const int cols = cl[s].ext - half * 32;              // columns of this wave's half that exist
+        uint16_t *Cq = Crow + cl[s].offC + (int64_t)(half * 32) * g.ldc;
         if (live) {
-            if (vec_store) {             // m is a multiple of 8 and every column of C starts 16-byte aligned
-                const int seg = 8 * (lane & 7);
+            const int seg = 8 * (lane & 7);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const int j = 8 * t + (lane >> 3);
-                    const u16x4 lo = *(const u16x4 *)(st + j * SPITCH2 + seg);
-                    const u16x4 hi = *(const u16x4 *)(st + j * SPITCH2 + seg + 4);
-                    if (seg < m && j < n) {
-                        u16x8 o = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        *(u16x8 *)(Cq + (int64_t)j * g.ldc + seg) = o;
+            for (int t = 0; t < 4; ++t) {
+                const int jj = 8 * t + (lane >> 3);
+                const u16x4 lo = *(const u16x4 *)(st + jj * SPITCH + seg);
+                const u16x4 hi = *(const u16x4 *)(st + jj * SPITCH + seg + 4);
+                if (jj < cols) {
+                    uint16_t *dst = Cq + (int64_t)jj * g.ldc + seg;
+                    if (!RAGGED || seg + 8 <= rows) {
+                        if (seg < rows) {
+                            u32x4 o;
+                            o[0] = (unsigned)lo[0] | ((unsigned)lo[1] << 16);
+                            o[1] = (unsigned)lo[2] | ((unsigned)lo[3] << 16);
+                            o[2] = (unsigned)hi[0] | ((unsigned)hi[1] << 16);
+                            o[3] = (unsigned)hi[2] | ((unsigned)hi[3] << 16);
+                            SB_PANEL_STORE((u32x4u *)dst, o);
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            if (seg + e < rows) dst[e] = lo[e];
+                            if (seg + 4 + e < rows) dst[4 + e] = hi[e];
+                        }
                     }
-                }
-            } else {
-#pragma unroll 4
-                for (int j = 0; j < TN; ++j) {
-                    const uint16_t v = st[j * SPITCH2 + lane];
-                    if (lane < m && j < n) Cq[(int64_t)j * g.ldc + lane] = v;
                 }
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    // beta == 0: product s+1 is multiplied while product s is rounded and staged.  Its B fragments are
+    // requested first; then, in program order, every pair of MFMAs is followed by an eighth of the
+    // staging work, so the epilogue's vector-ALU and LDS work runs under the matrix core's own time.
+    auto overlapped = [&](const f32x16 (&done)[2], f32x16 (&next)[2], int s) __attribute__((always_inline)) {
+        if (cb * BC + s + 1 < g.Cn) {                        // workgroup-uniform
+            bf16x8 fb[KS];
+            read_b(fb, s + 1);
+            clear(next);
+#pragma unroll
+            for (int part = 0; part < 8; ++part) {
+                if (part < KS) mfma_step(next, fb, part);
+                stage_part(done, s, part, std::false_type());
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int part = 0; part < 8; ++part) stage_part(done, s, part, std::false_type());
+        }
+        write_block(s);
     };
 
-    block(q0 + qi);
-    if (q0 + GQ2 < g.batch1) {           // workgroup-uniform: the second block exists
-        __syncthreads();                 // the staged results of the first block have been read
-        pb2.store(ldsB, n, kk);
-        __syncthreads();
-        block(q0 + GQ2 + qi);
+    f32x16 acc0[2], acc1[2];
+    {
+        bf16x8 fb[KS];
+        read_b(fb, 0);
+        clear(acc0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) mfma_step(acc0, fb, ks);
+    }
+    pb.template store<1, 4>(ldsB, cl, ca, kk);  // the other three column panels, while the matrix cores run
+    __syncthreads();
+    // written out: s is a constant in each call, so cl[] stays in registers
+    if (beta == 0.f) {
+        overlapped(acc0, acc1, 0);
+        if (cb * BC + 1 < g.Cn) overlapped(acc1, acc0, 1);
+        if (cb * BC + 2 < g.Cn) overlapped(acc0, acc1, 2);
+        if (cb * BC + 3 < g.Cn) overlapped(acc1, acc0, 3);
+    } else {                     // beta != 0 reads C as well: one product after the other
+#pragma unroll
+        for (int s = 0; s < BC; ++s) {
+            if (cb * BC + s < g.Cn) {
+                if (s > 0) {
+                    bf16x8 fb[KS];
+                    read_b(fb, s);
+                    clear(acc0);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) mfma_step(acc0, fb, ks);
+                }
+#pragma unroll
+                for (int part = 0; part < 8; ++part) stage_part(acc0, s, part, std::true_type());
+                write_block(s);
+            }
+        }
     }
 }
 
-}  // namespace
+// ---------------------------------------------------------------------------------------------
+// host side: an sb_gemm2 problem as a panel grid
 
-static bool outer_applies(const SbArgs &a);
-
-bool sb_panel_bf16_supports(const SbArgs &a)
+FastDiv make_fastdiv(uint32_t d)            // 1 <= d < 2^31
 {
-    if (a.batch0 * a.batch1 >= ((int64_t)1 << 31)) return false;
-    if (a.m > TM || a.n > TN || a.k > KMAX || a.k <= 0) return false;
+    uint32_t l = 0;
+    while (l < 32 && ((uint64_t)1 << l) < d) ++l;
+    const uint64_t m = (((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1;
+    return FastDiv{(uint32_t)m, l};
+}
+
+struct Grid {
+    PanelArgs p;
+    bool ok;
+    bool a_kc, b_kc, ragged;
+    int64_t blocks;          // launched workgroups (padding slots included)
+    int64_t real_blocks;     // blocks that hold at least one panel pair
+    double utilisation;      // panel pairs / (16 * real blocks)
+};
+
+Grid make_grid(const SbArgs &a)
+{
+    Grid gr;
+    gr.ok = false;
+    if (a.k < 1 || a.k > KMAX || a.m < 1 || a.n < 1) return gr;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
-    if (!a_kc && a.rsA != 1) return false;
-    if (!b_kc && a.csB != 1) return false;
-    auto al = [](int64_t v) { return v % 8 == 0; };
-    // 16-byte vector loads: aligned bases and strides, whole vectors along the contiguous dimension
-    if ((uintptr_t)a.A % 16 || (uintptr_t)a.B % 16) return false;
-    if (!al(a_kc ? a.rsA : a.csA) || !al(b_kc ? a.csB : a.rsB)) return false;
-    if (!al(a.bsA[0]) || !al(a.bsA[1]) || !al(a.bsB[0]) || !al(a.bsB[1])) return false;
-    if (a_kc ? !al(a.k) : !al(a.m)) return false;
-    if (b_kc ? !al(a.k) : !al(a.n)) return false;
-    return outer_applies(a);
+    if (!a_kc && a.rsA != 1) return gr;
+    if (!b_kc && a.csB != 1) return gr;
+    PanelArgs &p = gr.p;
+    p.A = (const uint16_t *)a.A;  p.B = (const uint16_t *)a.B;  p.C = (uint16_t *)a.C;
+    Side &r = p.row, &c = p.col;
+    auto flat = [](Side &s, int64_t extent, int64_t op_stride, int64_t c_stride, int64_t ld) {
+        s.nf = (int32_t)((extent + 63) / 64);
+        s.full = extent < 64 ? (int32_t)extent : 64;
+        s.last = (int32_t)(extent - 64 * (int64_t)(s.nf - 1));
+        s.sf = 64 * op_stride;  s.cf = 64 * c_stride;
+        s.n1 = s.n2 = 1;  s.s1 = s.s2 = s.c1 = s.c2 = 0;
+        s.ld = (uint32_t)ld;
+    };
+    const int64_t ldA = a_kc ? a.rsA : a.csA, ldB = b_kc ? a.csB : a.rsB;
+    if (ldA < 0 || ldB < 0 || ldA >= ((int64_t)1 << 31) || ldB >= ((int64_t)1 << 31)) return gr;
+    if (a.m > ((int64_t)1 << 36) || a.n > ((int64_t)1 << 36)) return gr;
+    flat(r, a.m, a.rsA, 1, ldA);
+    flat(c, a.n, a.csB, a.ldc, ldB);
+    p.z0 = p.z1 = 1;
+    for (int q = 0; q < 2; ++q) p.zA[q] = p.zB[q] = p.zC[q] = 0;
+    int nz = 0;
+    const int64_t cnt[2] = {a.batch0, a.batch1};
+    for (int q = 0; q < 2; ++q) {
+        if (cnt[q] <= 1) continue;
+        if (cnt[q] >= ((int64_t)1 << 31)) return gr;
+        const bool movesA = a.bsA[q] != 0, movesB = a.bsB[q] != 0;
+        Side *s = (movesA && !movesB) ? &r : ((movesB && !movesA) ? &c : nullptr);
+        if (s) {               // this level moves one operand only: it extends that operand's side
+            const int64_t so = movesA ? a.bsA[q] : a.bsB[q];
+            if (s->n1 == 1) { s->n1 = (int32_t)cnt[q]; s->s1 = so; s->c1 = a.bsC[q]; }
+            else            { s->n2 = (int32_t)cnt[q]; s->s2 = so; s->c2 = a.bsC[q]; }
+        } else {               // both operands (or neither) move: independent grids
+            (nz == 0 ? p.z0 : p.z1) = (int32_t)cnt[q];
+            p.zA[nz] = a.bsA[q];  p.zB[nz] = a.bsB[q];  p.zC[nz] = a.bsC[q];
+            ++nz;
+        }
+    }
+    const int64_t R = (int64_t)r.nf * r.n1 * r.n2, Cn = (int64_t)c.nf * c.n1 * c.n2;
+    if (R >= ((int64_t)1 << 30) || Cn >= ((int64_t)1 << 30)) return gr;
+    p.R = (int32_t)R;  p.Cn = (int32_t)Cn;
+    p.nrb = (int32_t)((R + BR - 1) / BR);  p.ncb = (int32_t)((Cn + BC - 1) / BC);
+    const int64_t nsr = (p.nrb + 3) / 4, nsc = (p.ncb + 7) / 8;
+    p.nsc = (int32_t)nsc;
+    const int64_t per_z = nsr * nsc * 32, Z = (int64_t)p.z0 * p.z1;
+    if (per_z >= ((int64_t)1 << 31) || per_z * Z > sb_max_grid_x(NT)) return gr;
+    p.per_z = (int32_t)per_z;
+    r.dnf = make_fastdiv((uint32_t)r.nf);  r.dn1 = make_fastdiv((uint32_t)r.n1);
+    c.dnf = make_fastdiv((uint32_t)c.nf);  c.dn1 = make_fastdiv((uint32_t)c.n1);
+    p.dper_z = make_fastdiv((uint32_t)per_z);  p.dnsc = make_fastdiv((uint32_t)nsc);  p.dz0 = make_fastdiv((uint32_t)p.z0);
+    p.ldc = a.ldc;
+    p.k = (int32_t)a.k;
+    p.alpha = (float)a.alpha;  p.beta = (float)a.beta;
+    gr.a_kc = a_kc;  gr.b_kc = b_kc;
+    // whole 16-byte vectors along the contiguous direction of both operands and of C
+    gr.ragged = (a_kc ? a.k % 8 != 0 : (r.full % 8 || r.last % 8)) || (b_kc ? a.k % 8 != 0 : (c.full % 8 || c.last % 8)) ||
+                r.full % 8 || r.last % 8;
+    gr.blocks = per_z * Z;
+    gr.real_blocks = (int64_t)p.nrb * p.ncb * Z;
+    gr.utilisation = (double)(R * Cn) / (double)(16 * (int64_t)p.nrb * p.ncb);
+    gr.ok = true;
+    return gr;
 }
 
 template <bool A_KC, bool B_KC>
-static hipError_t launch_outer(const SbArgs &a, hipStream_t stream)
+hipError_t launch_grid(const Grid &gr, hipStream_t stream)
 {
-    auto al8 = [](int64_t v) { return v % 8 == 0; };
-    const int vec_store = (uintptr_t)a.C % 16 == 0 && al8(a.ldc) && al8(a.bsC[0]) && al8(a.bsC[1]) && al8(a.m);
-    const int ks = (int)((a.k + 15) / 16);
-    const int64_t groups_p = (a.batch0 + GP2 - 1) / GP2, groups_q = (a.batch1 + 2 * GQ2 - 1) / (2 * GQ2);     // two blocks along q per workgroup
-    const size_t lds_bytes = (size_t)OUTER2_LDS * sizeof(uint16_t);
-    dim3 grid((unsigned)(groups_p * groups_q)), block(OT2);
-#define SB_OUTER(KS_)                                                                                                  \
+    const size_t lds_bytes = (size_t)LDS_ELEMS * sizeof(uint16_t);
+    const dim3 grid((unsigned)gr.blocks), block(NT);
+#define SB_PANELGRID(KS_, RG_)                                                                                          \
     do {                                                                                                                \
-        auto kern = sbgemm_outer2_bf16_kernel<A_KC, B_KC, KS_>;                                                         \
-        static std::atomic<bool> configured[SB_MAX_DEVICES] = {};                                                                    \
+        auto kern = sbgemm_panelgrid_bf16_kernel<A_KC, B_KC, KS_, RG_>;                                                 \
+        static std::atomic<bool> configured[SB_MAX_DEVICES] = {};                                                       \
         const int dev = sb_current_device();                                                                            \
         if (!configured[dev]) {                                                                                         \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes); \
             if (e != hipSuccess) return e;                                                                              \
             configured[dev] = true;                                                                                     \
         }                                                                                                               \
-        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, a, (int)groups_p, vec_store);                          \
+        hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, gr.p);                                                 \
     } while (0)
-    if (ks <= 2)      SB_OUTER(2);
-    else if (ks <= 4) SB_OUTER(4);
-    else              SB_OUTER(8);
-#undef SB_OUTER
+    const bool short_k = gr.p.k <= 64;
+    if (gr.ragged) { if (short_k) SB_PANELGRID(4, true);  else SB_PANELGRID(8, true); }
+    else           { if (short_k) SB_PANELGRID(4, false); else SB_PANELGRID(8, false); }
+#undef SB_PANELGRID
     return hipGetLastError();
 }
 
-// A varies only with batch level 0 and B only with level 1 (both really vary), enough of both
-static bool outer_applies(const SbArgs &a)
+}  // namespace
+
+// Can run: bf16 (the caller checks the type), 1 <= k <= 128, each operand contiguous along k or along
+// its rows (columns), grid within launch limits.
+bool sb_panel_bf16_supports(const SbArgs &a)
 {
-    return a.batch0 >= 4 && a.batch1 >= 4 && a.bsA[1] == 0 && a.bsB[0] == 0 && a.bsA[0] != 0 && a.bsB[1] != 0 &&
-           a.batch0 * a.batch1 / (GP2 * GQ2) < ((int64_t)1 << 30);
+    return make_grid(a).ok;
+}
+
+// Should run: at least 4 panels on both sides, blocks mostly full, and enough blocks to occupy half the
+// chip (a block keeps one compute unit busy).  Smaller problems are better off on 64 x 64 tiles.
+bool sb_panel_bf16_preferred(const SbArgs &a)
+{
+    const Grid gr = make_grid(a);
+    return gr.ok && gr.p.R >= 4 && gr.p.Cn >= 4 && gr.utilisation >= 0.55 && gr.real_blocks >= 128;
 }
 
 hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream)
 {
-    const bool ak = a.csA == 1, bk = a.rsB == 1;
-    if (ak && bk)  return launch_outer<true, true>(a, stream);
-    if (ak && !bk) return launch_outer<true, false>(a, stream);
-    if (!ak && bk) return launch_outer<false, true>(a, stream);
-    return launch_outer<false, false>(a, stream);
+    const Grid gr = make_grid(a);
+    if (!gr.ok) return hipErrorInvalidValue;
+    if (gr.a_kc && gr.b_kc)  return launch_grid<true, true>(gr, stream);
+    if (gr.a_kc && !gr.b_kc) return launch_grid<true, false>(gr, stream);
+    if (!gr.a_kc && gr.b_kc) return launch_grid<false, true>(gr, stream);
+    return launch_grid<false, false>(gr, stream);
 }

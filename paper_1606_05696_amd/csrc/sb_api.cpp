@@ -31,9 +31,11 @@ int choose(sb_dtype dt, const SbArgs &a, int forced)
     if (forced == SB_KERNEL_TINY && sb_tiny_supports(dt, a)) return SB_KERNEL_TINY;
     if (forced == SB_KERNEL_MFMA && sb_mfma_supports(dt, a)) return SB_KERNEL_MFMA;
     if (forced == SB_KERNEL_THIN && sb_thin_supports(dt, a)) return SB_KERNEL_THIN;
+    if (forced == SB_KERNEL_PANEL && dt == SB_BF16 && sb_panel_bf16_supports(a)) return SB_KERNEL_PANEL;
     if (forced == SB_KERNEL_AUTO) {
         if (sb_thin_supports(dt, a) && sb_thin_preferred(dt, a)) return SB_KERNEL_THIN;
         if (sb_tiny_supports(dt, a) && sb_tiny_preferred(dt, a)) return SB_KERNEL_TINY;
+        if (dt == SB_BF16 && sb_panel_bf16_preferred(a)) return SB_KERNEL_PANEL;
         if (sb_mfma_supports(dt, a) && sb_mfma_preferred(dt, a)) return SB_KERNEL_MFMA;
     }
     return SB_KERNEL_GENERIC;
@@ -67,6 +69,7 @@ int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
     case SB_KERNEL_TINY: err = sb_launch_tiny(dt, a, stream); break;
     case SB_KERNEL_MFMA: err = sb_launch_mfma(dt, a, stream); break;
     case SB_KERNEL_THIN: err = sb_launch_thin(dt, a, stream); break;
+    case SB_KERNEL_PANEL: err = sb_launch_panel_bf16(a, stream); break;
     default:             err = sb_launch_generic(dt, a, stream); break;
     }
     g_last_kernel = kernel;
@@ -404,7 +407,7 @@ extern "C" const char *sb_status_string(int status)
 
 extern "C" int sb_force_kernel(int kernel_id)
 {
-    if (kernel_id < SB_KERNEL_AUTO || kernel_id > SB_KERNEL_THIN) return -1;
+    if (kernel_id < SB_KERNEL_AUTO || kernel_id > SB_KERNEL_PANEL) return -1;
     g_force_kernel = kernel_id;
     return SB_OK;
 }

@@ -36,7 +36,8 @@ bool sb_mfma_supports(sb_dtype dt, const SbArgs &a);
 bool sb_mfma_preferred(sb_dtype dt, const SbArgs &a);
 hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream);   // bf16 member of the MFMA family
-bool sb_panel_bf16_supports(const SbArgs &a);
+bool sb_panel_bf16_supports(const SbArgs &a);             // bf16, k <= 128: the whole-K panel-grid kernel
+bool sb_panel_bf16_preferred(const SbArgs &a);
 hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream);
 bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a);       // extended op on the first operand (MFMA family)
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);

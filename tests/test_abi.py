@@ -168,6 +168,16 @@ def test_kernel_selector():
     assert fam("bf16", "N", "N", 16, 16, 16) == MFMA
     assert fam("bf16", "N", "N", 100, 10, 16) == MFMA
     assert fam("bf16", "N", "N", 4096, 3, 64) == THIN
+    # bf16 with k <= 128 and a large C: whole-k panels, blocks of 4 x 4 panels (the flattened form of the
+    # order-3 x order-3 benchmark contraction, and its form batched over q with A shared)
+    PANEL = sb.SB_KERNEL_PANEL
+    assert fam("bf16", "N", "N", 4096, 4096, 128, 1) == PANEL
+    assert sb.sb_select_kernel("bf16", "N", "N", 4096, 64, 128, 4096, 0, 128, 128 * 64, 4096, 4096 * 64, 64) == PANEL
+    assert fam("bf16", "T", "T", 2048, 4096, 40, 1) == PANEL
+    assert fam("bf16", "N", "N", 4096, 4096, 136, 1) == MFMA      # k too long for whole-k panels
+    assert fam("bf16", "N", "N", 512, 512, 128, 1) == MFMA        # four blocks would use four compute units
+    assert fam("bf16", "N", "N", 64, 64, 128, 4096) == MFMA       # every batch moves both operands: nothing to share
+    assert fam("f32", "N", "N", 4096, 4096, 128, 1) == MFMA
     # extended operations (section III-E): on the first operand the MFMA family, on the second the general kernel
     # (with the second operand shared by the batches, as in the exceptional cases of Table II)
     assert sb.sb_select_kernel("f32", sb.SB_OP_EX_N, "N", 64, 64, 64, 64, 4096, 64, 0, 64, 4096, 8) == MFMA

@@ -21,7 +21,7 @@ from paper_1606_05696_amd import inputs
 pytestmark = pytest.mark.gpu
 
 KERNELS = {"auto": sb.SB_KERNEL_AUTO, "generic": sb.SB_KERNEL_GENERIC, "tiny": sb.SB_KERNEL_TINY, "mfma": sb.SB_KERNEL_MFMA,
-           "thin": sb.SB_KERNEL_THIN}
+           "thin": sb.SB_KERNEL_THIN, "panel": sb.SB_KERNEL_PANEL}
 
 
 @pytest.fixture(autouse=True)
@@ -45,6 +45,8 @@ def family_takes(family, dtype, m, n, k):
         return dtype in ("f32", "f64") and m <= 32 and n <= 32 and k >= 1
     if family == "mfma":
         return k >= 1
+    if family == "panel":
+        return dtype == "bf16" and 1 <= k <= 128
     raise ValueError(family)
 
 
@@ -77,9 +79,13 @@ def run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, a
     return err, got, ref
 
 
-@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+RAGGED_CASES = [(dtype, kernel) for dtype in ("f64", "f32", "bf16") for kernel in ("auto", "generic", "mfma", "panel")
+                if family_takes(kernel, dtype, 150, 77, 45)]
+assert len(RAGGED_CASES) == 10
+
+
+@pytest.mark.parametrize("dtype,kernel", RAGGED_CASES)
 @pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
-@pytest.mark.parametrize("kernel", ["auto", "generic", "mfma"])
 def test_sb_gemm_ragged_tiles(dtype, opA, opB, kernel):
     # several 64-wide tiles plus a ragged tail in every dimension, padded leading dimensions,
     # alpha and beta both active
@@ -96,11 +102,11 @@ def test_sb_gemm_ragged_tiles(dtype, opA, opB, kernel):
 
 SHAPES = [(1, 1, 1, 1), (1, 9, 5, 4), (9, 1, 5, 4), (16, 16, 16, 1000), (8, 8, 8, 70001), (33, 17, 1, 3), (5, 6, 7, 2),
           (64, 64, 64, 5), (128, 128, 96, 2), (200, 130, 260, 2)]
-# every (family, element type, shape) the family takes: 30 x auto, 30 x generic, 30 x mfma, 12 x tiny, 9 x thin
+# every (family, element type, shape) the family takes: 30 x auto, 30 x generic, 30 x mfma, 12 x tiny, 9 x thin, 9 x panel
 SHAPE_CASES = [(dtype, kernel, m, n, k, batch) for dtype in ("f64", "f32", "bf16")
-               for kernel in ("auto", "generic", "tiny", "mfma", "thin") for (m, n, k, batch) in SHAPES
+               for kernel in ("auto", "generic", "tiny", "mfma", "thin", "panel") for (m, n, k, batch) in SHAPES
                if family_takes(kernel, dtype, m, n, k)]
-assert len(SHAPE_CASES) == 111
+assert len(SHAPE_CASES) == 120
 
 
 @pytest.mark.parametrize("dtype,kernel,m,n,k,batch", SHAPE_CASES)
@@ -369,6 +375,7 @@ def test_cfg5_order3_x_order3_full_size():
         tC = to_dev(np.full(1, np.nan), "bf16").repeat(ref.size)
         sb.sb_contract(ma, mb, mc, 1.0, tA, dA, tB, dB, 0.0, tC, dC, dt="bf16")
         sync()
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL, mc
         assert_close(from_dev(tC, dC), ref, "bf16", 128, np.abs(A).max(), np.abs(B).max(), what=mc)
     # same contraction in fp32 and fp64 at reduced extents, with alpha and beta
     ext = dict(m=24, p=5, n=40, q=3, k=50)
@@ -385,11 +392,40 @@ def test_two_level_batches_with_one_operand_per_level(ma, mb, mc):
     # ragged group counts, all operand orientations, short and full k, m and n below and at 64
     for ext in (dict(m=64, n=64, p=6, q=5, k=128), dict(m=40, n=24, p=9, q=4, k=72), dict(m=64, n=48, p=4, q=7, k=32),
                 dict(m=36, n=24, p=5, q=6, k=40)):
-        for dtype in ("bf16", "f32"):
-            err, text = contract_case(dtype, ma, mb, mc, ext, seed=91)
+        for dtype, kernel in (("bf16", "panel"), ("bf16", "mfma"), ("f32", "auto")):
+            err, text = contract_case(dtype, ma, mb, mc, ext, seed=91, kernel=kernel)
             assert err <= TOL[dtype], (text, ext, err)
-            err, text = contract_case(dtype, ma, mb, mc, ext, alpha=0.5, beta=-1.0, seed=92)
+            err, text = contract_case(dtype, ma, mb, mc, ext, alpha=0.5, beta=-1.0, seed=92, kernel=kernel)
             assert err <= TOL[dtype], (text, ext, err)
+
+
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
+def test_panel_grid_kernel(opA, opB):
+    # the whole-k panel-grid kernel on plain (batched) GEMMs: several blocks of 4 x 4 panels with ragged
+    # last panels and a ragged last block, extents that are and are not whole 16-byte vectors, odd leading
+    # dimensions (vector accesses at 2-byte alignment), short and full k, a shared operand (the batch then
+    # extends the other operand's side of the grid), beta = 0 and beta != 0
+    for m, n, k, batch, pad, share in ((520, 328, 128, 2, 0, ""), (300, 200, 100, 3, 1, ""), (333, 270, 77, 2, 1, "A"),
+                                       (64, 64, 128, 37, 0, "B"), (40, 24, 72, 23, 1, "A"), (256, 512, 16, 1, 0, ""),
+                                       (257, 65, 8, 2, 1, ""), (7, 300, 3, 5, 1, "B")):
+        lda = (m if opA == "N" else k) + 3 * pad
+        ldb = (k if opB == "N" else n) + 5 * pad
+        ldc = m + 1 * pad
+        loa = 0 if share == "A" else lda * (k if opA == "N" else m) + 7 * pad
+        lob = 0 if share == "B" else ldb * (n if opB == "N" else k) + pad
+        loc = ldc * n + 11 * pad
+        for alpha, beta in ((1.0, 0.0), (0.75, -0.5)):
+            run_sb_gemm("bf16", opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed=m + n + k,
+                        kernel="panel")
+
+
+def test_panel_grid_kernel_is_selected_for_the_large_short_k_products():
+    # flat bf16 GEMMs with k <= 128 and at least 128 blocks of 256 x 256: the selector's own choice
+    err, got, ref = run_sb_gemm("bf16", "N", "N", 4096, 2048, 64, 1, 4096, 64, 4096, 0, 0, 0, 1.0, 0.0, seed=5)
+    assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL
+    err, got, ref = run_sb_gemm("bf16", "T", "N", 1024, 1024, 128, 8, 128, 128, 1024, 128 * 1024, 128 * 1024, 1024 * 1024,
+                                1.0, 0.0, seed=6)
+    assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL
 
 
 @pytest.mark.parametrize("kernel", ["auto", "generic", "mfma"])
