@@ -50,9 +50,11 @@ typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4u __attribute__((ext_vector_type(4), aligned(2)));      // global access at any element address
 
-// how a result vector goes to C (a plain 16-byte store at any element address)
+// how a result vector goes to C (a 16-byte store at any element address)
+// C is written once and not read again by this kernel: non-temporal stores let the lines stream
+// through the L2 instead of waiting there for the write-back at the end of the kernel
 #ifndef SB_PANEL_STORE
-#define SB_PANEL_STORE(ptr, value) (*(ptr) = (value))
+#define SB_PANEL_STORE(ptr, value) __builtin_nontemporal_store((value), (ptr))
 #endif
 
 constexpr int TM = 64, KMAX = 128;
@@ -62,7 +64,7 @@ constexpr int BR = 4, BC = 4;             // panels per workgroup block
 constexpr int NT = 512;                   // eight waves
 constexpr int SPITCH = 68;                // staged column: 64 rows + 8 bytes
 constexpr int LDS_ELEMS = (BR + BC) * PANEL;
-static_assert(8 * 32 * SPITCH <= BR * PANEL, "the staging areas of the eight waves fit the A region");
+static_assert(8 * 2 * 32 * SPITCH <= BR * PANEL, "two staging areas for each of the eight waves fit the A region");
 
 // Division of a number below 2^31 by a divisor fixed on the host: one multiply-high, one add, one
 // shift (Granlund and Montgomery's round-up method; with n < 2^31 the add cannot overflow).  The
@@ -125,17 +127,24 @@ __device__ __forceinline__ void locate4(const Side &s, int idx0, int count, Loc 
     const unsigned t = fdiv((unsigned)idx0, s.dnf);
     unsigned f = (unsigned)idx0 - t * (unsigned)s.nf;
     unsigned l2 = fdiv(t, s.dn1), l1 = t - l2 * (unsigned)s.n1;
+    out[0].off = (int64_t)f * s.sf + (int64_t)l1 * s.s1 + (int64_t)l2 * s.s2;
+    out[0].offC = (int64_t)f * s.cf + (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
+    out[0].ext = (int)f == s.nf - 1 ? s.last : s.full;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        if (i > 0 && idx0 + i < count) {
-            if (++f == (unsigned)s.nf) {
+    for (int i = 1; i < 4; ++i) {
+        out[i] = out[i - 1];
+        if (idx0 + i < count) {
+            if (++f < (unsigned)s.nf) {          // the next piece of the same matrix: two additions
+                out[i].off += s.sf;
+                out[i].offC += s.cf;
+            } else {                             // first piece of the next batch entry
                 f = 0;
                 if (++l1 == (unsigned)s.n1) { l1 = 0; ++l2; }
+                out[i].off = (int64_t)l1 * s.s1 + (int64_t)l2 * s.s2;
+                out[i].offC = (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
             }
+            out[i].ext = (int)f == s.nf - 1 ? s.last : s.full;
         }
-        out[i].off = (int64_t)f * s.sf + (int64_t)l1 * s.s1 + (int64_t)l2 * s.s2;
-        out[i].offC = (int64_t)f * s.cf + (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
-        out[i].ext = (int)f == s.nf - 1 ? s.last : s.full;
     }
 }
 
@@ -159,13 +168,15 @@ struct FourPanels {
         return w;
     }
 
-    // loc: the four panels; mine: the panel of this lane's 8 x 8 block (rows-contiguous operands)
+    // loc: the four panels; mine: the panel of this lane's 8 x 8 block (rows-contiguous operands).
+    // Panels P0 .. P1-1 (rows-contiguous operands: all four together, with P0 == 0).
+    template <int P0, int P1>
     __device__ __forceinline__ void load(const uint16_t *X, const Loc (&loc)[4], const Loc &mine, uint32_t ld, int kk)
     {
         const int tid = (int)threadIdx.x;
         if (KC) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 2 * P0; i < 2 * P1; ++i) {
                 const int panel = i / 2, f = tid + NT * (i % 2);
                 const int row = f / (KMAX / 8), k = (f % (KMAX / 8)) * 8;
                 const uint16_t *base = X + loc[panel].off;
@@ -179,7 +190,7 @@ struct FourPanels {
                     v[i] = *(const u32x4u *)(base + (inside ? (uint64_t)((uint32_t)row * (uint64_t)ld + k) : 0));
                 }
             }
-        } else {
+        } else if (P0 == 0) {
             const int blk = tid % 128;
             const int rg = blk % 8, kg = blk / 8;                  // rows 8 rg .. +7, k 8 kg .. +7
             const uint16_t *base = X + mine.off;
@@ -273,10 +284,12 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
     FourPanels<B_KC, RAGGED> pb;
     locate4(g.row, rb * BR, g.R, rl);
     if (!A_KC) ra = locate1(g.row, rb * BR + tid / 128, g.R);
-    pa.load(g.A + (int64_t)zi0 * g.zA[0] + (int64_t)zi1 * g.zA[1], rl, ra, g.row.ld, kk);
+    pa.template load<0, 4>(g.A + (int64_t)zi0 * g.zA[0] + (int64_t)zi1 * g.zA[1], rl, ra, g.row.ld, kk);
     locate4(g.col, cb * BC, g.Cn, cl);
     if (!B_KC) ca = locate1(g.col, cb * BC + tid / 128, g.Cn);
-    pb.load(g.B + (int64_t)zi0 * g.zB[0] + (int64_t)zi1 * g.zB[1], cl, ca, g.col.ld, kk);
+    // only the first column panel for now: the other three would queue ahead of slower waves' A loads
+    const uint16_t *Bz = g.B + (int64_t)zi0 * g.zB[0] + (int64_t)zi1 * g.zB[1];
+    pb.template load<0, 1>(Bz, cl, ca, g.col.ld, kk);
 
     // wave w: row panel w % 4, columns 32 (w / 4) .. +31 of every column panel
     const int pi = wave & 3, half = wave >> 2;
@@ -285,17 +298,17 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
     const Loc my_row = locate1(g.row, rb * BR + pi, g.R);
     const int rows = my_row.ext;
     uint16_t *Crow = g.C + (int64_t)zi0 * g.zC[0] + (int64_t)zi1 * g.zC[1] + my_row.offC;
-    uint16_t *st = ldsA + wave * (32 * SPITCH);
+    uint16_t *st = ldsA + wave * (2 * 32 * SPITCH);       // two staging areas of 32 columns each
 
     pa.template store<0, 4>(ldsA, rl, ra, kk);
-    __syncthreads();
+    pb.template store<0, 1>(ldsB, cl, ca, kk);
+    pb.template load<1, 4>(Bz, cl, ca, g.col.ld, kk);
+    __syncthreads();             // the row panels and the first column panel are in LDS
     bf16x8 fa[2][KS];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) fa[a][ks] = panel_fragment<!A_KC>(ldsA + pi * PANEL, a * 32, ks, lane);
-    pb.template store<0, 1>(ldsB, cl, ca, kk);
-    __syncthreads();             // first column panel in LDS; every wave holds its A fragments: the A region is free
 
     // result register r of lane l of an MFMA: row 8 (r/4) + 4 (l/32) + r%4, column l%32 of the 32 x 32 block
     auto clear = [&](f32x16 (&acc)[2]) __attribute__((always_inline)) {
@@ -313,7 +326,7 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
         for (int a = 0; a < 2; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a][ks], fb[ks], acc[a], 0, 0, 0);
     };
     // One eighth of the finished product s (4 rows x 32 columns per half wave) scaled, rounded to bf16
-    // and parked in the wave's staging area.  WITH_BETA: plus beta times the old C.
+    // and parked in the wave's staging area s % 2.  WITH_BETA: plus beta times the old C.
     auto stage_part = [&](const f32x16 (&acc)[2], int s, int part, auto with_beta) __attribute__((always_inline)) {
         const int a = part >> 2, g4 = part & 3, j = lane & 31;
         const int i0 = a * 32 + 8 * g4 + 4 * (lane >> 5);
@@ -332,91 +345,109 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
         u16x4 pk;
 #pragma unroll
         for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(v[e]);
-        *(u16x4 *)(st + j * SPITCH + i0) = pk;
+        *(u16x4 *)(st + (s & 1) * (32 * SPITCH) + j * SPITCH + i0) = pk;
     };
-    // the staged 64 x 32 block goes to C as whole 128-byte lines
-    auto write_block = [&](int s) __attribute__((always_inline)) {
-        // the wave's own LDS accesses execute in order; the fences keep the compiler from moving them
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+    // A quarter (8 columns) of the staged 64 x 32 block s goes to C as whole 128-byte lines.  The wave's
+    // own LDS accesses execute in order, so the staged values are there; the fences at the call sites
+    // keep the compiler from moving the reads above the writes.
+    auto write_quarter = [&](int s, int t) __attribute__((always_inline)) {
         const bool live = row_live && cb * BC + s < g.Cn;
         const int cols = cl[s].ext - half * 32;              // columns of this wave's half that exist
         uint16_t *Cq = Crow + cl[s].offC + (int64_t)(half * 32) * g.ldc;
-        if (live) {
-            const int seg = 8 * (lane & 7);
+        const uint16_t *sb = st + (s & 1) * (32 * SPITCH);
+        const int seg = 8 * (lane & 7), jj = 8 * t + (lane >> 3);
+        const u16x4 lo = *(const u16x4 *)(sb + jj * SPITCH + seg);
+        const u16x4 hi = *(const u16x4 *)(sb + jj * SPITCH + seg + 4);
+        if (live && jj < cols) {
+            uint16_t *dst = Cq + (int64_t)jj * g.ldc + seg;
+            if (!RAGGED || seg + 8 <= rows) {
+                if (seg < rows) {
+                    u32x4 o;
+                    o[0] = (unsigned)lo[0] | ((unsigned)lo[1] << 16);
+                    o[1] = (unsigned)lo[2] | ((unsigned)lo[3] << 16);
+                    o[2] = (unsigned)hi[0] | ((unsigned)hi[1] << 16);
+                    o[3] = (unsigned)hi[2] | ((unsigned)hi[3] << 16);
+                    SB_PANEL_STORE((u32x4u *)dst, o);
+                }
+            } else {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int jj = 8 * t + (lane >> 3);
-                const u16x4 lo = *(const u16x4 *)(st + jj * SPITCH + seg);
-                const u16x4 hi = *(const u16x4 *)(st + jj * SPITCH + seg + 4);
-                if (jj < cols) {
-                    uint16_t *dst = Cq + (int64_t)jj * g.ldc + seg;
-                    if (!RAGGED || seg + 8 <= rows) {
-                        if (seg < rows) {
-                            u32x4 o;
-                            o[0] = (unsigned)lo[0] | ((unsigned)lo[1] << 16);
-                            o[1] = (unsigned)lo[2] | ((unsigned)lo[3] << 16);
-                            o[2] = (unsigned)hi[0] | ((unsigned)hi[1] << 16);
-                            o[3] = (unsigned)hi[2] | ((unsigned)hi[3] << 16);
-                            SB_PANEL_STORE((u32x4u *)dst, o);
-                        }
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            if (seg + e < rows) dst[e] = lo[e];
-                            if (seg + 4 + e < rows) dst[4 + e] = hi[e];
-                        }
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    if (seg + e < rows) dst[e] = lo[e];
+                    if (seg + 4 + e < rows) dst[4 + e] = hi[e];
                 }
             }
         }
+    };
+    auto wave_fence = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
-    // beta == 0: product s+1 is multiplied while product s is rounded and staged.  Its B fragments are
-    // requested first; then, in program order, every pair of MFMAs is followed by an eighth of the
-    // staging work, so the epilogue's vector-ALU and LDS work runs under the matrix core's own time.
-    auto overlapped = [&](const f32x16 (&done)[2], f32x16 (&next)[2], int s) __attribute__((always_inline)) {
-        if (cb * BC + s + 1 < g.Cn) {                        // workgroup-uniform
-            bf16x8 fb[KS];
-            read_b(fb, s + 1);
-            clear(next);
+    auto write_block = [&](int s) __attribute__((always_inline)) {
+        wave_fence();
 #pragma unroll
-            for (int part = 0; part < 8; ++part) {
-                if (part < KS) mfma_step(next, fb, part);
-                stage_part(done, s, part, std::false_type());
-                __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < 4; ++t) write_quarter(s, t);
+        wave_fence();
+    };
+    const int nsteps = g.Cn - cb * BC < BC ? g.Cn - cb * BC : BC;       // column panels of this block (workgroup-uniform)
+    // beta == 0: three products are in flight per wave.  In program order every pair of MFMAs of product
+    // s+1 is followed by an eighth of the rounding and staging of product s and, every other time, by a
+    // quarter of the stores of product s-1 (two staging areas alternate), so the matrix core, the vector
+    // ALU, LDS and the store path work side by side instead of one after the other.
+    // fb holds the B fragments of product s+1 on entry; each one is replaced by its successor of
+    // product s+2 as soon as its MFMAs are issued, so no product starts by waiting for LDS.
+    bf16x8 fb[KS];
+    auto pipe_loop = [&](const f32x16 (&done)[2], f32x16 (&next)[2], int s, auto refill) __attribute__((always_inline)) {
+        clear(next);
+#pragma unroll
+        for (int part = 0; part < 8; ++part) {
+            if (part < KS) {
+                mfma_step(next, fb, part);
+                if (decltype(refill)::value) fb[part] = panel_fragment<!B_KC>(ldsB + (s + 2) * PANEL, half * 32, part, lane);
             }
+            stage_part(done, s, part, std::false_type());
+            if (s > 0 && (part & 1)) write_quarter(s - 1, part >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto pipelined = [&](const f32x16 (&done)[2], f32x16 (&next)[2], int s) __attribute__((always_inline)) {
+        wave_fence();
+        if (s + 2 < nsteps) {
+            pipe_loop(done, next, s, std::true_type());
+        } else if (s + 1 < nsteps) {
+            pipe_loop(done, next, s, std::false_type());
         } else {
 #pragma unroll
-            for (int part = 0; part < 8; ++part) stage_part(done, s, part, std::false_type());
+            for (int part = 0; part < 8; ++part) {
+                stage_part(done, s, part, std::false_type());
+                if (s > 0 && (part & 1)) write_quarter(s - 1, part >> 1);
+            }
         }
-        write_block(s);
     };
 
     f32x16 acc0[2], acc1[2];
-    {
-        bf16x8 fb[KS];
-        read_b(fb, 0);
-        clear(acc0);
+    read_b(fb, 0);
+    clear(acc0);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) mfma_step(acc0, fb, ks);
-    }
+    for (int ks = 0; ks < KS; ++ks) mfma_step(acc0, fb, ks);
     pb.template store<1, 4>(ldsB, cl, ca, kk);  // the other three column panels, while the matrix cores run
-    __syncthreads();
+    __syncthreads();             // they are in LDS, and every wave holds its A fragments: the A region is free for staging
+    if (nsteps > 1) read_b(fb, 1);
     // written out: s is a constant in each call, so cl[] stays in registers
     if (beta == 0.f) {
-        overlapped(acc0, acc1, 0);
-        if (cb * BC + 1 < g.Cn) overlapped(acc1, acc0, 1);
-        if (cb * BC + 2 < g.Cn) overlapped(acc0, acc1, 2);
-        if (cb * BC + 3 < g.Cn) overlapped(acc1, acc0, 3);
+        pipelined(acc0, acc1, 0);
+        if (nsteps > 1) pipelined(acc1, acc0, 1);
+        if (nsteps > 2) pipelined(acc0, acc1, 2);
+        if (nsteps > 3) pipelined(acc1, acc0, 3);
+        if (nsteps == 1) write_block(0);
+        else if (nsteps == 2) write_block(1);
+        else if (nsteps == 3) write_block(2);
+        else write_block(3);
     } else {                     // beta != 0 reads C as well: one product after the other
 #pragma unroll
         for (int s = 0; s < BC; ++s) {
-            if (cb * BC + s < g.Cn) {
+            if (s < nsteps) {
                 if (s > 0) {
-                    bf16x8 fb[KS];
-                    read_b(fb, s);
+                    if (s > 1) read_b(fb, s);                // product 1's fragments were requested above
                     clear(acc0);
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) mfma_step(acc0, fb, ks);
