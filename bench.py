@@ -4,17 +4,26 @@
 A "step" is one pass of the whole path for one contraction: sb_contract() parses the mode strings,
 plans the evaluation, selects a kernel and launches it on tensors that are already resident in
 HBM.  The headline workload is the large cube C_mnp = sum_k A_km B_knp at 512^4 in fp32 evaluated
-as one StridedBatchedGemm over p; the other benchmark contractions are timed too and reported in
-the same JSON line under "workloads".
+as one StridedBatchedGemm over p; the other benchmark contractions are timed too.
 
 Prints ONE JSON line: metric / value (GFLOP/s) / ms_per_step ..., plus
-  "roofline":     achieved vs peak for the dominant kernel (HIP events on the launch stream),
-  "cpu_baseline": the CPU oracle timed on the host cores on a bounded sample of the same workload,
-  "baselines":    the conventional evaluation on the same GPU (torch permute/copy + vendor GEMM).
+  "roofline":     achieved vs peak for the headline kernel (HIP events on the launch stream; median, min
+                  and max over at least 30 timed iterations), the HBM traffic measured with rocprofv3
+                  counters (read from profiles/bench_default_hbm_traffic.txt), and under "configs" one
+                  compact row per benchmark configuration (kernel time, achieved rate, fraction of the
+                  roofline, the same over rotating buffers for working sets the last-level cache holds);
+  "cpu_baseline": the CPU oracle timed on the host cores on a bounded sample of the same workload, with
+                  all cores and with one thread (the paper's CPU figures are serial);
+  "baselines":    the conventional evaluation on the same GPU, twice: explicit mode permutation with this
+                  library's own permute kernel followed by this library's own GEMM (same GEMM code, so the
+                  difference is the copy), and torch's permute/copy + vendor GEMM;
+  "workloads":    the details behind "configs".
+Every timed output buffer is checked afterwards: a few thousand of its elements against the oracle.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -28,14 +37,16 @@ if ROOT not in sys.path:
 PEAK = {"hbm": 8000.0,                                   # GB/s
         "mfma": {"f64": 78.6, "f32": 157.3, "bf16": 2500.0}}   # TFLOP/s, dense
 ESIZE = {"f64": 8, "f32": 4, "bf16": 2}
+UNIT_ROUNDOFF = {"f64": 2.0 ** -53, "f32": 2.0 ** -24, "bf16": 2.0 ** -24}      # of the accumulation
+OUT_ROUNDOFF = {"f64": 0.0, "f32": 0.0, "bf16": 2.0 ** -8}                        # of the stored result
+TOL = {"f64": 1e-12, "f32": 1e-5, "bf16": 2e-2}
 # which roofline binds each workload: dense high-intensity contractions are priced against the
 # matrix cores, the batch-dominated / output-dominated ones against HBM
 BOUND = {1: "hbm", 3: "hbm", 40: "mfma", 41: "mfma", 5: "hbm"}
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same counters'
-# readings for a 1 GiB copy (profiles/bench_default_hbm_traffic.txt); measured offline, not in this run
+SHORT = {1: "cfg1", 3: "cfg3", 40: "cfg4a", 41: "cfg4b", 5: "cfg5"}
 MIB = 1 << 20
-MEASURED_TRAFFIC = {41: int(1127.02 * MIB), 40: int(2564.64 * MIB), 3: int(128.14 * MIB), 5: int(41.29 * MIB),
-                    1: int(0.65 * MIB)}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "bench_default_hbm_traffic.txt")
+LLC_BYTES = 256 << 20      # Infinity Cache: working sets below this can be served without touching HBM
 
 
 def parse_args():
@@ -49,6 +60,7 @@ def parse_args():
     ap.add_argument("--no-torch-baseline", action="store_true")
     ap.add_argument("--sweeps", action="store_true",
                     help="instead of the other workloads, add the size sweeps (cubic tensors, n = 8 .. 512) to the line")
+    ap.add_argument("--sweeps-summary", default=None, help="with --sweeps: also write the sweeps as a text table to this file")
     ap.add_argument("--no-tucker", action="store_true", help="skip the Tucker/HOOI timings (tens of thousands of small launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device copy of known size (to scale rocprofv3 byte counters)")
@@ -64,9 +76,12 @@ def dev(x, dtype):
     return torch.from_numpy(flat).cuda()
 
 
+def strip(s):
+    return "".join(c for c in s if c.isalpha())
+
+
 def workload_numbers(w):
     ext = w["ext"]
-    strip = lambda s: "".join(c for c in s if c.isalpha())
     nel = lambda s: int(np.prod([ext[c] for c in strip(s)], dtype=np.int64))
     labels = set(strip(w["A"])) | set(strip(w["B"]))
     flops = 2 * int(np.prod([ext[c] for c in labels], dtype=np.int64))
@@ -90,6 +105,28 @@ def time_steps(fn, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     return (t1 - t0) * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+
+def time_stats(fn, iters=30, warmup=10, target_us=200.0, max_inner=256):
+    """Device time per launch as median / min / max over `iters` timed iterations (HIP events on the
+    launch stream).  An iteration is `inner` back-to-back launches, enough of them to last about
+    target_us, so that event resolution and launch gaps do not dominate the small workloads."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    _, probe_ms = time_steps(fn, 5, 0)
+    inner = int(min(max_inner, max(1, round(target_us / max(probe_ms * 1e3, 1e-3)))))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for e0, e1 in evs:
+        e0.record()
+        for _ in range(inner):
+            fn()
+        e1.record()
+    torch.cuda.synchronize()
+    us = np.array([e0.elapsed_time(e1) for e0, e1 in evs]) * 1e3 / inner
+    return dict(median_us=float(np.median(us)), min_us=float(us.min()), max_us=float(us.max()), iters=iters,
+                launches_per_iter=inner)
 
 
 def measured_peaks(dtypes):
@@ -116,10 +153,58 @@ def measured_peaks(dtypes):
     return out
 
 
-LLC_BYTES = 256 << 20      # Infinity Cache: working sets below this can be served without touching HBM
+def measured_traffic():
+    """HBM-side bytes per launch of each workload's kernel, from the rocprofv3 counter summary kept
+    under profiles/ (lines `workload <name> fetch_MiB write_MiB total_MiB`), with the commit it was
+    taken at.  Measured offline with the profiler, not in this run."""
+    out = {"source": os.path.relpath(TRAFFIC_FILE, ROOT), "commit": None, "bytes": {}}
+    try:
+        for ln in open(TRAFFIC_FILE):
+            f = ln.split()
+            if len(f) >= 5 and f[0] == "workload":
+                out["bytes"][f[1]] = int(float(f[4]) * MIB)
+            elif len(f) >= 2 and f[0] == "commit":
+                out["commit"] = f[1]
+    except OSError:
+        out["source"] = None
+    return out
 
 
-def run_workload(cfg, steps, warmup, torch_baseline=True):
+def check_output(tC, dimsC, modesA, A, modesB, B, modesC, dtype, nsamples=3000, seed=99):
+    """A few thousand elements of a timed output buffer against the oracle (eq. (1) at those positions):
+    relative Frobenius error of the sample and the worst element relative to the running-error bound
+    (K + 4) u K amax bmax (+ the output rounding for bf16)."""
+    import torch
+    from oracle import oracle
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.integers(0, d, nsamples) for d in dimsC], axis=1).astype(np.int64)
+    corners = np.array([[0] * len(dimsC), [d - 1 for d in dimsC]], dtype=np.int64)
+    idx = np.concatenate([idx, corners])
+    ld = np.cumprod([1] + list(dimsC[:-1])).astype(np.int64)
+    off = torch.from_numpy(idx @ ld).cuda()
+    got = tC[off].to(torch.float64).cpu().numpy()
+    ref = oracle.contract_at(strip(modesA), A, strip(modesB), B, strip(modesC), idx, wide=(dtype == "f64"))
+    K = int(np.prod([A.shape[strip(modesA).index(c)] for c in set(strip(modesA)) & set(strip(modesB))]))
+    acc = (K + 4) * UNIT_ROUNDOFF[dtype] * K * float(np.abs(A).max()) * float(np.abs(B).max())
+    bound = OUT_ROUNDOFF[dtype] * (np.abs(ref) + acc) + acc
+    den = np.linalg.norm(ref)
+    rel = float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got))
+    worst = float(np.max(np.abs(got - ref) / bound))
+    ok = bool(np.isfinite(got).all() and rel <= TOL[dtype] and worst <= 1.0)
+    return dict(samples=int(idx.shape[0]), rel_fro=rel, worst_error_over_bound=worst, ok=ok)
+
+
+def roofline_of(bound, dtype, flops, nbytes, us):
+    if bound == "mfma":
+        ach, peak, unit = flops / us / 1e6, PEAK["mfma"][dtype], "TFLOP/s"
+    else:
+        ach, peak, unit = nbytes / us / 1e3, PEAK["hbm"], "GB/s"
+    return dict(bound=bound, achieved=ach, peak=peak, unit=unit, frac=ach / peak)
+
+
+def run_workload(cfg, steps, warmup, traffic, torch_baseline=True, evaluations=None):
+    """One benchmark configuration: wall time over `steps` steps (the headline figure), kernel time as
+    median / min / max, the cold-cache variant, the output check, the conventional baselines."""
     import torch
     import paper_1606_05696_amd as sb
     from paper_1606_05696_amd import inputs
@@ -139,15 +224,16 @@ def run_workload(cfg, steps, warmup, torch_baseline=True):
 
     ms, kernel_ms = time_steps(step, steps, warmup)
     kernel = sb.sb_last_kernel()
-    out = dict(workload=w["name"], dtype=dtype, evaluation=plan.text(), kernel_family=kernel,
-               ms_per_step=ms, kernel_ms=kernel_ms, gflops=flops / ms / 1e6, flops=flops, bytes=nbytes)
+    stats = time_stats(step, iters=max(30, steps), warmup=2)
+    tC.fill_(float("nan"))
+    step()
+    check = check_output(tC, dC, ma, A, mb, B, mc, dtype)
+    out = dict(workload=w["name"], short=SHORT[cfg], dtype=dtype, evaluation=plan.text(), kernel_family=kernel,
+               ms_per_step=ms, kernel_ms=kernel_ms, kernel_us=stats, gflops=flops / ms / 1e6, flops=flops, bytes=nbytes,
+               check=check)
     bound = BOUND[cfg]
-    if bound == "mfma":
-        ach, peak, unit = flops / kernel_ms / 1e9, PEAK["mfma"][dtype], "TFLOP/s"
-    else:
-        ach, peak, unit = nbytes / kernel_ms / 1e6, PEAK["hbm"], "GB/s"
-    out["roofline"] = dict(bound=bound, achieved=ach, peak=peak, unit=unit, frac=ach / peak,
-                           traffic=MEASURED_TRAFFIC.get(cfg))
+    out["roofline"] = roofline_of(bound, dtype, flops, nbytes, kernel_ms * 1e3)
+    out["roofline"]["traffic"] = traffic["bytes"].get(SHORT[cfg])
     if bound == "hbm" and nbytes > (8 << 20) and nbytes < 2 * LLC_BYTES:
         # same launch over rotating copies of B and C whose total size is twice the last-level
         # cache, so that no launch finds its operands cached from the previous one
@@ -164,6 +250,26 @@ def run_workload(cfg, steps, warmup, torch_baseline=True):
         out["cold_cache"] = dict(kernel_ms=cold_ms, buffer_sets=nsets, achieved=nbytes / cold_ms / 1e6,
                                  frac=nbytes / cold_ms / 1e6 / PEAK["hbm"], unit="GB/s")
         del sets
+    if evaluations:
+        # the other evaluations of the same contraction (flattened / partly flattened / batched elsewhere):
+        # the flat-versus-batched comparison of section IV-B on this machine
+        rows = []
+        for name, (ea, eb, ec) in evaluations:
+            rc2, plan2 = sb.sb_contract_plan(ea, eb, ec, dA, dB)
+
+            def other():
+                sb.sb_contract(ea, eb, ec, 1.0, tA, dA, tB, dB, 0.0, tC, dC)
+
+            st = time_stats(other, iters=30, warmup=5)
+            fam = sb.sb_last_kernel()
+            tC.fill_(float("nan"))
+            other()
+            chk = check_output(tC, dC, ea, A, eb, B, ec, dtype, nsamples=1000)
+            r = roofline_of(bound, dtype, flops, nbytes, st["median_us"])
+            rows.append(dict(name=name, evaluation=plan2.text(), kernel_family=fam, kernel_us=st, achieved=r["achieved"],
+                             unit=r["unit"], frac=r["frac"], check_ok=chk["ok"]))
+        out["evaluations"] = rows
+    out["conventional_own"] = conventional_own(ma, mb, mc, ext, dtype, tA, tB, tC, flops)
     if torch_baseline:
         out["torch_matmul"] = conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops)
     del tA, tB, tC
@@ -172,9 +278,9 @@ def run_workload(cfg, steps, warmup, torch_baseline=True):
 
 
 def conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops):
-    """The conventional evaluation on the same GPU: bring the operands into matricised form
-    (explicit permute + copy where the layout needs one) and call the vendor GEMM through torch.
-    A column-major tensor with extents (d0, d1, ..) is a row-major torch tensor of shape (.., d1, d0)."""
+    """The conventional evaluation on the same GPU with the vendor's code: bring the operands into
+    matricised form (explicit permute + copy where the layout needs one) and call the vendor GEMM through
+    torch.  A column-major tensor with extents (d0, d1, ..) is a row-major torch tensor of shape (.., d1, d0)."""
     import torch
     from paper_1606_05696_amd import inputs
     w = inputs.WORKLOADS[cfg]
@@ -190,83 +296,177 @@ def conventional_baseline(cfg, tA, tB, dA, dB, dC, steps, warmup, flops):
     return dict(ms_per_step=ms, gflops=flops / ms / 1e6, how="torch.einsum('%s') + contiguous()" % expr)
 
 
-def run_table2_cases(steps, warmup):
+def matricise(ma, mb, mc):
+    """The conventional algorithm of section II-D for C_mc = A_ma B_mb with one contracted index: the tensor
+    that holds C's first mode becomes the left matrix (free modes, k), the other the right matrix
+    (k, free modes), free modes in C's order; C is permuted back if it is not (left modes, right modes).
+    Returns (left is A?, perm of the left tensor, perm of the right tensor, perm of the product back to C,
+    rows, cols); a perm is None where the tensor already has the wanted mode order."""
+    ma, mb, mc = strip(ma), strip(mb), strip(mc)
+    k = (set(ma) & set(mb)).pop()
+    left_is_a = mc[0] in ma
+    L, R = (ma, mb) if left_is_a else (mb, ma)
+    rows = [c for c in mc if c in L]
+    cols = [c for c in mc if c in R]
+    want_l, want_r, have_c = rows + [k], [k] + cols, rows + cols
+    perm = lambda have, want: None if list(have) == list(want) else [list(have).index(c) for c in want]
+    return left_is_a, perm(L, want_l), perm(R, want_r), perm(have_c, mc), rows, cols
+
+
+def conventional_own(ma, mb, mc, ext, dtype, tA, tB, tC, flops, iters=30):
+    """The conventional evaluation with THIS library's kernels: explicit mode permutations (sb_permute)
+    into matricised form, one plain GEMM (sb_gemm with batch 1: the same GEMM code the copy-free path
+    runs), a permutation of the result where needed.  kappa = number of permutation kernels."""
+    import torch
+    import paper_1606_05696_amd as sb
+    left_is_a, pl, pr, pc, rows, cols = matricise(ma, mb, mc)
+    sa, sb_, sc = strip(ma), strip(mb), strip(mc)
+    tL, tR = (tA, tB) if left_is_a else (tB, tA)
+    mL, mR = (sa, sb_) if left_is_a else (sb_, sa)
+    k = (set(sa) & set(sb_)).pop()
+    M = int(np.prod([ext[c] for c in rows], dtype=np.int64)) if rows else 1
+    N = int(np.prod([ext[c] for c in cols], dtype=np.int64)) if cols else 1
+    K = ext[k]
+    bufL = torch.empty_like(tL) if pl else tL
+    bufR = torch.empty_like(tR) if pr else tR
+    bufC = torch.empty_like(tC) if pc else tC
+    dL, dR = [ext[c] for c in mL], [ext[c] for c in mR]
+    dP = [ext[c] for c in rows + cols]
+
+    def run():
+        if pl:
+            sb.sb_permute(dL, pl, tL, bufL, dt=dtype)
+        if pr:
+            sb.sb_permute(dR, pr, tR, bufR, dt=dtype)
+        sb.sb_gemm("N", "N", M, N, K, 1.0, bufL, M, 0, bufR, K, 0, 0.0, bufC, M, 0, 1, dt=dtype)
+        if pc:
+            sb.sb_permute(dP, pc, bufC, tC, dt=dtype)
+
+    st = time_stats(run, iters=iters, warmup=3)
+    kappa = sum(1 for p in (pl, pr, pc) if p)
+    return dict(kappa=kappa, us=st["median_us"], min_us=st["min_us"], max_us=st["max_us"], gflops=flops / st["median_us"] / 1e3,
+                how="%d x sb_permute + sb_gemm(N, N, %d, %d, %d, batch 1)" % (kappa, M, N, K))
+
+
+def run_table2_cases(steps, warmup, torch_baseline=True):
     """cfg2: every order-2 x order-3 single-mode contraction (Table II) at extent 64, fp32, in the
-    evaluation SB_AUTO picks, against the conventional route (explicit permute/copy + vendor GEMM).
-    These calls are launch-bound: the figure of merit is time per call, back to back."""
+    evaluation SB_AUTO picks, against the conventional route (explicit permutation + GEMM) in this
+    library's own kernels and in torch's.  These calls are launch-bound: the figure of merit is time per
+    call, back to back.  Also 1008 enqueues in a row twice: cycling through the 36 cases (no case finds its
+    plan in the eight-entry cache, so parsing and planning are inside every call) and case by case (28
+    calls of each in a row: every call but the first finds its plan)."""
     import itertools
     import torch
     import paper_1606_05696_amd as sb
     from paper_1606_05696_amd import inputs
     n = 64
     rows = []
+    ext = dict(m=n, n=n, p=n, k=n)
     tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
+    A = inputs.uniform_tensor(21, [n, n], np.float32)
+    B = inputs.uniform_tensor(22, [n, n, n], np.float32)
+    tA, tB = dev(A, "f32"), dev(B, "f32")
+    cases = []
     for free_a in "mnp":
         rest = [c for c in "mnp" if c != free_a]
         for ma in (free_a + "k", "k" + free_a):
             for perm in itertools.permutations(["k"] + rest):
-                mb = "".join(perm)
-                tA = dev(inputs.uniform_tensor(21, [n, n], np.float32), "f32")
-                tB = dev(inputs.uniform_tensor(22, [n, n, n], np.float32), "f32")
-                rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
-
-                def ours():
-                    sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
-
-                a, b = tA.view(n, n), tB.view(n, n, n)
-                expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
-
-                def conventional():
-                    return torch.einsum(expr, a, b).contiguous()
-
-                _, t_ours = time_steps(ours, steps, warmup)
-                _, t_conv = time_steps(conventional, steps, warmup)
-                rows.append(dict(A=ma, B=mb, evaluation=plan.text(), exceptional=int(plan.exceptional),
-                                 us_per_call=t_ours * 1e3, conventional_us_per_call=t_conv * 1e3))
+                cases.append((ma, "".join(perm)))
     flops = 2 * n ** 4
+    all_ok = True
+    for ma, mb in cases:
+        rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
+
+        def ours():
+            sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+
+        st = time_stats(ours, iters=30, warmup=warmup)
+        tC.fill_(float("nan"))
+        ours()
+        chk = check_output(tC, [n, n, n], ma, A, mb, B, "mnp", "f32", nsamples=300)
+        all_ok = all_ok and chk["ok"]
+        own = conventional_own(ma, mb, "mnp", ext, "f32", tA, tB, tC, flops, iters=10)
+        row = dict(A=ma, B=mb, evaluation=plan.text(), exceptional=int(plan.exceptional), us_per_call=st["median_us"],
+                   min_us=st["min_us"], max_us=st["max_us"], kappa=own["kappa"], conventional_own_us=own["us"])
+        if torch_baseline:
+            a, b = tA.view(n, n), tB.view(n, n, n)
+            expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
+            row["conventional_torch_us"] = time_stats(lambda: torch.einsum(expr, a, b).contiguous(), iters=10, warmup=3)["median_us"]
+        rows.append(row)
+
+    def enqueue(order, cache):
+        sb.sb_plan_cache_enable(cache)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for ma, mb in order:
+            sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+        t1 = time.perf_counter()              # host time to enqueue
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        sb.sb_plan_cache_enable(True)
+        return dict(calls=len(order), host_us_per_call=(t1 - t0) * 1e6 / len(order), total_us_per_call=(t2 - t0) * 1e6 / len(order))
+
+    cycling = cases * 28                                    # 1008 calls, consecutive calls always differ
+    grouped = [c for c in cases for _ in range(28)]         # the same 1008 calls, case by case
+    enqueue(cycling[:72], True)                             # warm-up
+    back_to_back = dict(cycling_cases_plan_cache_defeated=enqueue(cycling, True), case_by_case_plan_cache_hits=enqueue(grouped, True),
+                        cycling_cases_plan_cache_off=enqueue(cycling, False))
     ours = np.array([r["us_per_call"] for r in rows])
-    conv = np.array([r["conventional_us_per_call"] for r in rows])
-    return dict(workload="cfg2: all 36 order-2 x order-3 contractions at 64^4, f32, SB_AUTO evaluation",
-                calls_timed_per_case=steps, mean_us_per_call=float(ours.mean()), max_us_per_call=float(ours.max()),
-                mean_gflops=float(flops / ours.mean() / 1e3),
-                conventional_mean_us_per_call=float(conv.mean()),
-                speedup_over_conventional_mean=float((conv / ours).mean()),
-                speedup_over_conventional_min=float((conv / ours).min()),
-                speedup_over_conventional_max=float((conv / ours).max()),
-                cases=rows)
+    own = np.array([r["conventional_own_us"] for r in rows])
+    kap = np.array([r["kappa"] for r in rows])
+    out = dict(workload="cfg2: all 36 order-2 x order-3 contractions at 64^4, f32, SB_AUTO evaluation", short="cfg2",
+               median_us_per_call=float(np.median(ours)), max_us_per_call=float(ours.max()),
+               mean_gflops=float(flops / ours.mean() / 1e3), all_outputs_ok=bool(all_ok),
+               conventional_own_mean_us={int(kv): float(own[kap == kv].mean()) for kv in sorted(set(kap))},
+               speedup_over_conventional_own_by_kappa={int(kv): float((own[kap == kv] / ours[kap == kv]).mean()) for kv in sorted(set(kap))},
+               case_1_3=next(r for r in rows if (r["A"], r["B"]) == ("mk", "nkp")),
+               case_2_4=next(r for r in rows if (r["A"], r["B"]) == ("km", "pkn")),
+               back_to_back_1008_enqueues=back_to_back, cases=rows)
+    if torch_baseline:
+        conv = np.array([r["conventional_torch_us"] for r in rows])
+        out["conventional_torch_mean_us"] = float(conv.mean())
+        out["speedup_over_conventional_torch_mean"] = float((conv / ours).mean())
+    return out
 
 
-def run_exceptional_cases(steps, warmup, n=512):
+def run_exceptional_cases(steps, warmup, n=512, torch_baseline=True):
     """Two exceptional cases of Table II (3.6 and 6.4, the ones section III-E writes out) at n^4 in
     fp32: the extended-operation kernel against the two-step route the paper benchmarks it against
-    (explicit mode transposition + GEMM, here torch permute/copy + vendor GEMM)."""
+    (explicit mode transposition + GEMM), in this library's own kernels and in torch's."""
     import torch
     import paper_1606_05696_amd as sb
     from paper_1606_05696_amd import inputs
     rows = []
-    tA = dev(inputs.uniform_tensor(31, [n, n], np.float32), "f32")
-    tB = dev(inputs.uniform_tensor(32, [n, n, n], np.float32), "f32")
+    A = inputs.uniform_tensor(31, [n, n], np.float32)
+    B = inputs.uniform_tensor(32, [n, n, n], np.float32)
+    tA, tB = dev(A, "f32"), dev(B, "f32")
     tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
     flops = 2 * n ** 4
+    ext = dict(m=n, n=n, p=n, k=n)
     for case, ma, mb in (("3.6", "nk", "pmk"), ("6.4", "kp", "nkm")):
         rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
 
         def ours():
             sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
 
-        a, b = tA.view(n, n), tB.view(n, n, n)
-        expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
-
-        def conventional():
-            return torch.einsum(expr, a, b).contiguous()
-
-        _, t_ours = time_steps(ours, steps, warmup)
+        st = time_stats(ours, iters=max(30, steps), warmup=warmup)
         family = sb.sb_last_kernel()
-        _, t_conv = time_steps(conventional, steps, warmup)
-        rows.append(dict(case=case, evaluation=plan.text(), kernel_family=family, kernel_ms=t_ours,
-                         gflops=flops / t_ours / 1e6, frac_of_fp32_mfma_peak=flops / t_ours / 1e9 / PEAK["mfma"]["f32"],
-                         conventional_ms=t_conv, speedup_over_conventional=t_conv / t_ours))
-    return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, cases=rows)
+        tC.fill_(float("nan"))
+        ours()
+        chk = check_output(tC, [n, n, n], ma, A, mb, B, "mnp", "f32", nsamples=1000)
+        own = conventional_own(ma, mb, "mnp", ext, "f32", tA, tB, tC, flops, iters=10)
+        t_ours = st["median_us"] / 1e3
+        row = dict(case=case, evaluation=plan.text(), kernel_family=family, kernel_ms=t_ours, kernel_us=st,
+                   gflops=flops / t_ours / 1e6, frac_of_fp32_mfma_peak=flops / t_ours / 1e9 / PEAK["mfma"]["f32"],
+                   check_ok=chk["ok"], conventional_own=own, speedup_over_conventional_own=own["us"] / st["median_us"])
+        if torch_baseline:
+            a, b = tA.view(n, n), tB.view(n, n, n)
+            expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
+            _, t_conv = time_steps(lambda: torch.einsum(expr, a, b).contiguous(), steps, warmup)
+            row["conventional_torch_ms"] = t_conv
+            row["speedup_over_conventional_torch"] = t_conv / t_ours
+        rows.append(row)
+    return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, short="ext-op", cases=rows)
 
 
 def run_sweeps(steps, warmup):
@@ -368,6 +568,7 @@ def run_sweeps(steps, warmup):
     return out
 
 
+
 def run_batched_gemv(steps, warmup, n=512):
     """n matrix-vector products y_p = op(A_p) x_p with n x n fp32 matrices, both layouts: the level-2 end
     of the primitive (thin kernels), bound by reading the matrices once."""
@@ -378,13 +579,14 @@ def run_batched_gemv(steps, warmup, n=512):
     tx = dev(inputs.uniform_tensor(58, [n, n], np.float32), "f32")
     ty = torch.empty(n * n, dtype=torch.float32, device="cuda")
     nbytes = 4 * (n ** 3 + 2 * n * n)
-    out = dict(workload="%d matrix-vector products of %d x %d, f32: y_[p] = op(A_[p]) x_[p]" % (n, n, n),
+    out = dict(workload="%d matrix-vector products of %d x %d, f32: y_[p] = op(A_[p]) x_[p]" % (n, n, n), short="gemv",
                algorithmic_bytes=nbytes, cases=[])
     for op in ("N", "T"):
         def ours():
             sb.sb_gemm(op, "N", n, 1, n, 1.0, tA, n, n * n, tx, n, n, 0.0, ty, n, n, n, dt="f32")
-        _, t = time_steps(ours, max(steps, 100), warmup)
-        out["cases"].append(dict(op=op, kernel_family=sb.sb_last_kernel(), us=t * 1e3, gbps=nbytes / t / 1e6,
+        st = time_stats(ours, iters=max(30, steps), warmup=warmup)
+        t = st["median_us"] / 1e3
+        out["cases"].append(dict(op=op, kernel_family=sb.sb_last_kernel(), us=st["median_us"], kernel_us=st, gbps=nbytes / t / 1e6,
                                  frac_of_hbm_peak=nbytes / t / 1e6 / PEAK["hbm"]))
     return out
 
@@ -427,9 +629,13 @@ def run_tucker(sizes=(128, 512), core=10, iterations=20, oracle_n=128, with_orac
     return dict(workload="Tucker/HOOI (Algorithm 1): cubic tensors, core %d^3, f32" % core, cases=rows)
 
 
+
 def cpu_baseline(cfg, tensors, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the workload: the leading part of the
-    last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s."""
+    last mode of C (a whole number of slices), sized from a two-slice probe to take about budget_s with
+    every core; then once more with ONE thread on a sample a tenth of that time long (the paper's CPU
+    figures are serial)."""
+    import ctypes
     from oracle import oracle
     from paper_1606_05696_amd import inputs
     w = inputs.WORKLOADS[cfg]
@@ -453,9 +659,70 @@ def cpu_baseline(cfg, tensors, budget_s=12.0):
     n = int(max(probe, min(ext[last], budget_s / max(t_probe / probe, 1e-9))))
     t = run(n) if n > probe else t_probe
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return dict(value=flops_per_slice * n / t / 1e9, unit="GFLOP/s", cores=threads, kind="oracle",
-                sample="%d of %d slices of mode %s of C (%.3g GFLOP in %.2f s, %s accumulation)"
-                       % (n, ext[last], last, flops_per_slice * n / 1e9, t, "long double" if wide else "double"))
+    acc = "long double" if wide else "double"
+    out = dict(value=flops_per_slice * n / t / 1e9, unit="GFLOP/s", cores=threads, kind="oracle",
+               sample="%d of %d slices of mode %s of C (%.3g GFLOP in %.2f s, %s accumulation)"
+                      % (n, ext[last], last, flops_per_slice * n / 1e9, t, acc))
+    try:        # the oracle's loops are OpenMP-parallel: one thread through the OpenMP runtime it is linked to
+        omp = ctypes.CDLL("libgomp.so.1")
+        omp.omp_set_num_threads(1)
+        n1 = int(max(1, min(ext[last], round(4.0 * n / max(t * threads, 1e-9)))))      # about four seconds of one core
+        t1 = run(n1)
+        omp.omp_set_num_threads(threads)
+        out["one_thread"] = dict(value=flops_per_slice * n1 / t1 / 1e9, unit="GFLOP/s", cores=1,
+                                 sample="%d slices (%.3g GFLOP in %.2f s)" % (n1, flops_per_slice * n1 / 1e9, t1))
+    except OSError:
+        out["one_thread"] = None
+    return out
+
+
+def config_rows(head, others):
+    """The compact per-configuration table under "roofline": one row per benchmark configuration (and per
+    evaluation of cfg5), kernel time as the median of the timed iterations."""
+    rows = []
+    for r in [head] + [o for o in others if "roofline" in o]:
+        rf = roofline_of(r["roofline"]["bound"], r["dtype"], r["flops"], r["bytes"], r["kernel_us"]["median_us"])
+        row = dict(config=r["short"], kernel_family=r["kernel_family"], kernel_us=r["kernel_us"]["median_us"], min_us=r["kernel_us"]["min_us"],
+                   max_us=r["kernel_us"]["max_us"], bound=rf["bound"], achieved=rf["achieved"], unit=rf["unit"], frac=rf["frac"],
+                   cold_frac=r.get("cold_cache", {}).get("frac"), traffic=r["roofline"].get("traffic"),
+                   algorithmic_bytes=r["bytes"], check_ok=r["check"]["ok"])
+        rows.append(row)
+        for e in r.get("evaluations", []):
+            rows.append(dict(config="%s %s" % (r["short"], e["name"]), kernel_family=e["kernel_family"], kernel_us=e["kernel_us"]["median_us"],
+                             min_us=e["kernel_us"]["min_us"], max_us=e["kernel_us"]["max_us"], bound=rf["bound"], achieved=e["achieved"],
+                             unit=e["unit"], frac=e["frac"], cold_frac=None, traffic=None, algorithmic_bytes=r["bytes"], check_ok=e["check_ok"]))
+    for o in others:
+        if o.get("short") == "cfg2":
+            rows.append(dict(config="cfg2 (36 cases, per call)", kernel_family=None, kernel_us=o["median_us_per_call"], min_us=None,
+                             max_us=o["max_us_per_call"], bound="launch", achieved=None, unit=None, frac=None, cold_frac=None,
+                             traffic=None, algorithmic_bytes=2113536, check_ok=o["all_outputs_ok"]))
+        elif o.get("short") == "ext-op":
+            for c in o["cases"]:
+                rows.append(dict(config="ext-op case %s 512^4" % c["case"], kernel_family=c["kernel_family"], kernel_us=c["kernel_us"]["median_us"],
+                                 min_us=c["kernel_us"]["min_us"], max_us=c["kernel_us"]["max_us"], bound="mfma", achieved=c["gflops"] / 1e3,
+                                 unit="TFLOP/s", frac=c["frac_of_fp32_mfma_peak"], cold_frac=None, traffic=None,
+                                 algorithmic_bytes=4 * (512 ** 2 + 2 * 512 ** 3), check_ok=c["check_ok"]))
+        elif o.get("short") == "gemv":
+            for c in o["cases"]:
+                rows.append(dict(config="gemv %s 512 x 512^2" % c["op"], kernel_family=c["kernel_family"], kernel_us=c["kernel_us"]["median_us"],
+                                 min_us=c["kernel_us"]["min_us"], max_us=c["kernel_us"]["max_us"], bound="hbm", achieved=c["gbps"], unit="GB/s",
+                                 frac=c["frac_of_hbm_peak"], cold_frac=None, traffic=None, algorithmic_bytes=o["algorithmic_bytes"], check_ok=None))
+    return rows
+
+
+def sweeps_text(sw):
+    """The size sweeps as a plain text table (kept under profiles/ as sweeps_summary.txt)."""
+    out = ["Size sweeps over cubic fp32 tensors (the shapes of the paper's GPU plots, section IV), one MI355X.",
+           "command: python3 bench.py --sweeps --no-cpu-baseline --no-tucker --sweeps-summary <this file>",
+           "times are microseconds per call (HIP events around back-to-back calls); kf = kernel family", ""]
+    for name, rows in sw.items():
+        keys = list(rows[0].keys())
+        out.append(name)
+        out.append("  " + " ".join("%22s" % k for k in keys))
+        for r in rows:
+            out.append("  " + " ".join("%22s" % (("%.2f" % r[k]) if isinstance(r[k], float) else r[k]) for k in keys))
+        out.append("")
+    return "\n".join(out)
 
 
 def main():
@@ -478,43 +745,57 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    head, tensors = run_workload(args.workload, args.steps, args.warmup, not args.no_torch_baseline)
+    traffic = measured_traffic()
+    tb = not args.no_torch_baseline
+    cfg5_forms = [("flat (mp)(nq)", ("(mp)k", "k(nq)", "(mp)(nq)")), ("(mp)n[q]", ("(mp)k", "kn[q]", "(mp)n[q]")),
+                  ("m[p](nq)", ("m[p]k", "k(nq)", "m[p](nq)"))]
+    cfg4_forms = [("batched in n", ("km", "k[n]p", "m[n]p")), ("flat m(np)", ("km", "k(np)", "m(np)"))]
+    forms = {5: cfg5_forms, 41: cfg4_forms}
+    head, tensors = run_workload(args.workload, args.steps, args.warmup, traffic, tb, forms.get(args.workload))
     w = inputs.WORKLOADS[args.workload]
     peaks = measured_peaks(sorted({v["dtype"] for v in inputs.WORKLOADS.values()}))
-    measured = peaks["mfma_%s_tflops" % w["dtype"]] if head["roofline"]["bound"] == "mfma" else peaks["hbm_copy_gbps"]
-    head["roofline"]["measured_peak"] = measured
-    head["roofline"]["frac_of_measured"] = head["roofline"]["achieved"] / measured
+    roof = head["roofline"]
+    measured = peaks["mfma_%s_tflops" % w["dtype"]] if roof["bound"] == "mfma" else peaks["hbm_copy_gbps"]
+    roof["measured_peak"] = measured
+    roof["frac_of_measured"] = roof["achieved"] / measured
+    roof["traffic_source"] = "%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, offline, commit %s)" % (traffic["source"], traffic["commit"])
+    roof["kernel_us"] = head["kernel_us"]
     result = {
         "metric": "GFLOP/s per contraction (StridedBatchedGemm path), 1 GPU",
         "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w["dtype"], "data": "synthetic",
         "config": {"workload": w["name"], "evaluation": head["evaluation"], "kernel_family": head["kernel_family"],
-                   "flops_per_step": head["flops"], "algorithmic_bytes_per_step": head["bytes"]},
-        "roofline": head["roofline"],
+                   "flops_per_step": head["flops"], "algorithmic_bytes_per_step": head["bytes"], "output_check": head["check"]},
+        "roofline": roof,
     }
     result["measured_peaks"] = peaks
-    if not args.no_torch_baseline:
-        result["baselines"] = {"conventional_same_gpu": head["torch_matmul"]}
+    result["baselines"] = {"conventional_same_gpu_own_kernels": head["conventional_own"]}
+    if tb:
+        result["baselines"]["conventional_same_gpu"] = head["torch_matmul"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.workload, tensors)
     del tensors
+    others = []
     if args.sweeps:
         result["sweeps"] = run_sweeps(args.steps, args.warmup)
+        if args.sweeps_summary:
+            with open(args.sweeps_summary, "w") as f:
+                f.write(sweeps_text(result["sweeps"]))
     elif not args.only_headline:
-        others = []
         for cfg in inputs.WORKLOADS:
             if cfg == args.workload:
                 continue
             steps = args.steps if cfg in (40, 41) else max(args.steps, 200)
-            r, _ = run_workload(cfg, steps, args.warmup, not args.no_torch_baseline)
+            r, _ = run_workload(cfg, steps, args.warmup, traffic, tb, forms.get(cfg))
             others.append(r)
-        others.append(run_table2_cases(max(args.steps, 200), args.warmup))
-        others.append(run_exceptional_cases(args.steps, args.warmup))
+        others.append(run_table2_cases(max(args.steps, 200), args.warmup, tb))
+        others.append(run_exceptional_cases(args.steps, args.warmup, torch_baseline=tb))
         others.append(run_batched_gemv(args.steps, args.warmup))
         if not args.no_tucker:
             others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others
+    roof["configs"] = config_rows(head, others)
     print(json.dumps(result))
 
 

@@ -186,6 +186,16 @@ int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A
  * are merged first, the rest loops on the host as in Listing 2.  -1 for an invalid plan. */
 int64_t sb_plan_launches(const sb_plan *plan);
 
+/*
+ * Out-of-place mode permutation of a packed column-major device tensor: dst mode j is src mode
+ * perm[j] (dims: extents of src).  This is the explicit copy of the CONVENTIONAL evaluation of a
+ * contraction (section II-D: permute the operands into matricised form, one GEMM, permute the
+ * result back), which the contraction entry points above exist to avoid and never call; it is
+ * exported so that a benchmark can price that copy next to the same GEMM code.  src and dst must
+ * not overlap.  Argument numbers: dt=1 order=2 dims=3 perm=4 src=5 dst=6 stream=7.
+ */
+int sb_permute(sb_dtype dt, int order, const int64_t *dims, const int *perm, const void *src, void *dst, void *stream);
+
 /* Static text for a status code returned by any function above. */
 const char *sb_status_string(int status);
 

@@ -30,7 +30,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 __all__ = [n for n in dir() if n.startswith("SB_")] + ["SB_SYM_EIG_STATIC_MAX_N"] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
-    "sb_select_kernel", "sb_plan_cache_enable", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_sym_eig_static",
+    "sb_select_kernel", "sb_plan_cache_enable", "sb_permute", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_sym_eig_static",
     "sb_probe_mfma"]
 
 
@@ -89,6 +89,8 @@ def load():
     lib.sb_status_string.argtypes = [ci]
     lib.sb_force_kernel.restype = ci
     lib.sb_force_kernel.argtypes = [ci]
+    lib.sb_permute.restype = ci
+    lib.sb_permute.argtypes = [ci, ci, i64p, ctypes.POINTER(ci), vp, vp, vp]
     lib.sb_plan_cache_enable.restype = ci
     lib.sb_plan_cache_enable.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
@@ -265,6 +267,17 @@ def sb_force_kernel(kernel_id):
 
 def sb_last_kernel():
     return load().sb_last_kernel()
+
+
+def sb_permute(dims, perm, src, dst, dt=None, stream=None, check=True):
+    """Out-of-place mode permutation of a packed device tensor (see sbgemm.h: sb_permute): dst mode j = src mode perm[j]."""
+    order = len(dims)
+    d = (ctypes.c_int64 * max(order, 1))(*[int(x) for x in dims])
+    p = (ctypes.c_int * max(order, 1))(*[int(x) for x in perm])
+    rc = load().sb_permute(_dtype_of(dt, src, dst), order, d, p, _ptr(src), _ptr(dst), _stream(stream, src))
+    if check and rc != SB_OK:
+        raise SbError("sb_permute", rc)
+    return rc
 
 
 def sb_plan_cache_enable(on):

@@ -10,7 +10,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libsbgemm.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["sb_api.cpp", "mapper.cpp", "kernels_generic.hip", "kernels_tiny.hip", "kernels_thin.hip", "kernels_mfma.hip", "kernels_mfma_bf16.hip", "kernels_panel_bf16.hip", "kernels_mfma_ex.hip", "kernels_eig.hip", "kernels_probe.hip", "tucker.cpp"]
+SOURCES = ["sb_api.cpp", "mapper.cpp", "kernels_generic.hip", "kernels_tiny.hip", "kernels_thin.hip", "kernels_mfma.hip", "kernels_mfma_bf16.hip", "kernels_panel_bf16.hip", "kernels_mfma_ex.hip", "kernels_eig.hip", "kernels_probe.hip", "kernels_permute.hip", "tucker.cpp"]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form packed fp32 arithmetic.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -388,6 +388,28 @@ extern "C" int sb_contract(sb_dtype dt, const char *modesA, const char *modesB, 
     return rc;
 }
 
+extern "C" int sb_permute(sb_dtype dt, int order, const int64_t *dims, const int *perm, const void *src, void *dst, void *stream)
+{
+    if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
+    if (order < 1 || order > SB_MAX_MODES) return -2;
+    if (!dims) return -3;
+    if (!perm) return -4;
+    bool seen[SB_MAX_MODES] = {};
+    int64_t total = 1;
+    for (int i = 0; i < order; ++i) {
+        if (dims[i] < 0) return -3;
+        if (perm[i] < 0 || perm[i] >= order || seen[perm[i]]) return -4;
+        seen[perm[i]] = true;
+        total *= dims[i];
+    }
+    if (total == 0) return SB_OK;
+    if (!src) return -5;
+    if (!dst || dst == src) return -6;
+    const hipError_t err = sb_launch_permute(dt == SB_F64 ? 8 : (dt == SB_F32 ? 4 : 2), order, dims, perm, src, dst, (hipStream_t)stream);
+    if (err == hipErrorNoBinaryForGpu) return SB_ERR_NO_DEVICE_CODE;
+    return err == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)err;
+}
+
 extern "C" const char *sb_status_string(int status)
 {
     if (status == SB_OK) return "success";

@@ -42,6 +42,9 @@ hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream);
 bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a);       // extended op on the first operand (MFMA family)
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 
+// out-of-place mode permutation of a packed tensor (benchmark baseline: the conventional evaluation's copy)
+hipError_t sb_launch_permute(int esize, int order, const int64_t *dims, const int *perm, const void *src, void *dst, hipStream_t stream);
+
 // Estimated run time of `tiles` equal tiles (area and speed relative to a 128 x 128 tile) on the chip's
 // 256 compute units: the launchers use it to choose between tile sizes.
 double sb_tile_time(int64_t tiles, double area, double gain);

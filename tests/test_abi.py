@@ -110,6 +110,18 @@ def test_sb_contract_argument_validation():
     assert c(dA=[0, 6], dB=[6, 5, 3]) == sb.SB_OK
 
 
+def test_sb_permute_argument_validation():
+    perm = lambda dims=(4, 5, 6), p=(2, 0, 1), src=FAKE, dst=FAKE + 4096, dt="f32": \
+        sb.sb_permute(list(dims), list(p), src, dst, dt=dt, stream=0, check=False)
+    assert perm(dt=9) == -1
+    assert perm(dims=(), p=()) == -2
+    assert perm(dims=(4, -1, 6)) == -3
+    assert perm(p=(0, 0, 1)) == -4 and perm(p=(0, 1, 3)) == -4
+    assert perm(src=None) == -5
+    assert perm(dst=None) == -6 and perm(dst=FAKE) == -6
+    assert perm(dims=(4, 0, 6)) == sb.SB_OK            # empty tensor: nothing to do
+
+
 def test_status_strings():
     assert sb.sb_status_string(0) == "success"
     for code in (-3, 1, 2, 3, 4, 5, 6, 1000 + 98):

@@ -495,6 +495,24 @@ def test_runs_on_a_side_stream():
     assert_close(from_dev(tC, [48, 24, 9]), ref, "f32", 40, 1.0, 1.0)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+def test_mode_permutation_is_exact(dtype):
+    # sb_permute (the copy step of the conventional evaluation, used by the benchmark's baseline) moves
+    # bits: every permutation of an order-3 tensor with ragged extents, some of order 2 and 4
+    import torch
+    cases = [((70, 33, 129), p) for p in itertools.permutations(range(3))]
+    cases += [((300, 77), (1, 0)), ((5, 1, 66, 9), (2, 0, 3, 1)), ((64, 64, 64), (1, 0, 2)), ((4100,), (0,)), ((3, 4, 5, 6), (3, 2, 1, 0))]
+    for dims, perm in cases:
+        X = inputs.make_tensor(77, list(dims), dtype)
+        tX = to_dev(X, dtype)
+        tY = torch.zeros_like(tX)
+        sb.sb_permute(dims, perm, tX, tY, dt=dtype)
+        sync()
+        want = np.transpose(quantise(X, dtype), perm)
+        got = from_dev(tY, want.shape)
+        assert np.array_equal(got, want), (dims, perm)
+
+
 def test_plan_cache_alternating_contractions():
     # sb_contract keeps the plans of the last eight distinct contractions per thread: ten different
     # ones in rotation (more than the cache holds, so entries are evicted and re-planned), same
