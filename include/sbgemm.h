@@ -111,9 +111,28 @@ int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int6
              double beta, void *C, int64_t ldc, int64_t strideC0, int64_t strideC1,
              int64_t batch0, int64_t batch1, void *stream);
 
-/* The evaluation chosen for a contraction: the arguments of one (nested) StridedBatchedGemm. */
+/*
+ * Nested batching to any depth in ONE launch (section III-F: Listing 2 with as many loops as the
+ * contraction has batched modes, and none of them on the host): nlevels <= SB_MAX_BATCH_LEVELS levels,
+ *     X_{p0,p1,..} = X + sum_l p_l * strideX[l],   p_l < batch[l],   level 0 innermost.
+ * strideA / strideB / strideC / batch are HOST arrays of nlevels entries (NULL allowed when nlevels
+ * is 0), read before the call returns.  For an SB_OP_EX_* operand strideX[0] is the stored-column
+ * stride (see sb_op) and its level-0 batch stride is 1.  Distinct index tuples must address disjoint
+ * C (checked as for sb_gemm).  Every kernel family takes two levels directly; deeper levels are a
+ * mixed-radix decode of the level-1 index inside the tiled and small-matrix kernels (the level-2
+ * kernels of SB_KERNEL_THIN and the panel kernel of SB_KERNEL_PANEL leave such nests to them).
+ * Argument numbers: dt=1 transA=2 transB=3 m=4 n=5 k=6 alpha=7 A=8 lda=9 strideA=10 B=11 ldb=12
+ * strideB=13 beta=14 C=15 ldc=16 strideC=17 nlevels=18 batch=19 stream=20.
+ */
 #define SB_MAX_MODES 8          /* largest tensor order accepted */
-#define SB_MAX_BATCH_LEVELS 8   /* batch levels 0 and 1 run inside one launch, further levels loop on the host */
+#define SB_MAX_BATCH_LEVELS 8   /* most batch levels of one call; all of them run inside one launch */
+int sb_gemm_nested(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                   double alpha, const void *A, int64_t lda, const int64_t *strideA,
+                   const void *B, int64_t ldb, const int64_t *strideB,
+                   double beta, void *C, int64_t ldc, const int64_t *strideC,
+                   int nlevels, const int64_t *batch, void *stream);
+
+/* The evaluation chosen for a contraction: the arguments of one (nested) StridedBatchedGemm. */
 typedef struct {
     int32_t nbatch;       /* number of batched modes: 0 = one flattened GEMM, 1 = one StridedBatchedGemm, >1 = nested */
     int32_t exceptional;  /* 1 if the evaluation needs an extended operation or a matrix-vector form (section III-E) */
@@ -157,9 +176,9 @@ int sb_contract_plan(const char *modesA, const char *modesB, const char *modesC,
                      sb_strategy strat, sb_plan *out);
 
 /*
- * Tensor contraction on device tensors: plans as sb_contract_plan does, then launches the plan
- * (one launch for up to two batched modes; deeper nests loop over launches on the host, as in
- * Listing 2).  No operand is copied or transposed.
+ * Tensor contraction on device tensors: plans as sb_contract_plan does, then launches the plan:
+ * ONE launch whatever the number of batched modes (the loops of Listing 2 all run inside the
+ * kernel).  No operand is copied or transposed.
  * Argument numbers: dt=1 modesA=2 modesB=3 modesC=4 alpha=5 A=6 dimsA=7 stridesA=8 B=9 dimsB=10
  * stridesB=11 beta=12 C=13 dimsC=14 stridesC=15 strat=16 stream=17.
  */
@@ -181,9 +200,9 @@ int sb_plan_cache_enable(int on);
 int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
                    double beta, void *C, void *stream);
 
-/* Host only: the number of kernel launches sb_plan_launch issues for this plan.  A launch takes two
- * batch levels; levels whose strides nest in all three tensors (adjacent modes of packed tensors)
- * are merged first, the rest loops on the host as in Listing 2.  -1 for an invalid plan. */
+/* Host only: the number of kernel launches sb_plan_launch issues for this plan: always 1 (levels whose
+ * strides nest in all three tensors are merged, the others are decoded inside the kernel).  -1 for an
+ * invalid plan. */
 int64_t sb_plan_launches(const sb_plan *plan);
 
 /*

@@ -28,7 +28,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 
 
 __all__ = [n for n in dir() if n.startswith("SB_")] + ["SB_SYM_EIG_STATIC_MAX_N"] + [
-    "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2",
+    "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2", "sb_gemm_nested",
     "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
     "sb_select_kernel", "sb_plan_cache_enable", "sb_permute", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_sym_eig_static",
     "sb_probe_mfma"]
@@ -77,6 +77,8 @@ def load():
     lib.sb_gemm2.restype = ci
     lib.sb_gemm2.argtypes = [ci, ci, ci, i64, i64, i64, dbl, vp, i64, i64, i64, vp, i64, i64, i64,
                              dbl, vp, i64, i64, i64, i64, i64, vp]
+    lib.sb_gemm_nested.restype = ci
+    lib.sb_gemm_nested.argtypes = [ci, ci, ci, i64, i64, i64, dbl, vp, i64, i64p, vp, i64, i64p, dbl, vp, i64, i64p, ci, i64p, vp]
     lib.sb_contract_plan.restype = ci
     lib.sb_contract_plan.argtypes = [cp, cp, cp, i64p, i64p, i64p, i64p, i64p, i64p, ci, ctypes.POINTER(sb_plan)]
     lib.sb_contract.restype = ci
@@ -225,6 +227,17 @@ def sb_gemm2(transA, transB, m, n, k, alpha, A, lda, strideA0, strideA1, B, ldb,
                          float(beta), _ptr(C), ldc, strideC0, strideC1, batch0, batch1, _stream(stream, C))
     if check and rc != SB_OK:
         raise SbError("sb_gemm2", rc)
+    return rc
+
+
+def sb_gemm_nested(transA, transB, m, n, k, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC, batch,
+                   dt=None, stream=None, check=True):
+    """Any number of batch levels in one launch (see sbgemm.h: sb_gemm_nested); strideX and batch are sequences, level 0 first."""
+    rc = load().sb_gemm_nested(_dtype_of(dt, A, B, C), _op(transA), _op(transB), m, n, k, float(alpha),
+                               _ptr(A), lda, _i64arr(strideA), _ptr(B), ldb, _i64arr(strideB),
+                               float(beta), _ptr(C), ldc, _i64arr(strideC), len(batch), _i64arr(batch), _stream(stream, C))
+    if check and rc != SB_OK:
+        raise SbError("sb_gemm_nested", rc)
     return rc
 
 

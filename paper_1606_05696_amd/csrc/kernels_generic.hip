@@ -25,12 +25,13 @@ __global__ __launch_bounds__(256) void sbgemm_generic_kernel(SbArgs g, int64_t t
     if (bid >= tiles * g.batch0 * g.batch1) return;          // whole workgroup leaves together
     const int64_t b = bid / tiles, tile = bid - b * tiles;
     const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
+    const SbOff3 o1 = sb_level1(g, b1);
     const int64_t tm = tile % tiles_m, tn = tile / tiles_m;
     const int64_t i0 = tm * GM, j0 = tn * GN;
 
-    const T *A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1];
-    const T *B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1];
-    T *C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+    const T *A = (const T *)g.A + b0 * g.bsA[0] + o1.a;
+    const T *B = (const T *)g.B + b0 * g.bsB[0] + o1.b;
+    T *C = (T *)g.C + b0 * g.bsC[0] + o1.c;
 
     const int t = threadIdx.x;
     const int tx = t & 15, ty = t >> 4;                      // 4 rows x 4 columns per lane

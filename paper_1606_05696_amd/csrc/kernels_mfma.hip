@@ -318,13 +318,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 
         const int64_t b = logical / tiles;
         const int tile = (int)(logical - b * tiles);
         const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
+        const SbOff3 o1 = sb_level1(g, b1);
         const int tm = tile % tiles_m, tn = tile / tiles_m;
         const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
 
         // op(A)(i,l) = A[i*rsA + l*csA]: with k contiguous the row stride is rsA, else the k stride is csA
-        const T *A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
-        const T *B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
-        T *C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+        const T *A = (const T *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
+        const T *B = (const T *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
+        T *C = (T *)g.C + b0 * g.bsC[0] + o1.c;
         const int64_t m_left = g.m - i0, n_left = g.n - j0;
 
         typename MF::Acc acc[CF::NBM][CF::NBN];
@@ -443,12 +444,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_ker
     auto locate = [&](int64_t b, int tile) {
         int64_t b0 = b, b1 = 0;
         if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
+        const SbOff3 o1 = sb_level1(g, b1);
         const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
         const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
         Loc l;
-        l.A = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
-        l.B = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
-        l.C = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1] + i0 + j0 * g.ldc;
+        l.A = (const T *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
+        l.B = (const T *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
+        l.C = (T *)g.C + b0 * g.bsC[0] + o1.c + i0 + j0 * g.ldc;
         return l;
     };
     int64_t b = logical / tiles;

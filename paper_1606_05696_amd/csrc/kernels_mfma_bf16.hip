@@ -129,12 +129,13 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
     const int64_t b = logical / tiles;
     const int tile = (int)(logical - b * tiles);
     const int64_t b1 = b / g.batch0, b0 = b - b1 * g.batch0;
+    const SbOff3 o1 = sb_level1(g, b1);
     const int tm = tile % tiles_m, tn = tile / tiles_m;
     const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
 
-    const uint16_t *A = (const uint16_t *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
-    const uint16_t *B = (const uint16_t *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
-    uint16_t *C = (uint16_t *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+    const uint16_t *A = (const uint16_t *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
+    const uint16_t *B = (const uint16_t *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
+    uint16_t *C = (uint16_t *)g.C + b0 * g.bsC[0] + o1.c;
     const int64_t ldA = A_KC ? g.rsA : g.csA;
     const int64_t ldB = B_KC ? g.csB : g.rsB;
     const int64_t kstepA = A_KC ? 1 : g.csA;
@@ -265,12 +266,13 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
     auto locate = [&](int64_t b, int tile) __attribute__((always_inline)) {
         int64_t b0 = b, b1 = 0;
         if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
+        const SbOff3 o1 = sb_level1(g, b1);
         const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
         const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
         Loc l;
-        l.A = (const uint16_t *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1] + i0 * g.rsA;
-        l.B = (const uint16_t *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1] + j0 * g.csB;
-        l.C = (uint16_t *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1] + i0 + j0 * g.ldc;
+        l.A = (const uint16_t *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
+        l.B = (const uint16_t *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
+        l.C = (uint16_t *)g.C + b0 * g.bsC[0] + o1.c + i0 + j0 * g.ldc;
         return l;
     };
     int64_t b = logical / tiles;

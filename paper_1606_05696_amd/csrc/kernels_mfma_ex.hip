@@ -86,11 +86,12 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     const int tb = (int)(logical % tiles_b); logical /= tiles_b;
     const int ti = (int)(logical % tiles_i);
     const int64_t b1 = logical / tiles_i;
+    const SbOff3 o1 = sb_level1(g, b1);
     const int64_t bb = (int64_t)tb * PB, i0 = (int64_t)ti * MB, j0 = (int64_t)tn * BN;
     const int64_t b_left = g.batch0 - bb, m_left = g.m - i0, n_left = g.n - j0;
 
-    const T *A = (const T *)g.A + bb + b1 * g.bsA[1] + i0 * g.rsA;        // batch stride of level 0 is 1
-    const T *B = (const T *)g.B + b1 * g.bsB[1] + j0 * g.csB;             // B ignores level 0 here (checked by the launcher)
+    const T *A = (const T *)g.A + bb + o1.a + i0 * g.rsA;        // batch stride of level 0 is 1
+    const T *B = (const T *)g.B + o1.b + j0 * g.csB;             // B ignores level 0 here (checked by the launcher)
     const int64_t ldB = B_KC ? g.csB : g.rsB, kstepB = B_KC ? 1 : g.rsB;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
             const int rho = rho0 + a * MI + (lane % MI);
             const int bl = rho / MB, il = rho % MB;
             if (GUARD && (bl >= b_left || il >= m_left)) continue;
-            T *Cb = (T *)g.C + (bb + bl) * g.bsC[0] + b1 * g.bsC[1] + (i0 + il);
+            T *Cb = (T *)g.C + (bb + bl) * g.bsC[0] + o1.c + (i0 + il);
 #pragma unroll
             for (int c = 0; c < NBN; ++c) {
                 const int64_t jl = j0 + c * MI + MF::row_lane(lane);

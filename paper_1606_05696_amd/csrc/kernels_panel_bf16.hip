@@ -484,7 +484,7 @@ Grid make_grid(const SbArgs &a)
 {
     Grid gr;
     gr.ok = false;
-    if (a.k < 1 || a.k > KMAX || a.m < 1 || a.n < 1) return gr;
+    if (a.k < 1 || a.k > KMAX || a.m < 1 || a.n < 1 || a.nx > 0) return gr;
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
     if (!a_kc && a.rsA != 1) return gr;
     if (!b_kc && a.csB != 1) return gr;

@@ -409,6 +409,7 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
 
 bool sb_thin_supports(sb_dtype, const SbArgs &a)
 {
+    if (a.nx > 0) return false;             // two batch levels here; deeper nests run on the tiled kernels
     const int64_t lo = a.m < a.n ? a.m : a.n;
     return lo >= 1 && lo <= 4;
 }

@@ -117,9 +117,10 @@ __global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int
             live[u] = b < total;
             const int64_t bb = live[u] ? b : 0;
             const int64_t b1 = bb / g.batch0, b0 = bb - b1 * g.batch0;
-            Ap[u] = (const T *)g.A + b0 * g.bsA[0] + b1 * g.bsA[1];
-            Bp[u] = (const T *)g.B + b0 * g.bsB[0] + b1 * g.bsB[1];
-            Cp[u] = (T *)g.C + b0 * g.bsC[0] + b1 * g.bsC[1];
+            const SbOff3 o1 = sb_level1(g, b1);
+            Ap[u] = (const T *)g.A + b0 * g.bsA[0] + o1.a;
+            Bp[u] = (const T *)g.B + b0 * g.bsB[0] + o1.b;
+            Cp[u] = (T *)g.C + b0 * g.bsC[0] + o1.c;
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
@@ -250,7 +251,7 @@ hipError_t launch3(const SbArgs &a, hipStream_t stream)
 {
     const int64_t total = a.batch0 * a.batch1;
     constexpr int U = (TM * TN == 1) ? 4 : (TM * TN == 2 ? 2 : 1);
-    const bool hoist = (a.bsA[0] == 0 || a.batch0 == 1) && (a.bsA[1] == 0 || a.batch1 == 1) && a.k <= 16;
+    const bool hoist = (a.bsA[0] == 0 || a.batch0 == 1) && (a.bsA[1] == 0 || a.batch1 == 1) && a.nx == 0 && a.k <= 16;
     // vector accesses need no alignment beyond the element's (leading dimensions and offsets may be odd)
     const int vec_a = A_KC, vec_b = B_KC, vec_c = 1;
     // enough workgroups to fill the chip several waves deep, no more than the work needs

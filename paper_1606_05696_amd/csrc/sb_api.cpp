@@ -41,16 +41,18 @@ int choose(sb_dtype dt, const SbArgs &a, int forced)
     return SB_KERNEL_GENERIC;
 }
 
-// No two (i, j, p, q) may address the same element of C.  Sufficient test: sorted by stride, each of
-// the four directions (rows, columns, two batch levels) steps over everything the smaller ones span.
-// Batches interleaved inside one tensor (C_m[n]p: batch stride below ldc) pass.  Returns 0 if C is
-// fine, else which stride is too small: 1 = ldc, 2 = level-0 batch stride, 3 = level-1 batch stride.
-int c_overlap(int64_t m, int64_t n, int64_t ldc, int64_t stride0, int64_t batch0, int64_t stride1, int64_t batch1)
+// No two index tuples (i, j, p0, p1, ..) may address the same element of C.  Sufficient test: sorted by
+// stride, each direction (rows, columns, every batch level) steps over everything the smaller ones
+// span.  Batches interleaved inside one tensor (C_m[n]p: batch stride below ldc) pass.  Returns -1 if C
+// is fine, -2 if ldc is too small, else the batch level whose stride is too small.
+int c_overlap(int64_t m, int64_t n, int64_t ldc, int nlevels, const int64_t *stride, const int64_t *count)
 {
-    struct Dir { int64_t stride, extent; int which; } d[4] = {{1, m, 1}, {ldc, n, 1}, {stride0, batch0, 2}, {stride1, batch1, 3}};
+    struct Dir { int64_t stride, extent; int which; } d[2 + SB_MAX_BATCH_LEVELS];
     int nd = 0;
-    for (int q = 0; q < 4; ++q)
-        if (d[q].extent > 1) d[nd++] = d[q];
+    if (m > 1) d[nd++] = Dir{1, m, -2};
+    if (n > 1) d[nd++] = Dir{ldc, n, -2};
+    for (int l = 0; l < nlevels; ++l)
+        if (count[l] > 1) d[nd++] = Dir{stride[l], count[l], l};
     for (int a = 1; a < nd; ++a)
         for (int b = a; b > 0 && d[b].stride < d[b - 1].stride; --b) std::swap(d[b], d[b - 1]);
     int64_t span = 0;                      // largest offset reachable with the directions seen so far
@@ -58,7 +60,7 @@ int c_overlap(int64_t m, int64_t n, int64_t ldc, int64_t stride0, int64_t batch0
         if (q > 0 && d[q].stride <= span) return d[q].which;
         span += (d[q].extent - 1) * d[q].stride;
     }
-    return 0;
+    return -1;
 }
 
 int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
@@ -79,43 +81,59 @@ int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 
 }  // namespace
 
-extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
-                        double alpha, const void *A, int64_t lda, int64_t strideA0, int64_t strideA1,
-                        const void *B, int64_t ldb, int64_t strideB0, int64_t strideB1,
-                        double beta, void *C, int64_t ldc, int64_t strideC0, int64_t strideC1,
-                        int64_t batch0, int64_t batch1, void *stream)
+namespace {
+
+// Shared body of sb_gemm2 / sb_gemm_nested: validation, normalisation, launch.  Returns the status in
+// sb_gemm_nested's argument numbering; *level receives the batch level a stride or count error refers to.
+int gemm_levels(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                double alpha, const void *A, int64_t lda, const int64_t *strideA,
+                const void *B, int64_t ldb, const int64_t *strideB,
+                double beta, void *C, int64_t ldc, const int64_t *strideC,
+                int nlevels, const int64_t *batch, void *stream, int *level)
 {
+    *level = 0;
     if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
     if (!valid_op(transA)) return -2;
     if (!valid_op(transB)) return -3;
     if (m < 0) return -4;
     if (n < 0) return -5;
     if (k < 0) return -6;
-    if (batch0 < 0) return -21;
-    if (batch1 < 0) return -22;
-    if (m == 0 || n == 0 || batch0 == 0 || batch1 == 0) return SB_OK;
+    if (nlevels < 0 || nlevels > SB_MAX_BATCH_LEVELS) return -18;
+    if (nlevels > 0 && !batch) return -19;
+    if (nlevels > 0 && !strideA) return -10;
+    if (nlevels > 0 && !strideB) return -13;
+    if (nlevels > 0 && !strideC) return -17;
+    bool empty = (m == 0 || n == 0);
+    for (int l = 0; l < nlevels; ++l) {
+        *level = l;
+        if (batch[l] < 0) return -19;
+        if (batch[l] == 0) empty = true;
+    }
+    *level = 0;
+    if (empty) return SB_OK;
     const bool use_ab = (k > 0 && alpha != 0.0);
     // leading dimensions: at least the number of stored rows (N/T), at least 1 (extended)
     const int64_t rowsA = is_ex(transA) ? 1 : (transA == SB_OP_N ? m : k);
     const int64_t rowsB = is_ex(transB) ? 1 : (transB == SB_OP_N ? k : n);
+    // an extended operand reads its stored-column stride from level 0's slot even when there are no levels
+    const int64_t sA0 = nlevels > 0 ? strideA[0] : 0, sB0 = nlevels > 0 ? strideB[0] : 0;
     if (use_ab && !A) return -8;
     if (lda < std::max<int64_t>(1, rowsA)) return -9;
-    if (strideA0 < 0 || (is_ex(transA) && strideA0 < 1)) return -10;
-    if (strideA1 < 0) return -11;
-    if (use_ab && !B) return -12;
-    if (ldb < std::max<int64_t>(1, rowsB)) return -13;
-    if (strideB0 < 0 || (is_ex(transB) && strideB0 < 1)) return -14;
-    if (strideB1 < 0) return -15;
-    if (!C) return -17;
-    if (ldc < std::max<int64_t>(1, m)) return -18;
-    if (strideC0 < 0 || (strideC0 == 0 && batch0 > 1)) return -19;
-    if (strideC1 < 0 || (strideC1 == 0 && batch1 > 1)) return -20;
-    switch (c_overlap(m, n, ldc, strideC0, batch0, strideC1, batch1)) {
-    case 1: return -18;
-    case 2: return -19;
-    case 3: return -20;
-    default: break;
-    }
+    for (int l = 0; l < nlevels; ++l)
+        if (strideA[l] < 0) { *level = l; return -10; }
+    if (is_ex(transA) && sA0 < 1) return -10;
+    if (use_ab && !B) return -11;
+    if (ldb < std::max<int64_t>(1, rowsB)) return -12;
+    for (int l = 0; l < nlevels; ++l)
+        if (strideB[l] < 0) { *level = l; return -13; }
+    if (is_ex(transB) && sB0 < 1) return -13;
+    if (!C) return -15;
+    if (ldc < std::max<int64_t>(1, m)) return -16;
+    for (int l = 0; l < nlevels; ++l)
+        if (strideC[l] < 0 || (strideC[l] == 0 && batch[l] > 1)) { *level = l; return -17; }
+    const int ov = c_overlap(m, n, ldc, nlevels, strideC, batch);
+    if (ov == -2) return -16;
+    if (ov >= 0) { *level = ov; return -17; }
 
     SbArgs a;
     std::memset(&a, 0, sizeof(a));
@@ -123,13 +141,68 @@ extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int6
     a.m = m;  a.n = n;
     a.k = use_ab ? k : 0;                  // alpha == 0: A and B are not read, C = beta*C
     a.alpha = alpha;  a.beta = beta;
-    op_strides(transA, lda, strideA0, a.rsA, a.csA, a.bsA[0]);
-    op_strides(transB, ldb, strideB0, a.rsB, a.csB, a.bsB[0]);
-    a.bsA[1] = strideA1;  a.bsB[1] = strideB1;
+    op_strides(transA, lda, sA0, a.rsA, a.csA, a.bsA[0]);
+    op_strides(transB, ldb, sB0, a.rsB, a.csB, a.bsB[0]);
     a.ldc = ldc;
-    a.bsC[0] = strideC0;  a.bsC[1] = strideC1;
-    a.batch0 = batch0;  a.batch1 = batch1;
+    a.bsC[0] = nlevels > 0 ? strideC[0] : 0;
+    a.batch0 = nlevels > 0 ? batch[0] : 1;
+    a.batch1 = 1;
+    a.cnt1 = 1;
+    // levels of extent 1 above level 0 drop out; the first remaining one is level 1, the rest fold into its index
+    bool have1 = false;
+    for (int l = 1; l < nlevels; ++l) {
+        if (batch[l] == 1) continue;
+        if (!have1) {
+            have1 = true;
+            a.bsA[1] = strideA[l];  a.bsB[1] = strideB[l];  a.bsC[1] = strideC[l];
+            a.cnt1 = batch[l];
+        } else {
+            a.xcnt[a.nx] = batch[l];
+            a.xsA[a.nx] = strideA[l];  a.xsB[a.nx] = strideB[l];  a.xsC[a.nx] = strideC[l];
+            ++a.nx;
+        }
+        if (a.batch1 > (((int64_t)1 << 62) / batch[l])) { *level = l; return -19; }
+        a.batch1 *= batch[l];
+    }
     return run(dt, a, (hipStream_t)stream);
+}
+
+}  // namespace
+
+extern "C" int sb_gemm_nested(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                              double alpha, const void *A, int64_t lda, const int64_t *strideA,
+                              const void *B, int64_t ldb, const int64_t *strideB,
+                              double beta, void *C, int64_t ldc, const int64_t *strideC,
+                              int nlevels, const int64_t *batch, void *stream)
+{
+    int level = 0;
+    return gemm_levels(dt, transA, transB, m, n, k, alpha, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+                       nlevels, batch, stream, &level);
+}
+
+extern "C" int sb_gemm2(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
+                        double alpha, const void *A, int64_t lda, int64_t strideA0, int64_t strideA1,
+                        const void *B, int64_t ldb, int64_t strideB0, int64_t strideB1,
+                        double beta, void *C, int64_t ldc, int64_t strideC0, int64_t strideC1,
+                        int64_t batch0, int64_t batch1, void *stream)
+{
+    const int64_t sA[2] = {strideA0, strideA1}, sB[2] = {strideB0, strideB1}, sC[2] = {strideC0, strideC1};
+    const int64_t cnt[2] = {batch0, batch1};
+    int level = 0;
+    const int rc = gemm_levels(dt, transA, transB, m, n, k, alpha, A, lda, sA, B, ldb, sB, beta, C, ldc, sC, 2, cnt, stream, &level);
+    if (rc >= 0) return rc;
+    // sb_gemm_nested's argument positions -> sb_gemm2's (each array argument became two scalars)
+    switch (-rc) {
+    case 10: return -(10 + level);
+    case 11: return -12;
+    case 12: return -13;
+    case 13: return -(14 + level);
+    case 15: return -17;
+    case 16: return -18;
+    case 17: return -(19 + level);
+    case 19: return -(21 + level);
+    default: return rc;                 // 1 .. 9 keep their positions
+    }
 }
 
 extern "C" int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t m, int64_t n, int64_t k,
@@ -147,9 +220,9 @@ extern "C" int sb_select_kernel(sb_dtype dt, sb_op transA, sb_op transB, int64_t
     if (ldc < m) return -11;
     if (strideC < 0 || (strideC == 0 && batch > 1)) return -12;
     if (batch < 1) return -13;
-    switch (c_overlap(m, n, ldc, strideC, batch, 0, 1)) {
-    case 1: return -11;
-    case 2: return -12;
+    switch (c_overlap(m, n, ldc, 1, &strideC, &batch)) {
+    case -2: return -11;
+    case 0: return -12;
     default: break;
     }
     SbArgs a;
@@ -182,8 +255,9 @@ namespace {
 
 // The batch levels of a plan as the launcher sees them.  Two levels whose strides nest in all
 // three tensors (stride_outer == stride_inner * count_inner, or both 0) are one level with the
-// product of the counts, so an N-level nest over adjacent modes of packed tensors still fits the
-// two levels a launch can take; what cannot be merged below two levels loops on the host (Listing 2).
+// product of the counts: fewer digits for the kernels to decode, and more problems for the kernels
+// that only take two levels.  Whatever remains runs in the same single launch (Listing 2 without
+// its host loop).
 struct Levels {
     int n;
     int64_t count[SB_MAX_BATCH_LEVELS], sL[SB_MAX_BATCH_LEVELS], sR[SB_MAX_BATCH_LEVELS], sC[SB_MAX_BATCH_LEVELS];
@@ -229,10 +303,7 @@ Levels merged_levels(const sb_plan &plan)
 extern "C" int64_t sb_plan_launches(const sb_plan *plan)
 {
     if (!plan || plan->nbatch < 0 || plan->nbatch > SB_MAX_BATCH_LEVELS) return -1;
-    const Levels lv = merged_levels(*plan);
-    int64_t outer = 1;
-    for (int q = 2; q < lv.n; ++q) outer *= lv.count[q];
-    return outer;
+    return 1;
 }
 
 extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, const void *A, const void *B,
@@ -240,48 +311,23 @@ extern "C" int sb_plan_launch(sb_dtype dt, const sb_plan *plan, double alpha, co
 {
     if ((int)dt < SB_F64 || (int)dt > SB_BF16) return -1;
     if (!plan || plan->nbatch < 0 || plan->nbatch > SB_MAX_BATCH_LEVELS) return -2;
-    const size_t esz = (dt == SB_F64) ? 8 : (dt == SB_F32 ? 4 : 2);
-    const char *L = (const char *)(plan->left_is_B ? B : A);
-    const char *R = (const char *)(plan->left_is_B ? A : B);
-    char *Cb = (char *)C;
-    const Levels lv = merged_levels(*plan);
-    const int nb = lv.n;
-    // levels 0 and 1 run inside the launch; an extended operand passes its stored-column stride
-    // in place of the (implied, unit) level-0 batch stride
-    const int64_t b0 = nb > 0 ? lv.count[0] : 1, b1 = nb > 1 ? lv.count[1] : 1;
+    const void *L = plan->left_is_B ? B : A;
+    const void *R = plan->left_is_B ? A : B;
+    Levels lv = merged_levels(*plan);
+    // an extended operand passes its stored-column stride in place of the (implied, unit) level-0 batch stride
     const bool exL = plan->opL > SB_OP_T, exR = plan->opR > SB_OP_T;
-    const int64_t sL0 = exL ? plan->exL : (nb > 0 ? lv.sL[0] : 0);
-    const int64_t sR0 = exR ? plan->exR : (nb > 0 ? lv.sR[0] : 0);
-    const int64_t sC0 = nb > 0 ? lv.sC[0] : 0;
-    const int64_t sL1 = nb > 1 ? lv.sL[1] : 0, sR1 = nb > 1 ? lv.sR[1] : 0, sC1 = nb > 1 ? lv.sC[1] : 0;
-    // deeper levels: an odometer of host-side launches (Listing 2)
-    int64_t idx[SB_MAX_BATCH_LEVELS] = {0};
-    int64_t outer = 1;
-    for (int q = 2; q < nb; ++q) outer *= lv.count[q];
-    for (int64_t it = 0; it < outer; ++it) {
-        int64_t oL = 0, oR = 0, oC = 0;
-        for (int q = 2; q < nb; ++q) {
-            oL += idx[q] * lv.sL[q];
-            oR += idx[q] * lv.sR[q];
-            oC += idx[q] * lv.sC[q];
-        }
-        int rc = sb_gemm2(dt, (sb_op)plan->opL, (sb_op)plan->opR, plan->m, plan->n, plan->k, alpha,
-                          L ? L + oL * esz : nullptr, plan->ldL, sL0, sL1,
-                          R ? R + oR * esz : nullptr, plan->ldR, sR0, sR1,
-                          beta, Cb ? Cb + oC * esz : nullptr, plan->ldC, sC0, sC1, b0, b1, stream);
-        if (rc > 0) return rc;
-        if (rc < 0) {            // map the failing sb_gemm2 argument back to this function's
-            int p = -rc;
-            if (p >= 8 && p <= 15) return (((p <= 11) != (plan->left_is_B != 0)) ? -4 : -5);
-            if (p >= 17 && p <= 20) return -7;
-            return -2;
-        }
-        for (int q = 2; q < nb; ++q) {
-            if (++idx[q] < lv.count[q]) break;
-            idx[q] = 0;
-        }
-    }
-    return SB_OK;
+    if (lv.n == 0 && (exL || exR)) { lv.n = 1; lv.count[0] = 1; lv.sL[0] = lv.sR[0] = lv.sC[0] = 0; }
+    if (exL) lv.sL[0] = plan->exL;
+    if (exR) lv.sR[0] = plan->exR;
+    int level = 0;
+    const int rc = gemm_levels(dt, (sb_op)plan->opL, (sb_op)plan->opR, plan->m, plan->n, plan->k, alpha, L, plan->ldL, lv.sL,
+                               R, plan->ldR, lv.sR, beta, C, plan->ldC, lv.sC, lv.n, lv.count, stream, &level);
+    if (rc >= 0) return rc;
+    // map the failing argument back to this function's: operands 8..13 -> A (4) or B (5), C 15..17 -> 7
+    const int p = -rc;
+    if (p >= 8 && p <= 13) return (((p <= 10) != (plan->left_is_B != 0)) ? -4 : -5);
+    if (p >= 15 && p <= 17) return -7;
+    return -2;
 }
 
 namespace {

@@ -18,7 +18,34 @@ struct SbArgs {
     int64_t bsA[2], bsB[2], bsC[2];
     int64_t batch0, batch1;
     double alpha, beta;
+    // Nests deeper than two levels (section III-F, Listing 2 with more loops): the level-1 index q is a
+    // mixed-radix number.  Its lowest digit (extent cnt1) is level 1 proper with strides bsX[1]; the
+    // nx further digits (extents xcnt[]) are the outer levels with strides xsX[].  batch1 is the
+    // product of all these extents, so every kernel still sees two levels; nx == 0 is the plain case.
+    int32_t nx;
+    int64_t cnt1;
+    int64_t xcnt[SB_MAX_BATCH_LEVELS - 2], xsA[SB_MAX_BATCH_LEVELS - 2], xsB[SB_MAX_BATCH_LEVELS - 2], xsC[SB_MAX_BATCH_LEVELS - 2];
 };
+
+// element offsets that level-1 index q adds to the three pointers
+struct SbOff3 { int64_t a, b, c; };
+__host__ __device__ inline SbOff3 sb_level1(const SbArgs &g, int64_t q)
+{
+    SbOff3 o;
+    if (g.nx == 0) {
+        o.a = q * g.bsA[1];  o.b = q * g.bsB[1];  o.c = q * g.bsC[1];
+        return o;
+    }
+    int64_t rest = q / g.cnt1;
+    const int64_t d1 = q - rest * g.cnt1;
+    o.a = d1 * g.bsA[1];  o.b = d1 * g.bsB[1];  o.c = d1 * g.bsC[1];
+    for (int x = 0; x < g.nx; ++x) {
+        const int64_t up = rest / g.xcnt[x], d = rest - up * g.xcnt[x];
+        o.a += d * g.xsA[x];  o.b += d * g.xsB[x];  o.c += d * g.xsC[x];
+        rest = up;
+    }
+    return o;
+}
 
 // Each launcher returns a hipError_t (0 = launched).  The *_supports predicates say whether a
 // kernel family can run the problem at all; the selector decides whether it should.

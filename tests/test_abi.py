@@ -90,6 +90,24 @@ def test_sb_gemm2_argument_validation():
     assert g2(b1=0) == sb.SB_OK
 
 
+def test_sb_gemm_nested_argument_validation():
+    def gn(**over):
+        a = dict(sA=[0, 0, 0], sB=[30, 90, 180], sC=[20, 60, 120], cnt=[3, 2, 2], lda=4, ldb=6, ldc=4, A=FAKE, B=FAKE, C=FAKE)
+        a.update(over)
+        return sb.sb_gemm_nested("N", "N", 4, 5, 6, 1.0, a["A"], a["lda"], a["sA"], a["B"], a["ldb"], a["sB"], 0.0, a["C"], a["ldc"],
+                                 a["sC"], a["cnt"], dt=sb.SB_F32, stream=0, check=False)
+    assert gn(sA=[0, -1, 0]) == -10
+    assert gn(sB=[30, 90, -5]) == -13
+    assert gn(sC=[20, 60, 0]) == -17                # two batches of level 2 coincide
+    assert gn(sC=[20, 60, 119]) == -17              # ... or overlap
+    assert gn(sC=[20, 59, 120]) == -17
+    assert gn(cnt=[3, -2, 2]) == -19
+    assert gn(ldc=3) == -16
+    assert gn(C=None) == -15
+    assert gn(cnt=[3, 0, 2]) == sb.SB_OK            # an empty level: nothing to do
+    assert gn(cnt=[3, 2, 2, 1, 1, 1, 1, 1, 1], sA=[0] * 9, sB=[0] * 9, sC=[1] * 9) == -18     # more than SB_MAX_BATCH_LEVELS
+
+
 def test_sb_contract_argument_validation():
     def c(**over):
         a = dict(dt=sb.SB_F32, A="mk", B="knp", C="mnp", dA=[4, 6], dB=[6, 5, 3], pa=FAKE, pb=FAKE, pc=FAKE, strat=0)

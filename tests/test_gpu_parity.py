@@ -458,6 +458,55 @@ def test_three_and_four_level_nests():
         assert err <= TOL["f32"], (text, err)
 
 
+NESTED_CASES = [("f32", "generic", "N", "T", 37, 21, 13), ("f64", "tiny", "T", "N", 16, 9, 20), ("f32", "tiny", "N", "N", 32, 32, 8),
+                ("f32", "mfma", "N", "N", 70, 40, 24), ("f64", "mfma", "T", "N", 128, 128, 64), ("f32", "mfma", "T", "N", 128, 256, 96),
+                ("bf16", "mfma", "T", "N", 128, 128, 256), ("bf16", "mfma", "N", "T", 50, 90, 40), ("bf16", "generic", "N", "N", 20, 30, 10),
+                ("f32", "auto", "N", "N", 3, 50, 64), ("bf16", "auto", "N", "N", 64, 64, 128)]
+
+
+@pytest.mark.parametrize("dtype,kernel,opA,opB,m,n,k", NESTED_CASES)
+def test_sb_gemm_nested_four_levels_in_one_launch(dtype, kernel, opA, opB, m, n, k):
+    # section III-F with four batched modes and no loop on the host: levels whose strides do not nest in any
+    # tensor (C's levels are laid out in another order than they are counted, A skips two of them, B one),
+    # through every kernel family that decodes deep nests, against Listing 1 applied per outer index
+    cnt = [3, 2, 4, 2]
+    rng = np.random.default_rng(m + n + k)
+    lda = (m if opA == "N" else k) + 1
+    ldb = (k if opB == "N" else n) + 2
+    ldc = m + 3
+    sizeA, sizeB, sizeC = lda * (k if opA == "N" else m), ldb * (n if opB == "N" else k), ldc * n
+    # C: level order 2, 0, 3, 1 from the inside out, with a little padding
+    sC, step = [0] * 4, sizeC + 5
+    for l in (2, 0, 3, 1):
+        sC[l] = step
+        step = step * cnt[l] + 7
+    sA = [sizeA + 3, 0, (sizeA + 3) * cnt[0], 0]                     # A moves with levels 0 and 2 only
+    sB = [0, sizeB, sizeB * cnt[1] + 11, (sizeB * cnt[1] + 11) * cnt[2]]     # B ignores level 0
+    span = lambda s, size: size + sum(si * (c - 1) for si, c in zip(s, cnt)) + 3
+    a = quantise(rng.uniform(-1, 1, span(sA, sizeA)), dtype)
+    b = quantise(rng.uniform(-1, 1, span(sB, sizeB)), dtype)
+    c0 = quantise(rng.uniform(-1, 1, span(sC, sizeC)), dtype)
+    dA, dB, dC = to_dev(a, dtype), to_dev(b, dtype), to_dev(c0, dtype)
+    alpha, beta = 0.75, -0.5
+    sb.sb_force_kernel(KERNELS[kernel])
+    sb.sb_gemm_nested(opA, opB, m, n, k, alpha, dA, lda, sA, dB, ldb, sB, beta, dC, ldc, sC, cnt, dt=dtype)
+    sync()
+    if kernel != "auto":
+        assert sb.sb_last_kernel() == KERNELS[kernel]
+    ref = c0.copy()
+    inside = np.zeros(c0.size, dtype=bool)
+    for p1, p2, p3 in itertools.product(range(cnt[1]), range(cnt[2]), range(cnt[3])):
+        oa, ob, oc = (p1 * s[1] + p2 * s[2] + p3 * s[3] for s in (sA, sB, sC))
+        part = oracle.sb_gemm(opA, opB, m, n, k, alpha, a[oa:], lda, sA[0], b[ob:], ldb, sB[0], beta, c0[oc:], ldc, sC[0], cnt[0],
+                              wide=(dtype == "f64"))
+        window = gemm_window_mask(c0.size - oc, m, n, ldc, sC[0], cnt[0])
+        ref[oc:][window] = part[window]
+        inside[oc:] |= window
+    got = from_dev(dC)
+    assert np.array_equal(got[~inside], c0[~inside]), "elements outside the m x n windows were written"
+    assert_close(got[inside], ref[inside], dtype, k, 1.0, 1.0, alpha, beta, c0[inside], what=(dtype, kernel, opA, opB, m, n, k))
+
+
 def test_extended_operations_directly():
     # section III-E: sb_gemm(OP_EX_N, OP_T, M, N, K, 1, B, ldb<1>, ldb<2>, A, lda<1>, 0, 0, C, ldc<1>, ldc<2>, P)
     M, N, P, K = 40, 30, 17, 23
