@@ -572,17 +572,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_ker
 template <typename K, typename... Extra>
 hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStream_t stream, const SbArgs &a, int tm, int tn, Extra... extra)
 {
-    static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
-    const int dev = sb_current_device();
-    if (resident_of[dev] == 0) {
-        int per_cu = 0, cus = 0;
-        hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, nthreads, 0);
-        if (e != hipSuccess) return e;
-        if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
-        resident_of[dev] = per_cu * cus;
-    }
-    const int resident = resident_of[dev];
+    int resident = 0;
+    const hipError_t e = sb_resident_workgroups((const void *)kernel, nthreads, &resident);
+    if (e != hipSuccess) return e;
     int64_t grid = total_tiles < resident ? total_tiles : resident;
     grid = (grid + NXCD - 1) / NXCD * NXCD;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, extra...);

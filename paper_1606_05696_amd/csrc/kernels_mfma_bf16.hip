@@ -108,6 +108,68 @@ struct PanelBf16 {
     }
 };
 
+// The same swizzled [row][k] panel for an operand whose ROWS (m or n) are contiguous in memory: it is
+// transposed on the way in.  A lane loads NVEC vectors of 8 rows at NVEC consecutive k, transposes the
+// 8 x NVEC block in registers and writes, for each of its 8 rows, the NVEC k as one 4- or 8-byte piece of
+// that row's 16-byte chunk; fragments are read exactly as from a k-contiguous panel.
+// Lane -> block: the k index runs fastest (BK / NVEC = 16 lanes share 8 rows), because that is what the
+// LDS writes need: the 16 lanes' pieces are one whole row, i.e. consecutive banks, whereas lanes on the
+// same k and rows 8 apart would all hit the same bank.  Where a row is shorter than the 32 banks (BK = 32:
+// 64 bytes), neighbouring groups of 8 rows write their even and odd rows in opposite order, so that two
+// groups together cover all banks.  The price is global loads in runs of 64 bytes instead of 512.
+template <int ROWS, int BK, int NT>
+struct PanelBf16T {
+    typedef PanelBf16<true, ROWS, BK, true, NT> Kc;           // layout and fragment reads
+    static constexpr int NVEC = Kc::NVEC;
+    static constexpr int LDS_SIZE = Kc::LDS_SIZE;
+    static constexpr int KQ = BK / NVEC;                       // blocks along k
+    static constexpr bool FLIP = BK * 2 < 128;
+    static_assert(NVEC == 2 || NVEC == 4, "a lane's block is 8 rows x 2 or 4 k");
+    static_assert((ROWS / 8) * KQ == NT, "one block per lane");
+
+    static __device__ __forceinline__ void load_plain(u16x8 (&v)[NVEC], const uint16_t *p, int64_t ld)
+    {
+        const int f = (int)threadIdx.x, kq = f % KQ, rg = f / KQ;
+#pragma unroll
+        for (int q = 0; q < NVEC; ++q) v[q] = *(const u16x8u *)(p + (int64_t)(kq * NVEC + q) * ld + rg * 8);
+    }
+
+    static __device__ __forceinline__ void store(uint16_t *lds, const u16x8 (&v)[NVEC])
+    {
+        typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        const int f = (int)threadIdx.x, kq = f % KQ, rg = f / KQ;
+        const int k0 = kq * NVEC;                              // first k of this lane's block
+        const bool odd = FLIP && (rg & 1);
+        u32x4 d[NVEC];                                         // dword t of d[q]: rows 2t (low half) and 2t+1 at k0 + q
+#pragma unroll
+        for (int q = 0; q < NVEC; ++q) d[q] = __builtin_bit_cast(u32x4, v[q]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            u32x2 even, oddp;                                  // the pieces of rows 2t and 2t+1 (NVEC == 2: first word only)
+            even[0] = (d[0][t] & 0xffffu) | (d[1][t] << 16);
+            oddp[0] = (d[0][t] >> 16) | (d[1][t] & 0xffff0000u);
+            if (NVEC == 4) {
+                even[1] = (d[2][t] & 0xffffu) | (d[3][t] << 16);
+                oddp[1] = (d[2][t] >> 16) | (d[3][t] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {                      // first the even row (the odd one in flipped groups)
+                const int row = rg * 8 + 2 * t + (odd ? 1 - h : h);
+                const u32x2 piece = (h == 0) == !odd ? even : oddp;
+                uint16_t *dst = lds + row * Kc::LDS_LD + Kc::swizzled(row, k0 & ~7) + (k0 & 7);
+                if (NVEC == 2) *(uint32_t *)dst = piece[0];
+                else           *(u32x2 *)dst = piece;
+            }
+        }
+    }
+
+    static __device__ __forceinline__ bf16x8 fragment(const uint16_t *lds, int row0, int ks, int lane)
+    {
+        return Kc::fragment(lds, row0, ks, lane);
+    }
+};
+
 // WT: wave tile edge (64 -> 128x128 workgroup tile, 32 -> 64x64)
 template <bool A_KC, bool B_KC, int WT>
 __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, int tiles_m, int tiles_n, int vec_ok)
@@ -231,18 +293,21 @@ __global__ __launch_bounds__(NTHREADS) void sbgemm_mfma_bf16_kernel(SbArgs g, in
 // of a fragment per MFMA and half the panel bytes per flop.  (4 x 4 blocks on 2 x 2 waves, with 256
 // accumulator registers and one wave per SIMD, were slower: nothing hides a wave's own stalls.)
 // SBK: k per panel (64 for 2 x 2 blocks; 32 for 4 x 2, whose staging registers must share 256 with 128 accumulators).
-template <bool BETA, int NBM, int NBN, int SBK, int WAVES_M = 2, int WAVES_N = 2>
+template <bool BETA, int NBM, int NBN, int SBK, int WAVES_M = 2, int WAVES_N = 2, bool A_KC = true, bool B_KC = true>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, (NBM * NBN <= 4 && WAVES_M * WAVES_N == 4) ? 2 : 1)
 void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
     constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = WAVES_M * WM, TN = WAVES_N * WN, NT = 64 * WAVES_M * WAVES_N;
-    typedef PanelBf16<true, TM, SBK, true, NT> PA;
-    typedef PanelBf16<true, TN, SBK, true, NT> PB;
+    typedef typename std::conditional<A_KC, PanelBf16<true, TM, SBK, true, NT>, PanelBf16T<TM, SBK, NT>>::type PA;
+    typedef typename std::conditional<B_KC, PanelBf16<true, TN, SBK, true, NT>, PanelBf16T<TN, SBK, NT>>::type PB;
     constexpr int KG = SBK / 16;                 // MFMA k-steps per panel (even: two fragment sets alternate)
     __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
 
-    const int64_t ldA = g.rsA, ldB = g.csB;
+    // leading dimension of a panel (row stride of a k-contiguous operand, k stride of the other kind) and the
+    // element step from one k to the next
+    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
+    const int64_t panelA = A_KC ? SBK : (int64_t)SBK * g.csA, panelB = B_KC ? SBK : (int64_t)SBK * g.rsB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
     const float alpha = (float)g.alpha, beta = (float)g.beta;
@@ -333,14 +398,14 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
         block(I0(), std::false_type(), A, B);                             // panel 2 was requested before the previous stores
-        block(I1(), std::true_type(), A + 3 * SBK, B + 3 * SBK);
-        const uint16_t *pa = A + 4 * SBK, *pb = B + 4 * SBK;
+        block(I1(), std::true_type(), A + 3 * panelA, B + 3 * panelB);
+        const uint16_t *pa = A + 4 * panelA, *pb = B + 4 * panelB;
         for (int64_t kb = 2; kb < nkb; kb += 2) {
             if (kb + 2 == nkb) { pa = An; pb = Bn; }                      // the stream moves on to the next tile
             block(I0(), std::true_type(), pa, pb);
-            pa += SBK; pb += SBK;
+            pa += panelA; pb += panelB;
             block(I1(), std::true_type(), pa, pb);
-            pa += SBK; pb += SBK;
+            pa += panelA; pb += panelB;
         }
         gload(I0(), pa, pb);                                              // next tile's panel 2, ahead of the stores below
 #pragma unroll
@@ -361,12 +426,12 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
     Loc cur = locate(b, tile);
     {   // prime the stream with the first tile's panels 0, 1 and 2
         gload(I0(), cur.A, cur.B);
-        gload(I1(), cur.A + SBK, cur.B + SBK);
+        gload(I1(), cur.A + panelA, cur.B + panelB);
         PA::store(As[0], ra[0]);
         PB::store(Bs[0], rb[0]);
         __syncthreads();
         read_frags(I0(), I0(), 0);
-        gload(I0(), cur.A + 2 * SBK, cur.B + 2 * SBK);
+        gload(I0(), cur.A + 2 * panelA, cur.B + 2 * panelB);
     }
     // one tile and the step to the workgroup's next one; the last tile names itself as successor
     auto step = [&]() __attribute__((always_inline)) {
@@ -386,9 +451,22 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
     while (more) more = step();       // later tiles: follow a finished tile
 }
 
+// whole tiles, an even number (>= 4) of k panels; either orientation of each operand
 bool stream_applies(const SbArgs &a, int tile, int SBK)
 {
-    return a.csA == 1 && a.rsB == 1 && a.m % tile == 0 && a.n % tile == 0 && a.k % (2 * SBK) == 0 && a.k >= 4 * SBK;
+    const bool a_ok = a.csA == 1 || a.rsA == 1, b_ok = a.rsB == 1 || a.csB == 1;
+    return a_ok && b_ok && a.m % tile == 0 && a.n % tile == 0 && a.k % (2 * SBK) == 0 && a.k >= 4 * SBK;
+}
+
+// the streaming kernel for the orientation of the operands (k contiguous or rows contiguous, each)
+template <bool BETA, int NBM, int NBN, int SBK, int WAVES_M, int WAVES_N, typename Launch>
+hipError_t stream_by_layout(const SbArgs &a, Launch launch)
+{
+    const bool ak = a.csA == 1, bk = a.rsB == 1;
+    if (ak && bk)  return launch(sbgemm_bf16_stream_kernel<BETA, NBM, NBN, SBK, WAVES_M, WAVES_N, true, true>);
+    if (ak && !bk) return launch(sbgemm_bf16_stream_kernel<BETA, NBM, NBN, SBK, WAVES_M, WAVES_N, true, false>);
+    if (!ak && bk) return launch(sbgemm_bf16_stream_kernel<BETA, NBM, NBN, SBK, WAVES_M, WAVES_N, false, true>);
+    return launch(sbgemm_bf16_stream_kernel<BETA, NBM, NBN, SBK, WAVES_M, WAVES_N, false, false>);
 }
 
 template <typename K>
@@ -398,17 +476,9 @@ hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};       // one table per kernel instantiation
-    const int dev = sb_current_device();
-    if (resident_of[dev] == 0) {
-        int per_cu = 0, cus = 0;
-        hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, nthreads, 0);
-        if (e != hipSuccess) return e;
-        if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
-        resident_of[dev] = per_cu * cus;
-    }
-    const int64_t resident = resident_of[dev];
+    int resident = 0;
+    const hipError_t e = sb_resident_workgroups((const void *)kernel, nthreads, &resident);
+    if (e != hipSuccess) return e;
     int64_t grid = total < resident ? total : resident;
     grid = (grid + NXCD - 1) / NXCD * NXCD;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, (int)tiles_m, (int)tiles_n);
@@ -448,12 +518,14 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
     const int64_t batch = a.batch0 * a.batch1;
     if (stream_applies(a, 256, 32) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.15) <=
                                           sb_tile_time(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 1.0, 1.0)) {
-        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 4, 2, 32, 2, 4>, 256, a, stream, 512);
-        return launch_stream(sbgemm_bf16_stream_kernel<true, 4, 2, 32, 2, 4>, 256, a, stream, 512);
+        auto go = [&](auto kernel) { return launch_stream(kernel, 256, a, stream, 512); };
+        if (a.beta == 0.0) return stream_by_layout<false, 4, 2, 32, 2, 4>(a, go);
+        return stream_by_layout<true, 4, 2, 32, 2, 4>(a, go);
     }
     if (stream_applies(a, 128, 64)) {
-        if (a.beta == 0.0) return launch_stream(sbgemm_bf16_stream_kernel<false, 2, 2, 64>, 128, a, stream);
-        return launch_stream(sbgemm_bf16_stream_kernel<true, 2, 2, 64>, 128, a, stream);
+        auto go = [&](auto kernel) { return launch_stream(kernel, 128, a, stream); };
+        if (a.beta == 0.0) return stream_by_layout<false, 2, 2, 64, 2, 2>(a, go);
+        return stream_by_layout<true, 2, 2, 64, 2, 2>(a, go);
     }
     // small matrices per batch: 64x64 tiles waste less and give more workgroups
     if (a.m <= 64 || a.n <= 64) return launch<32>(a, stream);

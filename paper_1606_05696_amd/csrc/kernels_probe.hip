@@ -69,3 +69,27 @@ extern "C" int sb_probe_mfma(sb_dtype dt, int iterations, void *scratch, int64_t
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? SB_OK : SB_ERR_LAUNCH + (int)e;
 }
+
+// ---------------------------------------------------------------------------------------------
+// residency cache of the persistent launchers (declared in sb_internal.h)
+#include <mutex>
+
+hipError_t sb_resident_workgroups(const void *kernel, int threads, int *resident)
+{
+    struct Entry { const void *kernel; int dev, threads, value; };
+    static Entry table[512];
+    static int used = 0;
+    static std::mutex lock;
+    const int dev = sb_current_device();
+    std::lock_guard<std::mutex> hold(lock);
+    for (int i = 0; i < used; ++i)
+        if (table[i].kernel == kernel && table[i].dev == dev && table[i].threads == threads) { *resident = table[i].value; return hipSuccess; }
+    int per_cu = 0, cus = 0;
+    hipError_t e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
+    *resident = per_cu * cus;
+    if (used < 512) table[used++] = Entry{kernel, dev, threads, *resident};
+    return hipSuccess;
+}

@@ -76,6 +76,12 @@ hipError_t sb_launch_permute(int esize, int order, const int64_t *dims, const in
 // 256 compute units: the launchers use it to choose between tile sizes.
 double sb_tile_time(int64_t tiles, double area, double gain);
 
+// Workgroups of `kernel` (launched with `threads` lanes and no dynamic LDS) that the current device holds at
+// once: occupancy per compute unit x compute units, asked once per (device, kernel) and cached by the
+// kernel's address (many instantiations share one function-pointer type, so a table per C++ type would
+// hand one kernel another's answer).
+hipError_t sb_resident_workgroups(const void *kernel, int threads, int *resident);
+
 // A launch may not have more than 2^32 - 1 work-items along x: the most workgroups of `threads`
 // lanes a one-dimensional grid can hold.  Launchers that take one workgroup per tile either spill
 // into y beyond it or leave larger problems to another family.

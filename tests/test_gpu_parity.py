@@ -677,7 +677,11 @@ def test_sb_gemm_whole_tile_shapes_bf16():
     # three fill the chip with 256 x 256 tiles: the eight-wave variant (k a multiple of 64).
     for opA, opB, m, n, k, batch in (("T", "N", 256, 384, 256, 5), ("T", "N", 128, 128, 384, 3), ("T", "N", 128, 256, 1024, 1),
                                      ("T", "N", 512, 256, 256, 131), ("T", "N", 128, 128, 320, 3), ("N", "N", 256, 128, 256, 2),
-                                     ("T", "N", 512, 768, 128, 128), ("T", "N", 1024, 512, 1088, 32), ("T", "N", 256, 256, 192, 256)):
+                                     ("T", "N", 512, 768, 128, 128), ("T", "N", 1024, 512, 1088, 32), ("T", "N", 256, 256, 192, 256),
+                                     # operands with m or n contiguous are transposed on their way into LDS: the same
+                                     # streaming kernels in the other three layouts, 128 x 128 and 256 x 256 tiles
+                                     ("N", "N", 256, 384, 256, 5), ("N", "T", 128, 256, 384, 3), ("T", "T", 384, 128, 512, 2),
+                                     ("N", "N", 512, 768, 128, 128), ("N", "T", 256, 256, 192, 256), ("T", "T", 512, 512, 256, 70)):
         lda = (m if opA == "N" else k) + 8
         ldb = (k if opB == "N" else n) + 16
         ldc = m + 12
