@@ -226,8 +226,10 @@ const char *sb_status_string(int status);
  *   SB_KERNEL_GENERIC  every problem the entry points accept;
  *   SB_KERNEL_THIN     1 <= min(m, n) <= 4, any operation and element type;
  *   SB_KERNEL_TINY     SB_F64 / SB_F32, m <= 32 and n <= 32, k >= 1, operations N / T;
- *   SB_KERNEL_MFMA     k >= 1, operations N / T in every element type; an extended operation on the
- *                      first operand in SB_F64 / SB_F32 when m >= 8, n >= 16 and batch0 >= 8;
+ *   SB_KERNEL_MFMA     k >= 1, operations N / T in every element type; an extended operation on ONE
+ *                      operand (the other N / T with batch stride 0 at level 0) in every element type
+ *                      when batch0 >= 8 and op(X)'s free extent is >= 8 for the extended operand and
+ *                      >= 16 for the other (first operand: m >= 8, n >= 16; second: n >= 8, m >= 16);
  *   SB_KERNEL_PANEL    SB_BF16 with 1 <= k <= 128, operations N / T (whole-k operand panels in LDS: the
  *                      selector takes it when C has at least 4 x 4 blocks of 64 x 64 -- counting, on
  *                      each side, the batch levels that move only that side's operand -- and at least

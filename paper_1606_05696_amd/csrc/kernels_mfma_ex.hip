@@ -10,6 +10,12 @@
 // tile: all PB batches share the same B panel, so the PB small products are one tall GEMM.
 // The transposition between "b contiguous" and "i contiguous" happens for free in the LDS
 // addressing of the MFMA fragments (lanes run along i, the panel is stored with b fastest).
+//
+// The extended operation on the SECOND operand is the same kernel on the transposed problem,
+//     C_b^T = op(B_b)^T op(A)^T,
+// whose first operand is the strided one: the launcher swaps the operands and the kernel (CT) writes
+// its tile transposed, C_b(i,j) at i + j*ldc with i the tile's COLUMN.  The MFMA operands trade places
+// so that lanes still run along the unit-stride direction of C.
 #include <type_traits>
 
 #include "sb_device.h"
@@ -19,48 +25,76 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int NXCD = 8;
 constexpr int ET = 256;                 // lanes per workgroup (4 waves)
 
-// Instruction traits (layouts as measured on gfx950): operands hold X[l%MI][k = l/MI]; result slot
-// r of lane l is D[row_lane(l) + row_reg(r)][l%MI].
+// Instruction traits (layouts as measured on gfx950): a fragment (Vec) holds VEC consecutive k of row
+// l%MI, lane group l/MI taking the next VEC; it is spent in STEPS instructions (one k per lane group
+// each for fp32/fp64, all eight at once for bf16).  Result slot r of lane l is
+// D[row_lane(l) + row_reg(r)][l%MI].  S is the type the epilogue computes in.
 struct ExF32 {
     typedef float T;
+    typedef float S;
     typedef f32x16 Acc;
     typedef float Vec __attribute__((ext_vector_type(4)));
     typedef float VecU __attribute__((ext_vector_type(4), aligned(4)));       // global loads: any element address
-    static constexpr int MI = 32, VEC = 4, NREG = 16;       // 64/MI lane groups along k, VEC k each: 8 k per fragment
-    static __device__ __forceinline__ void mma(Acc &c, float first, float second) { c = __builtin_amdgcn_mfma_f32_32x32x2f32(first, second, c, 0, 0, 0); }
+    static constexpr int MI = 32, VEC = 4, NREG = 16, STEPS = 4;       // 64/MI lane groups along k, VEC k each: 8 k per fragment
+    static __device__ __forceinline__ void mma(Acc &c, const Vec &first, const Vec &second, int e) { c = __builtin_amdgcn_mfma_f32_32x32x2f32(first[e], second[e], c, 0, 0, 0); }
     static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 5); }
     static constexpr int row_reg(int r) { return 8 * (r >> 2) + (r & 3); }
+    static __device__ __forceinline__ S to_s(T v) { return v; }
+    static __device__ __forceinline__ T from_s(S v) { return v; }
+};
+struct ExBf16 {
+    typedef uint16_t T;                                      // bf16 bits
+    typedef float S;
+    typedef f32x16 Acc;
+    typedef uint16_t Vec __attribute__((ext_vector_type(8)));
+    typedef uint16_t VecU __attribute__((ext_vector_type(8), aligned(2)));
+    static constexpr int MI = 32, VEC = 8, NREG = 16, STEPS = 1;       // 16 k per fragment, one instruction
+    static __device__ __forceinline__ void mma(Acc &c, const Vec &first, const Vec &second, int)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int row_lane(int lane) { return 4 * (lane >> 5); }
+    static constexpr int row_reg(int r) { return 8 * (r >> 2) + (r & 3); }
+    static __device__ __forceinline__ S to_s(T v) { return sb_bf16_to_f32(v); }
+    static __device__ __forceinline__ T from_s(S v) { return sb_f32_to_bf16(v); }      // nearest, ties to even
 };
 struct ExF64 {
     typedef double T;
+    typedef double S;
     typedef f64x4 Acc;
     typedef double Vec __attribute__((ext_vector_type(2)));
     typedef double VecU __attribute__((ext_vector_type(2), aligned(8)));
-    static constexpr int MI = 16, VEC = 2, NREG = 4;
-    static __device__ __forceinline__ void mma(Acc &c, double first, double second) { c = __builtin_amdgcn_mfma_f64_16x16x4f64(first, second, c, 0, 0, 0); }
+    static constexpr int MI = 16, VEC = 2, NREG = 4, STEPS = 2;
+    static __device__ __forceinline__ void mma(Acc &c, const Vec &first, const Vec &second, int e) { c = __builtin_amdgcn_mfma_f64_16x16x4f64(first[e], second[e], c, 0, 0, 0); }
     static __device__ __forceinline__ int row_lane(int lane) { return lane >> 4; }
     static constexpr int row_reg(int r) { return 4 * r; }
+    static __device__ __forceinline__ S to_s(T v) { return v; }
+    static __device__ __forceinline__ T from_s(S v) { return v; }
 };
 
-// PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK deep panels (8: one group of
-// MFMA fragments per panel; 16: two, so that a barrier comes only every 32 MFMAs of a wave).
+// PB batches x MB rows per tile (PB*MB tile rows), BN columns, BK deep panels (one group of MFMA
+// fragments per panel, or two, so that a barrier comes only every 32 fp32 MFMAs of a wave).
 // The second launch bound (waves per SIMD the register allocation must leave room for) keeps two
 // fp64 workgroups on a compute unit; left alone the allocator gives the fp64 variant more than 256
 // registers and one workgroup per compute unit (35 instead of 54 TFLOP/s at 512^4).  The fp32 variant
 // with 16-deep panels takes 212-232 registers by itself, two workgroups per compute unit, and is
 // left alone: bounded to three it spills inside the k loop (0.50 instead of 0.70 of the peak), and
 // with 8-deep panels three fit but a barrier every 16 MFMAs costs more (0.67).
-template <typename MF, bool B_KC, int PB, int MB, int BN, int BK>
+template <typename MF, bool B_KC, bool CT, int PB, int MB, int BN, int BK>
 __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgemm_mfma_exa_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n, int vec_a, int vec_b)
 {
     typedef typename MF::T T;
     typedef typename MF::Vec Vec;
     typedef typename MF::VecU VecU;
-    constexpr int MI = MF::MI, VEC = MF::VEC, KG = BK / 8;     // KG groups of 8 k per panel
+    typedef typename MF::S S;
+    constexpr int MI = MF::MI, VEC = MF::VEC, STEPS = MF::STEPS;
+    constexpr int KF = (64 / MI) * VEC;               // k per fragment group: 8 (fp32, fp64) or 16 (bf16)
+    constexpr int KG = BK / KF;                       // fragment groups per panel
     static_assert(KG == 1 || KG == 2, "one or two fragment groups per panel");
     constexpr int BM = PB * MB;                       // tile rows = (batch, row) pairs
     constexpr int PBP = PB + 16 / (int)sizeof(T);     // b-run padded by 16 bytes: lanes that differ in i hit different banks
@@ -102,7 +136,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
 #pragma unroll
         for (int c = 0; c < NBN; ++c)
 #pragma unroll
-            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
+            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = S(0);
 
     // A panel vector f: k = f / (MB * PB/VEC), i = (f / (PB/VEC)) % MB, b = (f % (PB/VEC)) * VEC.
     // FAST: the whole brick lies inside the tensor and is 16-byte aligned (no tests, plain vector loads).
@@ -165,9 +199,9 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     const int kl = lane / MI;                          // lane group along k
     const int64_t nkb = (g.k + BK - 1) / BK;
 
-    // MFMA operands of one panel (a group of 8 k: lane group kl takes k = kl*VEC + e)
-    auto read_frags = [&](T (&fa)[NBM][VEC], T (&fb)[NBN][VEC], int buf, int kg = 0) {
-        const int k = kg * 8 + kl * VEC;
+    // MFMA operands of one fragment group of a panel (lane group kl takes k = kl*VEC + e)
+    auto read_frags = [&](Vec (&fa)[NBM], Vec (&fb)[NBN], int buf, int kg = 0) {
+        const int k = kg * KF + kl * VEC;
 #pragma unroll
         for (int a = 0; a < NBM; ++a) {
             const int rho = rho0 + a * MI + (lane % MI);
@@ -179,9 +213,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
         for (int c = 0; c < NBN; ++c) {
             const int col = c * MI + (lane % MI);
             if (B_KC) {
-                Vec v = *(const Vec *)(Bs[buf] + col * B_LD + k);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) fb[c][e] = v[e];
+                fb[c] = *(const Vec *)(Bs[buf] + col * B_LD + k);
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) fb[c][e] = Bs[buf][(k + e) * B_LD + col];
@@ -189,12 +221,19 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
         }
     };
 
+    // D = first x second^T has lanes along second's rows: tile rows (first = B fragment) when C_b is stored
+    // as computed, tile columns when it is stored transposed
+    auto mma = [](typename MF::Acc &c, const Vec &row_frag, const Vec &col_frag, int e) {
+        if (CT) MF::mma(c, row_frag, col_frag, e);
+        else    MF::mma(c, col_frag, row_frag, e);
+    };
+
     // The k loop, software-pipelined like the plain MFMA kernel: global loads run two panels ahead
     // (two staging register sets), the LDS store of the next panel sits in the middle of the MFMA
     // cluster, and the fragments of the next panel are read right after the barrier, before the
     // second half of the current cluster's successor starts.  CUR = parity of the panel.
     Vec ra[2][NVA], rb[2];
-    T fa[2][NBM][VEC], fb[2][NBN][VEC];
+    Vec fa[2][NBM], fb[2][NBN];
     auto k_loop = [&](auto fast_c) {
         auto block = [&](auto cur_c, auto steady_c, int64_t kb) {
             constexpr int CUR = decltype(cur_c)::value;
@@ -212,8 +251,8 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
                 read_frags(fa[1], fb[1], CUR, 1);
                 __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    if (e == VEC / 2 && hand_over) {
+                for (int e = 0; e < STEPS; ++e) {
+                    if (e == STEPS / 2 && hand_over) {
                         __builtin_amdgcn_sched_barrier(0);
                         store_a(As[CUR ^ 1], ra[CUR ^ 1]);
                         store_b(Bs[CUR ^ 1], rb[CUR ^ 1]);
@@ -222,7 +261,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
 #pragma unroll
                     for (int a = 0; a < NBM; ++a)
 #pragma unroll
-                        for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[0][c][e], fa[0][a][e]);
+                        for (int c = 0; c < NBN; ++c) mma(acc[a][c], fa[0][a], fb[0][c], e);
                 }
                 __builtin_amdgcn_s_setprio(0);
                 if (hand_over) {
@@ -231,18 +270,18 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
                 }
                 __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e)
+                for (int e = 0; e < STEPS; ++e)
 #pragma unroll
                     for (int a = 0; a < NBM; ++a)
 #pragma unroll
-                        for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[1][c][e], fa[1][a][e]);
+                        for (int c = 0; c < NBN; ++c) mma(acc[a][c], fa[1][a], fb[1][c], e);
                 __builtin_amdgcn_s_setprio(0);
                 return;
             }
             __builtin_amdgcn_s_setprio(2);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                if (e == VEC / 2 && hand_over) {
+            for (int e = 0; e < STEPS; ++e) {
+                if (e == STEPS / 2 && hand_over) {
                     __builtin_amdgcn_sched_barrier(0);
                     store_a(As[CUR ^ 1], ra[CUR ^ 1]);
                     store_b(Bs[CUR ^ 1], rb[CUR ^ 1]);
@@ -251,7 +290,7 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
 #pragma unroll
                 for (int a = 0; a < NBM; ++a)
 #pragma unroll
-                    for (int c = 0; c < NBN; ++c) MF::mma(acc[a][c], fb[CUR][c][e], fa[CUR][a][e]);     // C^T: lanes run along rows
+                    for (int c = 0; c < NBN; ++c) mma(acc[a][c], fa[CUR][a], fb[CUR][c], e);
             }
             __builtin_amdgcn_s_setprio(0);
             if (hand_over) {
@@ -289,9 +328,32 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     // epilogue: lane = tile row rho = (batch, row); consecutive lanes are consecutive rows of one C_b.
     // The variants (whole brick or not, beta or not) are chosen by workgroup-uniform branches so that
     // the common one is a straight run of stores.
-    const T alpha = (T)g.alpha, beta = (T)g.beta;
+    const S alpha = (S)g.alpha, beta = (S)g.beta;
     auto store_tile = [&](auto guard_c, auto beta_c) {
         constexpr bool GUARD = decltype(guard_c)::value, BETA = decltype(beta_c)::value;
+        if (CT) {
+            // lane = tile column = row of the stored C_b (unit stride); slots run over (batch, tile row) pairs,
+            // the tile row being the stored column
+#pragma unroll
+            for (int c = 0; c < NBN; ++c) {
+                const int col = c * MI + (lane % MI);
+                if (GUARD && col >= n_left) continue;
+                T *Cc = (T *)g.C + o1.c + (j0 + col);
+#pragma unroll
+                for (int a = 0; a < NBM; ++a)
+#pragma unroll
+                    for (int r = 0; r < MF::NREG; ++r) {
+                        const int rho = rho0 + a * MI + MF::row_lane(lane) + MF::row_reg(r);
+                        const int bl = rho / MB, il = rho % MB;
+                        if (GUARD && (bl >= b_left || il >= m_left)) continue;
+                        T *dst = Cc + (bb + bl) * g.bsC[0] + (i0 + il) * g.ldc;
+                        S v = alpha * acc[a][c][r];
+                        if (BETA) v += beta * MF::to_s(*dst);
+                        *dst = MF::from_s(v);
+                    }
+            }
+            return;
+        }
 #pragma unroll
         for (int a = 0; a < NBM; ++a) {
             const int rho = rho0 + a * MI + (lane % MI);
@@ -306,24 +368,24 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
                 for (int r = 0; r < MF::NREG; ++r) {
                     if (GUARD && jl + MF::row_reg(r) >= g.n) continue;
                     T *dst = col + MF::row_reg(r) * g.ldc;
-                    T v = alpha * acc[a][c][r];
-                    if (BETA) v += beta * *dst;
-                    *dst = v;
+                    S v = alpha * acc[a][c][r];
+                    if (BETA) v += beta * MF::to_s(*dst);
+                    *dst = MF::from_s(v);
                 }
             }
         }
     };
     const bool whole = b_left >= PB && m_left >= MB && n_left >= BN;
     if (whole) {
-        if (beta == T(0)) store_tile(std::false_type(), std::false_type());
+        if (beta == S(0)) store_tile(std::false_type(), std::false_type());
         else              store_tile(std::false_type(), std::true_type());
     } else {
-        if (beta == T(0)) store_tile(std::true_type(), std::false_type());
+        if (beta == S(0)) store_tile(std::true_type(), std::false_type());
         else              store_tile(std::true_type(), std::true_type());
     }
 }
 
-template <typename MF, int PB, int MB, int BN, int BK>
+template <typename MF, bool CT, int PB, int MB, int BN, int BK>
 hipError_t launch(const SbArgs &a, hipStream_t stream)
 {
     const int64_t tiles_b = (a.batch0 + PB - 1) / PB, tiles_i = (a.m + MB - 1) / MB, tiles_n = (a.n + BN - 1) / BN;
@@ -333,18 +395,15 @@ hipError_t launch(const SbArgs &a, hipStream_t stream)
     // 16-byte vector loads need no alignment beyond the element's: the hardware reads them anywhere
     const int vec_a = 1, vec_b = 1;
     dim3 grid((unsigned)total), block(ET);
-    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
-    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
+    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, true, CT, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
+    else            hipLaunchKernelGGL((sbgemm_mfma_exa_kernel<MF, false, CT, PB, MB, BN, BK>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n, vec_a, vec_b);
     return hipGetLastError();
 }
 
-}  // namespace
-
-// The first operand is "extended" (level-0 batch stride 1, rows and columns both strided), the second
-// is a plain N/T matrix that does not move with batch level 0, C_b are ordinary column-major matrices.
-bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
+// first-operand form: A strided in rows and columns with level-0 batch stride 1, B a plain N/T matrix that
+// does not move with level 0
+bool first_form(const SbArgs &a)
 {
-    if (dt != SB_F32 && dt != SB_F64) return false;
     if (a.k <= 0 || a.batch0 < 8) return false;
     if (a.bsA[0] != 1 || a.rsA == 1 || a.csA == 1) return false;
     if (a.bsB[0] != 0) return false;
@@ -355,9 +414,42 @@ bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
     return a.m >= 8 && a.n >= 16;
 }
 
+// the transposed problem C^T = op(B)^T op(A)^T: operands and their batch strides trade places, rows and
+// columns of each trade places; C itself is untouched (the kernel writes its tile transposed)
+SbArgs transposed(const SbArgs &a)
+{
+    SbArgs t = a;
+    t.A = a.B;  t.B = a.A;
+    t.m = a.n;  t.n = a.m;
+    t.rsA = a.csB;  t.csA = a.rsB;
+    t.rsB = a.csA;  t.csB = a.rsA;
+    for (int l = 0; l < 2; ++l) { t.bsA[l] = a.bsB[l];  t.bsB[l] = a.bsA[l]; }
+    for (int x = 0; x < SB_MAX_BATCH_LEVELS - 2; ++x) { t.xsA[x] = a.xsB[x];  t.xsB[x] = a.xsA[x]; }
+    return t;
+}
+
+}  // namespace
+
+// One operand is "extended" (level-0 batch stride 1, rows and columns both strided), the other is a plain
+// N/T matrix that does not move with batch level 0, C_b are ordinary column-major matrices.
+bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
+{
+    return first_form(a) || first_form(transposed(a));
+}
+
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
-    if (dt == SB_F32) return launch<ExF32, 16, 16, 64, 16>(a, stream);     // 16 batches x 16 rows x 64 columns per tile, 16 k per panel
-    if (dt == SB_F64) return launch<ExF64, 16, 16, 32, 8>(a, stream);
+    // 16 batches x 16 rows x 64 columns per tile and 16 k per panel (fp64: 32 columns, 8 k; bf16: 32 k)
+    if (first_form(a)) {
+        if (dt == SB_F32) return launch<ExF32, false, 16, 16, 64, 16>(a, stream);
+        if (dt == SB_F64) return launch<ExF64, false, 16, 16, 32, 8>(a, stream);
+        if (dt == SB_BF16) return launch<ExBf16, false, 16, 16, 64, 32>(a, stream);
+        return hipErrorInvalidValue;
+    }
+    const SbArgs t = transposed(a);
+    if (!first_form(t)) return hipErrorInvalidValue;
+    if (dt == SB_F32) return launch<ExF32, true, 16, 16, 64, 16>(t, stream);
+    if (dt == SB_F64) return launch<ExF64, true, 16, 16, 32, 8>(t, stream);
+    if (dt == SB_BF16) return launch<ExBf16, true, 16, 16, 64, 32>(t, stream);
     return hipErrorInvalidValue;
 }

@@ -529,6 +529,55 @@ def test_extended_operations_directly():
     assert_close(from_dev(tC, [M, N, P]), ref, "f32", K, 1.0, 1.0, what="case 6.4")
 
 
+EX_FORMS = [("EX_N", "N"), ("EX_N", "T"), ("EX_T", "N"), ("EX_T", "T"), ("N", "EX_N"), ("T", "EX_N"), ("N", "EX_T"), ("T", "EX_T")]
+
+
+@pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
+@pytest.mark.parametrize("kernel", ["mfma", "generic", "auto"])
+@pytest.mark.parametrize("opA,opB", EX_FORMS)
+def test_extended_operation_on_either_operand(dtype, kernel, opA, opB):
+    # section III-E on the first or on the second operand: the extended operand is a [P][rows][cols]
+    # (or [P][cols][rows]) tensor with padded leading extent, batched in its unit-stride mode; the
+    # other operand is a plain matrix shared by all batches; beta reads C; shapes span several bricks
+    # (16 batches x 16 rows) with ragged tails.  The MFMA family must take every form itself.
+    for (m, n, k, P, alpha, beta) in [(40, 30, 23, 17, 0.75, -0.5), (70, 130, 33, 37, 1.0, 0.0), (16, 16, 8, 8, -1.0, 1.0)]:
+        rng = np.random.default_rng(m + n)
+
+        def operand(op, rows, cols):             # op(X) is rows x cols; returns (ld, stride0, size)
+            if op in ("N", "T"):
+                r, c = (rows, cols) if op == "N" else (cols, rows)
+                return r + 2, 0, (r + 2) * c + 3
+            inner, outer = (rows, cols) if op == "EX_N" else (cols, rows)     # EX_N: rows next to the batch mode
+            ld = P + 1
+            return ld, ld * inner + 5, (ld * inner + 5) * outer + 3
+
+        lda, sA, sizeA = operand(opA, m, k)
+        ldb, sB, sizeB = operand(opB, k, n)
+        ldc, sC = m + 3, (m + 3) * n + 1
+        a = quantise(rng.uniform(-1, 1, sizeA), dtype)
+        b = quantise(rng.uniform(-1, 1, sizeB), dtype)
+        c0 = quantise(rng.uniform(-1, 1, sC * P + 2), dtype)
+        dA, dB, dC = to_dev(a, dtype), to_dev(b, dtype), to_dev(c0, dtype)
+        sb.sb_force_kernel(KERNELS[kernel])
+        sb.sb_gemm(opA, opB, m, n, k, alpha, dA, lda, sA, dB, ldb, sB, beta, dC, ldc, sC, P, dt=dtype)
+        sync()
+        if kernel != "auto":
+            assert sb.sb_last_kernel() == KERNELS[kernel], (kernel, sb.sb_last_kernel(), opA, opB, m, n, k, P)
+
+        def packed(x, op, rows, cols, ld, s0):   # the P matrices op(X_b), gathered into packed column-major copies
+            rs, cs, bs = {"N": (1, ld, s0), "T": (ld, 1, s0), "EX_N": (ld, s0, 1), "EX_T": (s0, ld, 1)}[op]
+            bb, jj, ii = np.meshgrid(np.arange(P), np.arange(cols), np.arange(rows), indexing="ij")
+            return x[bb * bs + ii * rs + jj * cs].ravel()
+
+        ref = oracle.sb_gemm("N", "N", m, n, k, alpha, packed(a, opA, m, k, lda, sA), m, m * k,
+                             packed(b, opB, k, n, ldb, sB), k, k * n, beta, c0, ldc, sC, P, wide=(dtype == "f64"))
+        got = from_dev(dC)
+        inside = gemm_window_mask(got.size, m, n, ldc, sC, P)
+        assert np.array_equal(got[~inside], c0[~inside]), "elements outside the m x n windows were written"
+        assert_close(got[inside], ref[inside], dtype, k, 1.0, 1.0, alpha, beta, c0[inside], what=(dtype, kernel, opA, opB, m, n, k, P))
+    sb.sb_force_kernel(KERNELS["auto"])
+
+
 def test_runs_on_a_side_stream():
     import torch
     s = torch.cuda.Stream()
