@@ -727,6 +727,9 @@ def test_sb_gemm_whole_tile_shapes_bf16():
     for opA, opB, m, n, k, batch in (("T", "N", 256, 384, 256, 5), ("T", "N", 128, 128, 384, 3), ("T", "N", 128, 256, 1024, 1),
                                      ("T", "N", 512, 256, 256, 131), ("T", "N", 128, 128, 320, 3), ("N", "N", 256, 128, 256, 2),
                                      ("T", "N", 512, 768, 128, 128), ("T", "N", 1024, 512, 1088, 32), ("T", "N", 256, 256, 192, 256),
+                                     # k a multiple of 128: the 256 x 256 member that loads straight into LDS (2, 6 and 10 panels of 64;
+                                     # more tiles than workgroups, so the panel stream crosses tile boundaries)
+                                     ("T", "N", 512, 512, 384, 128), ("T", "N", 256, 768, 640, 170),
                                      # operands with m or n contiguous are transposed on their way into LDS: the same
                                      # streaming kernels in the other three layouts, 128 x 128 and 256 x 256 tiles
                                      ("N", "N", 256, 384, 256, 5), ("N", "T", 128, 256, 384, 3), ("T", "T", 384, 128, 512, 2),
