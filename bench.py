@@ -483,6 +483,73 @@ def run_exceptional_cases(steps, warmup, n=512, torch_baseline=True):
     return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, short="ext-op", cases=rows)
 
 
+def run_bf16_family(torch_baseline=True, settle_ms=150.0):
+    """Large dense bf16 products (section IV-B: a batched evaluation must not trail the flat GEMM) through
+    sb_gemm in the three operand layouts: 4096^3 flat, eight batches of 2048^3 and 512 batches of 512^3.
+    A dense bf16 product runs this chip against its power limit, so the device is kept busy (the same call,
+    queued without gaps) for settle_ms before each timing, and the operands are normal random numbers: the
+    4096^3 T,N product is timed on all-zero operands too, which shows how much of the rate the data decide.
+    The vendor's batched GEMM (torch.bmm on the same buffers) is timed the same way."""
+    import torch
+    import paper_1606_05696_amd as sb
+    from paper_1606_05696_amd import inputs
+
+    def settled(fn):
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < settle_ms:
+            for _ in range(20):
+                fn()
+        torch.cuda.synchronize()
+        return time_stats(fn, iters=30, warmup=5, target_us=400.0)
+
+    layouts = {"T,N": ("km", "kn"), "N,N": ("mk", "kn"), "N,T": ("mk", "nk")}        # stored modes, first one contiguous
+    rows = []
+    for (n, batch) in ((4096, 1), (2048, 8), (512, 512)):
+        ext = dict(m=n, n=n, k=n, p=batch)
+        flops = 2 * n ** 3 * batch
+        for name, (ma, mb) in layouts.items():
+            mc = "mn"
+            dA, dB, dC = ([ext[c] for c in m + "p"] for m in (ma, mb, mc))       # the batch is the last, slowest mode of all three
+            A = inputs.make_tensor(7 * n + batch, dA, "bf16")
+            B = inputs.make_tensor(7 * n + batch + 1, dB, "bf16")
+            tA, tB = dev(A, "bf16"), dev(B, "bf16")
+            tC = torch.empty(int(np.prod(dC)), dtype=torch.bfloat16, device="cuda")
+
+            opA, opB = name.split(",")
+
+            def ours():
+                sb.sb_gemm(opA, opB, n, n, n, 1.0, tA, n, n * n, tB, n, n * n, 0.0, tC, n, n * n, batch, dt="bf16")
+
+            st = settled(ours)
+            family = sb.sb_last_kernel()
+            tC.fill_(float("nan"))
+            ours()
+            # eq. (1) has no index common to all three tensors: the first and the last batch are checked as matrices
+            ok = True
+            for q in sorted({0, batch - 1}):
+                chk = check_output(tC[q * n * n:(q + 1) * n * n], [n, n], ma, np.asfortranarray(A[:, :, q]), mb, np.asfortranarray(B[:, :, q]),
+                                   mc, "bf16", nsamples=1000)
+                ok = ok and chk["ok"]
+            tf = flops / st["median_us"] / 1e6
+            row = dict(layout=name, n=n, batch=batch, kernel_family=family, kernel_us=st, tflops=tf, frac_of_bf16_mfma_peak=tf / PEAK["mfma"]["bf16"],
+                       check_ok=ok)
+            if torch_baseline:
+                # the same buffers as (batch, rows, cols) views: the stored matrices are column-major
+                va = tA.view(batch, n, n).transpose(1, 2) if ma.startswith("m") else tA.view(batch, n, n)        # (m, k)
+                vb = tB.view(batch, n, n) if mb.startswith("k") else tB.view(batch, n, n).transpose(1, 2)        # (n, k)
+                sv = settled(lambda: torch.bmm(va, vb.transpose(1, 2)))
+                row["vendor_us"] = sv["median_us"]
+                row["vendor_tflops"] = flops / sv["median_us"] / 1e6
+            if n == 4096 and name == "T,N":
+                tA.zero_(); tB.zero_()
+                row["tflops_on_zero_operands"] = flops / settled(ours)["median_us"] / 1e6
+                if torch_baseline:
+                    row["vendor_tflops_on_zero_operands"] = flops / settled(lambda: torch.bmm(va, vb.transpose(1, 2)))["median_us"] / 1e6
+            rows.append(row)
+            del tA, tB, tC
+    return dict(workload="dense bf16 products 4096^3, 2048^3 x 8, 512^3 x 512 in three layouts", short="bf16-gemm", cases=rows)
+
+
 def run_sweeps(steps, warmup):
     """Size sweeps over cubic tensors in fp32, the shapes of the paper's GPU plots (section IV):
     batches of n small GEMMs (n x n x n) against the vendor's strided-batched GEMM; case 1.1 in its
@@ -716,6 +783,12 @@ def config_rows(head, others):
                                  min_us=c["kernel_us"]["min_us"], max_us=c["kernel_us"]["max_us"], bound="mfma", achieved=c["gflops"] / 1e3,
                                  unit="TFLOP/s", frac=c["frac_of_fp32_mfma_peak"], cold_frac=None, traffic=None,
                                  algorithmic_bytes=4 * (512 ** 2 + 2 * 512 ** 3), check_ok=c["check_ok"]))
+        elif o.get("short") == "bf16-gemm":
+            for c in o["cases"]:
+                rows.append(dict(config="bf16 %s %d^3 x %d" % (c["layout"], c["n"], c["batch"]), kernel_family=c["kernel_family"],
+                                 kernel_us=c["kernel_us"]["median_us"], min_us=c["kernel_us"]["min_us"], max_us=c["kernel_us"]["max_us"], bound="mfma",
+                                 achieved=c["tflops"], unit="TFLOP/s", frac=c["frac_of_bf16_mfma_peak"], cold_frac=None, traffic=None,
+                                 algorithmic_bytes=2 * 3 * c["n"] ** 2 * c["batch"], check_ok=c["check_ok"]))
         elif o.get("short") == "gemv":
             for c in o["cases"]:
                 rows.append(dict(config="gemv %s 512 x 512^2" % c["op"], kernel_family=c["kernel_family"], kernel_us=c["kernel_us"]["median_us"],
@@ -809,6 +882,7 @@ def main():
         others.append(run_table2_cases(max(args.steps, 200), args.warmup, tb))
         others.append(run_exceptional_cases(args.steps, args.warmup, torch_baseline=tb))
         others.append(run_batched_gemv(args.steps, args.warmup))
+        others.append(run_bf16_family(tb))
         if not args.no_tucker:
             others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others

@@ -8,6 +8,10 @@
 //   m/n contiguous operand (A with N, B with T): LDS [k][row]; the 8 k of a fragment are gathered
 //     with 2-byte LDS reads (conflict-free: the lanes of a read run along the row dimension).
 // The epilogue rounds alpha*acc + beta*C to bf16 (nearest even).
+// Three members: the plain kernel above (any size and alignment), the streaming kernel (whole 128 x 128 or
+// 256 x 256 tiles, persistent workgroups, panels staged through registers; an m/n-contiguous operand is
+// transposed in registers into the k-contiguous LDS layout), and the direct-to-LDS kernel (256 x 256 tiles,
+// both operands k-contiguous).
 #include "sb_device.h"
 #include "sb_internal.h"
 
@@ -451,163 +455,6 @@ void sbgemm_bf16_stream_kernel(SbArgs g, int tiles_m, int tiles_n)
     while (more) more = step();       // later tiles: follow a finished tile
 }
 
-// Ping-pong variant of the streaming kernel for 256 x 256 tiles: the same eight waves of 128 x 64, the same
-// panels and the same walk over tiles, but the two waves of a SIMD never do the same thing at the same
-// time.  Waves 0-3 (one per SIMD) and waves 4-7 alternate between a MEMORY phase (read the twelve
-// fragments of panel p from LDS, store the staged panel p+1 into the other LDS buffer, request panel p+3
-// from memory) and an MFMA phase (the sixteen products of panel p), with a workgroup barrier between
-// phases; the second group starts one barrier late, so while one wave of a SIMD feeds the matrix core the
-// other one does its LDS and memory work.  With both waves in step (the plain streaming kernel: a
-// barrier per panel keeps them there) all eight waves read LDS together while no MFMA is issued, and the
-// fragment reads alone cost a quarter of the run time.
-// Hazards with two LDS buffers, phases numbered t: group 0 runs MEM_p at t = 2p and MFMA_p at 2p+1, group
-// 1 one later.  Panel p is read at t = 2p and 2p+1; it was stored (each group its own share) at 2p-2 and
-// 2p-1; buffer (p+1)%2 is rewritten at t = 2p and 2p+1, after panel p-1 was last read at 2p-1.
-// k must hold an even number (>= 4) of 32-deep panels, so that every tile starts in buffer 0.
-template <bool BETA, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(512, 1) void sbgemm_bf16_pingpong_kernel(SbArgs g, int tiles_m, int tiles_n)
-{
-    constexpr int NBM = 4, NBN = 2, SBK = 32, WAVES_M = 2, WAVES_N = 4;
-    constexpr int WM = 32 * NBM, WN = 32 * NBN, TM = WAVES_M * WM, TN = WAVES_N * WN, NT = 64 * WAVES_M * WAVES_N;
-    typedef typename std::conditional<A_KC, PanelBf16<true, TM, SBK, true, NT>, PanelBf16T<TM, SBK, NT>>::type PA;
-    typedef typename std::conditional<B_KC, PanelBf16<true, TN, SBK, true, NT>, PanelBf16T<TN, SBK, NT>>::type PB;
-    constexpr int KG = SBK / 16;
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][PA::LDS_SIZE];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][PB::LDS_SIZE];
-
-    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
-    const int64_t panelA = A_KC ? SBK : (int64_t)SBK * g.csA, panelB = B_KC ? SBK : (int64_t)SBK * g.rsB;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) % WAVES_N * WN;
-    const bool late = wave >= 4;                 // second group: one phase behind
-    const float alpha = (float)g.alpha, beta = (float)g.beta;
-    const int64_t nkb = g.k / SBK;
-
-    const int64_t tiles = (int64_t)tiles_m * tiles_n;
-    const int64_t total = tiles * g.batch0 * g.batch1;
-    const int64_t nslots = (int64_t)gridDim.x / NXCD;           // the launcher makes gridDim.x a multiple of 8
-    const int64_t xcd = blockIdx.x % NXCD, slot = blockIdx.x / NXCD;
-    const int64_t q8 = total / NXCD, r8 = total % NXCD;
-    const int64_t first = xcd * q8 + (xcd < r8 ? xcd : r8);
-    const int64_t last = first + q8 + (xcd < r8 ? 1 : 0);
-    int64_t logical = first + slot;
-    if (logical >= last) return;
-
-    u16x8 ra[2][PA::NVEC], rb[2][PB::NVEC];
-    bf16x8 fa[KG][NBM], fb[KG][NBN];
-    f32x16 acc[NBM][NBN];
-
-    struct Loc { const uint16_t *A, *B; uint16_t *C; };
-    auto locate = [&](int64_t b, int tile) __attribute__((always_inline)) {
-        int64_t b0 = b, b1 = 0;
-        if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
-        const SbOff3 o1 = sb_level1(g, b1);
-        const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
-        const int64_t i0 = (int64_t)tm * TM, j0 = (int64_t)tn * TN;
-        Loc l;
-        l.A = (const uint16_t *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
-        l.B = (const uint16_t *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
-        l.C = (uint16_t *)g.C + b0 * g.bsC[0] + o1.c + i0 + j0 * g.ldc;
-        return l;
-    };
-    int64_t b = logical / tiles;
-    int tile = (int)(logical - b * tiles);
-    const int64_t dq = nslots / tiles;
-    const int dr = (int)(nslots - dq * tiles);
-
-    typedef std::integral_constant<int, 0> I0;
-    typedef std::integral_constant<int, 1> I1;
-    auto gload = [&](auto set, const uint16_t *pa, const uint16_t *pb) __attribute__((always_inline)) {
-        PA::load_plain(ra[decltype(set)::value], pa, ldA);
-        PB::load_plain(rb[decltype(set)::value], pb, ldB);
-    };
-    auto phase_end = [&]() __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // panel p with p % 2 == CUR: memory phase, then MFMA phase; pa / pb point at panel p + 3
-    auto panel = [&](auto cur_c, const uint16_t *pa, const uint16_t *pb) __attribute__((always_inline)) {
-        constexpr int CUR = decltype(cur_c)::value;
-#pragma unroll
-        for (int kg = 0; kg < KG; ++kg) {
-#pragma unroll
-            for (int a = 0; a < NBM; ++a) fa[kg][a] = PA::fragment(As[CUR], wm + a * 32, kg, lane);
-#pragma unroll
-            for (int c = 0; c < NBN; ++c) fb[kg][c] = PB::fragment(Bs[CUR], wn + c * 32, kg, lane);
-        }
-        PA::store(As[CUR ^ 1], ra[CUR ^ 1]);
-        PB::store(Bs[CUR ^ 1], rb[CUR ^ 1]);
-        gload(std::integral_constant<int, CUR ^ 1>(), pa, pb);
-        phase_end();
-#pragma unroll
-        for (int kg = 0; kg < KG; ++kg)
-#pragma unroll
-            for (int a = 0; a < NBM; ++a)
-#pragma unroll
-                for (int c = 0; c < NBN; ++c)     // C^T = B^T A^T: lanes run along rows of C
-                    acc[a][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kg][c], fa[kg][a], acc[a][c], 0, 0, 0);
-        phase_end();
-    };
-    // One tile.  On entry its panel 0 is complete in LDS buffer 0 (as seen by this wave's group), panel 1 is in
-    // staging set 1 and panel 2 in staging set 0 (both in flight), pa / pb point at panel 3.
-    auto run_tile = [&](const Loc &cur, const Loc &nxt, const uint16_t *&pa, const uint16_t *&pb) __attribute__((always_inline)) {
-#pragma unroll
-        for (int a = 0; a < NBM; ++a)
-#pragma unroll
-            for (int c = 0; c < NBN; ++c)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[a][c][r] = 0.f;
-        for (int64_t kb = 0; kb < nkb; kb += 2) {
-            panel(I0(), pa, pb);
-            pa += panelA; pb += panelB;
-            if (kb + 4 == nkb) { pa = nxt.A; pb = nxt.B; }                // panel kb + 4 is the next tile's first
-            panel(I1(), pa, pb);
-            pa += panelA; pb += panelB;
-        }
-        uint16_t *C = cur.C;
-#pragma unroll
-        for (int a = 0; a < NBM; ++a)
-#pragma unroll
-            for (int c = 0; c < NBN; ++c) {
-                uint16_t *col = C + wm + a * 32 + (lane & 31) + (int64_t)(wn + c * 32 + 4 * (lane >> 5)) * g.ldc;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    uint16_t *dst = col + (8 * (r >> 2) + (r & 3)) * g.ldc;
-                    float v = alpha * acc[a][c][r];
-                    if (BETA) v += beta * sb_bf16_to_f32(*dst);
-                    *dst = sb_f32_to_bf16(v);
-                }
-            }
-    };
-
-    Loc cur = locate(b, tile);
-    const uint16_t *pa = cur.A + 3 * panelA, *pb = cur.B + 3 * panelB;
-    {   // prime the stream with the first tile's panels 0, 1 and 2
-        gload(I0(), cur.A, cur.B);
-        gload(I1(), cur.A + panelA, cur.B + panelB);
-        PA::store(As[0], ra[0]);
-        PB::store(Bs[0], rb[0]);
-        gload(I0(), cur.A + 2 * panelA, cur.B + 2 * panelB);
-        phase_end();
-    }
-    if (late) phase_end();            // the second group starts one phase behind ...
-    bool more = true;
-    while (more) {
-        more = logical + nslots < last;
-        int tile2 = tile + dr;
-        int64_t b2 = b + dq;
-        if (tile2 >= tiles) { tile2 -= (int)tiles; ++b2; }
-        const Loc nxt = more ? locate(b2, tile2) : cur;       // the last tile names itself as successor: loads that are never used
-        run_tile(cur, nxt, pa, pb);
-        logical += nslots;
-        b = b2;
-        tile = tile2;
-        cur = nxt;
-    }
-    if (!late) phase_end();           // ... and the first one waits for it at the end: every wave passes the same number of barriers
-}
-
 // 16 bytes per lane from global memory straight into LDS (no staging registers, no LDS store instruction):
 // lane l of the wave lands at lds_addr + 16 l.  lds_addr and base are wave-uniform; voff is the lane's byte
 // offset from base (unsigned 32 bit).  The compiler does not see the LDS write behind this statement: the
@@ -818,16 +665,6 @@ hipError_t stream_by_layout(const SbArgs &a, Launch launch)
     return launch(sbgemm_bf16_stream_kernel<BETA, NBM, NBN, SBK, WAVES_M, WAVES_N, false, false>);
 }
 
-template <bool BETA, typename Launch>
-hipError_t pingpong_by_layout(const SbArgs &a, Launch launch)
-{
-    const bool ak = a.csA == 1, bk = a.rsB == 1;
-    if (ak && bk)  return launch(sbgemm_bf16_pingpong_kernel<BETA, true, true>);
-    if (ak && !bk) return launch(sbgemm_bf16_pingpong_kernel<BETA, true, false>);
-    if (!ak && bk) return launch(sbgemm_bf16_pingpong_kernel<BETA, false, true>);
-    return launch(sbgemm_bf16_pingpong_kernel<BETA, false, false>);
-}
-
 template <typename K>
 hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream, int nthreads = NTHREADS)
 {
@@ -911,16 +748,9 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
     if (stream_applies(a, 256, 32) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.15) <=
                                           sb_tile_time(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 1.0, 1.0)) {
         auto go = [&](auto kernel) { return launch_stream(kernel, 256, a, stream, 512); };
-#ifndef SB_BF16_NO_DMA
         if (dma_applies(a)) return a.beta == 0.0 ? launch_dma<false>(a, stream) : launch_dma<true>(a, stream);
-#endif
-#ifndef SB_BF16_NO_PINGPONG
-        if (a.beta == 0.0) return pingpong_by_layout<false>(a, go);
-        return pingpong_by_layout<true>(a, go);
-#else
         if (a.beta == 0.0) return stream_by_layout<false, 4, 2, 32, 2, 4>(a, go);
         return stream_by_layout<true, 4, 2, 32, 2, 4>(a, go);
-#endif
     }
     if (stream_applies(a, 128, 64)) {
         auto go = [&](auto kernel) { return launch_stream(kernel, 128, a, stream); };
