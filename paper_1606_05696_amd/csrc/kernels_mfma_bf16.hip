@@ -491,6 +491,38 @@ __device__ __forceinline__ void store_wave_tile(uint16_t *area, const f32x16 (&a
     }
 }
 
+// LDS panel of the direct-to-LDS kernel for an operand whose 256 ROWS (m or n) are contiguous in memory: it is
+// kept as it lies, [k][row], and transposed by the fragment read (ds_read_b64_tr_b16: in each group of 16 lanes,
+// lanes 4r .. 4r+3 point at 16 consecutive rows of k-row r and lane j receives row j of the four k-rows, so two
+// reads give a lane its 8 consecutive k).  A k-row is 512 bytes = 16 segments of 16 rows; segment s of k-row k
+// sits at position s ^ 2 (k % 4), which puts the eight segments a half wave reads (two neighbouring ones at four
+// consecutive k) on all banks.  Only whole 16-byte slots move, so the placement is free: the loads decide it.
+struct PanelRows {
+    static constexpr int ROWS = 256;
+    // element offset inside the panel of (k, row), row a multiple of 4: slot of 16 rows, then the row inside it
+    static __device__ __forceinline__ int at(int k, int row) { return k * ROWS + (((row >> 4) ^ (2 * (k & 3))) << 4) + (row & 15); }
+    // what the 16-byte slot `slot16` of the panel holds: k and first row
+    static __device__ __forceinline__ void source(int slot16, int &k, int &row)
+    {
+        k = slot16 >> 5;
+        const int pos = slot16 & 31;                      // 16-byte position inside the k-row
+        row = ((((pos >> 1) ^ (2 * (k & 3))) << 1) | (pos & 1)) << 3;
+    }
+    static __device__ __forceinline__ bf16x8 fragment(const uint16_t *lds, int row0, int ks, int lane)
+    {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const int i = lane & 15, g16 = lane >> 4;
+        const int k = ks * 16 + 8 * (g16 >> 1) + (i >> 2);                   // this lane's address: k-row of its quad, +4 for the second read
+        const int row = row0 + 16 * (g16 & 1) + 4 * (i & 3);
+        const uint16_t *p = lds + at(k, row);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * ROWS));     // (k + 4) % 4 == k % 4: same placement
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+};
+
 // 16 bytes per lane from global memory straight into LDS (no staging registers, no LDS store instruction):
 // lane l of the wave lands at lds_addr + 16 l.  lds_addr and base are wave-uniform; voff is the lane's byte
 // offset from base (unsigned 32 bit).  The compiler does not see the LDS write behind this statement: the
@@ -517,9 +549,11 @@ __device__ __forceinline__ void dma_wait()
 // issue rate (the same instruction stream is 1.25-1.35x faster on zeros), so bytes moved per flop count twice.
 // Per panel and wave: four k-steps of 6 fragment reads and 8 MFMAs, two fragment sets; before the last k-step:
 // wait for the panel in flight, barrier, request the panel after it, first fragments of the new stage.
-// The swizzled [row][k] layout is produced by the choice of what each lane fetches: lane l of load j fills
-// chunk slot 64 (8 j + wave) + l, i.e. row slot / 8, and fetches that row's k-chunk (slot % 8) ^ f(row).
-template <bool BETA>
+// The swizzled [row][k] layout of a k-contiguous operand is produced by the choice of what each lane fetches:
+// lane l of load j fills chunk slot 64 (8 j + wave) + l, i.e. row slot / 8, and fetches that row's k-chunk
+// (slot % 8) ^ f(row).  An operand with m or n contiguous lands as [k][row] (PanelRows) and is transposed by its
+// fragment reads: twice as many LDS instructions for that operand, nothing else.
+template <bool BETA, bool A_KC, bool B_KC>
 __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
     constexpr int NBM = 4, NBN = 2, SBK = 64, WAVES_M = 2, WAVES_N = 4, KG = SBK / 16;
@@ -534,7 +568,10 @@ __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int t
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
     const float alpha = (float)g.alpha, beta = (float)g.beta;
     const int64_t nkb = g.k / SBK;
-    const int64_t ldA = g.rsA, ldB = g.csB;
+    // leading dimension of a panel (row stride of a k-contiguous operand, k stride of the other kind) and the
+    // element step from one panel to the next
+    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
+    const int64_t panelA = A_KC ? SBK : (int64_t)SBK * g.csA, panelB = B_KC ? SBK : (int64_t)SBK * g.rsB;
 
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
     const int64_t total = tiles * g.batch0 * g.batch1;
@@ -551,9 +588,11 @@ __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int t
 #pragma unroll
     for (int j = 0; j < NLOAD; ++j) {
         const int slot16 = 64 * (8 * j + wave) + lane;          // 16-byte slot inside the panel
-        const int row = slot16 / P::CPR, k = P::swizzled(row, (slot16 % P::CPR) * 8);      // the swizzle is its own inverse
-        offA[j] = (unsigned)(((int64_t)row * ldA + k) * 2);
-        offB[j] = (unsigned)(((int64_t)row * ldB + k) * 2);
+        int rowk = slot16 / P::CPR, kk = P::swizzled(rowk, (slot16 % P::CPR) * 8);      // the swizzle is its own inverse
+        int kr, rowr;
+        PanelRows::source(slot16, kr, rowr);
+        offA[j] = (unsigned)((A_KC ? (int64_t)rowk * ldA + kk : (int64_t)kr * ldA + rowr) * 2);
+        offB[j] = (unsigned)((B_KC ? (int64_t)rowk * ldB + kk : (int64_t)kr * ldB + rowr) * 2);
     }
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) uint16_t *)lds;
     const unsigned land = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);           // + 8192 j, + P::LDS_SIZE * 2 for B, + STAGE * 2 per stage
@@ -593,9 +632,9 @@ __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int t
         constexpr int SET = decltype(set_c)::value, ST = decltype(st_c)::value;
         const uint16_t *As = lds + ST * STAGE, *Bs = As + P::LDS_SIZE;
 #pragma unroll
-        for (int a = 0; a < NBM; ++a) fa[SET][a] = P::fragment(As, wm + a * 32, kg, lane);
+        for (int a = 0; a < NBM; ++a) fa[SET][a] = A_KC ? P::fragment(As, wm + a * 32, kg, lane) : PanelRows::fragment(As, wm + a * 32, kg, lane);
 #pragma unroll
-        for (int c = 0; c < NBN; ++c) fb[SET][c] = P::fragment(Bs, wn + c * 32, kg, lane);
+        for (int c = 0; c < NBN; ++c) fb[SET][c] = B_KC ? P::fragment(Bs, wn + c * 32, kg, lane) : PanelRows::fragment(Bs, wn + c * 32, kg, lane);
     };
     auto mfmas = [&](auto set_c) __attribute__((always_inline)) {
         constexpr int SET = decltype(set_c)::value;
@@ -642,9 +681,9 @@ __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int t
         for (int64_t kb = 0; kb < nkb; kb += 2) {
             if (kb + 2 == nkb) { pa = nxt.A; pb = nxt.B; }                // panel kb + 2 is the next tile's first
             panel(I0(), pa, pb);
-            pa += SBK; pb += SBK;
+            pa += panelA; pb += panelB;
             panel(I1(), pa, pb);
-            pa += SBK; pb += SBK;
+            pa += panelA; pb += panelB;
         }
         uint16_t *C = cur.C;
         if (!BETA) {
@@ -667,9 +706,9 @@ __global__ __launch_bounds__(512, 1) void sbgemm_bf16_dma_kernel(SbArgs g, int t
     };
 
     Loc cur = locate(b, tile);
-    const uint16_t *pa = cur.A + 2 * SBK, *pb = cur.B + 2 * SBK;
+    const uint16_t *pa = cur.A + 2 * panelA, *pb = cur.B + 2 * panelB;
     request(I0(), cur.A, cur.B);
-    request(I1(), cur.A + SBK, cur.B + SBK);
+    request(I1(), cur.A + panelA, cur.B + panelB);
     dma_wait<2 * NLOAD>();                 // panel 0 has landed; panel 1 may still be under way
     __syncthreads();
     read_frags(I0(), I0(), 0);
@@ -723,19 +762,20 @@ hipError_t launch_stream(K kernel, int tile, const SbArgs &a, hipStream_t stream
     return hipGetLastError();
 }
 
-// the direct-to-LDS kernel: both operands k-contiguous, an even number of 64-deep panels, row offsets inside
-// a tile that fit the 32-bit lane offsets of its loads
+// the direct-to-LDS kernel: each operand k-contiguous or row-contiguous, an even number of 64-deep panels,
+// offsets inside a panel (256 rows or 64 k-rows of the leading dimension) that fit the 32-bit lane offsets
 bool dma_applies(const SbArgs &a)
 {
     const int64_t most = (int64_t)1 << 22;
-    return a.csA == 1 && a.rsB == 1 && a.k % 128 == 0 && a.rsA <= most && a.csB <= most;
+    const bool a_ok = a.csA == 1 || a.rsA == 1, b_ok = a.rsB == 1 || a.csB == 1;
+    return a_ok && b_ok && a.k % 128 == 0 && a.rsA <= most && a.csA <= most && a.rsB <= most && a.csB <= most;
 }
 
-template <bool BETA>
+template <bool BETA, bool A_KC, bool B_KC>
 hipError_t launch_dma(const SbArgs &a, hipStream_t stream)
 {
     const int lds_bytes = 2 * 2 * 256 * 64 * 2 + 8 * 4096;  // two stages of an A and a B panel, the epilogue areas of eight waves
-    auto kernel = sbgemm_bf16_dma_kernel<BETA>;
+    auto kernel = sbgemm_bf16_dma_kernel<BETA, A_KC, B_KC>;
     static std::atomic<bool> configured[SB_MAX_DEVICES] = {};
     const int dev = sb_current_device();
     if (!configured[dev]) {
@@ -790,7 +830,13 @@ hipError_t sb_launch_mfma_bf16(const SbArgs &a, hipStream_t stream)
     if (stream_applies(a, 256, 32) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.15) <=
                                           sb_tile_time(((a.m + 127) / 128) * ((a.n + 127) / 128) * batch, 1.0, 1.0)) {
         auto go = [&](auto kernel) { return launch_stream(kernel, 256, a, stream, 512); };
-        if (dma_applies(a)) return a.beta == 0.0 ? launch_dma<false>(a, stream) : launch_dma<true>(a, stream);
+        if (dma_applies(a)) {
+            const bool ak = a.csA == 1, bk = a.rsB == 1, b0 = a.beta == 0.0;
+            if (ak && bk)  return b0 ? launch_dma<false, true, true>(a, stream) : launch_dma<true, true, true>(a, stream);
+            if (ak && !bk) return b0 ? launch_dma<false, true, false>(a, stream) : launch_dma<true, true, false>(a, stream);
+            if (!ak && bk) return b0 ? launch_dma<false, false, true>(a, stream) : launch_dma<true, false, true>(a, stream);
+            return b0 ? launch_dma<false, false, false>(a, stream) : launch_dma<true, false, false>(a, stream);
+        }
         if (a.beta == 0.0) return stream_by_layout<false, 4, 2, 32, 2, 4>(a, go);
         return stream_by_layout<true, 4, 2, 32, 2, 4>(a, go);
     }

@@ -730,6 +730,8 @@ def test_sb_gemm_whole_tile_shapes_bf16():
                                      # k a multiple of 128: the 256 x 256 member that loads straight into LDS (2, 6 and 10 panels of 64;
                                      # more tiles than workgroups, so the panel stream crosses tile boundaries)
                                      ("T", "N", 512, 512, 384, 128), ("T", "N", 256, 768, 640, 170),
+                                     # the same member with row-contiguous operands (kept [k][row] in LDS, transposed by the fragment reads)
+                                     ("N", "T", 512, 512, 384, 128), ("T", "T", 256, 768, 256, 170), ("N", "N", 768, 256, 128, 171),
                                      # operands with m or n contiguous are transposed on their way into LDS: the same
                                      # streaming kernels in the other three layouts, 128 x 128 and 256 x 256 tiles
                                      ("N", "N", 256, 384, 256, 5), ("N", "T", 128, 256, 384, 3), ("T", "T", 384, 128, 512, 2),
