@@ -63,6 +63,7 @@ def parse_args():
     ap.add_argument("--sweeps", action="store_true",
                     help="instead of the other workloads, add the size sweeps (cubic tensors, n = 8 .. 512) to the line")
     ap.add_argument("--sweeps-summary", default=None, help="with --sweeps: also write the sweeps as a text table to this file")
+    ap.add_argument("--no-bf16-family", action="store_true", help="skip the dense bf16 products (the profiler commands under profiles/ do)")
     ap.add_argument("--no-tucker", action="store_true", help="skip the Tucker/HOOI timings (tens of thousands of small launches)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one device copy of known size (to scale rocprofv3 byte counters)")
@@ -882,7 +883,8 @@ def main():
         others.append(run_table2_cases(max(args.steps, 200), args.warmup, tb))
         others.append(run_exceptional_cases(args.steps, args.warmup, torch_baseline=tb))
         others.append(run_batched_gemv(args.steps, args.warmup))
-        others.append(run_bf16_family(tb))
+        if not args.no_bf16_family:
+            others.append(run_bf16_family(tb))
         if not args.no_tucker:
             others.append(run_tucker(with_oracle=not args.no_cpu_baseline))
         result["workloads"] = others
