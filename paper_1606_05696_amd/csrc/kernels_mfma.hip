@@ -567,6 +567,205 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_stream_ker
     while (more) more = step();       // later tiles: follow a finished tile
 }
 
+// 16 bytes per lane from global memory straight into LDS (no staging registers, no LDS store instruction):
+// lane l of the wave lands at lds_addr + 16 l.  lds_addr and base are wave-uniform; voff is the lane's byte
+// offset from base (unsigned 32 bit).  The compiler does not see the LDS write behind this statement: the
+// code that reads the data waits for it itself (dma_wait) before the barrier that publishes it.  M0 is not
+// allocated by the compiler and nothing else in these kernels uses it.
+__device__ __forceinline__ void dma16(unsigned lds_addr, const void *base, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+}
+// wait until at most N vector-memory operations of this wave are outstanding (they complete in order)
+template <int N>
+__device__ __forceinline__ void dma_wait()
+{
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));      // expcnt and lgkmcnt fields: no wait
+}
+
+// Direct-to-LDS member of the streaming family: whole tiles, both operands k-contiguous, an even number of
+// BK-deep panels, rows of BK elements = 128 bytes (whole cache lines).  Same walk over the tiles and the same
+// fragment schedule as sbgemm_mfma_stream_kernel, but the panels travel from memory into one of two LDS stages
+// without passing through registers: the panel after the next one is requested right after the barrier that
+// frees its stage and has a whole panel's MFMAs to arrive.  What this saves is the staging registers and,
+// measured on the register-staged kernel at 512^4, the 3 % of the run time that its LDS stores cost and part
+// of the 3 % of its global loads.  The swizzled [row][k] layout (Panel<.., KC = true>) is produced by the
+// choice of what each lane fetches: lane l of load j fills 16-byte slot 64 (NW j + wave) + l of the panel,
+// i.e. row slot / CPR, and fetches that row's chunk (slot % CPR) ^ f(row).
+template <typename MFT, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel(SbArgs g, int tiles_m, int tiles_n)
+{
+    typedef Config<MFT, true, true, BK, WM, WN, WAVES_M, WAVES_N, 2> CF;
+    typedef typename CF::MF MF;
+    typedef typename MF::T T;
+    typedef typename CF::PA PA;
+    typedef typename CF::PB PB;
+    constexpr int MI = MF::MI, VEC = MF::VEC, BM = CF::BM, BN = CF::BN, KG = BK / MF::KGROUP, NW = WAVES_M * WAVES_N;
+    static_assert(BK * sizeof(T) == 128 && PA::CPR == 8, "a panel row is one 128-byte line of eight chunks");
+    static_assert((BM * 8) % (64 * NW) == 0 && (BN * 8) % (64 * NW) == 0, "whole wave loads per panel");
+    constexpr int NLA = BM * 8 / (64 * NW), NLB = BN * 8 / (64 * NW);        // 16-byte loads per lane and panel
+    constexpr int STAGE = PA::LDS_SIZE + PB::LDS_SIZE;                       // elements per stage: A panel, B panel
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
+    T *lds = (T *)lds_bytes;                                                 // [stage][A | B]
+
+    const int64_t ldA = g.rsA, ldB = g.csB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
+    const T alpha = (T)g.alpha, beta = (T)g.beta;
+    const int64_t nkb = g.k / BK;
+
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int64_t total = tiles * g.batch0 * g.batch1;
+    const int64_t nslots = (int64_t)gridDim.x / NXCD;
+    const int64_t xcd = blockIdx.x % NXCD, slot = blockIdx.x / NXCD;
+    const int64_t q8 = total / NXCD, r8 = total % NXCD;
+    const int64_t first = xcd * q8 + (xcd < r8 ? xcd : r8);
+    const int64_t last = first + q8 + (xcd < r8 ? 1 : 0);
+    int64_t logical = first + slot;
+    if (logical >= last) return;
+
+    // what this lane fetches: byte offsets from the panel's first element, per load; and where its wave's loads land
+    unsigned offA[NLA], offB[NLB];
+#pragma unroll
+    for (int j = 0; j < NLA; ++j) {
+        const int slot16 = 64 * (NW * j + wave) + lane;
+        const int row = slot16 / 8, k = PA::swizzled(row, (slot16 % 8) * VEC);      // the swizzle is its own inverse
+        offA[j] = (unsigned)(((int64_t)row * ldA + k) * sizeof(T));
+    }
+#pragma unroll
+    for (int j = 0; j < NLB; ++j) {
+        const int slot16 = 64 * (NW * j + wave) + lane;
+        const int row = slot16 / 8, k = PB::swizzled(row, (slot16 % 8) * VEC);
+        offB[j] = (unsigned)(((int64_t)row * ldB + k) * sizeof(T));
+    }
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_bytes;
+    const unsigned land = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+
+    T fa[2][CF::NBM][VEC], fb[2][CF::NBN][VEC];
+    typename MF::Acc acc[CF::NBM][CF::NBN];
+
+    struct Loc { const T *A, *B; T *C; };
+    auto locate = [&](int64_t b, int tile) __attribute__((always_inline)) {
+        int64_t b0 = b, b1 = 0;
+        if (g.batch1 != 1) { b1 = b / g.batch0; b0 = b - b1 * g.batch0; }
+        const SbOff3 o1 = sb_level1(g, b1);
+        const unsigned tn = (unsigned)tile / (unsigned)tiles_m, tm = (unsigned)tile - tn * (unsigned)tiles_m;
+        const int64_t i0 = (int64_t)tm * BM, j0 = (int64_t)tn * BN;
+        Loc l;
+        l.A = (const T *)g.A + b0 * g.bsA[0] + o1.a + i0 * g.rsA;
+        l.B = (const T *)g.B + b0 * g.bsB[0] + o1.b + j0 * g.csB;
+        l.C = (T *)g.C + b0 * g.bsC[0] + o1.c + i0 + j0 * g.ldc;
+        return l;
+    };
+    int64_t b = logical / tiles;
+    int tile = (int)(logical - b * tiles);
+    const int64_t dq = nslots / tiles;
+    const int dr = (int)(nslots - dq * tiles);
+
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    auto request = [&](auto st_c, const T *pa, const T *pb) __attribute__((always_inline)) {
+        constexpr unsigned at = decltype(st_c)::value * STAGE * sizeof(T);
+#pragma unroll
+        for (int j = 0; j < NLA; ++j) dma16(land + at + j * NW * 1024, pa, offA[j]);
+#pragma unroll
+        for (int j = 0; j < NLB; ++j) dma16(land + at + PA::LDS_SIZE * sizeof(T) + j * NW * 1024, pb, offB[j]);
+    };
+    auto read_frags = [&](auto set_c, auto st_c, int kg) __attribute__((always_inline)) {
+        constexpr int SET = decltype(set_c)::value, ST = decltype(st_c)::value;
+        const T *As = lds + ST * STAGE, *Bs = As + PA::LDS_SIZE;
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+#pragma unroll
+        for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[SET][c], Bs, wn + c * MI, kg, lane);
+    };
+    // One panel in stage ST: KG k-groups on two alternating fragment sets.  Before the last group's MFMAs: wait
+    // for the panel in flight, barrier (all waves have read this stage's last fragments), request the panel
+    // after the next one into this stage, read the first fragments of the other stage.
+    auto panel = [&](auto st_c, const T *pa, const T *pb) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        typedef std::integral_constant<int, ST> S;
+        typedef std::integral_constant<int, ST ^ 1> SN;
+#pragma unroll
+        for (int kg = 0; kg < KG; ++kg) {
+            const int fs = kg & 1;
+            if (kg + 1 < KG) {
+                if (fs == 0) read_frags(I1(), S(), kg + 1);
+                else         read_frags(I0(), S(), kg + 1);
+            } else {
+                __builtin_amdgcn_sched_barrier(0);
+                dma_wait<0>();
+                __syncthreads();
+                request(S(), pa, pb);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(I0(), SN(), 0);
+            }
+            __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+                    for (int c = 0; c < CF::NBN; ++c) MF::mma(acc[a][c], fb[fs][c][e], fa[fs][a][e]);   // C^T = B^T A^T
+            __builtin_amdgcn_s_setprio(0);
+        }
+    };
+    // One tile: its panel 0 is complete in stage 0 with the first fragments requested, panel 1 in flight into
+    // stage 1; pa / pb point at panel 2.
+    auto run_tile = [&](const Loc &cur, const Loc &nxt, const T *&pa, const T *&pb) __attribute__((always_inline)) {
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c)
+#pragma unroll
+                for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = T(0);
+        for (int64_t kb = 0; kb < nkb; kb += 2) {
+            if (kb + 2 == nkb) { pa = nxt.A; pb = nxt.B; }                // panel kb + 2 is the next tile's first
+            panel(I0(), pa, pb);
+            pa += BK; pb += BK;
+            panel(I1(), pa, pb);
+            pa += BK; pb += BK;
+        }
+        T *C = cur.C;
+#pragma unroll
+        for (int a = 0; a < CF::NBM; ++a)
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c) {
+                T *col = C + wm + a * MI + (lane % MI) + (int64_t)(wn + c * MI + MF::result_row_lane(lane)) * g.ldc;
+#pragma unroll
+                for (int r = 0; r < MF::NREG; ++r) {
+                    T *dst = col + MF::result_row_reg(r) * g.ldc;
+                    T v = alpha * acc[a][c][r];
+                    if (BETA) v += beta * *dst;
+                    *dst = v;
+                }
+            }
+    };
+
+    Loc cur = locate(b, tile);
+    const T *pa = cur.A + 2 * BK, *pb = cur.B + 2 * BK;
+    request(I0(), cur.A, cur.B);
+    request(I1(), cur.A + BK, cur.B + BK);
+    dma_wait<NLA + NLB>();                 // panel 0 has landed; panel 1 may still be under way
+    __syncthreads();
+    read_frags(I0(), I0(), 0);
+    bool more = true;
+    while (more) {
+        more = logical + nslots < last;
+        int tile2 = tile + dr;
+        int64_t b2 = b + dq;
+        if (tile2 >= tiles) { tile2 -= (int)tiles; ++b2; }
+        const Loc nxt = more ? locate(b2, tile2) : cur;       // the last tile names itself as successor: panels that are never used
+        run_tile(cur, nxt, pa, pb);
+        logical += nslots;
+        b = b2;
+        tile = tile2;
+        cur = nxt;
+    }
+    dma_wait<0>();                         // nothing of this workgroup may still be writing LDS when it ends
+}
+
 // Launch `kernel` with as many workgroups as can be resident at once (a multiple of the XCD
 // count), or fewer if there are fewer tiles.  The residency of a kernel is asked once per device.
 template <typename K, typename... Extra>
@@ -579,6 +778,54 @@ hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStr
     grid = (grid + NXCD - 1) / NXCD * NXCD;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(nthreads), 0, stream, a, tm, tn, extra...);
     return hipGetLastError();
+}
+
+// The direct-to-LDS kernel of a configuration: whole tiles, both operands k-contiguous, an even number of
+// BK-deep panels, row offsets inside a tile that fit the 32-bit lane offsets of its loads.
+template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+bool dma_applies(const SbArgs &a)
+{
+    const int64_t most = (int64_t)1 << 21;
+    return a.csA == 1 && a.rsB == 1 && a.m % (WM * WAVES_M) == 0 && a.n % (WN * WAVES_N) == 0 && a.k % (2 * BK) == 0 &&
+           a.rsA <= most && a.csB <= most;
+}
+
+// (one function per kernel: the set-up flags below belong to that kernel alone)
+template <typename MFT, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+hipError_t launch_dma_kernel(const SbArgs &a, hipStream_t stream)
+{
+    typedef typename MFT::T T;
+    constexpr int BM = WM * WAVES_M, BN = WN * WAVES_N, NT = 64 * WAVES_M * WAVES_N;
+    const int lds_bytes = 2 * (BM + BN) * BK * (int)sizeof(T);
+    const int64_t tiles_m = a.m / BM, tiles_n = a.n / BN;
+    const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
+    if (total <= 0) return hipSuccess;
+    if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
+    auto kernel = sbgemm_mfma_dma_kernel<MFT, BETA, BK, WM, WN, WAVES_M, WAVES_N>;
+    static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};          // 0: this device has not been set up for the kernel yet
+    const int dev = sb_current_device();
+    int resident = resident_of[dev];
+    if (resident == 0) {
+        int per_cu = 0, cus = 0;
+        hipError_t e = hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, NT, lds_bytes);
+        if (e != hipSuccess) return e;
+        if (per_cu < 1 || cus < 1) return hipErrorInvalidConfiguration;
+        resident = per_cu * cus;
+        resident_of[dev] = resident;
+    }
+    int64_t grid = total < resident ? total : resident;
+    grid = (grid + NXCD - 1) / NXCD * NXCD;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(NT), lds_bytes, stream, a, (int)tiles_m, (int)tiles_n);
+    return hipGetLastError();
+}
+
+template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+hipError_t launch_dma(const SbArgs &a, hipStream_t stream)
+{
+    if (a.beta == 0.0) return launch_dma_kernel<MFT, false, BK, WM, WN, WAVES_M, WAVES_N>(a, stream);
+    return launch_dma_kernel<MFT, true, BK, WM, WN, WAVES_M, WAVES_N>(a, stream);
 }
 
 // STREAM_ONLY: the caller has checked that the problem is made of whole tiles (stream_applies), so
@@ -695,8 +942,12 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         {
             const int64_t batch = a.batch0 * a.batch1;
             const double t128 = sb_tile_time(tiles128, 1.0, 1.0);
-            if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.04) <= t128)
+            if (stream_applies<MfmaF32x32>(a, 256, 256, 16) && sb_tile_time((a.m / 256) * (a.n / 256) * batch, 4.0, 1.04) <= t128) {
+#ifndef SB_F32_NO_DMA
+                if (dma_applies<MfmaF32x32, 32, 128, 64, 2, 4>(a)) return launch_dma<MfmaF32x32, 32, 128, 64, 2, 4>(a, stream);
+#endif
                 return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
+            }
             if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_tile_time((a.m / 128) * (a.n / 256) * batch, 2.0, 1.02) <= t128)
                 return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
         }
@@ -705,6 +956,9 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF64x16, 16, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
         if (small_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
+#ifndef SB_F64_NO_DMA
+        if (dma_applies<MfmaF64x16, 16, 32, 32, 4, 4>(a)) return launch_dma<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);
+#endif
         return launch<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);                                 // 128 x 128 tiles, 16 waves
     case SB_BF16: return sb_launch_mfma_bf16(a, stream);
     default: break;

@@ -705,7 +705,10 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
     # of the last five, two fill the chip with 128 x 256 tiles and two with 256 x 256 tiles (the eight-wave fp32
     # configurations); the one between them would leave a round mostly empty with either and stays on 128 x 128
     for m, n, k, batch in ((256, 384, 64, 5), (256, 384, 64, 30), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1),
-                           (384, 512, 96, 128), (128, 256, 160, 512), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128)):
+                           (384, 512, 96, 128), (128, 256, 160, 512), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128),
+                           # 256 x 256 tiles with k a multiple of 64: in fp32 with both operands k-contiguous the member that
+                           # loads straight into LDS (2, 6 and 4 panels of 32; the last with two tiles per workgroup)
+                           (256, 256, 192, 256), (512, 512, 128, 128)):
         lda = (m if opA == "N" else k) + 4
         ldb = (k if opB == "N" else n) + 8
         ldc = m + 12
