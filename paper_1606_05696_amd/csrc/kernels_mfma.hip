@@ -584,6 +584,35 @@ __device__ __forceinline__ void dma_wait()
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));      // expcnt and lgkmcnt fields: no wait
 }
 
+// LDS panel of the direct-to-LDS kernel for an operand whose ROWS (m or n) are contiguous in memory: kept as it
+// lies, [k][row], in 16-byte slots of RPS rows.  A fragment is VEC scalar reads, VEC k-rows apart, with lanes
+// along the rows; the lane groups of a wave read k-rows VEC apart, which a plain layout would put on the same
+// banks, so the slots of k-row k sit at position slot ^ 8 ((k / VEC) % 2): neighbouring lane groups read from
+// different halves of the banks.  Only whole slots move, so the loads produce this placement by what they fetch.
+template <typename MF, int ROWS, int BK>
+struct RowPanel {
+    typedef typename MF::T T;
+    static constexpr int VEC = MF::VEC, RPS = 16 / (int)sizeof(T), SLOTS = ROWS / RPS;      // rows per slot, slots per k-row
+    static constexpr int LDS_SIZE = ROWS * BK;
+    static_assert(SLOTS >= 16 && RPS == VEC, "a 16-byte slot holds VEC rows; the placement flips slot bit 3");
+    static __device__ __forceinline__ int flip(int k) { return ((k / VEC) & 1) << 3; }
+    // what the 16-byte slot `slot16` of the panel holds: k and first row
+    static __device__ __forceinline__ void source(int slot16, int &k, int &row)
+    {
+        k = slot16 / SLOTS;
+        row = ((slot16 % SLOTS) ^ flip(k)) * RPS;
+    }
+    static __device__ __forceinline__ void fragment(T (&frag)[VEC], const T *lds, int row0, int kg, int lane)
+    {
+        constexpr int MI = MF::MI;
+        const int row = row0 + (lane % MI);
+        const int k = kg * MF::KGROUP + (lane / MI) * VEC;                 // (k + e) / VEC == k / VEC for e < VEC: one placement per lane
+        const T *p = lds + k * ROWS + (((row / RPS) ^ flip(k)) * RPS) + row % RPS;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) frag[e] = p[e * ROWS];
+    }
+};
+
 // Direct-to-LDS member of the streaming family: whole tiles, both operands k-contiguous, an even number of
 // BK-deep panels, rows of BK elements = 128 bytes (whole cache lines).  Same walk over the tiles and the same
 // fragment schedule as sbgemm_mfma_stream_kernel, but the panels travel from memory into one of two LDS stages
@@ -592,15 +621,18 @@ __device__ __forceinline__ void dma_wait()
 // measured on the register-staged kernel at 512^4, the 3 % of the run time that its LDS stores cost and part
 // of the 3 % of its global loads.  The swizzled [row][k] layout (Panel<.., KC = true>) is produced by the
 // choice of what each lane fetches: lane l of load j fills 16-byte slot 64 (NW j + wave) + l of the panel,
-// i.e. row slot / CPR, and fetches that row's chunk (slot % CPR) ^ f(row).
-template <typename MFT, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+// i.e. row slot / CPR, and fetches that row's chunk (slot % CPR) ^ f(row).  An operand with m or n contiguous
+// lands as [k][row] (RowPanel) and is read with lanes along the rows, one element per k.
+template <typename MFT, bool A_KC, bool B_KC, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
-    typedef Config<MFT, true, true, BK, WM, WN, WAVES_M, WAVES_N, 2> CF;
+    typedef Config<MFT, true, true, BK, WM, WN, WAVES_M, WAVES_N, 2> CF;         // k-contiguous layouts and fragment reads
     typedef typename CF::MF MF;
     typedef typename MF::T T;
     typedef typename CF::PA PA;
     typedef typename CF::PB PB;
+    typedef RowPanel<MFT, CF::BM, BK> RA;
+    typedef RowPanel<MFT, CF::BN, BK> RB;
     constexpr int MI = MF::MI, VEC = MF::VEC, BM = CF::BM, BN = CF::BN, KG = BK / MF::KGROUP, NW = WAVES_M * WAVES_N;
     static_assert(BK * sizeof(T) == 128 && PA::CPR == 8, "a panel row is one 128-byte line of eight chunks");
     static_assert((BM * 8) % (64 * NW) == 0 && (BN * 8) % (64 * NW) == 0, "whole wave loads per panel");
@@ -609,7 +641,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_bytes[];
     T *lds = (T *)lds_bytes;                                                 // [stage][A | B]
 
-    const int64_t ldA = g.rsA, ldB = g.csB;
+    // leading dimension of a panel (row stride of a k-contiguous operand, k stride of the other kind) and the
+    // element step from one panel to the next
+    const int64_t ldA = A_KC ? g.rsA : g.csA, ldB = B_KC ? g.csB : g.rsB;
+    const int64_t panelA = A_KC ? BK : (int64_t)BK * g.csA, panelB = B_KC ? BK : (int64_t)BK * g.rsB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave % WAVES_M) * WM, wn = (wave / WAVES_M) * WN;
     const T alpha = (T)g.alpha, beta = (T)g.beta;
@@ -630,14 +665,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel
 #pragma unroll
     for (int j = 0; j < NLA; ++j) {
         const int slot16 = 64 * (NW * j + wave) + lane;
-        const int row = slot16 / 8, k = PA::swizzled(row, (slot16 % 8) * VEC);      // the swizzle is its own inverse
-        offA[j] = (unsigned)(((int64_t)row * ldA + k) * sizeof(T));
+        int row = slot16 / 8, k = PA::swizzled(row, (slot16 % 8) * VEC);            // the swizzle is its own inverse
+        if (!A_KC) RA::source(slot16, k, row);
+        offA[j] = (unsigned)((A_KC ? (int64_t)row * ldA + k : (int64_t)k * ldA + row) * sizeof(T));
     }
 #pragma unroll
     for (int j = 0; j < NLB; ++j) {
         const int slot16 = 64 * (NW * j + wave) + lane;
-        const int row = slot16 / 8, k = PB::swizzled(row, (slot16 % 8) * VEC);
-        offB[j] = (unsigned)(((int64_t)row * ldB + k) * sizeof(T));
+        int row = slot16 / 8, k = PB::swizzled(row, (slot16 % 8) * VEC);
+        if (!B_KC) RB::source(slot16, k, row);
+        offB[j] = (unsigned)((B_KC ? (int64_t)row * ldB + k : (int64_t)k * ldB + row) * sizeof(T));
     }
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_bytes;
     const unsigned land = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
@@ -676,9 +713,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel
         constexpr int SET = decltype(set_c)::value, ST = decltype(st_c)::value;
         const T *As = lds + ST * STAGE, *Bs = As + PA::LDS_SIZE;
 #pragma unroll
-        for (int a = 0; a < CF::NBM; ++a) PA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+        for (int a = 0; a < CF::NBM; ++a) {
+            if (A_KC) PA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+            else      RA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+        }
 #pragma unroll
-        for (int c = 0; c < CF::NBN; ++c) PB::fragment(fb[SET][c], Bs, wn + c * MI, kg, lane);
+        for (int c = 0; c < CF::NBN; ++c) {
+            if (B_KC) PB::fragment(fb[SET][c], Bs, wn + c * MI, kg, lane);
+            else      RB::fragment(fb[SET][c], Bs, wn + c * MI, kg, lane);
+        }
     };
     // One panel in stage ST: KG k-groups on two alternating fragment sets.  Before the last group's MFMAs: wait
     // for the panel in flight, barrier (all waves have read this stage's last fragments), request the panel
@@ -723,9 +766,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel
         for (int64_t kb = 0; kb < nkb; kb += 2) {
             if (kb + 2 == nkb) { pa = nxt.A; pb = nxt.B; }                // panel kb + 2 is the next tile's first
             panel(I0(), pa, pb);
-            pa += BK; pb += BK;
+            pa += panelA; pb += panelB;
             panel(I1(), pa, pb);
-            pa += BK; pb += BK;
+            pa += panelA; pb += panelB;
         }
         T *C = cur.C;
 #pragma unroll
@@ -744,9 +787,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel
     };
 
     Loc cur = locate(b, tile);
-    const T *pa = cur.A + 2 * BK, *pb = cur.B + 2 * BK;
+    const T *pa = cur.A + 2 * panelA, *pb = cur.B + 2 * panelB;
     request(I0(), cur.A, cur.B);
-    request(I1(), cur.A + BK, cur.B + BK);
+    request(I1(), cur.A + panelA, cur.B + panelB);
     dma_wait<NLA + NLB>();                 // panel 0 has landed; panel 1 may still be under way
     __syncthreads();
     read_frags(I0(), I0(), 0);
@@ -780,18 +823,19 @@ hipError_t launch_persistent(K kernel, int nthreads, int64_t total_tiles, hipStr
     return hipGetLastError();
 }
 
-// The direct-to-LDS kernel of a configuration: whole tiles, both operands k-contiguous, an even number of
-// BK-deep panels, row offsets inside a tile that fit the 32-bit lane offsets of its loads.
+// The direct-to-LDS kernel of a configuration: whole tiles, each operand k-contiguous or row-contiguous, an even
+// number of BK-deep panels, offsets inside a panel that fit the 32-bit lane offsets of its loads.
 template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 bool dma_applies(const SbArgs &a)
 {
     const int64_t most = (int64_t)1 << 21;
-    return a.csA == 1 && a.rsB == 1 && a.m % (WM * WAVES_M) == 0 && a.n % (WN * WAVES_N) == 0 && a.k % (2 * BK) == 0 &&
-           a.rsA <= most && a.csB <= most;
+    const bool a_ok = a.csA == 1 || a.rsA == 1, b_ok = a.rsB == 1 || a.csB == 1;
+    return a_ok && b_ok && a.m % (WM * WAVES_M) == 0 && a.n % (WN * WAVES_N) == 0 && a.k % (2 * BK) == 0 &&
+           a.rsA <= most && a.csA <= most && a.rsB <= most && a.csB <= most;
 }
 
 // (one function per kernel: the set-up flags below belong to that kernel alone)
-template <typename MFT, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
+template <typename MFT, bool A_KC, bool B_KC, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 hipError_t launch_dma_kernel(const SbArgs &a, hipStream_t stream)
 {
     typedef typename MFT::T T;
@@ -801,7 +845,7 @@ hipError_t launch_dma_kernel(const SbArgs &a, hipStream_t stream)
     const int64_t total = tiles_m * tiles_n * a.batch0 * a.batch1;
     if (total <= 0) return hipSuccess;
     if (total >= (int64_t)1 << 31) return hipErrorInvalidConfiguration;
-    auto kernel = sbgemm_mfma_dma_kernel<MFT, BETA, BK, WM, WN, WAVES_M, WAVES_N>;
+    auto kernel = sbgemm_mfma_dma_kernel<MFT, A_KC, B_KC, BETA, BK, WM, WN, WAVES_M, WAVES_N>;
     static std::atomic<int> resident_of[SB_MAX_DEVICES] = {};          // 0: this device has not been set up for the kernel yet
     const int dev = sb_current_device();
     int resident = resident_of[dev];
@@ -824,8 +868,14 @@ hipError_t launch_dma_kernel(const SbArgs &a, hipStream_t stream)
 template <typename MFT, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
 hipError_t launch_dma(const SbArgs &a, hipStream_t stream)
 {
-    if (a.beta == 0.0) return launch_dma_kernel<MFT, false, BK, WM, WN, WAVES_M, WAVES_N>(a, stream);
-    return launch_dma_kernel<MFT, true, BK, WM, WN, WAVES_M, WAVES_N>(a, stream);
+    const bool ak = a.csA == 1, bk = a.rsB == 1, b0 = a.beta == 0.0;
+#define SB_DMA(AK, BKC) (b0 ? launch_dma_kernel<MFT, AK, BKC, false, BK, WM, WN, WAVES_M, WAVES_N>(a, stream) \
+                            : launch_dma_kernel<MFT, AK, BKC, true, BK, WM, WN, WAVES_M, WAVES_N>(a, stream))
+    if (ak && bk)  return SB_DMA(true, true);
+    if (ak && !bk) return SB_DMA(true, false);
+    if (!ak && bk) return SB_DMA(false, true);
+    return SB_DMA(false, false);
+#undef SB_DMA
 }
 
 // STREAM_ONLY: the caller has checked that the problem is made of whole tiles (stream_applies), so
