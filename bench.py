@@ -496,11 +496,16 @@ def run_bf16_family(torch_baseline=True, settle_ms=150.0):
     from paper_1606_05696_amd import inputs
 
     def settled(fn):
+        # batches of 20 calls, each batch waited for: the queue never holds more than that, however slow a
+        # call is (under a profiler that serialises dispatches a loop bounded by host time alone would
+        # queue tens of thousands)
         t0 = time.perf_counter()
         while (time.perf_counter() - t0) * 1e3 < settle_ms:
             for _ in range(20):
                 fn()
-        torch.cuda.synchronize()
+            torch.cuda.synchronize()
+        for _ in range(20):
+            fn()
         return time_stats(fn, iters=30, warmup=5, target_us=400.0)
 
     layouts = {"T,N": ("km", "kn"), "N,N": ("mk", "kn"), "N,T": ("mk", "nk")}        # stored modes, first one contiguous
