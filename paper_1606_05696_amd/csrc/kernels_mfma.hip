@@ -624,7 +624,7 @@ struct RowPanel {
 // i.e. row slot / CPR, and fetches that row's chunk (slot % CPR) ^ f(row).  An operand with m or n contiguous
 // lands as [k][row] (RowPanel) and is read with lanes along the rows, one element per k.
 template <typename MFT, bool A_KC, bool B_KC, bool BETA, int BK, int WM, int WN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void sbgemm_mfma_dma_kernel(SbArgs g, int tiles_m, int tiles_n)
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 : 1) void sbgemm_mfma_dma_kernel(SbArgs g, int tiles_m, int tiles_n)
 {
     typedef Config<MFT, true, true, BK, WM, WN, WAVES_M, WAVES_N, 2> CF;         // k-contiguous layouts and fragment reads
     typedef typename CF::MF MF;
@@ -985,7 +985,10 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
         // tile is long in that operand's direction (big panels in flight) and one MFMA block wide
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF32x32, 32, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF32x32, 32, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (small_tiles) return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);     // 64 x 64 tiles
+        if (small_tiles) {                                                               // 64 x 64 tiles
+            if (dma_applies<MfmaF32x32, 32, 32, 32, 2, 2>(a) && a.k >= 128) return launch_dma<MfmaF32x32, 32, 32, 32, 2, 2>(a, stream);
+            return launch<MfmaF32x32, 16, 32, 32, 2, 2>(a, stream);
+        }
         // whole 256 x 256 or 128 x 256 tiles: eight waves of 128 x 64 or 64 x 64 (fewer panel loads per
         // flop and fewer, longer tiles: 4-5 % and 2-3 % over the 128 x 128 tiles at 512^4), unless the
         // bigger tiles would leave compute units idle (few tiles, or a last round that is mostly empty)
@@ -998,14 +1001,17 @@ hipError_t sb_launch_mfma(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 #endif
                 return launch<MfmaF32x32, 16, 128, 64, 2, 4, 2, true>(a, stream);
             }
-            if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_tile_time((a.m / 128) * (a.n / 256) * batch, 2.0, 1.02) <= t128)
+            if (stream_applies<MfmaF32x32>(a, 128, 256, 16) && sb_tile_time((a.m / 128) * (a.n / 256) * batch, 2.0, 1.02) <= t128) {
+                if (dma_applies<MfmaF32x32, 32, 64, 64, 2, 4>(a)) return launch_dma<MfmaF32x32, 32, 64, 64, 2, 4>(a, stream);
                 return launch<MfmaF32x32, 16, 64, 64, 2, 4, 2, true>(a, stream);
+            }
         }
+        if (dma_applies<MfmaF32x32, 32, 64, 64, 2, 2>(a)) return launch_dma<MfmaF32x32, 32, 64, 64, 2, 2>(a, stream);
         return launch<MfmaF32x32, 16, 64, 64, 2, 2>(a, stream);                                  // 128 x 128 tiles
     case SB_F64:
         if (a.n <= 32 && a.m >= 256) return launch<MfmaF64x16, 16, 32, 32, 4, 1>(a, stream);     // 128 x 32 tiles, 4 waves
         if (a.m <= 32 && a.n >= 256) return launch<MfmaF64x16, 16, 32, 32, 1, 4>(a, stream);     // 32 x 128 tiles
-        if (small_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);
+        if (small_tiles) return launch<MfmaF64x16, 16, 32, 32, 2, 2>(a, stream);      // (direct-to-LDS loads: no gain on 64 x 64 fp64 tiles)
 #ifndef SB_F64_NO_DMA
         if (dma_applies<MfmaF64x16, 16, 32, 32, 4, 4>(a)) return launch_dma<MfmaF64x16, 16, 32, 32, 4, 4>(a, stream);
 #endif

@@ -708,7 +708,9 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
                            (384, 512, 96, 128), (128, 256, 160, 512), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128),
                            # 256 x 256 tiles with k a multiple of 64: in fp32 with both operands k-contiguous the member that
                            # loads straight into LDS (2, 6 and 4 panels of 32; the last with two tiles per workgroup)
-                           (256, 256, 192, 256), (512, 512, 128, 128)):
+                           (256, 256, 192, 256), (512, 512, 128, 128),
+                           # the same member on 128 x 128 tiles (8 panels) and, in fp32, on 128 x 256 tiles (4 panels)
+                           (128, 384, 256, 60), (128, 512, 128, 200)):
         lda = (m if opA == "N" else k) + 4
         ldb = (k if opB == "N" else n) + 8
         ldc = m + 12
