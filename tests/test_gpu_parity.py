@@ -706,9 +706,9 @@ def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
     # configurations); the one between them would leave a round mostly empty with either and stays on 128 x 128
     for m, n, k, batch in ((256, 384, 64, 5), (256, 384, 64, 30), (128, 128, 96, 3), (64, 192, 160, 7), (512, 256, 64, 37), (128, 256, 512, 1),
                            (384, 512, 96, 128), (128, 256, 160, 512), (384, 256, 64, 260), (256, 256, 64, 256), (512, 256, 96, 128),
-                           # 256 x 256 tiles with k a multiple of 64: in fp32 with both operands k-contiguous the member that
-                           # loads straight into LDS (2, 6 and 4 panels of 32; the last with two tiles per workgroup)
-                           (256, 256, 192, 256), (512, 512, 128, 128),
+                           # whole tiles with k a multiple of 64: the members that load straight into LDS, in fp32 on 128 x 256
+                           # tiles (6 and 4 panels of 32) and, with k >= 256 and two rounds of tiles, on 256 x 256 tiles
+                           (256, 256, 192, 256), (512, 512, 128, 128), (256, 256, 256, 512),
                            # the same member on 128 x 128 tiles (8 panels) and, in fp32, on 128 x 256 tiles (4 panels)
                            (128, 384, 256, 60), (128, 512, 128, 200)):
         lda = (m if opA == "N" else k) + 4
