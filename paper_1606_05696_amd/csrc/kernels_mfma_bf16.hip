@@ -523,23 +523,6 @@ struct PanelRows {
     }
 };
 
-// 16 bytes per lane from global memory straight into LDS (no staging registers, no LDS store instruction):
-// lane l of the wave lands at lds_addr + 16 l.  lds_addr and base are wave-uniform; voff is the lane's byte
-// offset from base (unsigned 32 bit).  The compiler does not see the LDS write behind this statement: the
-// code that reads the data waits for it itself (dma_wait) before the barrier that publishes it.  M0 is not
-// allocated by the compiler and nothing else in these kernels uses it.
-__device__ __forceinline__ void dma16(unsigned lds_addr, const void *base, unsigned voff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" :: "s"(lds_addr), "v"(voff), "s"(base) : "memory");
-}
-// wait until at most N vector-memory operations of this wave are outstanding (they complete in order)
-template <int N>
-__device__ __forceinline__ void dma_wait()
-{
-    static_assert(N >= 0 && N < 64, "6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));      // expcnt and lgkmcnt fields: no wait
-}
-
 // Direct-to-LDS member of the streaming family: 256 x 256 tiles on eight waves of 128 x 64, both operands
 // k-contiguous, 64 k per panel, two LDS stages of 64 KB.  The next panel travels from memory into the stage that
 // the barrier has just freed while the current one is multiplied; no registers stage it, which leaves room for

@@ -120,9 +120,10 @@ __device__ __forceinline__ Loc locate1(const Side &s, int idx, int count)
     return r;
 }
 
-// the four consecutive panels idx0 .. idx0+3 of a side; beyond `count` the last valid one is repeated
+// the N consecutive panels idx0 .. idx0+N-1 of a side; beyond `count` the last valid one is repeated
 // (its data is loaded again and never stored).  One decode, then a mixed-radix odometer.
-__device__ __forceinline__ void locate4(const Side &s, int idx0, int count, Loc (&out)[4])
+template <int N>
+__device__ __forceinline__ void locate_run(const Side &s, int idx0, int count, Loc (&out)[N])
 {
     const unsigned t = fdiv((unsigned)idx0, s.dnf);
     unsigned f = (unsigned)idx0 - t * (unsigned)s.nf;
@@ -131,7 +132,7 @@ __device__ __forceinline__ void locate4(const Side &s, int idx0, int count, Loc 
     out[0].offC = (int64_t)f * s.cf + (int64_t)l1 * s.c1 + (int64_t)l2 * s.c2;
     out[0].ext = (int)f == s.nf - 1 ? s.last : s.full;
 #pragma unroll
-    for (int i = 1; i < 4; ++i) {
+    for (int i = 1; i < N; ++i) {
         out[i] = out[i - 1];
         if (idx0 + i < count) {
             if (++f < (unsigned)s.nf) {          // the next piece of the same matrix: two additions
@@ -282,10 +283,10 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
     Loc ra = {0, 0, 0}, ca = {0, 0, 0};          // rows-contiguous operands: the panel this lane's 8 x 8 block belongs to
     FourPanels<A_KC, RAGGED> pa;
     FourPanels<B_KC, RAGGED> pb;
-    locate4(g.row, rb * BR, g.R, rl);
+    locate_run<4>(g.row, rb * BR, g.R, rl);
     if (!A_KC) ra = locate1(g.row, rb * BR + tid / 128, g.R);
     pa.template load<0, 4>(g.A + (int64_t)zi0 * g.zA[0] + (int64_t)zi1 * g.zA[1], rl, ra, g.row.ld, kk);
-    locate4(g.col, cb * BC, g.Cn, cl);
+    locate_run<4>(g.col, cb * BC, g.Cn, cl);
     if (!B_KC) ca = locate1(g.col, cb * BC + tid / 128, g.Cn);
     // only the first column panel for now: the other three would queue ahead of slower waves' A loads
     const uint16_t *Bz = g.B + (int64_t)zi0 * g.zB[0] + (int64_t)zi1 * g.zB[1];
@@ -461,6 +462,290 @@ __global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_bf16_kernel(PanelArgs 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Wide-block member: a workgroup takes 2 x 8 panels, and the operands travel straight into LDS.
+//
+// A compute unit that runs ONE block pays its whole start-up chain (launch, arguments, fetch, first
+// product) before the first line of C leaves, and the stores, which bound the kernel (a step of 16 KB per
+// compute unit takes 0.55-0.6 us whatever else happens: 7-7.5 TB/s over the chip), cannot start earlier
+// than that.  So what the first product needs is small and everything else arrives behind it: two row panels
+// and ONE column panel (48 KB instead of the 80 KB of a 4 x 4 block), after which a product (2 row panels
+// x 1 column panel) follows every column panel as it lands.  Loads are global_load_lds_dwordx4 (no staging
+// registers, no LDS store instructions, no register transposition), issued in the order of need, the
+// first four column panels during start-up and one more behind each product's stores.  Vector-memory
+// operations of a wave complete in issue order, so "column panel s+1 has landed" is a count of the
+// operations the wave has issued after that panel's loads (wide_pending): younger loads plus two stores
+// per finished product.
+// Wave w owns row panel w % 2 and 16 of the 64 columns of every column panel (v_mfma_f32_16x16x32_bf16,
+// lanes along the columns, four consecutive rows per lane); its A fragments (64 rows x 128 k) stay in
+// registers, a product reads 4 KB of B fragments.  Per step: product s is rounded into the wave's staging
+// area and leaves as whole 128-byte lines (non-temporal); then wait + barrier (panel s+1 is there), its B
+// fragments, and the 16 MFMAs of product s+1.
+// Panels are unpadded (ten of them fill the 160 KB), so conflicts are avoided by placement, which costs
+// nothing because each lane chooses what it fetches into its linear 16-byte LDS slot:
+//   k contiguous in memory:  [row][k], the 16-byte chunk c of row r at position c ^ (r % 16);
+//   rows contiguous:         [k][row], kept as it lies and transposed by the fragment read
+//                            (ds_read_b64_tr_b16), the 16-row segment s of k-row k at position
+//                            s ^ (bit 1 of k | bit 3 of k << 1): the eight segments a half wave reads
+//                            (four consecutive k at two k-groups) then lie on all banks.
+// Taken when k == 128, beta == 0, every panel is whole, the grid is made of whole blocks and all
+// addresses are 16-byte aligned; everything else runs the 4 x 4 kernel above.
+constexpr int WR = 2, WC = 8;
+constexpr int WPANEL = TM * KMAX;                    // elements of an unpadded panel (16 KB)
+constexpr int WLDS_ELEMS = (WR + WC) * WPANEL;       // 160 KB
+constexpr int WSTAGE = 16 * TM;                      // a staged product of a wave: 16 columns x 64 rows (2 KB)
+static_assert(8 * 2 * WSTAGE <= WR * WPANEL, "two staging areas for each of the eight waves fit the A region");
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Column panels 0 .. WAHEAD-1 are requested before the first product, panel s + WAHEAD in step s.
+constexpr int WAHEAD = 4;
+// Vector-memory operations a wave has issued after the two loads of column panel s+1 when step s waits for
+// that panel.  A wave's sequence: the row panels, column panels 0 .. WAHEAD-1, then per step t the two stores
+// of product t followed by the loads of panel t + WAHEAD (if there is one); step s waits at its end.
+constexpr int wide_pending(int s)
+{
+    int n = 0;
+    bool seen = false;
+    for (int p = 0; p < WAHEAD; ++p) {
+        if (seen) n += 2;
+        if (p == s + 1) seen = true;
+    }
+    for (int t = 0; t <= s; ++t) {
+        if (seen) n += 2;                                       // stores of product t
+        if (t + WAHEAD < WC) {
+            if (seen) n += 2;
+            if (t + WAHEAD == s + 1) seen = true;
+        }
+    }
+    return n;
+}
+static_assert(WAHEAD != 4 || (wide_pending(0) == 8 && wide_pending(1) == 10 && wide_pending(2) == 12 && wide_pending(3) == 12 &&
+                              wide_pending(4) == 10 && wide_pending(5) == 8 && wide_pending(6) == 6), "hand count for four panels ahead");
+
+// what the 16-byte LDS slot `slot16` of a panel holds, as an element offset into the operand (ld: elements
+// between rows of a k-contiguous operand, between k of a row-contiguous one)
+template <bool KC>
+__device__ __forceinline__ unsigned wide_source(int slot16, unsigned ld)
+{
+    if (KC) {
+        const int row = slot16 >> 4, chunk = (slot16 & 15) ^ (row & 15);
+        return (unsigned)row * ld + (unsigned)chunk * 8;
+    }
+    const int k = slot16 >> 3, pos = slot16 & 7;
+    const int f = ((k >> 1) & 1) | (((k >> 3) & 1) << 1);
+    const int row = ((((pos >> 1) ^ f) << 1) | (pos & 1)) << 3;
+    return (unsigned)k * ld + (unsigned)row;
+}
+
+// MFMA operand (16x16x32: lane l holds row row0 + l % 16, k = 32 ks + 8 (l / 16) .. + 7) of a panel
+template <bool KC>
+__device__ __forceinline__ bf16x8 wide_fragment(const uint16_t *panel, int row0, int ks, int lane)
+{
+    if (KC) {
+        const int row = row0 + (lane & 15), chunk = (4 * ks + (lane >> 4)) ^ (row & 15);
+        return __builtin_bit_cast(bf16x8, *(const u16x8 *)(panel + row * KMAX + chunk * 8));
+    }
+    // in each group of 16 lanes, lanes 4r .. 4r+3 point at 16 consecutive rows of k-row r and lane j receives
+    // row j of the four k-rows: two reads give a lane its 8 consecutive k
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int i = lane & 15, g16 = lane >> 4;
+    const int k = ks * 32 + 8 * g16 + (i >> 2);
+    const int f = ((k >> 1) & 1) | (((k >> 3) & 1) << 1);
+    const uint16_t *p = panel + k * TM + (((row0 >> 4) ^ f) << 4) + 4 * (i & 3);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * TM));      // k + 4: same placement
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// PADDED: the launch holds padding slots (super-tiles at the edge of the block grid that are not full).  Without
+// them nothing branches before the loads, so all kernel arguments are fetched in one round trip (a scalar load
+// of arguments takes some 0.3 us here, and the early exit would put a second one behind the first).
+template <bool A_KC, bool B_KC, bool PADDED>
+__global__ __launch_bounds__(NT, 1) void sbgemm_panelgrid_wide_bf16_kernel(PanelArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];      // [A0 A1 | B0 .. B7]; the A region becomes the staging area
+    uint16_t *ldsA = lds, *ldsB = lds + WR * WPANEL;
+    const int tid = (int)threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // Workgroup -> block: as above, with super-tiles of 8 x 4 blocks (again 16 row and 32 column panels).
+    const unsigned total = gridDim.x, bid = blockIdx.x;
+    const unsigned q8 = total >> 3, r8 = total & 7, xcd = bid & 7, slot = bid >> 3;
+    const unsigned logical = xcd * q8 + (xcd < r8 ? xcd : r8) + slot;
+    const unsigned z = fdiv(logical, g.dper_z), within = logical - z * (unsigned)g.per_z;
+    const unsigned stile = within >> 5, in = within & 31;
+    const unsigned srow = fdiv(stile, g.dnsc), scol = stile - srow * (unsigned)g.nsc;
+    const int rb = (int)(srow * 8 + (in & 7)), cb = (int)(scol * 4 + (in >> 3));
+    if (PADDED && (rb >= g.nrb || cb >= g.ncb)) return;     // padding slot of a ragged super-tile (whole workgroup)
+    const unsigned zi1 = fdiv(z, g.dz0), zi0 = z - zi1 * (unsigned)g.z0;
+
+    // Load j of a wave into a panel fills the 1 KB at 1024 (8 j + wave): 16-byte slot 64 (8 j + wave) + lane.
+    unsigned offA[2], offB[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int slot16 = 64 * (8 * j + wave) + lane;
+        offA[j] = 2 * wide_source<A_KC>(slot16, g.row.ld);
+        offB[j] = 2 * wide_source<B_KC>(slot16, g.col.ld);
+    }
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) uint16_t *)lds;
+    const unsigned land = __builtin_amdgcn_readfirstlane(lds0 + wave * 1024);
+
+    // Where the block's panels lie: lane i decodes panel i of the side (one pass of vector arithmetic for all
+    // of them; a scalar odometer over ten panels would hold the loads back by hundreds of dependent
+    // instructions) and the results are broadcast into wave-uniform registers.
+    auto uniform64 = [](int64_t v, int src) __attribute__((always_inline)) {
+        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(uint32_t)v, src);
+        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), src);
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+    // every load of the block, in the order of need: A0, A1, B0, then B1 .. B7
+    int64_t offA_p[WR], offC_r[WR], offB_s[WC], offC_s[WC];
+    const Loc mine_r = locate1(g.row, rb * WR + (lane & (WR - 1)), g.R);
+#pragma unroll
+    for (int p = 0; p < WR; ++p) { offA_p[p] = uniform64(mine_r.off, p);  offC_r[p] = uniform64(mine_r.offC, p); }
+    const uint16_t *Az = g.A + (int64_t)zi0 * g.zA[0] + (int64_t)zi1 * g.zA[1];
+#pragma unroll
+    for (int p = 0; p < WR; ++p)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) dma16(land + p * (WPANEL * 2) + j * 8192, Az + offA_p[p], offA[j]);
+    const Loc mine_c = locate1(g.col, cb * WC + (lane & (WC - 1)), g.Cn);
+#pragma unroll
+    for (int s = 0; s < WC; ++s) { offB_s[s] = uniform64(mine_c.off, s);  offC_s[s] = uniform64(mine_c.offC, s); }
+    const uint16_t *Bz = g.B + (int64_t)zi0 * g.zB[0] + (int64_t)zi1 * g.zB[1];
+    auto request_b = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) dma16(land + (WR + s) * (WPANEL * 2) + j * 8192, Bz + offB_s[s], offB[j]);
+    };
+    static_assert(WAHEAD == 4, "the start-up below requests column panels 0 .. 3");
+    request_b(0);
+
+    // wave w: row panel w % 2, columns 16 (w / 2) .. +15 of every column panel
+    const int pi = wave & 1, q = wave >> 1;
+    const float alpha = g.alpha;
+    uint16_t *Crow = g.C + (int64_t)zi0 * g.zC[0] + (int64_t)zi1 * g.zC[1] + (pi ? offC_r[1] : offC_r[0]) + (int64_t)(q * 16) * g.ldc;
+    uint16_t *st = ldsA + wave * (2 * WSTAGE);
+
+    // Start-up: the A fragments are 16 KB of LDS reads per wave (half a microsecond for the eight of them), so
+    // they start as soon as the wave's row panel is there, while the next panels are still on their way: row
+    // panel 0, row panel 1 and column panel 0 each get their own wait (always two younger panels) and barrier.
+    // These barriers only publish what the loads wrote; they must not wait for the fragment reads in flight,
+    // hence no fence (the empty asm statements keep the compiler from moving LDS accesses across).
+    auto publish = [&]() __attribute__((always_inline)) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    bf16x8 fa[4][4], fb[4];
+    auto read_a = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) fa[rt][ks] = wide_fragment<A_KC>(ldsA + pi * WPANEL, rt * 16, ks, lane);
+    };
+    dma_wait<4>();               // behind A0: A1, B0
+    publish();
+    if (pi == 0) read_a();
+    request_b(1);
+    dma_wait<4>();               // behind A1: B0, B1
+    publish();
+    if (pi == 1) read_a();
+    request_b(2);
+    dma_wait<4>();               // behind B0: B1, B2
+    publish();
+    request_b(3);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) fb[ks] = wide_fragment<B_KC>(ldsB, q * 16, ks, lane);
+
+    auto read_b = [&](bf16x8 (&fb)[4], int s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) fb[ks] = wide_fragment<B_KC>(ldsB + s * WPANEL, q * 16, ks, lane);
+    };
+    // result register r of lane l: row 16 rt + 4 (l / 16) + r, column l % 16 of the wave's 64 x 16 piece
+    auto clear = [&](f32x4 (&acc)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    auto half_product = [&](f32x4 (&acc)[4], const bf16x8 (&fb)[4], int h) __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 2 * h; ks < 2 * h + 2; ++ks)
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rt][ks], fb[ks], acc[rt], 0, 0, 0);
+    };
+    // Staging area: [16 columns][64 rows], the 8-byte unit u of column j at position u ^ j, so that the 8-byte
+    // writes of a half wave (16 columns x 2 units) and the 16-byte reads (2 columns x 8 pairs) cover all banks.
+    auto stage = [&](const f32x4 (&acc)[4], int s) __attribute__((always_inline)) {
+        const int j = lane & 15;
+        uint16_t *area = st + (s & 1) * WSTAGE + j * TM;
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            u16x4 pk;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pk[e] = sb_f32_to_bf16(alpha * acc[rt][e]);
+            *(u16x4 *)(area + (((4 * rt + (lane >> 4)) ^ j) << 2)) = pk;
+        }
+    };
+    auto wave_fence = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
+    // the staged product s as two 16-byte vectors per lane: whole 128-byte lines of C, 8 lanes to a column
+    auto read_staged = [&](u32x4 (&o)[2], int s) __attribute__((always_inline)) {
+        const uint16_t *area = st + (s & 1) * WSTAGE;
+        const int pr = lane & 7;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int jj = 8 * t + (lane >> 3);
+            const u32x4 v = *(const u32x4 *)(area + jj * TM + ((pr ^ (jj >> 1)) << 3));
+            o[t] = (jj & 1) ? u32x4{v[2], v[3], v[0], v[1]} : v;          // an odd column holds its unit pairs swapped
+        }
+    };
+    // exactly two store instructions per product and wave (the waits count them)
+    auto write_out = [&](const u32x4 (&o)[2], int64_t offC) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+            SB_PANEL_STORE((u32x4u *)(Crow + offC + (int64_t)(8 * t + (lane >> 3)) * g.ldc + 8 * (lane & 7)), o[t]);
+    };
+
+    f32x4 acc0[4], acc1[4];
+    clear(acc0);
+    half_product(acc0, fb, 0);
+    half_product(acc0, fb, 1);
+    __syncthreads();             // every wave holds its A fragments: the staging areas may overwrite the A panels
+    // One step: product s, finished in `done`, is rounded, staged and stored; then the next column panel is
+    // waited for (wide_pending: vector-memory operations this wave has issued after that panel's loads), the
+    // barrier publishes it, and product s+1 is multiplied.  The stores of a product thus never wait for a
+    // panel, and the panel WAHEAD steps ahead is requested behind them (the memory pipeline of a compute unit
+    // accepts a 1 KB load every ~25 clocks: a wave that issued all its loads up front would reach its first
+    // wait 1.5 us into the kernel).
+    auto step = [&](const f32x4 (&done)[4], f32x4 (&next)[4], auto s_c, int64_t offC) __attribute__((always_inline)) {
+        constexpr int S = decltype(s_c)::value;
+        stage(done, S);
+        wave_fence();
+        u32x4 o[2];
+        read_staged(o, S);
+        write_out(o, offC);
+        wave_fence();
+        if (S + 1 < WC) {
+            if (S + WAHEAD < WC) request_b(S + WAHEAD);
+            dma_wait<wide_pending(S)>();
+            __syncthreads();
+            read_b(fb, S + 1);
+            clear(next);
+            half_product(next, fb, 0);
+            half_product(next, fb, 1);
+        }
+    };
+    step(acc0, acc1, std::integral_constant<int, 0>(), offC_s[0]);
+    step(acc1, acc0, std::integral_constant<int, 1>(), offC_s[1]);
+    step(acc0, acc1, std::integral_constant<int, 2>(), offC_s[2]);
+    step(acc1, acc0, std::integral_constant<int, 3>(), offC_s[3]);
+    step(acc0, acc1, std::integral_constant<int, 4>(), offC_s[4]);
+    step(acc1, acc0, std::integral_constant<int, 5>(), offC_s[5]);
+    step(acc0, acc1, std::integral_constant<int, 6>(), offC_s[6]);
+    step(acc1, acc0, std::integral_constant<int, 7>(), offC_s[7]);
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side: an sb_gemm2 problem as a panel grid
 
 FastDiv make_fastdiv(uint32_t d)            // 1 <= d < 2^31
@@ -475,10 +760,30 @@ struct Grid {
     PanelArgs p;
     bool ok;
     bool a_kc, b_kc, ragged;
+    bool wide;               // blocks of 2 x 8 panels for the wide-block kernel (else 4 x 4)
     int64_t blocks;          // launched workgroups (padding slots included)
     int64_t real_blocks;     // blocks that hold at least one panel pair
     double utilisation;      // panel pairs / (16 * real blocks)
 };
+
+// The wide-block kernel takes the problem if nothing needs a guard or a fix-up: k == 128, beta == 0, whole panels
+// in whole blocks, 16-byte aligned addresses everywhere, lane offsets inside a panel that fit 32 bits.
+bool wide_applies(const SbArgs &a, const PanelArgs &p, bool a_kc, bool b_kc)
+{
+    if (a.k != KMAX || a.beta != 0.0) return false;
+    const Side &r = p.row, &c = p.col;
+    if (r.full != TM || r.last != TM || c.full != TM || c.last != TM) return false;
+    if (p.R % WR != 0 || p.Cn % WC != 0) return false;
+    if (r.ld >= (1u << 24) || c.ld >= (1u << 24)) return false;
+    auto al = [](int64_t v) { return v % 8 == 0; };
+    if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C) % 16 != 0) return false;
+    if (!al(r.ld) || !al(c.ld) || !al(a.ldc)) return false;
+    if (!al(r.sf) || !al(r.s1) || !al(r.s2) || !al(c.sf) || !al(c.s1) || !al(c.s2)) return false;
+    if (!al(r.cf) || !al(r.c1) || !al(r.c2) || !al(c.cf) || !al(c.c1) || !al(c.c2)) return false;
+    for (int q = 0; q < 2; ++q)
+        if (!al(p.zA[q]) || !al(p.zB[q]) || !al(p.zC[q])) return false;
+    return true;
+}
 
 Grid make_grid(const SbArgs &a)
 {
@@ -526,8 +831,12 @@ Grid make_grid(const SbArgs &a)
     const int64_t R = (int64_t)r.nf * r.n1 * r.n2, Cn = (int64_t)c.nf * c.n1 * c.n2;
     if (R >= ((int64_t)1 << 30) || Cn >= ((int64_t)1 << 30)) return gr;
     p.R = (int32_t)R;  p.Cn = (int32_t)Cn;
-    p.nrb = (int32_t)((R + BR - 1) / BR);  p.ncb = (int32_t)((Cn + BC - 1) / BC);
-    const int64_t nsr = (p.nrb + 3) / 4, nsc = (p.ncb + 7) / 8;
+    p.ldc = a.ldc;
+    gr.wide = wide_applies(a, p, a_kc, b_kc);
+    // blocks of 4 x 4 panels in super-tiles of 4 x 8 blocks, or blocks of 2 x 8 panels in super-tiles of 8 x 4
+    const int br = gr.wide ? WR : BR, bc = gr.wide ? WC : BC;
+    p.nrb = (int32_t)((R + br - 1) / br);  p.ncb = (int32_t)((Cn + bc - 1) / bc);
+    const int64_t nsr = gr.wide ? (p.nrb + 7) / 8 : (p.nrb + 3) / 4, nsc = gr.wide ? (p.ncb + 3) / 4 : (p.ncb + 7) / 8;
     p.nsc = (int32_t)nsc;
     const int64_t per_z = nsr * nsc * 32, Z = (int64_t)p.z0 * p.z1;
     if (per_z >= ((int64_t)1 << 31) || per_z * Z > sb_max_grid_x(NT)) return gr;
@@ -535,7 +844,6 @@ Grid make_grid(const SbArgs &a)
     r.dnf = make_fastdiv((uint32_t)r.nf);  r.dn1 = make_fastdiv((uint32_t)r.n1);
     c.dnf = make_fastdiv((uint32_t)c.nf);  c.dn1 = make_fastdiv((uint32_t)c.n1);
     p.dper_z = make_fastdiv((uint32_t)per_z);  p.dnsc = make_fastdiv((uint32_t)nsc);  p.dz0 = make_fastdiv((uint32_t)p.z0);
-    p.ldc = a.ldc;
     p.k = (int32_t)a.k;
     p.alpha = (float)a.alpha;  p.beta = (float)a.beta;
     gr.a_kc = a_kc;  gr.b_kc = b_kc;
@@ -544,7 +852,7 @@ Grid make_grid(const SbArgs &a)
                 r.full % 8 || r.last % 8;
     gr.blocks = per_z * Z;
     gr.real_blocks = (int64_t)p.nrb * p.ncb * Z;
-    gr.utilisation = (double)(R * Cn) / (double)(16 * (int64_t)p.nrb * p.ncb);
+    gr.utilisation = (double)(R * Cn) / (double)(16 * (int64_t)p.nrb * p.ncb);         // 16 panel pairs per block of either shape
     gr.ok = true;
     return gr;
 }
@@ -552,11 +860,12 @@ Grid make_grid(const SbArgs &a)
 template <bool A_KC, bool B_KC>
 hipError_t launch_grid(const Grid &gr, hipStream_t stream)
 {
-    const size_t lds_bytes = (size_t)LDS_ELEMS * sizeof(uint16_t);
+    const size_t lds_bytes = (size_t)(gr.wide ? WLDS_ELEMS : LDS_ELEMS) * sizeof(uint16_t);
     const dim3 grid((unsigned)gr.blocks), block(NT);
-#define SB_PANELGRID(KS_, RG_)                                                                                          \
+#define SB_PANELGRID(KS_, RG_) SB_PANELGRID_KERNEL((sbgemm_panelgrid_bf16_kernel<A_KC, B_KC, KS_, RG_>))
+#define SB_PANELGRID_KERNEL(KERNEL_)                                                                                    \
     do {                                                                                                                \
-        auto kern = sbgemm_panelgrid_bf16_kernel<A_KC, B_KC, KS_, RG_>;                                                 \
+        auto kern = KERNEL_;                                                                                            \
         static std::atomic<bool> configured[SB_MAX_DEVICES] = {};                                                       \
         const int dev = sb_current_device();                                                                            \
         if (!configured[dev]) {                                                                                         \
@@ -567,9 +876,12 @@ hipError_t launch_grid(const Grid &gr, hipStream_t stream)
         hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, gr.p);                                                 \
     } while (0)
     const bool short_k = gr.p.k <= 64;
-    if (gr.ragged) { if (short_k) SB_PANELGRID(4, true);  else SB_PANELGRID(8, true); }
+    if (gr.wide && gr.blocks == gr.real_blocks) SB_PANELGRID_KERNEL((sbgemm_panelgrid_wide_bf16_kernel<A_KC, B_KC, false>));
+    else if (gr.wide) SB_PANELGRID_KERNEL((sbgemm_panelgrid_wide_bf16_kernel<A_KC, B_KC, true>));
+    else if (gr.ragged) { if (short_k) SB_PANELGRID(4, true);  else SB_PANELGRID(8, true); }
     else           { if (short_k) SB_PANELGRID(4, false); else SB_PANELGRID(8, false); }
 #undef SB_PANELGRID
+#undef SB_PANELGRID_KERNEL
     return hipGetLastError();
 }
 

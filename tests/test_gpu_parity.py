@@ -419,6 +419,38 @@ def test_panel_grid_kernel(opA, opB):
                         kernel="panel")
 
 
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
+def test_panel_grid_kernel_wide_blocks(opA, opB):
+    # the member of the panel-grid kernel that loads straight into LDS (blocks of 2 x 8 panels): k = 128,
+    # beta = 0, whole 64-wide panels in whole blocks, everything 16-byte aligned.  One and several blocks
+    # along either side, padded leading dimensions, independent batches, a shared operand (the batch then
+    # extends the other operand's side of the grid), alpha != 1.  beta != 0 runs the same shapes through the
+    # 4 x 4 member.
+    for m, n, batch, pad, share in ((128, 512, 1, 0, ""), (512, 1024, 1, 8, ""), (384, 512, 3, 16, ""), (64, 512, 6, 8, "B"),
+                                    (128, 64, 8, 24, "A"), (640, 1536, 2, 0, "")):
+        k = 128
+        lda = (m if opA == "N" else k) + pad
+        ldb = (k if opB == "N" else n) + 2 * pad
+        ldc = m + pad
+        loa = 0 if share == "A" else lda * (k if opA == "N" else m) + 8 * pad
+        lob = 0 if share == "B" else ldb * (n if opB == "N" else k) + 16 * pad
+        loc = ldc * n + 8 * pad
+        for alpha, beta in ((1.0, 0.0), (-0.75, 0.0), (0.5, 1.5)):
+            run_sb_gemm("bf16", opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed=m + n + batch,
+                        kernel="panel")
+
+
+@pytest.mark.parametrize("ma,mb,mc", [("m[p]k", "kn[q]", "m[p]n[q]"), ("k[p]m", "nk[q]", "m[p]n[q]"), ("mk[p]", "nk[q]", "mn[p][q]"),
+                                      ("km[p]", "kn[q]", "mn[p][q]")])
+def test_panel_grid_kernel_wide_blocks_nested(ma, mb, mc):
+    # nests whose row side counts p and whose column side counts q in whole blocks of 2 x 8 panels, and
+    # extents of 128 that put two panels of one matrix next to the batch digit on either side
+    for ext in (dict(m=64, n=64, p=6, q=8, k=128), dict(m=128, n=64, p=3, q=16, k=128), dict(m=64, n=128, p=4, q=4, k=128)):
+        for alpha in (1.0, 0.5):
+            err, text = contract_case("bf16", ma, mb, mc, ext, alpha=alpha, seed=93, kernel="panel")
+            assert err <= TOL["bf16"], (text, ext, err)
+
+
 def test_panel_grid_kernel_is_selected_for_the_large_short_k_products():
     # flat bf16 GEMMs with k <= 128 and at least 128 blocks of 256 x 256: the selector's own choice
     err, got, ref = run_sb_gemm("bf16", "N", "N", 4096, 2048, 64, 1, 4096, 64, 4096, 0, 0, 0, 1.0, 0.0, seed=5)
