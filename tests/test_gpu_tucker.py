@@ -52,6 +52,15 @@ def test_symmetric_eigensolver(dtype, n):
     assert np.max(np.abs(tk.projector(V[:, :r]) - tk.projector(V_ref[:, :r]))) <= (1e-8 if dtype == "f64" else 2e-2)
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("n", [513, 1024, 2048])
+def test_symmetric_eigensolver_large_orders(dtype, n):
+    # orders far beyond LDS run a FIXED number of sweeps of the multi-launch solver (no convergence test on
+    # that path): residual, orthogonality and eigenvalues at the largest orders a Tucker initialisation is
+    # likely to meet, even (tournament-ordered step) and odd (general step)
+    test_symmetric_eigensolver(dtype, n)
+
+
 def run_hooi(dtype, T, core, iterations, init=True, start=None):
     import torch
     dims = T.shape
