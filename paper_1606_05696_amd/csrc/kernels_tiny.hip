@@ -246,11 +246,12 @@ __global__ __launch_bounds__(TINY_THREADS) void sbgemm_tiny_kernel(SbArgs g, int
     }
 }
 
-template <typename T, int TM, int TN, bool A_KC, bool B_KC>
+// ONE: one problem per wave at a time (a short batch split into 16 x 16 blocks: as many waves as possible)
+template <typename T, int TM, int TN, bool A_KC, bool B_KC, bool ONE = false>
 hipError_t launch3(const SbArgs &a, hipStream_t stream)
 {
     const int64_t total = a.batch0 * a.batch1;
-    constexpr int U = (TM * TN == 1) ? 4 : (TM * TN == 2 ? 2 : 1);
+    constexpr int U = ONE ? 1 : (TM * TN == 1) ? 4 : (TM * TN == 2 ? 2 : 1);
     const bool hoist = (a.bsA[0] == 0 || a.batch0 == 1) && (a.bsA[1] == 0 || a.batch1 == 1) && a.nx == 0 && a.k <= 16;
     // vector accesses need no alignment beyond the element's (leading dimensions and offsets may be odd)
     const int vec_a = A_KC, vec_b = B_KC, vec_c = 1;
@@ -260,26 +261,51 @@ hipError_t launch3(const SbArgs &a, hipStream_t stream)
     if (groups > cap) groups = cap;
     if (groups < 1) return hipSuccess;
     dim3 grid((unsigned)groups), block(TINY_THREADS);
-    if (hoist)         hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, true, U, false>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
+    if (hoist && !ONE) hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, true, U, false>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
     else if (a.k > 16) hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U, true>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
     else               hipLaunchKernelGGL((sbgemm_tiny_kernel<T, TM, TN, A_KC, B_KC, false, U, false>), grid, block, 0, stream, a, vec_a, vec_b, vec_c);
     return hipGetLastError();
 }
 
-template <typename T, int TM, int TN>
+template <typename T, int TM, int TN, bool ONE = false>
 hipError_t launch2(const SbArgs &a, hipStream_t stream)
 {
     const bool a_kc = (a.csA == 1), b_kc = (a.rsB == 1);
-    if (a_kc && b_kc)  return launch3<T, TM, TN, true, true>(a, stream);
-    if (a_kc && !b_kc) return launch3<T, TM, TN, true, false>(a, stream);
-    if (!a_kc && b_kc) return launch3<T, TM, TN, false, true>(a, stream);
-    return launch3<T, TM, TN, false, false>(a, stream);
+    if (a_kc && b_kc)  return launch3<T, TM, TN, true, true, ONE>(a, stream);
+    if (a_kc && !b_kc) return launch3<T, TM, TN, true, false, ONE>(a, stream);
+    if (!a_kc && b_kc) return launch3<T, TM, TN, false, true, ONE>(a, stream);
+    return launch3<T, TM, TN, false, false, ONE>(a, stream);
+}
+
+// A short batch of 32-wide matrices leaves most of the chip idle behind a few long chains (32 waves of 32
+// dependent MFMA rounds for 32 problems of 32 x 32 x 32).  The 16 x 16 blocks of C_p are independent products
+// of a row block of op(A_p) and a column block of op(B_p), i.e. further batch digits: the row half moves A by
+// 16 rows and C by 16 elements, the column half moves B by 16 columns and C by 16 columns.  The same kernel
+// then runs four times as many waves, each with a quarter of the chain.  Whole blocks only (m, n multiples
+// of 16), while the split batch still fits the chip one wave per SIMD.
+bool split_into_blocks(const SbArgs &a, int tm, int tn, SbArgs &s)
+{
+    if (tm * tn == 1 || (tm == 2 && a.m != 32) || (tn == 2 && a.n != 32)) return false;
+    if (a.batch0 * a.batch1 * tm * tn > 1024) return false;
+    if (a.nx + (tm == 2) + (tn == 2) > SB_MAX_BATCH_LEVELS - 2) return false;
+    s = a;
+    if (s.nx == 0) s.cnt1 = s.batch1;
+    auto digit = [&](int64_t stepA, int64_t stepB, int64_t stepC) {
+        const int x = s.nx++;
+        s.xcnt[x] = 2;  s.xsA[x] = stepA;  s.xsB[x] = stepB;  s.xsC[x] = stepC;
+        s.batch1 *= 2;
+    };
+    if (tm == 2) { digit(16 * a.rsA, 0, 16);  s.m = 16; }
+    if (tn == 2) { digit(0, 16 * a.csB, 16 * a.ldc);  s.n = 16; }
+    return true;
 }
 
 template <typename T>
 hipError_t launch1(const SbArgs &a, hipStream_t stream)
 {
     const int tm = a.m > 16 ? 2 : 1, tn = a.n > 16 ? 2 : 1;
+    SbArgs blocks;
+    if (split_into_blocks(a, tm, tn, blocks)) return launch2<T, 1, 1, true>(blocks, stream);
     if (tm == 1 && tn == 1) return launch2<T, 1, 1>(a, stream);
     if (tm == 2 && tn == 1) return launch2<T, 2, 1>(a, stream);
     if (tm == 1 && tn == 2) return launch2<T, 1, 2>(a, stream);

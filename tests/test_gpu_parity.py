@@ -118,6 +118,34 @@ def test_sb_gemm_shapes(dtype, kernel, m, n, k, batch):
     assert err <= TOL[dtype], err
 
 
+@pytest.mark.parametrize("dtype", ["f64", "f32"])
+@pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
+def test_sb_gemm_tiny_short_batches_of_32(dtype, opA, opB):
+    # the tiny-matrix kernel runs a SHORT batch of 32-wide problems as independent 16 x 16 blocks (extra
+    # batch digits: row half, column half): split in both, in m only, in n only; k below, at and beyond one
+    # step of 16; batch 1, odd and the largest that is still split; padded leading dimensions; a shared
+    # operand; alpha and beta.  The last two shapes are not split (300 problems; m not 32) and run as before.
+    for m, n, k, batch, pad, share in ((32, 32, 32, 32, 0, ""), (32, 32, 7, 1, 1, ""), (32, 16, 40, 9, 1, "A"), (8, 32, 16, 33, 1, "B"),
+                                       (32, 32, 64, 256, 0, ""), (32, 32, 5, 300, 1, ""), (24, 32, 20, 6, 1, "")):
+        lda = (m if opA == "N" else k) + 3 * pad
+        ldb = (k if opB == "N" else n) + 5 * pad
+        ldc = m + 2 * pad
+        loa = 0 if share == "A" else lda * (k if opA == "N" else m) + 7 * pad
+        lob = 0 if share == "B" else ldb * (n if opB == "N" else k) + pad
+        loc = ldc * n + 11 * pad
+        for alpha, beta in ((1.0, 0.0), (0.75, -0.5)):
+            run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed=m + n + k + batch,
+                        kernel="tiny")
+
+
+def test_tiny_short_batches_of_32_in_a_nest():
+    # the split adds its digits on top of a nest that already has more than two levels
+    for dtype in ("f64", "f32"):
+        err, text = contract_case(dtype, "mk", "kn[p][q][r]", "mn[p][q][r]", dict(m=32, n=32, k=24, p=3, q=2, r=5), seed=17,
+                                  kernel="tiny", alpha=0.5, beta=2.0)
+        assert err <= TOL[dtype], (text, err)
+
+
 @pytest.mark.parametrize("dtype", ["f64", "f32", "bf16"])
 @pytest.mark.parametrize("opA,opB", [("N", "N"), ("N", "T"), ("T", "N"), ("T", "T")])
 @pytest.mark.parametrize("thin", [1, 2, 3, 4])
