@@ -238,6 +238,16 @@ const char *sb_status_string(int status);
 enum { SB_KERNEL_AUTO = -1, SB_KERNEL_GENERIC = 0, SB_KERNEL_TINY = 1, SB_KERNEL_MFMA = 2, SB_KERNEL_THIN = 3, SB_KERNEL_PANEL = 4 };
 int sb_force_kernel(int kernel_id);
 int sb_last_kernel(void);
+/* Which member of its family the calling thread's most recent launch ran, for the families whose
+ * members differ in more than tile size (0 for the others): tests use it to make sure that a problem
+ * built for a member still reaches it.
+ *   SB_KERNEL_PANEL: SB_MEMBER_PANEL_4X4 (4 x 4 panels per workgroup, staged through registers: any shape)
+ *                    or SB_MEMBER_PANEL_WIDE (2 x 8 panels straight into LDS: k == 128, beta == 0, whole
+ *                    64-wide panels in whole blocks, every address 16-byte aligned);
+ *   SB_KERNEL_TINY:  SB_MEMBER_TINY_WHOLE (one wave per C_p) or SB_MEMBER_TINY_BLOCKS (a batch of at most
+ *                    1024 / (blocks per C_p) problems with m or n == 32 run as independent 16 x 16 blocks). */
+enum { SB_MEMBER_PANEL_4X4 = 1, SB_MEMBER_PANEL_WIDE = 2, SB_MEMBER_TINY_WHOLE = 1, SB_MEMBER_TINY_BLOCKS = 2 };
+int sb_last_kernel_member(void);
 
 /* Host only: the kernel family the selector sends an sb_gemm problem to (sizes, operations and
  * strides as for sb_gemm, all of m, n, k, batch at least 1; no pointers: the family depends on the

@@ -18,6 +18,7 @@ SB_OK = 0
 SB_ERR_MODES, SB_ERR_CONTRACTION, SB_ERR_EXTENT, SB_ERR_STRIDE, SB_ERR_ILLEGAL_EVAL, SB_ERR_NO_DEVICE_CODE = 1, 2, 3, 4, 5, 6
 SB_ERR_LAUNCH = 1000
 SB_KERNEL_AUTO, SB_KERNEL_GENERIC, SB_KERNEL_TINY, SB_KERNEL_MFMA, SB_KERNEL_THIN, SB_KERNEL_PANEL = -1, 0, 1, 2, 3, 4
+SB_MEMBER_PANEL_4X4, SB_MEMBER_PANEL_WIDE, SB_MEMBER_TINY_WHOLE, SB_MEMBER_TINY_BLOCKS = 1, 2, 1, 2
 SB_MAX_MODES = 8
 SB_MAX_BATCH_LEVELS = 8
 
@@ -29,7 +30,7 @@ STRATEGIES = {"auto": SB_AUTO, "flatten": SB_FLATTEN, "batch_last": SB_BATCH_LAS
 
 __all__ = [n for n in dir() if n.startswith("SB_")] + ["SB_SYM_EIG_STATIC_MAX_N"] + [
     "OPS", "DTYPES", "STRATEGIES", "sb_plan", "SbError", "load", "sb_status_string", "sb_gemm", "sb_gemm2", "sb_gemm_nested",
-    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel",
+    "sb_contract_plan", "sb_contract", "sb_plan_launch", "sb_plan_launches", "sb_force_kernel", "sb_last_kernel", "sb_last_kernel_member",
     "sb_select_kernel", "sb_plan_cache_enable", "sb_permute", "sb_tucker_workspace", "sb_tucker_hooi", "sb_sym_eig_workspace", "sb_sym_eig", "sb_sym_eig_static",
     "sb_probe_mfma"]
 
@@ -97,6 +98,8 @@ def load():
     lib.sb_plan_cache_enable.argtypes = [ci]
     lib.sb_last_kernel.restype = ci
     lib.sb_last_kernel.argtypes = []
+    lib.sb_last_kernel_member.restype = ci
+    lib.sb_last_kernel_member.argtypes = []
     lib.sb_select_kernel.restype = ci
     lib.sb_select_kernel.argtypes = [ci, ci, ci, i64, i64, i64, i64, i64, i64, i64, i64, i64, i64]
     lib.sb_probe_mfma.restype = ci
@@ -280,6 +283,10 @@ def sb_force_kernel(kernel_id):
 
 def sb_last_kernel():
     return load().sb_last_kernel()
+
+
+def sb_last_kernel_member():
+    return load().sb_last_kernel_member()
 
 
 def sb_permute(dims, perm, src, dst, dt=None, stream=None, check=True):

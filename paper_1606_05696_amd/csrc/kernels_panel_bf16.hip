@@ -906,6 +906,7 @@ hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream)
 {
     const Grid gr = make_grid(a);
     if (!gr.ok) return hipErrorInvalidValue;
+    sb_note_member(gr.wide ? SB_MEMBER_PANEL_WIDE : SB_MEMBER_PANEL_4X4);
     if (gr.a_kc && gr.b_kc)  return launch_grid<true, true>(gr, stream);
     if (gr.a_kc && !gr.b_kc) return launch_grid<true, false>(gr, stream);
     if (!gr.a_kc && gr.b_kc) return launch_grid<false, true>(gr, stream);

@@ -305,7 +305,11 @@ hipError_t launch1(const SbArgs &a, hipStream_t stream)
 {
     const int tm = a.m > 16 ? 2 : 1, tn = a.n > 16 ? 2 : 1;
     SbArgs blocks;
-    if (split_into_blocks(a, tm, tn, blocks)) return launch2<T, 1, 1, true>(blocks, stream);
+    if (split_into_blocks(a, tm, tn, blocks)) {
+        sb_note_member(SB_MEMBER_TINY_BLOCKS);
+        return launch2<T, 1, 1, true>(blocks, stream);
+    }
+    sb_note_member(SB_MEMBER_TINY_WHOLE);
     if (tm == 1 && tn == 1) return launch2<T, 1, 1>(a, stream);
     if (tm == 2 && tn == 1) return launch2<T, 2, 1>(a, stream);
     if (tm == 1 && tn == 2) return launch2<T, 1, 2>(a, stream);

@@ -10,6 +10,7 @@ namespace {
 // diagnostics state is per host thread: a thread pins and reads the family of its own calls
 thread_local int g_force_kernel = SB_KERNEL_AUTO;
 thread_local int g_last_kernel = -1;
+thread_local int g_last_member = 0;
 
 bool valid_op(int op) { return op >= SB_OP_N && op <= SB_OP_EX_T; }
 bool is_ex(int op) { return op == SB_OP_EX_N || op == SB_OP_EX_T; }
@@ -67,6 +68,7 @@ int run(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
     const int kernel = choose(dt, a, g_force_kernel);
     hipError_t err;
+    g_last_member = 0;
     switch (kernel) {
     case SB_KERNEL_TINY: err = sb_launch_tiny(dt, a, stream); break;
     case SB_KERNEL_MFMA: err = sb_launch_mfma(dt, a, stream); break;
@@ -481,3 +483,5 @@ extern "C" int sb_force_kernel(int kernel_id)
 }
 
 extern "C" int sb_last_kernel(void) { return g_last_kernel; }
+extern "C" int sb_last_kernel_member(void) { return g_last_member; }
+void sb_note_member(int member) { g_last_member = member; }

@@ -69,6 +69,10 @@ hipError_t sb_launch_panel_bf16(const SbArgs &a, hipStream_t stream);
 bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a);       // extended op on the first operand (MFMA family)
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream);
 
+// Diagnostics: a launcher whose family has several members says which one it launched (the numbers are listed
+// with sb_last_kernel_member in sbgemm.h); the front end resets the note to 0 before every dispatch.
+void sb_note_member(int member);
+
 // out-of-place mode permutation of a packed tensor (benchmark baseline: the conventional evaluation's copy)
 hipError_t sb_launch_permute(int esize, int order, const int64_t *dims, const int *perm, const void *src, void *dst, hipStream_t stream);
 

@@ -50,7 +50,7 @@ def family_takes(family, dtype, m, n, k):
     raise ValueError(family)
 
 
-def run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed, kernel="auto"):
+def run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed, kernel="auto", member=None):
     """One sb_gemm call on random buffers vs Listing 1 on the CPU, both gates plus untouched padding;
     a forced family must be the one that ran.  Returns (relative error, got, ref)."""
     assert family_takes(kernel, dtype, m, n, k), "the test's own table generated a problem this family does not take"
@@ -69,6 +69,8 @@ def run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, a
     sync()
     if kernel != "auto":
         assert sb.sb_last_kernel() == KERNELS[kernel], (kernel, sb.sb_last_kernel(), dtype, opA, opB, m, n, k, batch)
+    if member is not None:
+        assert sb.sb_last_kernel_member() == member, (member, sb.sb_last_kernel_member(), dtype, opA, opB, m, n, k, batch, beta)
     ref = oracle.sb_gemm(opA, opB, m, n, k, alpha, a, lda, loa, b, ldb, lob, beta, c0, ldc, loc, batch,
                          wide=(dtype == "f64"))
     got = from_dev(dC)
@@ -127,6 +129,7 @@ def test_sb_gemm_tiny_short_batches_of_32(dtype, opA, opB):
     # operand; alpha and beta.  The last two shapes are not split (300 problems; m not 32) and run as before.
     for m, n, k, batch, pad, share in ((32, 32, 32, 32, 0, ""), (32, 32, 7, 1, 1, ""), (32, 16, 40, 9, 1, "A"), (8, 32, 16, 33, 1, "B"),
                                        (32, 32, 64, 256, 0, ""), (32, 32, 5, 300, 1, ""), (24, 32, 20, 6, 1, "")):
+        split = batch <= 256 and m in (32, 8) and (m, n) != (24, 32)
         lda = (m if opA == "N" else k) + 3 * pad
         ldb = (k if opB == "N" else n) + 5 * pad
         ldc = m + 2 * pad
@@ -135,7 +138,7 @@ def test_sb_gemm_tiny_short_batches_of_32(dtype, opA, opB):
         loc = ldc * n + 11 * pad
         for alpha, beta in ((1.0, 0.0), (0.75, -0.5)):
             run_sb_gemm(dtype, opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed=m + n + k + batch,
-                        kernel="tiny")
+                        kernel="tiny", member=sb.SB_MEMBER_TINY_BLOCKS if split else sb.SB_MEMBER_TINY_WHOLE)
 
 
 def test_tiny_short_batches_of_32_in_a_nest():
@@ -403,7 +406,7 @@ def test_cfg5_order3_x_order3_full_size():
         tC = to_dev(np.full(1, np.nan), "bf16").repeat(ref.size)
         sb.sb_contract(ma, mb, mc, 1.0, tA, dA, tB, dB, 0.0, tC, dC, dt="bf16")
         sync()
-        assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL, mc
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL and sb.sb_last_kernel_member() == sb.SB_MEMBER_PANEL_WIDE, mc
         assert_close(from_dev(tC, dC), ref, "bf16", 128, np.abs(A).max(), np.abs(B).max(), what=mc)
     # same contraction in fp32 and fp64 at reduced extents, with alpha and beta
     ext = dict(m=24, p=5, n=40, q=3, k=50)
@@ -465,7 +468,10 @@ def test_panel_grid_kernel_wide_blocks(opA, opB):
         loc = ldc * n + 8 * pad
         for alpha, beta in ((1.0, 0.0), (-0.75, 0.0), (0.5, 1.5)):
             run_sb_gemm("bf16", opA, opB, m, n, k, batch, lda, ldb, ldc, loa, lob, loc, alpha, beta, seed=m + n + batch,
-                        kernel="panel")
+                        kernel="panel", member=sb.SB_MEMBER_PANEL_WIDE if beta == 0.0 else sb.SB_MEMBER_PANEL_4X4)
+    # one element off 16-byte alignment, one odd leading dimension: the 4 x 4 member
+    run_sb_gemm("bf16", opA, opB, 128, 512, 128, 1, 129 if opA == "N" else 128, 128 if opB == "N" else 512, 128, 0, 0, 0, 1.0, 0.0,
+                seed=3, kernel="panel", member=sb.SB_MEMBER_PANEL_WIDE if opA == "T" else sb.SB_MEMBER_PANEL_4X4)
 
 
 @pytest.mark.parametrize("ma,mb,mc", [("m[p]k", "kn[q]", "m[p]n[q]"), ("k[p]m", "nk[q]", "m[p]n[q]"), ("mk[p]", "nk[q]", "mn[p][q]"),
@@ -477,6 +483,7 @@ def test_panel_grid_kernel_wide_blocks_nested(ma, mb, mc):
         for alpha in (1.0, 0.5):
             err, text = contract_case("bf16", ma, mb, mc, ext, alpha=alpha, seed=93, kernel="panel")
             assert err <= TOL["bf16"], (text, ext, err)
+            assert sb.sb_last_kernel_member() == sb.SB_MEMBER_PANEL_WIDE, (text, ext)
 
 
 def test_panel_grid_kernel_is_selected_for_the_large_short_k_products():
