@@ -437,19 +437,25 @@ bool sb_mfma_exa_supports(sb_dtype dt, const SbArgs &a)
     return first_form(a) || first_form(transposed(a));
 }
 
+// Tiles: 16 batches x 16 rows x 64 columns and 16 k per panel (fp64: 32 columns, 8 k; bf16: 32 k).  A problem
+// that makes fewer than 128 such tiles (64^4: 16) would leave most of the chip idle behind long chains of
+// dependent MFMAs (128 per wave at 64^4), so fp32 and fp64 then take tiles of a quarter the size: 16 batches x
+// 8 rows x 32 columns (fp64: 4 rows x 16 columns), one MFMA block per wave.
+template <bool CT>
+static hipError_t launch_form(sb_dtype dt, const SbArgs &a, hipStream_t stream)
+{
+    const int64_t bn = dt == SB_F64 ? 32 : 64;
+    const bool few = ((a.batch0 + 15) / 16) * ((a.m + 15) / 16) * ((a.n + bn - 1) / bn) * a.batch1 < 128;
+    if (dt == SB_F32) return few ? launch<ExF32, CT, 16, 8, 32, 16>(a, stream) : launch<ExF32, CT, 16, 16, 64, 16>(a, stream);
+    if (dt == SB_F64) return few ? launch<ExF64, CT, 16, 4, 16, 8>(a, stream) : launch<ExF64, CT, 16, 16, 32, 8>(a, stream);
+    if (dt == SB_BF16) return launch<ExBf16, CT, 16, 16, 64, 32>(a, stream);
+    return hipErrorInvalidValue;
+}
+
 hipError_t sb_launch_mfma_exa(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
-    // 16 batches x 16 rows x 64 columns per tile and 16 k per panel (fp64: 32 columns, 8 k; bf16: 32 k)
-    if (first_form(a)) {
-        if (dt == SB_F32) return launch<ExF32, false, 16, 16, 64, 16>(a, stream);
-        if (dt == SB_F64) return launch<ExF64, false, 16, 16, 32, 8>(a, stream);
-        if (dt == SB_BF16) return launch<ExBf16, false, 16, 16, 64, 32>(a, stream);
-        return hipErrorInvalidValue;
-    }
+    if (first_form(a)) return launch_form<false>(dt, a, stream);
     const SbArgs t = transposed(a);
     if (!first_form(t)) return hipErrorInvalidValue;
-    if (dt == SB_F32) return launch<ExF32, true, 16, 16, 64, 16>(t, stream);
-    if (dt == SB_F64) return launch<ExF64, true, 16, 16, 32, 8>(t, stream);
-    if (dt == SB_BF16) return launch<ExBf16, true, 16, 16, 64, 32>(t, stream);
-    return hipErrorInvalidValue;
+    return launch_form<true>(dt, t, stream);
 }
