@@ -763,6 +763,54 @@ def test_replays_inside_a_hip_graph():
         tB.mul_(1.0)                         # eager work between replays
 
 
+def test_replays_of_the_wide_block_and_block_split_members_inside_a_hip_graph():
+    # the same for the members that count their own outstanding loads and stores (wide-block panel kernel)
+    # or re-describe the batch (tiny kernel's 16 x 16 blocks): a nested bf16 product and a short fp64 batch
+    import torch
+    e5 = dict(m=64, n=64, p=4, q=8, k=128)
+    A5 = inputs.make_tensor(21, [e5["m"], e5["p"], e5["k"]], "bf16")
+    B5 = inputs.make_tensor(22, [e5["k"], e5["n"], e5["q"]], "bf16")
+    e1 = dict(m=32, n=32, p=8, k=32)
+    A1 = inputs.uniform_tensor(23, [e1["m"], e1["k"]])
+    B1 = inputs.uniform_tensor(24, [e1["k"], e1["n"], e1["p"]])
+    tA5, tB5, tA1, tB1 = to_dev(A5, "bf16"), to_dev(B5, "bf16"), to_dev(A1, "f64"), to_dev(B1, "f64")
+    d5, d1 = [e5[c] for c in "mpnq"], [e1[c] for c in "mnp"]
+    tC5 = to_dev(np.zeros(int(np.prod(d5))), "bf16")
+    tC1 = to_dev(np.zeros(int(np.prod(d1))), "f64")
+
+    def work():
+        sb.sb_force_kernel(sb.SB_KERNEL_PANEL)       # two blocks only: the selector would take 64 x 64 tiles
+        sb.sb_contract("m[p]k", "kn[q]", "m[p]n[q]", 1.0, tA5, list(A5.shape), tB5, list(B5.shape), 0.0, tC5, d5, dt="bf16")
+        sb.sb_force_kernel(sb.SB_KERNEL_AUTO)
+        sb.sb_contract("mk", "kn[p]", "mn[p]", 1.0, tA1, list(A1.shape), tB1, list(B1.shape), 0.0, tC1, d1, dt="f64")
+
+    ref5 = oracle.contract("mpk", A5, "knq", B5, "mpnq", wide=False)
+    ref1 = oracle.contract("mk", A1, "knp", B1, "mnp", wide=True)
+    work()                                   # warm-up outside the capture; and the members are the intended ones
+    sync()
+    assert sb.sb_last_kernel() == sb.SB_KERNEL_TINY and sb.sb_last_kernel_member() == sb.SB_MEMBER_TINY_BLOCKS
+    sb.sb_force_kernel(sb.SB_KERNEL_PANEL)
+    sb.sb_contract("m[p]k", "kn[q]", "m[p]n[q]", 1.0, tA5, list(A5.shape), tB5, list(B5.shape), 0.0, tC5, d5, dt="bf16")
+    sync()
+    assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL and sb.sb_last_kernel_member() == sb.SB_MEMBER_PANEL_WIDE
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            work()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        tC5.fill_(float("nan"))
+        tC1.fill_(float("nan"))
+        sync()
+        graph.replay()
+        sync()
+        assert_close(from_dev(tC5, d5), ref5, "bf16", e5["k"], np.abs(A5).max(), np.abs(B5).max(), what=rep)
+        assert_close(from_dev(tC1, d1), ref1, "f64", e1["k"], 1.0, 1.0, what=rep)
+        tB1.mul_(1.0)                        # eager work between replays
+
+
 @pytest.mark.parametrize("dtype", ["f64", "f32"])
 @pytest.mark.parametrize("opA,opB", [("N", "N"), ("T", "N"), ("N", "T"), ("T", "T")])
 def test_sb_gemm_whole_tile_shapes(dtype, opA, opB):
