@@ -245,8 +245,14 @@ int sb_last_kernel(void);
  *                    or SB_MEMBER_PANEL_WIDE (2 x 8 panels straight into LDS: k == 128, beta == 0, whole
  *                    64-wide panels in whole blocks, every address 16-byte aligned);
  *   SB_KERNEL_TINY:  SB_MEMBER_TINY_WHOLE (one wave per C_p) or SB_MEMBER_TINY_BLOCKS (a batch of at most
- *                    1024 / (blocks per C_p) problems with m or n == 32 run as independent 16 x 16 blocks). */
-enum { SB_MEMBER_PANEL_4X4 = 1, SB_MEMBER_PANEL_WIDE = 2, SB_MEMBER_TINY_WHOLE = 1, SB_MEMBER_TINY_BLOCKS = 2 };
+ *                    1024 / (blocks per C_p) problems with m or n == 32 run as independent 16 x 16 blocks);
+ *   SB_KERNEL_MFMA, extended operation only: SB_MEMBER_MFMA_EX_BRICK (bricks of 16 batches x 16 rows, staged
+ *                    through registers: any shape), SB_MEMBER_MFMA_EX_SMALL (quarter-size tiles when there are
+ *                    fewer than 128 large ones; SB_F32 / SB_F64) or SB_MEMBER_MFMA_EX_DMA (SB_F32, whole bricks
+ *                    -- batch a multiple of 16, the extended operand's free extent of 16, the other's of 64, k of
+ *                    16 -- loaded straight into LDS; operands 16-byte aligned, strides multiples of 4). */
+enum { SB_MEMBER_PANEL_4X4 = 1, SB_MEMBER_PANEL_WIDE = 2, SB_MEMBER_TINY_WHOLE = 1, SB_MEMBER_TINY_BLOCKS = 2,
+       SB_MEMBER_MFMA_EX_BRICK = 1, SB_MEMBER_MFMA_EX_SMALL = 2, SB_MEMBER_MFMA_EX_DMA = 3 };
 int sb_last_kernel_member(void);
 
 /* Host only: the kernel family the selector sends an sb_gemm problem to (sizes, operations and

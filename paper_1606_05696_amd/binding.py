@@ -19,6 +19,7 @@ SB_ERR_MODES, SB_ERR_CONTRACTION, SB_ERR_EXTENT, SB_ERR_STRIDE, SB_ERR_ILLEGAL_E
 SB_ERR_LAUNCH = 1000
 SB_KERNEL_AUTO, SB_KERNEL_GENERIC, SB_KERNEL_TINY, SB_KERNEL_MFMA, SB_KERNEL_THIN, SB_KERNEL_PANEL = -1, 0, 1, 2, 3, 4
 SB_MEMBER_PANEL_4X4, SB_MEMBER_PANEL_WIDE, SB_MEMBER_TINY_WHOLE, SB_MEMBER_TINY_BLOCKS = 1, 2, 1, 2
+SB_MEMBER_MFMA_EX_BRICK, SB_MEMBER_MFMA_EX_SMALL, SB_MEMBER_MFMA_EX_DMA = 1, 2, 3
 SB_MAX_MODES = 8
 SB_MAX_BATCH_LEVELS = 8
 

@@ -645,6 +645,57 @@ def test_extended_operation_on_either_operand(dtype, kernel, opA, opB):
     sb.sb_force_kernel(KERNELS["auto"])
 
 
+@pytest.mark.parametrize("opA,opB", EX_FORMS)
+def test_extended_operation_members(opA, opB):
+    # the members of the extended-operation kernel on whole bricks (16 batches x 16 rows x 64 columns, 16 k): in
+    # fp32 the direct-to-LDS member when every load is 16-byte aligned (leading extent padded by 4), the
+    # register-staged bricks otherwise (padded by 1); quarter-size tiles when the large ones are few; either
+    # operand, both orientations of the plain one, alpha and beta
+    ex_first = opA.startswith("EX")
+    for (m, n, k, P, pad, alpha, beta, member) in [
+            (128, 128, 32, 128, 4, 1.0, 0.0, sb.SB_MEMBER_MFMA_EX_DMA), (128, 128, 48, 128, 0, 0.75, -0.5, sb.SB_MEMBER_MFMA_EX_DMA),
+            (64, 256, 16, 256, 4, -1.0, 0.0, sb.SB_MEMBER_MFMA_EX_DMA), (256, 64, 80, 256, 0, 1.0, 1.0, sb.SB_MEMBER_MFMA_EX_DMA),
+            (512, 512, 32, 128, 4, 0.5, 0.25, sb.SB_MEMBER_MFMA_EX_DMA),          # enough tiles for the 128-column ones
+            (128, 128, 32, 128, 1, 1.0, 0.0, sb.SB_MEMBER_MFMA_EX_BRICK), (64, 64, 32, 64, 0, 1.0, 0.0, sb.SB_MEMBER_MFMA_EX_SMALL)]:
+        # (64, 256) / (256, 64): whole bricks for one operand position only (16 rows of the extended operand, 64 of the other)
+        rows_ex, rows_other = (m, n) if ex_first else (n, m)
+        if member == sb.SB_MEMBER_MFMA_EX_DMA and (rows_ex % 16 or rows_other % 64):
+            continue
+        rng = np.random.default_rng(m + n + k)
+
+        def operand(op, rows, cols):             # op(X) is rows x cols; returns (ld, stride0, size)
+            if op in ("N", "T"):
+                r, c = (rows, cols) if op == "N" else (cols, rows)
+                return r + pad, 0, (r + pad) * c
+            inner, outer = (rows, cols) if op == "EX_N" else (cols, rows)     # EX_N: rows next to the batch mode
+            ld = P + pad
+            return ld, ld * inner + 4 * pad, (ld * inner + 4 * pad) * outer
+
+        lda, sA, sizeA = operand(opA, m, k)
+        ldb, sB, sizeB = operand(opB, k, n)
+        ldc, sC = m + pad, (m + pad) * n + pad
+        a = rng.uniform(-1, 1, sizeA).astype(np.float32).astype(np.float64)
+        b = rng.uniform(-1, 1, sizeB).astype(np.float32).astype(np.float64)
+        c0 = rng.uniform(-1, 1, sC * P).astype(np.float32).astype(np.float64)
+        dA, dB, dC = to_dev(a, "f32"), to_dev(b, "f32"), to_dev(c0, "f32")
+        sb.sb_gemm(opA, opB, m, n, k, alpha, dA, lda, sA, dB, ldb, sB, beta, dC, ldc, sC, P, dt="f32")
+        sync()
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_MFMA and sb.sb_last_kernel_member() == member, \
+            (opA, opB, m, n, k, P, pad, sb.sb_last_kernel(), sb.sb_last_kernel_member(), member)
+
+        def packed(x, op, rows, cols, ld, s0):   # the P matrices op(X_b), gathered into packed column-major copies
+            rs, cs, bs = {"N": (1, ld, s0), "T": (ld, 1, s0), "EX_N": (ld, s0, 1), "EX_T": (s0, ld, 1)}[op]
+            bb, jj, ii = np.meshgrid(np.arange(P), np.arange(cols), np.arange(rows), indexing="ij")
+            return x[bb * bs + ii * rs + jj * cs].ravel()
+
+        ref = oracle.sb_gemm("N", "N", m, n, k, alpha, packed(a, opA, m, k, lda, sA), m, m * k,
+                             packed(b, opB, k, n, ldb, sB), k, k * n, beta, c0, ldc, sC, P, wide=False)
+        got = from_dev(dC)
+        inside = gemm_window_mask(got.size, m, n, ldc, sC, P)
+        assert np.array_equal(got[~inside], c0[~inside]), "elements outside the m x n windows were written"
+        assert_close(got[inside], ref[inside], "f32", k, 1.0, 1.0, alpha, beta, c0[inside], what=(opA, opB, m, n, k, P, pad))
+
+
 def test_runs_on_a_side_stream():
     import torch
     s = torch.cuda.Stream()
