@@ -248,9 +248,10 @@ int sb_last_kernel(void);
  *                    1024 / (blocks per C_p) problems with m or n == 32 run as independent 16 x 16 blocks);
  *   SB_KERNEL_MFMA, extended operation only: SB_MEMBER_MFMA_EX_BRICK (bricks of 16 batches x 16 rows, staged
  *                    through registers: any shape), SB_MEMBER_MFMA_EX_SMALL (quarter-size tiles when there are
- *                    fewer than 128 large ones; SB_F32 / SB_F64) or SB_MEMBER_MFMA_EX_DMA (SB_F32, whole bricks
- *                    -- batch a multiple of 16, the extended operand's free extent of 16, the other's of 64, k of
- *                    16 -- loaded straight into LDS; operands 16-byte aligned, strides multiples of 4). */
+ *                    fewer than 128 large ones; SB_F32 / SB_F64) or SB_MEMBER_MFMA_EX_DMA (SB_F32 / SB_F64, whole
+ *                    bricks -- batch a multiple of 16, the extended operand's free extent of 16, the other's of
+ *                    64, k of 64 bytes -- loaded straight into LDS; operands 16-byte aligned, strides multiples
+ *                    of 16 bytes). */
 enum { SB_MEMBER_PANEL_4X4 = 1, SB_MEMBER_PANEL_WIDE = 2, SB_MEMBER_TINY_WHOLE = 1, SB_MEMBER_TINY_BLOCKS = 2,
        SB_MEMBER_MFMA_EX_BRICK = 1, SB_MEMBER_MFMA_EX_SMALL = 2, SB_MEMBER_MFMA_EX_DMA = 3 };
 int sb_last_kernel_member(void);

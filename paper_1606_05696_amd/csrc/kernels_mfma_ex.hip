@@ -385,27 +385,38 @@ __global__ __launch_bounds__(ET, sizeof(typename MF::T) == 8 ? 2 : 1) void sbgem
     }
 }
 
-// Direct-to-LDS member (fp32, whole bricks): the same brick and the same MFMA tile, but the panels travel from
-// memory straight into two LDS stages (global_load_lds_dwordx4: no staging registers, no LDS store
+// Direct-to-LDS member (fp32 and fp64, whole bricks): the same brick and the same MFMA tile, but the panels travel
+// from memory straight into two LDS stages (global_load_lds_dwordx4: no staging registers, no LDS store
 // instructions), one barrier per panel.  LDS cannot be padded by such loads (lane l lands at base + 16 l), so
 // the layouts are unpadded and conflicts are avoided by what each lane fetches into its slot:
-//   A brick   [k][i][16 b]: the four 16-byte chunks (4 batches each) of row i sit at chunk ^ (i / 4) % 4, so the
-//             16 lanes of a fragment read that differ in i cover 16 different 16-byte columns of the banks;
-//   B panel   k contiguous: [col][16 k], chunk (4 k) of column col at chunk ^ (col / 4) % 4; otherwise
-//             [k][64 columns] as it lies (lanes along the columns).
-// A load instruction of a wave fetches one k of the brick (16 rows x 64 bytes), so its base pointer carries k
-// and the lane offsets stay small.  Per panel and wave: five loads requested two panels ahead, 32 MFMAs in
-// two fragment sets.
-template <bool B_KC, bool CT, int BN>
+//   A brick   [k][i][16 b]: the 16-byte chunks of row i (four of 4 batches in fp32, eight of 2 in fp64) sit at
+//             chunk ^ f(i), f(i) = (i / 4) % 4 or (i / 2) % 8: the 16 lanes of a fragment read that differ in i
+//             then cover 16 different 16-byte columns of the banks;
+//   B panel   k contiguous: [col][64 bytes of k], chunk of column col at chunk ^ (col / 4) % 4; otherwise
+//             [k][BN columns] as it lies (lanes along the columns).
+// A load instruction of a wave fetches one k of the brick (fp64: half of one), so its base pointer carries k and
+// the lane offsets stay small.  fp32: 16-deep panels of two fragment groups (the second group is read while the
+// first is multiplied, the barrier sits between them), tiles 64 or 128 columns wide (a wave's 64 rows x 128
+// columns reuse each A fragment four times); fp64: 8-deep panels of one group, 64 columns, the next panel's
+// fragments read ahead of the current panel's MFMAs.  Per panel and wave: five or six loads requested two panels
+// ahead, 32 or 64 MFMAs.
+template <typename MF, bool B_KC, bool CT, int BN>
 __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, int tiles_b, int tiles_i, int tiles_n)
 {
-    typedef ExF32 MF;
-    typedef float T;
-    typedef MF::Vec Vec;
-    constexpr int PB = 16, MB = 16, BK = 16, MI = 32, VEC = 4, STEPS = 4;
+    typedef typename MF::T T;
+    typedef typename MF::Vec Vec;
+    typedef typename MF::S S;
+    constexpr int PB = 16, MB = 16, MI = MF::MI, VEC = MF::VEC, STEPS = MF::STEPS;
+    constexpr int KF = (64 / MI) * VEC;               // k per fragment group: 8
+    constexpr int BK = 64 / (int)sizeof(T);           // 64 bytes of k per panel: 16 (fp32) or 8 (fp64)
+    constexpr int KG = BK / KF;                       // fragment groups per panel: 2 or 1
+    constexpr int CPR = PB / VEC;                     // 16-byte chunks of a (k, i) run of 16 batches
+    constexpr int RPI = 64 / CPR, IPK = MB / RPI;     // rows i per load instruction, load instructions per k
+    constexpr int ISH = sizeof(T) == 4 ? 2 : 1;       // f(i) = (i >> ISH) % CPR
     constexpr int NLB = BN / 64;                      // loads of B per wave and panel (1 KB each)
     constexpr int BM = PB * MB, NBM = BM / 4 / MI, NBN = BN / MI;
-    constexpr int A_SIZE = BK * MB * PB, B_SIZE = BN * BK, STAGE = A_SIZE + B_SIZE;       // floats
+    constexpr int A_SIZE = BK * MB * PB, B_SIZE = BN * BK, STAGE = A_SIZE + B_SIZE;       // elements
+    static_assert(BK * IPK == 16 && (KG == 1 || KG == 2) && NLB >= 1, "four loads of A per wave and panel");
     __shared__ __attribute__((aligned(16))) T lds[2 * STAGE];
 
     const int64_t total = (int64_t)gridDim.x;
@@ -425,32 +436,38 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
     const int64_t nkb = g.k / BK;
 
     // what this lane fetches (byte offsets from the load's base) and where the wave's loads land
-    unsigned voffA, voffB[NLB];
+    unsigned voffA[IPK], voffB[NLB];
     {
-        const int i = lane >> 2, c = (lane & 3) ^ ((i >> 2) & 3);
-        voffA = (unsigned)((4 * c + (int64_t)i * g.rsA) * 4);
+#pragma unroll
+        for (int h = 0; h < IPK; ++h) {               // the load's rows i = RPI h .. + RPI - 1 (its base points at row RPI h)
+            const int il = lane / CPR, i = RPI * h + il, c = (lane % CPR) ^ ((i >> ISH) % CPR);
+            voffA[h] = (unsigned)((VEC * c + (int64_t)il * g.rsA) * (int64_t)sizeof(T));
+        }
 #pragma unroll
         for (int j = 0; j < NLB; ++j) {
             const int u = NLB * wave + j;             // which KB of the B panel
             if (B_KC) {                               // 16 columns of 64 bytes
                 const int col = 16 * u + (lane >> 2), ck = (lane & 3) ^ ((col >> 2) & 3);
-                voffB[j] = (unsigned)(((int64_t)col * g.csB + 4 * ck) * 4);
-            } else {                                  // 1024 / (4 BN) k-rows of BN columns
-                constexpr int LPR = BN / 4;           // lanes per k-row
+                voffB[j] = (unsigned)(((int64_t)col * g.csB + VEC * ck) * (int64_t)sizeof(T));
+            } else {                                  // whole k-rows of BN columns
+                constexpr int LPR = BN / VEC;         // lanes per k-row
                 const int kr = (64 / LPR) * u + lane / LPR, cc = lane % LPR;
-                voffB[j] = (unsigned)(((int64_t)kr * g.rsB + 4 * cc) * 4);
+                voffB[j] = (unsigned)(((int64_t)kr * g.rsB + VEC * cc) * (int64_t)sizeof(T));
             }
         }
     }
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) T *)lds;
-    const unsigned landA = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);          // k = 4 wave + j: + 1024 j
-    const unsigned landB = __builtin_amdgcn_readfirstlane(lds0 + A_SIZE * 4 + wave * (NLB * 1024));
+    const unsigned landA = __builtin_amdgcn_readfirstlane(lds0 + wave * 4096);          // load 4 wave + j: + 1024 j
+    const unsigned landB = __builtin_amdgcn_readfirstlane(lds0 + A_SIZE * (int)sizeof(T) + wave * (NLB * 1024));
     auto request = [&](int st, int64_t kb) __attribute__((always_inline)) {
-        const T *pa = A + (kb * BK + 4 * wave) * g.csA;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dma16(landA + st * (STAGE * 4) + j * 1024, pa + j * g.csA, voffA);
+        for (int j = 0; j < 4; ++j) {                 // load t = 4 wave + j: k = t / IPK, rows from RPI (t % IPK)
+            const int k = (4 * wave + j) / IPK, h = j % IPK;          // 4 wave is a multiple of IPK
+            dma16(landA + st * (STAGE * (int)sizeof(T)) + j * 1024, A + (kb * BK + k) * g.csA + (int64_t)(RPI * h) * g.rsA, voffA[h]);
+        }
 #pragma unroll
-        for (int j = 0; j < NLB; ++j) dma16(landB + st * (STAGE * 4) + j * 1024, B_KC ? B + kb * BK : B + kb * BK * g.rsB, voffB[j]);
+        for (int j = 0; j < NLB; ++j)
+            dma16(landB + st * (STAGE * (int)sizeof(T)) + j * 1024, B_KC ? B + kb * BK : B + kb * BK * g.rsB, voffB[j]);
     };
 
     typename MF::Acc acc[NBM][NBN];
@@ -459,18 +476,18 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
 #pragma unroll
         for (int c = 0; c < NBN; ++c)
 #pragma unroll
-            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = 0.f;
+            for (int r = 0; r < MF::NREG; ++r) acc[a][c][r] = S(0);
 
     const int rho0 = wave * (BM / 4), kl = lane / MI;
     Vec fa[2][NBM], fb[2][NBN];
     auto read_frags = [&](Vec (&xa)[NBM], Vec (&xb)[NBN], int st, int kg) __attribute__((always_inline)) {
         const T *As = lds + st * STAGE, *Bs = As + A_SIZE;
-        const int k = kg * 8 + kl * VEC;
+        const int k = kg * KF + kl * VEC;
 #pragma unroll
         for (int a = 0; a < NBM; ++a) {
             const int rho = rho0 + a * MI + (lane % MI);
             const int i = rho % MB, b = rho / MB;
-            const T *p = As + (i * 4 + ((b >> 2) ^ ((i >> 2) & 3))) * 4 + (b & 3);
+            const T *p = As + (i * CPR + ((b / VEC) ^ ((i >> ISH) % CPR))) * VEC + (b % VEC);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) xa[a][e] = p[(k + e) * (MB * PB)];
         }
@@ -478,7 +495,7 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
         for (int c = 0; c < NBN; ++c) {
             const int col = c * MI + (lane % MI);
             if (B_KC) {
-                xb[c] = *(const Vec *)(Bs + (col * 4 + ((k >> 2) ^ ((col >> 2) & 3))) * 4);
+                xb[c] = *(const Vec *)(Bs + (col * 4 + ((k / VEC) ^ ((col >> 2) & 3))) * VEC);
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) xb[c][e] = Bs[(k + e) * BN + col];
@@ -508,21 +525,41 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
     }
     __syncthreads();
     read_frags(fa[0], fb[0], 0, 0);
-    for (int64_t kb = 0; kb < nkb; ++kb) {
-        const int st = (int)(kb & 1);
-        read_frags(fa[1], fb[1], st, 1);
-        mfmas(fa[0], fb[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        dma_wait<0>();               // this wave's share of the next panel is in LDS
-        __syncthreads();             // ... everybody's, and nobody reads this stage any more
-        if (kb + 2 < nkb) request(st, kb + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        if (kb + 1 < nkb) read_frags(fa[0], fb[0], st ^ 1, 0);
-        mfmas(fa[1], fb[1]);
+    if constexpr (KG == 2) {
+        for (int64_t kb = 0; kb < nkb; ++kb) {
+            const int st = (int)(kb & 1);
+            read_frags(fa[1], fb[1], st, 1);
+            mfmas(fa[0], fb[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            dma_wait<0>();               // this wave's share of the next panel is in LDS
+            __syncthreads();             // ... everybody's, and nobody reads this stage any more
+            if (kb + 2 < nkb) request(st, kb + 2);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kb + 1 < nkb) read_frags(fa[0], fb[0], st ^ 1, 0);
+            mfmas(fa[1], fb[1]);
+        }
+    } else {
+        // one fragment group per panel: panel kb's fragments are in set kb % 2 when its turn comes; the next
+        // panel is waited for, published and read BEFORE this panel's MFMAs, which then cover those reads
+        auto one = [&](int64_t kb, auto set_c) __attribute__((always_inline)) {
+            constexpr int SET = decltype(set_c)::value;
+            if (kb + 1 < nkb) {
+                dma_wait<0>();
+                __syncthreads();         // panel kb + 1 is in LDS, and everybody has finished reading panel kb's stage
+                if (kb + 2 < nkb) request(SET, kb + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(fa[SET ^ 1], fb[SET ^ 1], SET ^ 1, 0);
+            }
+            mfmas(fa[SET], fb[SET]);
+        };
+        for (int64_t kb = 0; kb < nkb; kb += 2) {
+            one(kb, std::integral_constant<int, 0>());
+            if (kb + 1 < nkb) one(kb + 1, std::integral_constant<int, 1>());
+        }
     }
 
     // epilogue (whole bricks only): as in the kernel above
-    const float alpha = (float)g.alpha, beta = (float)g.beta;
+    const S alpha = (S)g.alpha, beta = (S)g.beta;
     auto store_tile = [&](auto beta_c) __attribute__((always_inline)) {
         constexpr bool BETA = decltype(beta_c)::value;
         if (CT) {
@@ -535,7 +572,7 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
                     for (int r = 0; r < MF::NREG; ++r) {
                         const int rho = rho0 + a * MI + MF::row_lane(lane) + MF::row_reg(r);
                         T *dst = Cc + (bb + rho / MB) * g.bsC[0] + (i0 + rho % MB) * g.ldc;
-                        float v = alpha * acc[a][c][r];
+                        S v = alpha * acc[a][c][r];
                         if (BETA) v += beta * *dst;
                         *dst = v;
                     }
@@ -552,31 +589,34 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
 #pragma unroll
                 for (int r = 0; r < MF::NREG; ++r) {
                     T *dst = col + MF::row_reg(r) * g.ldc;
-                    float v = alpha * acc[a][c][r];
+                    S v = alpha * acc[a][c][r];
                     if (BETA) v += beta * *dst;
                     *dst = v;
                 }
             }
         }
     };
-    if (beta == 0.f) store_tile(std::false_type());
-    else             store_tile(std::true_type());
+    if (beta == S(0)) store_tile(std::false_type());
+    else              store_tile(std::true_type());
 }
 
-// the direct-to-LDS member takes whole bricks whose every load is 16-byte aligned and whose lane offsets fit 32 bits
-bool dma_applies(const SbArgs &a)
+// the direct-to-LDS member takes whole bricks (64 bytes of k per panel) whose every load is 16-byte aligned and
+// whose lane offsets fit 32 bits; vec: elements per 16 bytes
+bool dma_applies(const SbArgs &a, int vec)
 {
-    if (a.batch0 % 16 || a.m % 16 || a.n % 64 || a.k % 16 || a.k < 16) return false;
-    auto al = [](int64_t v) { return v % 4 == 0; };
+    const int bk = 16 * vec / 4;
+    if (a.batch0 % 16 || a.m % 16 || a.n % 64 || a.k % bk || a.k < bk) return false;
+    auto al = [vec](int64_t v) { return v % vec == 0; };
+    const int64_t ldB = a.rsB == 1 ? a.csB : a.rsB;
     if (((uintptr_t)a.A | (uintptr_t)a.B) % 16) return false;
-    if (!al(a.rsA) || !al(a.csA) || !al(a.rsB == 1 ? a.csB : a.rsB) || !al(a.bsA[1]) || !al(a.bsB[1])) return false;
+    if (!al(a.rsA) || !al(a.csA) || !al(ldB) || !al(a.bsA[1]) || !al(a.bsB[1])) return false;
     for (int x = 0; x < a.nx; ++x)
         if (!al(a.xsA[x]) || !al(a.xsB[x])) return false;
     const int64_t most = (int64_t)1 << 24;
-    return a.rsA > 0 && a.rsA < most && a.csA > 0 && (a.rsB == 1 ? a.csB : a.rsB) < most && (a.rsB == 1 ? a.csB : a.rsB) > 0;
+    return a.rsA > 0 && a.rsA < most && a.csA > 0 && ldB > 0 && ldB < most;
 }
 
-template <bool CT, int BN>
+template <typename MF, bool CT, int BN>
 hipError_t launch_dma(const SbArgs &a, hipStream_t stream)
 {
     const int64_t tiles_b = a.batch0 / 16, tiles_i = a.m / 16, tiles_n = a.n / BN;
@@ -584,8 +624,8 @@ hipError_t launch_dma(const SbArgs &a, hipStream_t stream)
     if (total <= 0) return hipSuccess;
     if (total > sb_max_grid_x(256)) return hipErrorInvalidConfiguration;
     dim3 grid((unsigned)total), block(256);
-    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_dma_kernel<true, CT, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n);
-    else            hipLaunchKernelGGL((sbgemm_mfma_exa_dma_kernel<false, CT, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n);
+    if (a.rsB == 1) hipLaunchKernelGGL((sbgemm_mfma_exa_dma_kernel<MF, true, CT, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n);
+    else            hipLaunchKernelGGL((sbgemm_mfma_exa_dma_kernel<MF, false, CT, BN>), grid, block, 0, stream, a, (int)tiles_b, (int)tiles_i, (int)tiles_n);
     return hipGetLastError();
 }
 
@@ -650,11 +690,15 @@ static hipError_t launch_form(sb_dtype dt, const SbArgs &a, hipStream_t stream)
 {
     const int64_t bn = dt == SB_F64 ? 32 : 64;
     const bool few = ((a.batch0 + 15) / 16) * ((a.m + 15) / 16) * ((a.n + bn - 1) / bn) * a.batch1 < 128;
-    if (dt == SB_F32 && !few && dma_applies(a)) {
+    if (dt == SB_F32 && !few && dma_applies(a, 4)) {
         sb_note_member(SB_MEMBER_MFMA_EX_DMA);
         // 128-column tiles when they still make a full round of workgroups (two per compute unit)
         const bool wide = a.n % 128 == 0 && (a.batch0 / 16) * (a.m / 16) * (a.n / 128) * a.batch1 >= 512;
-        return wide ? launch_dma<CT, 128>(a, stream) : launch_dma<CT, 64>(a, stream);
+        return wide ? launch_dma<ExF32, CT, 128>(a, stream) : launch_dma<ExF32, CT, 64>(a, stream);
+    }
+    if (dt == SB_F64 && !few && dma_applies(a, 2)) {
+        sb_note_member(SB_MEMBER_MFMA_EX_DMA);
+        return launch_dma<ExF64, CT, 64>(a, stream);
     }
     sb_note_member(few && dt != SB_BF16 ? SB_MEMBER_MFMA_EX_SMALL : SB_MEMBER_MFMA_EX_BRICK);
     if (dt == SB_F32) return few ? launch<ExF32, CT, 16, 8, 32, 16>(a, stream) : launch<ExF32, CT, 16, 16, 64, 16>(a, stream);

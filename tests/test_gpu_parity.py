@@ -645,10 +645,11 @@ def test_extended_operation_on_either_operand(dtype, kernel, opA, opB):
     sb.sb_force_kernel(KERNELS["auto"])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f64"])
 @pytest.mark.parametrize("opA,opB", EX_FORMS)
-def test_extended_operation_members(opA, opB):
-    # the members of the extended-operation kernel on whole bricks (16 batches x 16 rows x 64 columns, 16 k): in
-    # fp32 the direct-to-LDS member when every load is 16-byte aligned (leading extent padded by 4), the
+def test_extended_operation_members(opA, opB, dtype):
+    # the members of the extended-operation kernel on whole bricks (16 batches x 16 rows x 64 columns, 64 bytes of
+    # k): in fp32 and fp64 the direct-to-LDS member when every load is 16-byte aligned (leading extent padded by 4), the
     # register-staged bricks otherwise (padded by 1); quarter-size tiles when the large ones are few; either
     # operand, both orientations of the plain one, alpha and beta
     ex_first = opA.startswith("EX")
@@ -674,11 +675,11 @@ def test_extended_operation_members(opA, opB):
         lda, sA, sizeA = operand(opA, m, k)
         ldb, sB, sizeB = operand(opB, k, n)
         ldc, sC = m + pad, (m + pad) * n + pad
-        a = rng.uniform(-1, 1, sizeA).astype(np.float32).astype(np.float64)
-        b = rng.uniform(-1, 1, sizeB).astype(np.float32).astype(np.float64)
-        c0 = rng.uniform(-1, 1, sC * P).astype(np.float32).astype(np.float64)
-        dA, dB, dC = to_dev(a, "f32"), to_dev(b, "f32"), to_dev(c0, "f32")
-        sb.sb_gemm(opA, opB, m, n, k, alpha, dA, lda, sA, dB, ldb, sB, beta, dC, ldc, sC, P, dt="f32")
+        a = quantise(rng.uniform(-1, 1, sizeA), dtype)
+        b = quantise(rng.uniform(-1, 1, sizeB), dtype)
+        c0 = quantise(rng.uniform(-1, 1, sC * P), dtype)
+        dA, dB, dC = to_dev(a, dtype), to_dev(b, dtype), to_dev(c0, dtype)
+        sb.sb_gemm(opA, opB, m, n, k, alpha, dA, lda, sA, dB, ldb, sB, beta, dC, ldc, sC, P, dt=dtype)
         sync()
         assert sb.sb_last_kernel() == sb.SB_KERNEL_MFMA and sb.sb_last_kernel_member() == member, \
             (opA, opB, m, n, k, P, pad, sb.sb_last_kernel(), sb.sb_last_kernel_member(), member)
@@ -689,11 +690,11 @@ def test_extended_operation_members(opA, opB):
             return x[bb * bs + ii * rs + jj * cs].ravel()
 
         ref = oracle.sb_gemm("N", "N", m, n, k, alpha, packed(a, opA, m, k, lda, sA), m, m * k,
-                             packed(b, opB, k, n, ldb, sB), k, k * n, beta, c0, ldc, sC, P, wide=False)
+                             packed(b, opB, k, n, ldb, sB), k, k * n, beta, c0, ldc, sC, P, wide=(dtype == "f64"))
         got = from_dev(dC)
         inside = gemm_window_mask(got.size, m, n, ldc, sC, P)
         assert np.array_equal(got[~inside], c0[~inside]), "elements outside the m x n windows were written"
-        assert_close(got[inside], ref[inside], "f32", k, 1.0, 1.0, alpha, beta, c0[inside], what=(opA, opB, m, n, k, P, pad))
+        assert_close(got[inside], ref[inside], dtype, k, 1.0, 1.0, alpha, beta, c0[inside], what=(dtype, opA, opB, m, n, k, P, pad))
 
 
 def test_runs_on_a_side_stream():
