@@ -1,9 +1,9 @@
 // MFMA kernel for the extended operation on the first operand (section III-E): the batched mode is
 // the FIRST, unit-stride mode of the tensor, so each batch's matrix is strided in rows and columns,
 //     op(A_b)(i,l) = A[b + i*rs + l*cs],        C_b(i,j) = C[b*strideC + i + j*ldc].
-// This is the kernel the paper asks for when it says an extended-transpose implementation should
-// "perform a 3D tiling of B into cache": reading one batch at a time would use one element per
-// cache line, so a workgroup takes a 3-D brick of the tensor instead, PB consecutive batches x
+// This is the kernel section III-E asks for (an extended-transpose implementation has to tile the
+// tensor in all three of its modes on its way into cache): reading one batch at a time would use one
+// element per cache line, so a workgroup takes a 3-D brick of the tensor instead, PB consecutive batches x
 // MB rows x BK columns, which is read along b (contiguous runs of PB elements) and, because the
 // brick holds MB consecutive rows of every batch, written along i (contiguous runs of MB
 // elements of every C_b).  The brick's PB*MB (batch,row) pairs are simply the rows of one MFMA

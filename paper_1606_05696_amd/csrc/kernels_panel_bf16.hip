@@ -11,9 +11,9 @@
 //   - its flattened GEMM  C_(mp)(nq) = A_(mp)k B_k(nq)  (priority 1 of section IV-D): rows and columns
 //     are 64-wide pieces of the flat extents,
 //   - the partly flattened forms  C_(mp)n[q]  and  C_m[p](nq),
-// so all evaluations of such a contraction run through the same code at the same speed: "the batch
-// loop takes part in the tiling" (section III-D).  Batch levels that move both operands (or
-// neither) are an outer index z: independent grids.
+// so all evaluations of such a contraction run through the same code at the same speed: the batch
+// loops are part of the tiling (what section III-D expects of a StridedBatchedGemm implementation).
+// Batch levels that move both operands (or neither) are an outer index z: independent grids.
 //
 // A workgroup of eight waves takes a block of 4 x 4 panels (256 x 256 outputs): 4 + 4 panels are
 // fetched for 16 small products, so the nest gets the operand reuse of a tiled GEMM although
@@ -35,6 +35,9 @@
 // at any element address).  RAGGED instantiations handle extents that are not whole vectors with
 // guarded element accesses; the others keep every load unconditional so that the hand-over to LDS
 // can wait for exactly the loads it needs.
+//
+// A second member further down takes the whole-panel k = 128 problems: blocks of 2 x 8 panels whose operands
+// travel straight into LDS (sbgemm_panelgrid_wide_bf16_kernel); this one serves every other shape.
 #include "sb_device.h"
 #include "sb_internal.h"
 
