@@ -612,8 +612,8 @@ bool dma_applies(const SbArgs &a, int vec)
     if (!al(a.rsA) || !al(a.csA) || !al(ldB) || !al(a.bsA[1]) || !al(a.bsB[1])) return false;
     for (int x = 0; x < a.nx; ++x)
         if (!al(a.xsA[x]) || !al(a.xsB[x])) return false;
-    const int64_t most = (int64_t)1 << 24;
-    return a.rsA > 0 && a.rsA < most && a.csA > 0 && ldB > 0 && ldB < most;
+    // lane offsets are 32-bit byte offsets: up to 15 rows of A, up to 127 columns (or 15 k-rows) of B
+    return a.rsA > 0 && a.rsA < ((int64_t)1 << 24) && a.csA > 0 && ldB > 0 && ldB < ((int64_t)1 << 22);
 }
 
 template <typename MF, bool CT, int BN>
