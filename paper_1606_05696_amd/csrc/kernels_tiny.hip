@@ -286,7 +286,7 @@ hipError_t launch2(const SbArgs &a, hipStream_t stream)
 bool split_into_blocks(const SbArgs &a, int tm, int tn, SbArgs &s)
 {
     if (tm * tn == 1 || (tm == 2 && a.m != 32) || (tn == 2 && a.n != 32)) return false;
-    if (a.batch0 * a.batch1 * tm * tn > 1024) return false;
+    if (a.batch0 * a.batch1 > 1024 / (tm * tn)) return false;
     if (a.nx + (tm == 2) + (tn == 2) > SB_MAX_BATCH_LEVELS - 2) return false;
     s = a;
     if (s.nx == 0) s.cnt1 = s.batch1;
