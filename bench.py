@@ -444,44 +444,49 @@ def run_table2_cases(steps, warmup, torch_baseline=True):
     return out
 
 
-def run_exceptional_cases(steps, warmup, n=512, torch_baseline=True):
+def run_exceptional_cases(steps, warmup, n=512, torch_baseline=True, dtypes=("f32", "f64")):
     """Two exceptional cases of Table II (3.6 and 6.4, the ones section III-E writes out) at n^4 in
-    fp32: the extended-operation kernel against the two-step route the paper benchmarks it against
-    (explicit mode transposition + GEMM), in this library's own kernels and in torch's."""
+    fp32 and fp64: the extended-operation kernel against the two-step route the paper benchmarks it
+    against (explicit mode transposition + GEMM), in this library's own kernels and in torch's."""
     import torch
     import paper_1606_05696_amd as sb
     from paper_1606_05696_amd import inputs
     rows = []
-    A = inputs.uniform_tensor(31, [n, n], np.float32)
-    B = inputs.uniform_tensor(32, [n, n, n], np.float32)
-    tA, tB = dev(A, "f32"), dev(B, "f32")
-    tC = torch.empty(n ** 3, dtype=torch.float32, device="cuda")
     flops = 2 * n ** 4
     ext = dict(m=n, n=n, p=n, k=n)
-    for case, ma, mb in (("3.6", "nk", "pmk"), ("6.4", "kp", "nkm")):
-        rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
+    for dtype in dtypes:
+        npdt, tdt = (np.float32, torch.float32) if dtype == "f32" else (np.float64, torch.float64)
+        A = inputs.uniform_tensor(31, [n, n], npdt)
+        B = inputs.uniform_tensor(32, [n, n, n], npdt)
+        tA, tB = dev(A, dtype), dev(B, dtype)
+        tC = torch.empty(n ** 3, dtype=tdt, device="cuda")
+        for case, ma, mb in (("3.6", "nk", "pmk"), ("6.4", "kp", "nkm")):
+            rc, plan = sb.sb_contract_plan(ma, mb, "mnp", [n, n], [n, n, n])
 
-        def ours():
-            sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n])
+            def ours():
+                sb.sb_contract(ma, mb, "mnp", 1.0, tA, [n, n], tB, [n, n, n], 0.0, tC, [n, n, n], dt=dtype)
 
-        st = time_stats(ours, iters=max(30, steps), warmup=warmup)
-        family = sb.sb_last_kernel()
-        tC.fill_(float("nan"))
-        ours()
-        chk = check_output(tC, [n, n, n], ma, A, mb, B, "mnp", "f32", nsamples=1000)
-        own = conventional_own(ma, mb, "mnp", ext, "f32", tA, tB, tC, flops, iters=10)
-        t_ours = st["median_us"] / 1e3
-        row = dict(case=case, evaluation=plan.text(), kernel_family=family, kernel_ms=t_ours, kernel_us=st,
-                   gflops=flops / t_ours / 1e6, frac_of_fp32_mfma_peak=flops / t_ours / 1e9 / PEAK["mfma"]["f32"],
-                   check_ok=chk["ok"], conventional_own=own, speedup_over_conventional_own=own["us"] / st["median_us"])
-        if torch_baseline:
-            a, b = tA.view(n, n), tB.view(n, n, n)
-            expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
-            _, t_conv = time_steps(lambda: torch.einsum(expr, a, b).contiguous(), steps, warmup)
-            row["conventional_torch_ms"] = t_conv
-            row["speedup_over_conventional_torch"] = t_conv / t_ours
-        rows.append(row)
-    return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, f32: extended-operation kernel" % n, short="ext-op", cases=rows)
+            st = time_stats(ours, iters=max(30, steps), warmup=warmup)
+            family = sb.sb_last_kernel()
+            tC.fill_(float("nan"))
+            ours()
+            chk = check_output(tC, [n, n, n], ma, A, mb, B, "mnp", dtype, nsamples=1000)
+            own = conventional_own(ma, mb, "mnp", ext, dtype, tA, tB, tC, flops, iters=10)
+            t_ours = st["median_us"] / 1e3
+            row = dict(case=case, dtype=dtype, evaluation=plan.text(), kernel_family=family, kernel_ms=t_ours, kernel_us=st,
+                       gflops=flops / t_ours / 1e6, frac_of_mfma_peak=flops / t_ours / 1e9 / PEAK["mfma"][dtype],
+                       check_ok=chk["ok"], conventional_own=own, speedup_over_conventional_own=own["us"] / st["median_us"])
+            if dtype == "f32":
+                row["frac_of_fp32_mfma_peak"] = row["frac_of_mfma_peak"]
+            if torch_baseline:
+                a, b = tA.view(n, n), tB.view(n, n, n)
+                expr = "%s,%s->pnm" % (ma[::-1], mb[::-1])
+                _, t_conv = time_steps(lambda: torch.einsum(expr, a, b).contiguous(), steps, warmup)
+                row["conventional_torch_ms"] = t_conv
+                row["speedup_over_conventional_torch"] = t_conv / t_ours
+            rows.append(row)
+        del tA, tB, tC
+    return dict(workload="exceptional cases 3.6 and 6.4 at %d^4, %s: extended-operation kernel" % (n, " and ".join(dtypes)), short="ext-op", cases=rows)
 
 
 def run_bf16_family(torch_baseline=True, settle_ms=150.0):
@@ -785,10 +790,11 @@ def config_rows(head, others):
                              traffic=None, algorithmic_bytes=2113536, check_ok=o["all_outputs_ok"]))
         elif o.get("short") == "ext-op":
             for c in o["cases"]:
-                rows.append(dict(config="ext-op case %s 512^4" % c["case"], kernel_family=c["kernel_family"], kernel_us=c["kernel_us"]["median_us"],
+                rows.append(dict(config="ext-op case %s 512^4%s" % (c["case"], "" if c["dtype"] == "f32" else " " + c["dtype"]),
+                                 kernel_family=c["kernel_family"], kernel_us=c["kernel_us"]["median_us"],
                                  min_us=c["kernel_us"]["min_us"], max_us=c["kernel_us"]["max_us"], bound="mfma", achieved=c["gflops"] / 1e3,
-                                 unit="TFLOP/s", frac=c["frac_of_fp32_mfma_peak"], cold_frac=None, traffic=None,
-                                 algorithmic_bytes=4 * (512 ** 2 + 2 * 512 ** 3), check_ok=c["check_ok"]))
+                                 unit="TFLOP/s", frac=c["frac_of_mfma_peak"], cold_frac=None, traffic=None,
+                                 algorithmic_bytes=ESIZE[c["dtype"]] * (512 ** 2 + 2 * 512 ** 3), check_ok=c["check_ok"]))
         elif o.get("short") == "bf16-gemm":
             for c in o["cases"]:
                 rows.append(dict(config="bf16 %s %d^3 x %d" % (c["layout"], c["n"], c["batch"]), kernel_family=c["kernel_family"],
