@@ -474,6 +474,31 @@ def test_panel_grid_kernel_wide_blocks(opA, opB):
                 seed=3, kernel="panel", member=sb.SB_MEMBER_PANEL_WIDE if opA == "T" else sb.SB_MEMBER_PANEL_4X4)
 
 
+def test_panel_grid_kernel_wide_blocks_two_independent_levels():
+    # sb_gemm2 with both levels moving both operands: two outer indices of independent panel grids; and with
+    # level 0 moving A only and level 1 moving both (a row-side digit plus an outer index)
+    m, n, k, b0, b1 = 128, 512, 128, 2, 3
+    rng = np.random.default_rng(77)
+    for share_b in (False, True):
+        A = inputs.round_to_bf16(rng.standard_normal((b1, b0, k, m)).astype(np.float32)).astype(np.float64)       # [q][p][k][m]: column-major m x k
+        B = inputs.round_to_bf16(rng.standard_normal((b1, 1 if share_b else b0, n, k)).astype(np.float32)).astype(np.float64)
+        tA, tB = to_dev(A.reshape(-1), "bf16"), to_dev(B.reshape(-1), "bf16")
+        tC = to_dev(np.zeros(b1 * b0 * n * m), "bf16")
+        sb.sb_force_kernel(sb.SB_KERNEL_PANEL)
+        sb.sb_gemm2("N", "N", m, n, k, 0.5, tA, m, k * m, b0 * k * m, tB, k, 0 if share_b else n * k, (1 if share_b else b0) * n * k,
+                    0.0, tC, m, n * m, b0 * n * m, b0, b1, dt="bf16")
+        sync()
+        assert sb.sb_last_kernel() == sb.SB_KERNEL_PANEL and sb.sb_last_kernel_member() == sb.SB_MEMBER_PANEL_WIDE
+        got = from_dev(tC).reshape(b1, b0, n, m)
+        for q in range(b1):
+            for p_ in range(b0):
+                Ap = A[q, p_].T                                   # m x k (A[q][p] is k x m in C order, i.e. column-major m x k)
+                Bp = B[q, 0 if share_b else p_].T                 # k x n
+                ref = 0.5 * (Ap @ Bp)                             # m x n
+                assert_close(got[q, p_].T, ref, "bf16", k, np.abs(A).max(), np.abs(B).max(), 0.5, what=(share_b, p_, q))
+    sb.sb_force_kernel(sb.SB_KERNEL_AUTO)
+
+
 @pytest.mark.parametrize("ma,mb,mc", [("m[p]k", "kn[q]", "m[p]n[q]"), ("k[p]m", "nk[q]", "m[p]n[q]"), ("mk[p]", "nk[q]", "mn[p][q]"),
                                       ("km[p]", "kn[q]", "mn[p][q]")])
 def test_panel_grid_kernel_wide_blocks_nested(ma, mb, mc):
