@@ -618,6 +618,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 
     typedef RowPanel<MFT, CF::BN, BK> RB;
     constexpr int MI = MF::MI, VEC = MF::VEC, BM = CF::BM, BN = CF::BN, KG = BK / MF::KGROUP, NW = WAVES_M * WAVES_N;
     static_assert(BK * sizeof(T) == 128 && PA::CPR == 8, "a panel row is one 128-byte line of eight chunks");
+    // A row-contiguous fp32 A panel lies [k][row], so one LDS read of NBM consecutive rows at one k feeds all NBM
+    // MFMA blocks of the wave if lane j of block a stands for tile row wm + NBM j + a (instead of wm + 32 a + j):
+    // a quarter (half) of the read instructions, and the lane then holds NBM consecutive rows of every column,
+    // which leave as one vector store.  The row <-> (block, lane) map is free as long as every k uses the same one.
+    constexpr bool A_IL = !A_KC && sizeof(T) == 4 && (CF::NBM == 2 || CF::NBM == 4);
+    typedef T RowVec __attribute__((ext_vector_type(CF::NBM > 1 ? CF::NBM : 2)));
+    typedef T RowVecU __attribute__((ext_vector_type(CF::NBM > 1 ? CF::NBM : 2), aligned(sizeof(T))));
     static_assert((BM * 8) % (64 * NW) == 0 && (BN * 8) % (64 * NW) == 0, "whole wave loads per panel");
     constexpr int NLA = BM * 8 / (64 * NW), NLB = BN * 8 / (64 * NW);        // 16-byte loads per lane and panel
     constexpr int STAGE = PA::LDS_SIZE + PB::LDS_SIZE;                       // elements per stage: A panel, B panel
@@ -695,10 +702,22 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 
     auto read_frags = [&](auto set_c, auto st_c, int kg) __attribute__((always_inline)) {
         constexpr int SET = decltype(set_c)::value, ST = decltype(st_c)::value;
         const T *As = lds + ST * STAGE, *Bs = As + PA::LDS_SIZE;
+        if constexpr (A_IL) {
+            const int row = wm + CF::NBM * (lane % MI);
+            const int k = kg * MF::KGROUP + (lane / MI) * VEC;
+            const T *p = As + k * BM + (((row / RA::RPS) ^ RA::flip(k)) * RA::RPS) + row % RA::RPS;
 #pragma unroll
-        for (int a = 0; a < CF::NBM; ++a) {
-            if (A_KC) PA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
-            else      RA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+            for (int e = 0; e < VEC; ++e) {
+                const RowVec v = *(const RowVec *)(p + e * BM);
+#pragma unroll
+                for (int a = 0; a < CF::NBM; ++a) fa[SET][a][e] = v[a];
+            }
+        } else {
+#pragma unroll
+            for (int a = 0; a < CF::NBM; ++a) {
+                if (A_KC) PA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+                else      RA::fragment(fa[SET][a], As, wm + a * MI, kg, lane);
+            }
         }
 #pragma unroll
         for (int c = 0; c < CF::NBN; ++c) {
@@ -754,6 +773,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, WAVES_M * WAVES_N <= 4 ? 2 
             pa += panelA; pb += panelB;
         }
         T *C = cur.C;
+        if constexpr (A_IL) {            // lane j: rows wm + NBM j .. + NBM - 1 of its columns, one vector per column
+#pragma unroll
+            for (int c = 0; c < CF::NBN; ++c) {
+                T *col = C + wm + CF::NBM * (lane % MI) + (int64_t)(wn + c * MI + MF::result_row_lane(lane)) * g.ldc;
+#pragma unroll
+                for (int r = 0; r < MF::NREG; ++r) {
+                    T *dst = col + MF::result_row_reg(r) * g.ldc;
+                    RowVec v;
+#pragma unroll
+                    for (int a = 0; a < CF::NBM; ++a) v[a] = alpha * acc[a][c][r];
+                    if (BETA) {
+                        const RowVec old = *(const RowVecU *)dst;
+#pragma unroll
+                        for (int a = 0; a < CF::NBM; ++a) v[a] += beta * old[a];
+                    }
+                    *(RowVecU *)dst = v;
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int a = 0; a < CF::NBM; ++a)
 #pragma unroll
