@@ -417,6 +417,12 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
     constexpr int BM = PB * MB, NBM = BM / 4 / MI, NBN = BN / MI;
     constexpr int A_SIZE = BK * MB * PB, B_SIZE = BN * BK, STAGE = A_SIZE + B_SIZE;       // elements
     static_assert(BK * IPK == 16 && (KG == 1 || KG == 2) && NLB >= 1, "four loads of A per wave and panel");
+    // A column-contiguous fp32 B panel lies [k][col]: one LDS read of NBN consecutive columns at one k feeds all
+    // NBN MFMA blocks of the wave if lane j of block c stands for tile column NBN j + c (instead of 32 c + j);
+    // the column <-> (block, lane) map is free as long as every k uses it.  (Not with the transposed tile write,
+    // whose lanes run along these columns when they store.)
+    constexpr bool B_IL = !B_KC && !CT && sizeof(T) == 4 && (NBN == 2 || NBN == 4);
+    typedef T ColVec __attribute__((ext_vector_type(NBN > 1 ? NBN : 2)));
     __shared__ __attribute__((aligned(16))) T lds[2 * STAGE];
 
     const int64_t total = (int64_t)gridDim.x;
@@ -490,6 +496,15 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
             const T *p = As + (i * CPR + ((b / VEC) ^ ((i >> ISH) % CPR))) * VEC + (b % VEC);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) xa[a][e] = p[(k + e) * (MB * PB)];
+        }
+        if constexpr (B_IL) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const ColVec v = *(const ColVec *)(Bs + (k + e) * BN + NBN * (lane % MI));
+#pragma unroll
+                for (int c = 0; c < NBN; ++c) xb[c][e] = v[c];
+            }
+            return;
         }
 #pragma unroll
         for (int c = 0; c < NBN; ++c) {
@@ -585,10 +600,10 @@ __global__ __launch_bounds__(256, 2) void sbgemm_mfma_exa_dma_kernel(SbArgs g, i
             T *Cb = (T *)g.C + (bb + rho / MB) * g.bsC[0] + o1.c + (i0 + rho % MB);
 #pragma unroll
             for (int c = 0; c < NBN; ++c) {
-                T *col = Cb + (j0 + c * MI + MF::row_lane(lane)) * g.ldc;
 #pragma unroll
                 for (int r = 0; r < MF::NREG; ++r) {
-                    T *dst = col + MF::row_reg(r) * g.ldc;
+                    const int idx = MF::row_lane(lane) + MF::row_reg(r);        // index of the column inside its MFMA block
+                    T *dst = Cb + (j0 + (B_IL ? NBN * idx + c : c * MI + idx)) * g.ldc;
                     S v = alpha * acc[a][c][r];
                     if (BETA) v += beta * *dst;
                     *dst = v;
